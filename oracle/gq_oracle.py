@@ -1,0 +1,170 @@
+"""Plain fp64 CPU oracle for the computation GuidedQuant adds to layer-wise PTQ.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of
+what the HIP path must compute.  It shares no code with the HIP path and is
+never imported by the product package; only tests, the smoke check and the
+benchmark's cpu_baseline leg call it.
+
+Every function is the definition from the paper written out in numpy float64
+(a matmul is used as a library step where the definition is a matrix product;
+there is no blocking, fusion or reordering beyond what the definition states).
+
+Notation (paper, Section 3 "GuidedQuant", Algorithm 1):
+    X   [n, d_in]    input feature map of one linear layer, rows = tokens
+    dZ  [n, d_out]   gradient of the end loss w.r.t. the layer output Z = X W
+    g   (here G)     number of groups of output channels
+    J_k              k-th group: d_out/G consecutive output channels
+    s_k [n]          mean over j in J_k of dZ[:, j]**2
+    Hbar_k           X^T Diag(s_k) X                       [d_in, d_in]
+    W, What          weights before/after quantization; HERE stored
+                     [d_out, d_in] (row j = output channel j), i.e. the
+                     transpose of the paper's [d_in, d_out] layout.
+
+Pins (tests/test_oracle_pins.py) check every function against closed forms,
+a hand-worked example, an independent BLAS routine (dsyrk), and brute-force
+evaluation of the paper's *un-averaged* definitions (per-channel Hessians,
+the Frobenius form of the objective) on tiny inputs.  No function here is
+"parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_F64 = np.float64
+
+
+def group_partition(d_out: int, G: int):
+    """Algorithm 1, line 1: contiguous groups J_k of d_out/G channels.
+
+    Returns a list of (start, stop) half-open, 0-based channel ranges.
+    The paper assumes G divides d_out; anything else is an error.
+    """
+    if G <= 0 or d_out <= 0 or d_out % G != 0:
+        raise ValueError("G must be positive and divide d_out")
+    m = d_out // G
+    return [(k * m, (k + 1) * m) for k in range(G)]
+
+
+def group_weights(dZ, G: int, grad_scale: float = 1.0) -> np.ndarray:
+    """Algorithm 1, line 2: s[i, k] = (1/|J_k|) * sum_{j in J_k} (c * dZ[i, j])**2.
+
+    `grad_scale` (c) is the constant the paper multiplies the gradients by while
+    computing the averaged Hessians (Section 3.2, last paragraph before
+    Algorithm 1; 1e3 in its experiments).  It is applied to dZ before squaring
+    and is not undone.
+    """
+    dZ = np.asarray(dZ, dtype=_F64)
+    n, d_out = dZ.shape
+    s = np.empty((n, G), dtype=_F64)
+    for k, (j0, j1) in enumerate(group_partition(d_out, G)):
+        g = grad_scale * dZ[:, j0:j1]
+        s[:, k] = np.sum(g * g, axis=1) / (j1 - j0)
+    return s
+
+
+def fisher_gram(X, s, H=None) -> np.ndarray:
+    """Algorithm 1, line 4: Hbar_k = X^T Diag(s_k) X for every group k.
+
+    X [n, d_in], s [n, G] -> H [G, d_in, d_in] (full squares).  If `H` is given
+    the result is added to it (accumulation over token chunks: the sum over
+    tokens in the definition splits over disjoint chunks).
+    """
+    X = np.asarray(X, dtype=_F64)
+    s = np.asarray(s, dtype=_F64)
+    n, d_in = X.shape
+    G = s.shape[1]
+    assert s.shape[0] == n
+    if H is None:
+        H = np.zeros((G, d_in, d_in), dtype=_F64)
+    for k in range(G):
+        H[k] += X.T @ (s[:, k][:, None] * X)
+    return H
+
+
+def fisher_gram_block(X, s_k, rows, cols) -> np.ndarray:
+    """Entries Hbar_k[rows, cols] of Algorithm 1, line 4, for one group.
+
+    s_k is the length-n weight vector of that group; rows/cols are slices or
+    index arrays into the d_in axis.  Same definition as `fisher_gram`,
+    restricted to a block of entries so that large shapes can be sampled.
+    """
+    X = np.asarray(X)
+    s_k = np.asarray(s_k, dtype=_F64)
+    A = np.asarray(X[:, rows], dtype=_F64)
+    B = np.asarray(X[:, cols], dtype=_F64)
+    return A.T @ (s_k[:, None] * B)
+
+
+def objective(W, What, H, G: int | None = None):
+    """Eq. (ours2): sum_k sum_{j in J_k} (w_j - what_j)^T Hbar_k (w_j - what_j).
+
+    W, What [d_out, d_in] (row j = channel j), H [G, d_in, d_in].
+    Returns (obj[G], obj_row[d_out]); obj[k] is the inner sum over J_k and
+    obj_row[j] the single quadratic form of channel j.  The layer objective of
+    the paper is obj.sum().
+    """
+    W = np.asarray(W, dtype=_F64)
+    What = np.asarray(What, dtype=_F64)
+    H = np.asarray(H, dtype=_F64)
+    if G is None:
+        G = H.shape[0]
+    d_out, d_in = W.shape
+    assert H.shape == (G, d_in, d_in)
+    delta = W - What
+    obj = np.zeros(G, dtype=_F64)
+    obj_row = np.zeros(d_out, dtype=_F64)
+    for k, (j0, j1) in enumerate(group_partition(d_out, G)):
+        Dk = delta[j0:j1]
+        obj_row[j0:j1] = np.sum((Dk @ H[k]) * Dk, axis=1)
+        obj[k] = obj_row[j0:j1].sum()
+    return obj, obj_row
+
+
+# ----------------------------------------------------------------------------
+# Definitional variants: the paper's un-averaged quantities.  They never go
+# through s or Hbar and are used by the tests to pin the functions above.
+# ----------------------------------------------------------------------------
+
+def per_channel_hessian(X, dZ, j: int, grad_scale: float = 1.0) -> np.ndarray:
+    """H_j = X^T Diag(dZ[:, j])^2 X (Section 3.2, the chain-rule identity for
+    H_j = n F_j), built as an explicit sum of outer products over tokens."""
+    X = np.asarray(X, dtype=_F64)
+    dZ = np.asarray(dZ, dtype=_F64)
+    n, d_in = X.shape
+    Hj = np.zeros((d_in, d_in), dtype=_F64)
+    for i in range(n):
+        g = grad_scale * dZ[i, j]
+        Hj += (g * g) * np.outer(X[i], X[i])
+    return Hj
+
+
+def unaveraged_objective(X, dZ, W, What, grad_scale: float = 1.0) -> float:
+    """Eq. (ours): || dZ (.) (X W - X What) ||_F^2, with W stored [d_out, d_in]
+    so that Z = X W^T in this layout.  Written as the double sum over tokens
+    and channels of the right-hand side of that equation."""
+    X = np.asarray(X, dtype=_F64)
+    dZ = np.asarray(dZ, dtype=_F64)
+    W = np.asarray(W, dtype=_F64)
+    What = np.asarray(What, dtype=_F64)
+    n, d_out = dZ.shape
+    total = 0.0
+    for i in range(n):
+        for j in range(d_out):
+            z = float(np.dot(X[i], W[j]))
+            zhat = float(np.dot(X[i], What[j]))
+            total += (grad_scale * dZ[i, j] * (z - zhat)) ** 2
+    return total
+
+
+def objective_from_tokens(X, s_k, delta_j) -> float:
+    """sum_i s_k[i] * (x_i . delta_j)^2: the quadratic form delta^T Hbar_k delta
+    evaluated from X without ever forming Hbar_k (same step as in the proof of
+    Remark 3.1, applied to the averaged weights)."""
+    X = np.asarray(X, dtype=_F64)
+    s_k = np.asarray(s_k, dtype=_F64)
+    delta_j = np.asarray(delta_j, dtype=_F64)
+    total = 0.0
+    for i in range(X.shape[0]):
+        t = float(np.dot(X[i], delta_j))
+        total += s_k[i] * t * t
+    return total

@@ -1,0 +1,191 @@
+"""Pins for the CPU oracle: closed forms, a hand-worked example, an independent
+BLAS routine, and brute force through the paper's *un-averaged* definitions.
+None of these tests touches the HIP path."""
+import numpy as np
+import pytest
+import scipy.linalg.blas as blas
+
+import oracle
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- worked example
+# Worked by hand from Algorithm 1 (lines 1, 2, 4) and Eq. (ours2); n=3, d_in=2,
+# d_out=4, G=2 so J_0={0,1}, J_1={2,3}.
+X_EX = np.array([[1.0, 2.0], [3.0, 4.0], [0.0, -1.0]])
+DZ_EX = np.array([[1.0, -1.0, 2.0, 0.0], [0.0, 2.0, 1.0, 1.0], [3.0, 0.0, 0.0, 1.0]])
+S_EX = np.array([[1.0, 2.0], [2.0, 1.0], [4.5, 0.5]])
+H_EX = np.array([[[19.0, 26.0], [26.0, 40.5]], [[11.0, 16.0], [16.0, 24.5]]])
+DELTA_EX = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0], [1.0, -1.0]])
+OBJ_ROW_EX = np.array([19.0, 40.5, 67.5, 3.5])
+OBJ_EX = np.array([59.5, 71.0])
+
+
+def test_worked_example_group_weights():
+    np.testing.assert_allclose(oracle.group_weights(DZ_EX, 2), S_EX, rtol=0, atol=1e-15)
+
+
+def test_worked_example_gram():
+    np.testing.assert_allclose(oracle.fisher_gram(X_EX, S_EX), H_EX, rtol=0, atol=1e-13)
+
+
+def test_worked_example_objective():
+    What = np.zeros((4, 2))
+    obj, obj_row = oracle.objective(DELTA_EX, What, H_EX, 2)
+    np.testing.assert_allclose(obj_row, OBJ_ROW_EX, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(obj, OBJ_EX, rtol=0, atol=1e-13)
+    # sign convention: only the difference W - What matters
+    obj2, _ = oracle.objective(What, DELTA_EX, H_EX, 2)
+    np.testing.assert_allclose(obj2, OBJ_EX, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- group partition / s
+def test_partition_is_contiguous_and_rejects_nondivisible():
+    assert oracle.group_partition(8, 4) == [(0, 2), (2, 4), (4, 6), (6, 8)]
+    with pytest.raises(ValueError):
+        oracle.group_partition(10, 4)
+    with pytest.raises(ValueError):
+        oracle.group_weights(np.ones((3, 10)), 4)
+
+
+def test_s_constant_gradient_closed_form():
+    s = oracle.group_weights(np.full((7, 12), -0.5), 3, grad_scale=4.0)
+    np.testing.assert_allclose(s, np.full((7, 3), 16.0 * 0.25), rtol=1e-15)
+
+
+def test_s_one_hot_column_lands_in_its_group_only():
+    n, d_out, G = 5, 12, 3
+    v = np.arange(1.0, n + 1)
+    for j in range(d_out):
+        dZ = np.zeros((n, d_out))
+        dZ[:, j] = v
+        s = oracle.group_weights(dZ, G)
+        expect = np.zeros((n, G))
+        expect[:, j // 4] = v * v / 4.0
+        np.testing.assert_allclose(s, expect, rtol=1e-15)
+
+
+def test_s_g_equals_dout_is_elementwise_square_and_g1_is_row_mean():
+    dZ = _rng(0).standard_normal((9, 6))
+    np.testing.assert_allclose(oracle.group_weights(dZ, 6), dZ ** 2, rtol=1e-15)
+    np.testing.assert_allclose(oracle.group_weights(dZ, 1)[:, 0], np.mean(dZ ** 2, axis=1), rtol=1e-14)
+
+
+def test_scale_law_s_h_obj():
+    r = _rng(1)
+    X, dZ = r.standard_normal((20, 5)), r.standard_normal((20, 8))
+    W, What = r.standard_normal((8, 5)), r.standard_normal((8, 5))
+    c = 1e3
+    s1, sc = oracle.group_weights(dZ, 2), oracle.group_weights(dZ, 2, grad_scale=c)
+    np.testing.assert_allclose(sc, c * c * s1, rtol=1e-13)
+    H1, Hc = oracle.fisher_gram(X, s1), oracle.fisher_gram(X, sc)
+    np.testing.assert_allclose(Hc, c * c * H1, rtol=1e-12)
+    np.testing.assert_allclose(oracle.objective(W, What, Hc)[0], c * c * oracle.objective(W, What, H1)[0], rtol=1e-12)
+
+
+# ---------------------------------------------------------------- Gram
+def test_gram_g1_unit_gradient_is_plain_xtx_dsyrk():
+    X = _rng(2).standard_normal((37, 11))
+    H = oracle.fisher_gram(X, oracle.group_weights(np.ones((37, 4)), 1))[0]
+    C = blas.dsyrk(1.0, X, trans=1, lower=0)           # upper triangle of X^T X
+    iu = np.triu_indices(11)
+    np.testing.assert_allclose(H[iu], C[iu], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(H, H.T, rtol=1e-14, atol=1e-14)
+
+
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_gram_is_group_mean_of_per_channel_hessians(G):
+    r = _rng(3 + G)
+    n, d_in, d_out = 64, 16, 8
+    X, dZ = r.standard_normal((n, d_in)), r.standard_normal((n, d_out)) * np.exp(r.standard_normal((n, 1)))
+    H = oracle.fisher_gram(X, oracle.group_weights(dZ, G))
+    m = d_out // G
+    for k in range(G):
+        Hbar = sum(oracle.per_channel_hessian(X, dZ, j) for j in range(k * m, (k + 1) * m)) / m
+        np.testing.assert_allclose(H[k], Hbar, rtol=1e-12, atol=1e-12 * np.abs(Hbar).max())
+
+
+def test_gram_entrywise_brute_force_nonsquare_and_block():
+    r = _rng(9)
+    n, d_in, G = 13, 7, 3
+    X, s = r.standard_normal((n, d_in)), r.random((n, G))
+    H = oracle.fisher_gram(X, s)
+    assert H.shape == (G, d_in, d_in)
+    for k in range(G):
+        for a in range(d_in):
+            for b in range(d_in):
+                ref = sum(s[i, k] * X[i, a] * X[i, b] for i in range(n))
+                assert abs(H[k, a, b] - ref) <= 1e-12 * (1 + abs(ref))
+    blk = oracle.fisher_gram_block(X, s[:, 1], slice(1, 4), np.array([6, 0, 2]))
+    np.testing.assert_allclose(blk, H[1][1:4][:, [6, 0, 2]], rtol=1e-13, atol=1e-13)
+
+
+def test_gram_symmetric_psd_rank_and_single_token():
+    r = _rng(10)
+    n, d_in, G = 6, 10, 2
+    X, s = r.standard_normal((n, d_in)), r.random((n, G))
+    H = oracle.fisher_gram(X, s)
+    for k in range(G):
+        np.testing.assert_allclose(H[k], H[k].T, rtol=1e-13, atol=1e-13)
+        ev = np.linalg.eigvalsh(0.5 * (H[k] + H[k].T))
+        assert ev.min() >= -1e-12 * ev.max()
+        assert np.linalg.matrix_rank(H[k]) <= n
+    H1 = oracle.fisher_gram(X[:1], s[:1])
+    for k in range(G):
+        np.testing.assert_allclose(H1[k], s[0, k] * np.outer(X[0], X[0]), rtol=1e-14)
+
+
+def test_gram_chunk_additivity():
+    r = _rng(11)
+    X, s = r.standard_normal((50, 6)), r.random((50, 2))
+    H = oracle.fisher_gram(X[:20], s[:20])
+    H = oracle.fisher_gram(X[20:], s[20:], H=H)
+    np.testing.assert_allclose(H, oracle.fisher_gram(X, s), rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------- objective
+def test_objective_equals_sum_over_tokens_form():
+    r = _rng(12)
+    n, d_in, d_out, G = 40, 6, 8, 4
+    X, dZ = r.standard_normal((n, d_in)), r.standard_normal((n, d_out))
+    W, What = r.standard_normal((d_out, d_in)), r.standard_normal((d_out, d_in))
+    s = oracle.group_weights(dZ, G)
+    obj, obj_row = oracle.objective(W, What, oracle.fisher_gram(X, s), G)
+    m = d_out // G
+    for j in range(d_out):
+        ref = oracle.objective_from_tokens(X, s[:, j // m], W[j] - What[j])
+        assert abs(obj_row[j] - ref) <= 1e-11 * ref
+    np.testing.assert_allclose(obj, obj_row.reshape(G, m).sum(1), rtol=1e-13)
+
+
+def test_objective_with_one_group_per_channel_is_the_unaveraged_frobenius_form():
+    # Remark 3.1 / Eq. (ours): with |J_k| = 1 nothing is averaged away.
+    r = _rng(13)
+    n, d_in, d_out = 30, 5, 6
+    X, dZ = r.standard_normal((n, d_in)), r.standard_normal((n, d_out))
+    W, What = r.standard_normal((d_out, d_in)), r.standard_normal((d_out, d_in))
+    H = oracle.fisher_gram(X, oracle.group_weights(dZ, d_out, grad_scale=3.0))
+    obj, _ = oracle.objective(W, What, H, d_out)
+    ref = oracle.unaveraged_objective(X, dZ, W, What, grad_scale=3.0)
+    assert abs(obj.sum() - ref) <= 1e-11 * ref
+
+
+def test_objective_zero_nonneg_single_perturbation_and_group_routing():
+    r = _rng(14)
+    n, d_in, d_out, G = 25, 7, 6, 3
+    X, s = r.standard_normal((n, d_in)), r.random((n, G))
+    H = oracle.fisher_gram(X, s)
+    W = r.standard_normal((d_out, d_in))
+    obj0, row0 = oracle.objective(W, W.copy(), H, G)
+    assert np.all(obj0 == 0) and np.all(row0 == 0)
+    eps, a, j = 0.25, 4, 3                              # row 3 lives in group 1
+    What = W.copy()
+    What[j, a] += eps
+    obj, row = oracle.objective(W, What, H, G)
+    assert abs(obj[1] - eps * eps * H[1, a, a]) <= 1e-13 * obj[1]
+    assert obj[0] == 0 and obj[2] == 0 and row[j] == obj[1]
+    objr, _ = oracle.objective(W, r.standard_normal((d_out, d_in)), H, G)
+    assert np.all(objr > 0)

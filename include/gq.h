@@ -1,0 +1,155 @@
+/*
+ * libgq — the computation GuidedQuant adds to layer-wise post-training
+ * quantization, as hand-written HIP kernels for AMD MI355X (gfx950).
+ *
+ * For one linear layer with calibration input X[n, d_in] and output gradients
+ * dZ[n, d_out], and G contiguous groups J_k of d_out/G output channels
+ * (GuidedQuant, Algorithm 1, line 1):
+ *
+ *   gq_group_weights  s[i,k]  = c^2/|J_k| * sum_{j in J_k} dZ[i,j]^2      (Algorithm 1, line 2)
+ *   gq_fisher_gram    H[k]   (+)= X^T Diag(s[:,k]) X                      (Algorithm 1, line 4)
+ *   gq_fisher_mirror  H[k][b,a] = H[k][a,b]  for a < b                    (storage of the full square)
+ *   gq_objective      obj[k]  = sum_{j in J_k} (w_j-what_j)^T H[k] (w_j-what_j)   (Eq. "ours2", Section 3.2)
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is DEVICE memory on the current HIP device, allocated
+ *     and owned by the caller.  The library never allocates, frees or keeps a
+ *     pointer past the call.
+ *   - All matrices are row-major.  `ld_*` is the distance between consecutive
+ *     rows in ELEMENTS.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls validate their arguments on the host, enqueue kernels on that stream
+ *     and return without synchronising; outputs are valid once the stream has
+ *     been synchronised.
+ *   - Return value: GQ_OK (0) or a negative gq_status.  On any error nothing has
+ *     been enqueued and no output has been touched.
+ *   - Results are deterministic: identical arguments give bit-identical outputs
+ *     (no floating-point atomics whose order can vary).
+ *   - NaN/Inf in the inputs propagate; nothing is checked.
+ */
+#ifndef GQ_H_
+#define GQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GQ_OK = 0,
+  GQ_ERR_NULLPTR = -1,     /* a required pointer is NULL                                  */
+  GQ_ERR_SHAPE = -2,       /* negative/zero size, G does not divide d_out, ld < width     */
+  GQ_ERR_DTYPE = -3,       /* unknown gq_dtype                                            */
+  GQ_ERR_ALIGN = -4,       /* base pointer or row pitch not aligned as documented         */
+  GQ_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than *_workspace_bytes()          */
+  GQ_ERR_HIP = -6,         /* a HIP runtime call or kernel launch failed                  */
+  GQ_ERR_UNSUPPORTED = -7  /* valid request that this build does not implement            */
+} gq_status;
+
+typedef enum {
+  GQ_F32 = 0,   /* IEEE binary32                                                        */
+  GQ_BF16 = 1   /* bfloat16 (upper 16 bits of binary32)                                 */
+} gq_dtype;
+
+/* flags of gq_fisher_gram */
+enum {
+  GQ_ACCUMULATE = 1u << 0, /* H += ... ; without it the upper triangle of H is overwritten */
+  GQ_MIRROR = 1u << 1      /* after the update also fill the strictly lower triangle       */
+};
+
+/* Library version: major*10000 + minor*100 + patch. */
+int gq_version(void);
+
+/* Static, never-freed description of a gq_status value. */
+const char* gq_status_string(int status);
+
+/*
+ * Averaged squared output gradients (Algorithm 1, line 2; the gradient scaling
+ * constant of Section 3.2 is `grad_scale`, applied to dZ before squaring and
+ * never undone; pass 1.0f for none).
+ *
+ *   dZ   [n, d_out]  device, dz_dtype GQ_F32 (GQ_BF16 also accepted), row pitch ld_dz elements
+ *   s    [n, G]      device, fp32, dense (row pitch G)
+ *   s[i,k] = grad_scale^2 / (d_out/G) * sum_{j = k*d_out/G}^{(k+1)*d_out/G - 1} dZ[i,j]^2
+ *
+ * n == 0 is a valid no-op.  Errors: GQ_ERR_SHAPE if n < 0, d_out <= 0, G <= 0,
+ * d_out % G != 0 or ld_dz < d_out; GQ_ERR_ALIGN if dZ is not 16-byte aligned or
+ * the row pitch in bytes is not a multiple of 16.
+ */
+int gq_group_weights(const void* dZ, gq_dtype dz_dtype, int64_t n, int64_t d_out, int64_t ld_dz,
+                     int32_t G, float grad_scale, float* s, void* hip_stream);
+
+/*
+ * Bytes of device workspace gq_fisher_gram needs for these sizes (may be 0).
+ * Returns 0 for invalid arguments as well; gq_fisher_gram reports those.
+ */
+size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in, int32_t G);
+
+/*
+ * Grouped Fisher/Hessian blocks (Algorithm 1, line 4), one token chunk at a time:
+ *
+ *   H[k][a,b] (+)= sum_{i<n} s[i,k] * X[i,a] * X[i,b]      for a <= b, k < G
+ *
+ *   X    [n, d_in]        device, x_dtype, row pitch ld_x elements
+ *   s    [n, G]           device fp32 (as written by gq_group_weights)
+ *   H    [G, d_in, d_in]  device fp32, dense.  Only the upper triangle (incl.
+ *                         diagonal) of each H[k] is read and written; the strictly
+ *                         lower triangle is left untouched unless GQ_MIRROR is set,
+ *                         in which case it is overwritten with the transpose and
+ *                         H[k] is bit-exactly symmetric afterwards.
+ *   flags  GQ_ACCUMULATE adds to the existing upper triangle (streaming over token
+ *          chunks: first call without it, later calls with it).
+ *   x_dtype selects the arithmetic: GQ_F32 -> fp32 matrix-core path (fp32 products,
+ *          fp32 accumulation); GQ_BF16 -> bf16 matrix-core path: one operand is
+ *          bf16_rne(s[i,k]*X[i,a]) (fp32 multiply, round to nearest even), the
+ *          other the raw X[i,b]; fp32 accumulation.
+ *   workspace  device buffer of at least gq_fisher_gram_workspace_bytes() bytes,
+ *          256-byte aligned (may be NULL when that size is 0); contents are
+ *          scratch.
+ *
+ * n == 0: valid; without GQ_ACCUMULATE the upper triangle is zero-filled.
+ * Errors: GQ_ERR_SHAPE (n < 0, d_in <= 0, G <= 0, ld_x < d_in), GQ_ERR_DTYPE,
+ * GQ_ERR_ALIGN (X or H not 16-byte aligned, or ld_x*sizeof(element) not a multiple
+ * of 16), GQ_ERR_WORKSPACE, GQ_ERR_HIP.
+ */
+int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int64_t ld_x,
+                   const float* s, int32_t G, float* H, uint32_t flags,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Fill the strictly lower triangle of every H[k] from its upper triangle, in
+ * place (the paper's cached Hessians are full squares).  H [G, d_in, d_in] fp32.
+ */
+int gq_fisher_mirror(float* H, int64_t d_in, int32_t G, void* hip_stream);
+
+/* Bytes of device workspace gq_objective needs (never 0 for valid sizes). */
+size_t gq_objective_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G);
+
+/*
+ * GuidedQuant layer objective (Eq. "ours2", Section 3.2):
+ *
+ *   obj_row[j] = (W[j,:]-What[j,:])^T H[k(j)] (W[j,:]-What[j,:]),  k(j) = j / (d_out/G)
+ *   obj[k]     = sum_{j in J_k} obj_row[j]
+ *
+ *   W, What  [d_out, d_in]    device fp32, row pitch ld_w elements; row j is output
+ *                             channel j (the transpose of the paper's [d_in, d_out])
+ *   H        [G, d_in, d_in]  device fp32; only the upper triangle (incl. diagonal)
+ *                             of each H[k] is read (symmetry supplies the rest)
+ *   obj      [G]              device fp64
+ *   obj_row  [d_out]          device fp32, or NULL if not wanted
+ *   workspace  at least gq_objective_workspace_bytes() bytes, 256-byte aligned
+ *
+ * Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_out <= 0, d_in <= 0, G <= 0,
+ * d_out % G != 0, ld_w < d_in), GQ_ERR_ALIGN (W/What/H not 16-byte aligned or
+ * ld_w*4 not a multiple of 16), GQ_ERR_WORKSPACE, GQ_ERR_HIP.
+ */
+int gq_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld_w,
+                 const float* H, int32_t G, double* obj, float* obj_row,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GQ_H_ */

@@ -1,0 +1,185 @@
+"""Thin ctypes binding of libgq's C ABI (include/gq.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the computation runs inside libgq's kernels.  There is no
+CPU or PyTorch fallback: a missing library or a non-GPU tensor raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libgq.so")
+
+GQ_F32, GQ_BF16 = 0, 1
+GQ_ACCUMULATE, GQ_MIRROR = 1, 2
+
+_lib = None
+
+
+class GQError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {status_string(status)} (gq_status {status})")
+        self.status = status
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libgq.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(p)
+    c = ctypes
+    lib.gq_version.restype = c.c_int
+    lib.gq_version.argtypes = []
+    lib.gq_status_string.restype = c.c_char_p
+    lib.gq_status_string.argtypes = [c.c_int]
+    lib.gq_group_weights.restype = c.c_int
+    lib.gq_group_weights.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_int32,
+                                     c.c_float, c.c_void_p, c.c_void_p]
+    lib.gq_fisher_gram_workspace_bytes.restype = c.c_size_t
+    lib.gq_fisher_gram_workspace_bytes.argtypes = [c.c_int, c.c_int64, c.c_int64, c.c_int32]
+    lib.gq_fisher_gram.restype = c.c_int
+    lib.gq_fisher_gram.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
+                                   c.c_int32, c.c_void_p, c.c_uint32, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.gq_fisher_mirror.restype = c.c_int
+    lib.gq_fisher_mirror.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p]
+    lib.gq_objective_workspace_bytes.restype = c.c_size_t
+    lib.gq_objective_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
+    lib.gq_objective.restype = c.c_int
+    lib.gq_objective.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
+                                 c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def gq_version() -> int:
+    return int(load_library().gq_version())
+
+
+def status_string(status: int) -> str:
+    return load_library().gq_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise GQError(status, what)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GQ_F32
+    if t.dtype == torch.bfloat16:
+        return GQ_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: libgq takes float32 or bfloat16")
+
+
+def _require_gpu(*tensors: torch.Tensor) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("libgq runs on the GPU only: got a tensor on %s" % t.device)
+
+
+def _rows(t: torch.Tensor) -> int:
+    """Row pitch in elements of a 2-D tensor whose rows are contiguous."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a 2-D tensor with contiguous rows")
+    return int(t.stride(0)) if t.shape[0] > 1 else int(max(t.stride(0), t.shape[1]))
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
+    if nbytes == 0:
+        return None, 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return ws, ws.data_ptr()
+
+
+def gq_group_weights(dZ: torch.Tensor, G: int, grad_scale: float = 1.0,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """s[i,k] = grad_scale^2/(d_out/G) * sum_{j in J_k} dZ[i,j]^2 -> fp32 [n, G]."""
+    _require_gpu(dZ, out)
+    n, d_out = dZ.shape
+    s = out if out is not None else torch.empty((n, G), dtype=torch.float32, device=dZ.device)
+    assert s.dtype == torch.float32 and s.is_contiguous() and tuple(s.shape) == (n, G)
+    st = load_library().gq_group_weights(dZ.data_ptr(), _dtype_code(dZ), n, d_out, _rows(dZ), G,
+                                         float(grad_scale), s.data_ptr(), _stream())
+    _check(st, "gq_group_weights")
+    return s
+
+
+def gq_fisher_gram_workspace_bytes(x_dtype: torch.dtype, n: int, d_in: int, G: int) -> int:
+    code = GQ_BF16 if x_dtype == torch.bfloat16 else GQ_F32
+    return int(load_library().gq_fisher_gram_workspace_bytes(code, n, d_in, G))
+
+
+def gq_fisher_gram(X: torch.Tensor, s: torch.Tensor, H: Optional[torch.Tensor] = None,
+                   accumulate: bool = False, mirror: bool = False,
+                   workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """H[k] (+)= X^T Diag(s[:,k]) X on the upper triangle -> fp32 [G, d_in, d_in]."""
+    _require_gpu(X, s, H, workspace)
+    n, d_in = X.shape
+    G = int(s.shape[1])
+    assert s.dtype == torch.float32 and s.is_contiguous() and s.shape[0] == n
+    if H is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs an existing H")
+        H = torch.empty((G, d_in, d_in), dtype=torch.float32, device=X.device)
+    assert H.dtype == torch.float32 and H.is_contiguous() and tuple(H.shape) == (G, d_in, d_in)
+    lib = load_library()
+    need = int(lib.gq_fisher_gram_workspace_bytes(_dtype_code(X), n, d_in, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(need, X.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    flags = (GQ_ACCUMULATE if accumulate else 0) | (GQ_MIRROR if mirror else 0)
+    st = lib.gq_fisher_gram(X.data_ptr(), _dtype_code(X), n, d_in, _rows(X) if n > 0 else d_in,
+                            s.data_ptr(), G, H.data_ptr(), flags, ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_fisher_gram")
+    return H
+
+
+def gq_fisher_mirror(H: torch.Tensor) -> torch.Tensor:
+    """Fill the strictly lower triangle of every H[k] from the upper one, in place."""
+    _require_gpu(H)
+    assert H.dtype == torch.float32 and H.is_contiguous() and H.dim() == 3 and H.shape[1] == H.shape[2]
+    st = load_library().gq_fisher_mirror(H.data_ptr(), int(H.shape[1]), int(H.shape[0]), _stream())
+    _check(st, "gq_fisher_mirror")
+    return H
+
+
+def gq_objective(W: torch.Tensor, What: torch.Tensor, H: torch.Tensor, want_rows: bool = False,
+                 workspace: Optional[torch.Tensor] = None):
+    """obj[k] = sum_{j in J_k} (W[j]-What[j])^T H[k] (W[j]-What[j]) -> fp64 [G]
+    (and the per-channel terms, fp32 [d_out], if want_rows)."""
+    _require_gpu(W, What, H, workspace)
+    d_out, d_in = W.shape
+    G = int(H.shape[0])
+    assert W.dtype == torch.float32 and What.dtype == torch.float32 and H.dtype == torch.float32
+    assert What.shape == W.shape and _rows(W) == _rows(What) and H.is_contiguous()
+    lib = load_library()
+    need = int(lib.gq_objective_workspace_bytes(d_out, d_in, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(max(need, 1), W.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    obj = torch.empty(G, dtype=torch.float64, device=W.device)
+    rows = torch.empty(d_out, dtype=torch.float32, device=W.device) if want_rows else None
+    st = lib.gq_objective(W.data_ptr(), What.data_ptr(), d_out, d_in, _rows(W), H.data_ptr(), G,
+                          obj.data_ptr(), rows.data_ptr() if want_rows else None, ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_objective")
+    return (obj, rows) if want_rows else obj

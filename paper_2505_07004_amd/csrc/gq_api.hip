@@ -1,0 +1,99 @@
+// C ABI of libgq: argument validation and dispatch to the gfx950 kernels.
+// Every entry point checks its arguments on the host, enqueues work on the caller's
+// stream and returns without synchronising.
+#include "gq_internal.hpp"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+inline size_t elem_size(gq_dtype dt) { return dt == GQ_BF16 ? 2 : 4; }
+inline bool valid_dtype(int dt) { return dt == GQ_F32 || dt == GQ_BF16; }
+inline int from_hip(hipError_t e) { return e == hipSuccess ? GQ_OK : GQ_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int gq_version(void) { return 100; }  // 0.1.0
+
+const char* gq_status_string(int status) {
+  switch (status) {
+    case GQ_OK: return "ok";
+    case GQ_ERR_NULLPTR: return "a required pointer is NULL";
+    case GQ_ERR_SHAPE: return "invalid shape (sizes must be positive, G must divide d_out, ld >= width)";
+    case GQ_ERR_DTYPE: return "unknown dtype";
+    case GQ_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
+    case GQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GQ_ERR_HIP: return "HIP runtime error";
+    case GQ_ERR_UNSUPPORTED: return "unsupported request";
+    default: return "unknown status";
+  }
+}
+
+int gq_group_weights(const void* dZ, gq_dtype dz_dtype, int64_t n, int64_t d_out, int64_t ld_dz, int32_t G,
+                     float grad_scale, float* s, void* hip_stream) {
+  if (!valid_dtype((int)dz_dtype)) return GQ_ERR_DTYPE;
+  if (n < 0 || d_out <= 0 || G <= 0 || d_out % G != 0 || ld_dz < d_out) return GQ_ERR_SHAPE;
+  if (n == 0) return GQ_OK;
+  if (!dZ || !s) return GQ_ERR_NULLPTR;
+  if (!aligned16(dZ) || ((size_t)ld_dz * elem_size(dz_dtype)) % 16 != 0) return GQ_ERR_ALIGN;
+  return from_hip(gq::launch_group_weights(dZ, dz_dtype, n, d_out, ld_dz, G, grad_scale, s, (hipStream_t)hip_stream));
+}
+
+size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in, int32_t G) {
+  if (!valid_dtype((int)x_dtype) || n < 0 || d_in <= 0 || G <= 0) return 0;
+  return x_dtype == GQ_BF16 ? gq::fisher_gram_bf16_workspace(n, d_in, G) : 0;
+}
+
+int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int64_t ld_x, const float* s, int32_t G,
+                   float* H, uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!valid_dtype((int)x_dtype)) return GQ_ERR_DTYPE;
+  if (n < 0 || d_in <= 0 || G <= 0 || ld_x < d_in) return GQ_ERR_SHAPE;
+  if (flags & ~(uint32_t)(GQ_ACCUMULATE | GQ_MIRROR)) return GQ_ERR_UNSUPPORTED;
+  if (!H) return GQ_ERR_NULLPTR;
+  if (n > 0 && (!X || !s)) return GQ_ERR_NULLPTR;
+  if (!aligned16(H)) return GQ_ERR_ALIGN;
+  if (n > 0 && (!aligned16(X) || ((size_t)ld_x * elem_size(x_dtype)) % 16 != 0)) return GQ_ERR_ALIGN;
+  const size_t need = gq_fisher_gram_workspace_bytes(x_dtype, n, d_in, G);
+  if (need > 0 && (!workspace || workspace_bytes < need || !aligned256(workspace))) return GQ_ERR_WORKSPACE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool accumulate = (flags & GQ_ACCUMULATE) != 0;
+  hipError_t e = hipSuccess;
+  if (n == 0) {
+    if (!accumulate) e = gq::launch_zero_upper(H, d_in, G, st);
+  } else if (x_dtype == GQ_F32) {
+    e = gq::launch_fisher_gram_f32((const float*)X, n, d_in, ld_x, s, G, H, accumulate, st);
+  } else {
+    e = gq::launch_fisher_gram_bf16(X, n, d_in, ld_x, s, G, H, accumulate, workspace, workspace_bytes, st);
+  }
+  if (e != hipSuccess) return GQ_ERR_HIP;
+  if (flags & GQ_MIRROR) e = gq::launch_mirror(H, d_in, G, st);
+  return from_hip(e);
+}
+
+int gq_fisher_mirror(float* H, int64_t d_in, int32_t G, void* hip_stream) {
+  if (d_in <= 0 || G <= 0) return GQ_ERR_SHAPE;
+  if (!H) return GQ_ERR_NULLPTR;
+  if (!aligned16(H)) return GQ_ERR_ALIGN;
+  return from_hip(gq::launch_mirror(H, d_in, G, (hipStream_t)hip_stream));
+}
+
+size_t gq_objective_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G) {
+  if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0) return 0;
+  return gq::objective_workspace(d_out, d_in, G);
+}
+
+int gq_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld_w, const float* H,
+                 int32_t G, double* obj, float* obj_row, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in) return GQ_ERR_SHAPE;
+  if (!W || !What || !H || !obj) return GQ_ERR_NULLPTR;
+  if (!aligned16(W) || !aligned16(What) || !aligned16(H) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;
+  const size_t need = gq_objective_workspace_bytes(d_out, d_in, G);
+  if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
+  return from_hip(gq::launch_objective(W, What, d_out, d_in, ld_w, H, G, obj, obj_row, workspace,
+                                       (hipStream_t)hip_stream));
+}
+
+}  // extern "C"

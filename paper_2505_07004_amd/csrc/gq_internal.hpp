@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libgq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gq.h"
+
+namespace gq {
+
+// ---- vector types used with the CDNA4 matrix-core builtins -----------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// Number of tiles on or above the diagonal of a T x T tile grid.
+__host__ __device__ inline int64_t tri_count(int64_t T) { return T * (T + 1) / 2; }
+
+// Decode a linear index t in [0, tri_count(T)) into (i, j), i <= j, column-major over
+// the upper triangle: column j holds rows 0..j, columns in increasing order.
+__host__ __device__ inline void tri_decode(int64_t t, int& i, int& j) {
+  // j = floor((sqrt(8t+1)-1)/2), fixed up for rounding.
+  int64_t jj = (int64_t)((sqrt((double)(8 * t + 1)) - 1.0) * 0.5);
+  while (jj * (jj + 1) / 2 > t) --jj;
+  while ((jj + 1) * (jj + 2) / 2 <= t) ++jj;
+  j = (int)jj;
+  i = (int)(t - jj * (jj + 1) / 2);
+}
+
+// ---- launchers (each validates nothing; the C ABI layer has done that) -----
+hipError_t launch_group_weights(const void* dZ, gq_dtype dt, int64_t n, int64_t d_out, int64_t ld,
+                                int G, float grad_scale, float* s, hipStream_t st);
+
+hipError_t launch_fisher_gram_f32(const float* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
+                                  int G, float* H, bool accumulate, hipStream_t st);
+
+hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
+                                   int G, float* H, bool accumulate, void* ws, size_t ws_bytes,
+                                   hipStream_t st);
+size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
+
+hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st);
+hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st);
+
+hipError_t launch_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld,
+                            const float* H, int G, double* obj, float* obj_row, void* ws,
+                            hipStream_t st);
+size_t objective_workspace(int64_t d_out, int64_t d_in, int G);
+
+}  // namespace gq

@@ -1,0 +1,60 @@
+// Triangle utilities for the cached Hessians H[G, d_in, d_in]:
+//  - mirror: H[k][b,a] = H[k][a,b] for a < b (the paper stores full squares; the Gram
+//    kernels only produce the upper triangle),
+//  - zero_upper: clear the upper triangle (an overwrite call with no tokens).
+// Both are HBM-bound copies through a padded LDS tile.
+#include "gq_internal.hpp"
+
+namespace gq {
+namespace {
+
+constexpr int kT = 64;  // tile edge
+
+__global__ __launch_bounds__(256) void mirror_kernel(float* __restrict__ H, int64_t d, int64_t n_tri) {
+  __shared__ float tile[kT][kT + 1];
+  const int k = blockIdx.y;
+  float* Hk = H + (int64_t)k * d * d;
+  int ti, tj;
+  tri_decode(blockIdx.x, ti, tj);  // ti <= tj
+  const int64_t r0 = (int64_t)ti * kT, c0 = (int64_t)tj * kT;
+  const int tx = threadIdx.x % kT, ty = threadIdx.x / kT;  // 64 x 4
+  for (int r = ty; r < kT; r += 4) {
+    const int64_t a = r0 + r, b = c0 + tx;
+    tile[r][tx] = (a < d && b < d) ? Hk[a * d + b] : 0.f;
+  }
+  __syncthreads();
+  // write the transposed tile: rows b in tile tj, columns a in tile ti
+  for (int r = ty; r < kT; r += 4) {
+    const int64_t b = c0 + r, a = r0 + tx;
+    if (a < d && b < d && a < b) Hk[b * d + a] = tile[tx][r];
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_upper_kernel(float* __restrict__ H, int64_t d) {
+  const int k = blockIdx.y;
+  float* Hk = H + (int64_t)k * d * d;
+  int ti, tj;
+  tri_decode(blockIdx.x, ti, tj);
+  const int64_t r0 = (int64_t)ti * kT, c0 = (int64_t)tj * kT;
+  const int tx = threadIdx.x % kT, ty = threadIdx.x / kT;
+  for (int r = ty; r < kT; r += 4) {
+    const int64_t a = r0 + r, b = c0 + tx;
+    if (a < d && b < d && a <= b) Hk[a * d + b] = 0.f;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st) {
+  const int64_t T = (d_in + kT - 1) / kT;
+  mirror_kernel<<<dim3((unsigned)tri_count(T), (unsigned)G), dim3(256), 0, st>>>(H, d_in, tri_count(T));
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st) {
+  const int64_t T = (d_in + kT - 1) / kT;
+  zero_upper_kernel<<<dim3((unsigned)tri_count(T), (unsigned)G), dim3(256), 0, st>>>(H, d_in);
+  return hipGetLastError();
+}
+
+}  // namespace gq

@@ -1,0 +1,77 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_07004_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "gq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gq_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_calls():
+    syms = _declared_symbols()
+    for name in ("gq_group_weights", "gq_fisher_gram", "gq_objective", "gq_fisher_mirror",
+                 "gq_fisher_gram_workspace_bytes", "gq_objective_workspace_bytes",
+                 "gq_version", "gq_status_string"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    for name in _declared_symbols():
+        assert hasattr(lib, name), name
+    assert binding.gq_version() >= 100
+    assert binding.status_string(0) == "ok"
+    assert "shape" in binding.status_string(-2)
+
+
+def test_host_side_validation_needs_no_gpu():
+    lib = binding.load_library()
+    P = ctypes.c_void_p
+    a16 = P(0x1000)           # fake, aligned, never dereferenced: every call below must fail before launch
+    odd = P(0x1004)
+    # group weights
+    assert lib.gq_group_weights(a16, 7, 4, 8, 8, 2, 1.0, a16, None) == -3          # dtype
+    assert lib.gq_group_weights(a16, 0, 4, 10, 10, 4, 1.0, a16, None) == -2         # G does not divide d_out
+    assert lib.gq_group_weights(a16, 0, -1, 8, 8, 2, 1.0, a16, None) == -2
+    assert lib.gq_group_weights(a16, 0, 4, 8, 4, 2, 1.0, a16, None) == -2           # ld < width
+    assert lib.gq_group_weights(None, 0, 4, 8, 8, 2, 1.0, a16, None) == -1
+    assert lib.gq_group_weights(odd, 0, 4, 8, 8, 2, 1.0, a16, None) == -4
+    assert lib.gq_group_weights(a16, 0, 4, 6, 6, 2, 1.0, a16, None) == -4           # pitch 24 B
+    assert lib.gq_group_weights(None, 0, 0, 8, 8, 2, 1.0, None, None) == 0           # n == 0 is a no-op
+    # fisher gram
+    assert lib.gq_fisher_gram(a16, 5, 4, 8, 8, a16, 2, a16, 0, None, 0, None) == -3
+    assert lib.gq_fisher_gram(a16, 1, 4, 0, 8, a16, 2, a16, 0, None, 0, None) == -2
+    assert lib.gq_fisher_gram(a16, 1, 4, 8, 4, a16, 2, a16, 0, None, 0, None) == -2
+    assert lib.gq_fisher_gram(a16, 1, 4, 8, 8, a16, 0, a16, 0, None, 0, None) == -2
+    assert lib.gq_fisher_gram(a16, 1, 4, 8, 8, a16, 2, None, 0, None, 0, None) == -1
+    assert lib.gq_fisher_gram(None, 1, 4, 8, 8, a16, 2, a16, 0, None, 0, None) == -1
+    assert lib.gq_fisher_gram(odd, 1, 4, 8, 8, a16, 2, a16, 0, None, 0, None) == -4
+    assert lib.gq_fisher_gram(a16, 1, 4, 12, 12, a16, 2, a16, 0, None, 0, None) == -4  # bf16 pitch 24 B
+    assert lib.gq_fisher_gram(a16, 1, 4, 8, 8, a16, 2, a16, 64, None, 0, None) == -7   # unknown flag
+    # mirror
+    assert lib.gq_fisher_mirror(None, 8, 2, None) == -1
+    assert lib.gq_fisher_mirror(a16, 0, 2, None) == -2
+    # objective
+    assert lib.gq_objective(a16, a16, 10, 8, 8, a16, 4, a16, None, a16, 1 << 20, None) == -2
+    assert lib.gq_objective(a16, None, 8, 8, 8, a16, 4, a16, None, a16, 1 << 20, None) == -1
+    assert lib.gq_objective(a16, a16, 8, 8, 8, a16, 4, a16, None, None, 0, None) == -5
+    assert lib.gq_objective(a16, a16, 8, 8, 8, a16, 4, a16, None, P(0x1100), 4, None) == -5
+    assert lib.gq_objective(a16, a16, 8, 6, 6, a16, 4, a16, None, P(0x1100), 1 << 20, None) == -4
+    assert lib.gq_objective_workspace_bytes(8, 8, 4) > 0
+    assert lib.gq_objective_workspace_bytes(10, 8, 4) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(RuntimeError):
+        binding.gq_group_weights(torch.zeros(4, 8), 2)

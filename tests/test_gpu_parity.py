@@ -1,0 +1,239 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 CPU oracle, element by
+element, on seeded inputs small enough for the oracle to finish in seconds."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_07004_amd import binding as gq
+from paper_2505_07004_amd import workloads as wl
+from parity_utils import TOL_BF16, TOL_F32, TOL_S, rel_fro, say, to_np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _pitched(t: torch.Tensor, ld: int) -> torch.Tensor:
+    """Same values in a buffer whose row pitch is ld elements."""
+    buf = torch.zeros((t.shape[0], ld), dtype=t.dtype, device=t.device)
+    buf[:, : t.shape[1]] = t
+    return buf[:, : t.shape[1]]
+
+
+# ------------------------------------------------------------------ group weights
+@pytest.mark.parametrize("n,d_out,G,scale,dtype,ld", [
+    (2048, 512, 2, 1.0, torch.float32, None),       # config 1
+    (333, 4096, 4, 1e3, torch.float32, None),       # Llama width, paper's gradient scale
+    (100, 24, 3, 1.0, torch.float32, None),         # m = 8
+    (77, 20, 4, 2.0, torch.float32, None),          # m = 5: scalar path
+    (50, 12, 12, 1.0, torch.float32, None),         # one channel per group
+    (65, 640, 1, 1.0, torch.float32, 648),          # padded pitch
+    (129, 1024, 8, 1.0, torch.bfloat16, None),      # bf16 gradients
+    (31, 40, 2, 1.0, torch.bfloat16, None),         # bf16, m = 20: scalar path
+])
+def test_group_weights(n, d_out, G, scale, dtype, ld):
+    say(f"group_weights n={n} d_out={d_out} G={G} scale={scale} {dtype} ld={ld}")
+    dZ = wl.make_dz(n, d_out, 1.0, 1.0, seed=11 + n, device=DEV).to(dtype)
+    if ld:
+        dZ = _pitched(dZ, ld)
+    s = gq.gq_group_weights(dZ, G, grad_scale=scale)
+    torch.cuda.synchronize()
+    ref = oracle.group_weights(to_np64(dZ), G, grad_scale=scale)
+    got = to_np64(s)
+    assert got.shape == ref.shape
+    assert np.all(np.abs(got - ref) <= TOL_S * np.abs(ref) + 1e-300)
+
+
+def test_group_weights_empty():
+    s = gq.gq_group_weights(torch.empty((0, 16), device=DEV), 4)
+    assert tuple(s.shape) == (0, 4)
+
+
+# ------------------------------------------------------------------ fisher gram
+def _gram_case(n, d_in, G, dtype, seed, ld=None, kind="outlier"):
+    if kind == "outlier":
+        X = wl.make_x_outlier(n, d_in, max(1, d_in // 64), 20.0, seed, DEV, dtype)
+    else:
+        X = wl.make_x_silu(n, d_in, seed, DEV, dtype)
+    if ld:
+        X = _pitched(X, ld)
+    dZ = wl.make_dz(n, 8 * G, 1.0, 1.5, seed + 1, DEV)
+    s = gq.gq_group_weights(dZ, G)
+    return X, s
+
+
+def _check_gram(H, X, s, tol, what):
+    torch.cuda.synchronize()
+    ref = oracle.fisher_gram(to_np64(X), to_np64(s))
+    got = to_np64(H)
+    errs = [rel_fro(np.triu(got[k]), np.triu(ref[k])) for k in range(ref.shape[0])]
+    say(f"{what}: rel-Frobenius per group {['%.2e' % e for e in errs]} (tol {tol:g})")
+    assert max(errs) <= tol
+    return ref
+
+
+def test_gram_f32_config1_full():
+    spec = wl.CONFIGS["tiny_f32"]
+    X, dZ = wl.make_x(spec, DEV), wl.make_dz_for(spec, DEV)
+    s = gq.gq_group_weights(dZ, spec.G)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    ref = _check_gram(H, X, s, TOL_F32, "config 1 fp32")
+    got = to_np64(H)
+    assert np.array_equal(got, np.transpose(got, (0, 2, 1)))        # bit-exact symmetry after mirror
+    assert max(rel_fro(got[k], ref[k]) for k in range(spec.G)) <= TOL_F32
+    for k in range(spec.G):
+        ev = np.linalg.eigvalsh(got[k])
+        assert ev.min() >= -1e-5 * ev.max()
+
+
+@pytest.mark.parametrize("n,d_in,G,ld", [
+    (1000, 200, 2, None),      # ragged tokens and columns, several tiles
+    (1, 128, 1, None),         # single token
+    (517, 130, 3, 132),        # padded pitch, odd group count
+    (4100, 64, 4, None),       # crosses the accumulator flush boundary
+    (40, 7, 2, 8),             # d_in not a multiple of the vector width
+])
+def test_gram_f32_shapes(n, d_in, G, ld):
+    say(f"gram f32 n={n} d_in={d_in} G={G} ld={ld}")
+    X, s = _gram_case(n, d_in, G, torch.float32, 100 + n, ld)
+    H = gq.gq_fisher_gram(X, s)
+    _check_gram(H, X, s, TOL_F32, f"fp32 n={n} d_in={d_in}")
+
+
+@pytest.mark.parametrize("dtype,tol", [(torch.float32, TOL_F32), (torch.bfloat16, TOL_BF16)])
+def test_gram_lower_triangle_untouched_without_mirror_and_zero_tokens(dtype, tol):
+    X, s = _gram_case(300, 136, 2, dtype, 7)
+    H = torch.full((2, 136, 136), 777.0, device=DEV)
+    gq.gq_fisher_gram(X, s, H=H)
+    torch.cuda.synchronize()
+    got = to_np64(H)
+    il = np.tril_indices(136, -1)
+    for k in range(2):
+        assert np.all(got[k][il] == 777.0)
+    # n == 0: overwrite clears the upper triangle, accumulate leaves H alone
+    H2 = torch.full((2, 136, 136), 5.0, device=DEV)
+    gq.gq_fisher_gram(X[:0], s[:0], H=H2, accumulate=True)
+    torch.cuda.synchronize()
+    assert bool((H2 == 5.0).all())
+    gq.gq_fisher_gram(X[:0], s[:0], H=H2)
+    torch.cuda.synchronize()
+    g2 = to_np64(H2)
+    assert np.all(np.triu(g2[0]) == 0) and np.all(g2[0][il] == 5.0)
+
+
+@pytest.mark.parametrize("dtype,tol", [(torch.float32, TOL_F32), (torch.bfloat16, TOL_BF16)])
+def test_gram_chunk_accumulation(dtype, tol):
+    X, s = _gram_case(3000, 264, 4, dtype, 21)
+    H = None
+    for c0 in range(0, 3000, 1000):
+        H = gq.gq_fisher_gram(X[c0:c0 + 1000], s[c0:c0 + 1000], H=H, accumulate=c0 > 0)
+    gq.gq_fisher_mirror(H)
+    ref = _check_gram(H, X, s, tol, f"3 chunks {dtype}")
+    got = to_np64(H)
+    assert np.array_equal(got, np.transpose(got, (0, 2, 1)))
+    one = to_np64(gq.gq_fisher_gram(X, s, mirror=True))
+    assert max(rel_fro(got[k], one[k]) for k in range(4)) <= 1e-5   # only fp32 re-association differs
+    assert max(rel_fro(got[k], ref[k]) for k in range(4)) <= tol
+
+
+def test_gram_bf16_config1_values():
+    spec = wl.CONFIGS["tiny_f32"]
+    X = wl.make_x(spec, DEV).to(torch.bfloat16)
+    s = gq.gq_group_weights(wl.make_dz_for(spec, DEV), spec.G)
+    H = gq.gq_fisher_gram(X, s)
+    _check_gram(H, X, s, TOL_BF16, "config 1 values, bf16 path")
+
+
+@pytest.mark.parametrize("n,d_in,G,ld,kind", [
+    (4096, 512, 4, None, "outlier"),   # several tiles, group-fused workgroups
+    (4096, 512, 1, None, "outlier"),   # one group: 256x256 tiles
+    (2048, 768, 2, None, "silu"),      # two groups
+    (1500, 520, 8, None, "outlier"),   # two group sets, ragged tokens, ragged column tile
+    (1000, 328, 3, None, "silu"),      # odd group count
+    (700, 300, 4, 304, "outlier"),     # d_in not a multiple of 8, padded pitch
+    (33, 72, 2, None, "outlier"),      # barely more than one token step
+    (5, 16, 4, None, "outlier"),       # tiny
+])
+def test_gram_bf16_shapes(n, d_in, G, ld, kind):
+    say(f"gram bf16 n={n} d_in={d_in} G={G} ld={ld} {kind}")
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 300 + n, ld, kind)
+    H = gq.gq_fisher_gram(X, s)
+    _check_gram(H, X, s, TOL_BF16, f"bf16 n={n} d_in={d_in} G={G}")
+
+
+def test_gram_bf16_matches_its_documented_rounding():
+    """The bf16 path rounds exactly one operand, bf16_rne(fp32(s)*fp32(x)); with that
+    operand reproduced on the host the remaining difference is fp32 accumulation only."""
+    n, d_in, G = 2048, 384, 4
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 55)
+    H = to_np64(gq.gq_fisher_gram(X, s))
+    Xc, sc = X.float().cpu(), s.cpu()
+    X64 = Xc.double().numpy()
+    for k in range(G):
+        A = (sc[:, k:k + 1] * Xc).to(torch.bfloat16).double().numpy()
+        ref = A.T @ X64
+        err = rel_fro(np.triu(H[k]), np.triu(ref))
+        say(f"group {k}: vs rounded-operand model {err:.2e}")
+        assert err <= 2e-6
+
+
+def test_gram_is_deterministic():
+    X, s = _gram_case(2048, 512, 4, torch.bfloat16, 77)
+    a = gq.gq_fisher_gram(X, s, mirror=True).clone()
+    b = gq.gq_fisher_gram(X, s, mirror=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------ objective
+def _check_objective(W, What, H_gpu, H_ref64, G, tol, what):
+    obj, rows = gq.gq_objective(W, What, H_gpu, want_rows=True)
+    torch.cuda.synchronize()
+    ref, ref_rows = oracle.objective(to_np64(W), to_np64(What), H_ref64, G)
+    e_obj = np.max(np.abs(to_np64(obj) - ref) / ref)
+    e_rows = rel_fro(to_np64(rows), ref_rows)
+    say(f"{what}: obj rel err {e_obj:.2e}, per-channel rel-Frobenius {e_rows:.2e} (tol {tol:g})")
+    assert e_obj <= tol and e_rows <= tol
+
+
+def test_objective_config1_isolated_and_end_to_end():
+    spec = wl.CONFIGS["tiny_f32"]
+    X, dZ = wl.make_x(spec, DEV), wl.make_dz_for(spec, DEV)
+    W, What = wl.make_weights(spec, DEV)
+    s = gq.gq_group_weights(dZ, spec.G)
+    H = gq.gq_fisher_gram(X, s)                       # upper triangle only: lower stays garbage
+    H_ref = oracle.fisher_gram(to_np64(X), oracle.group_weights(to_np64(dZ), spec.G))
+    # isolation: both sides read the same fp32 H (the oracle sees its symmetric completion)
+    Hg = to_np64(H)
+    Hsym = np.stack([np.triu(Hg[k]) + np.triu(Hg[k], 1).T for k in range(spec.G)])
+    _check_objective(W, What, H, Hsym, spec.G, TOL_F32, "config 1 objective, isolated")
+    _check_objective(W, What, H, H_ref, spec.G, TOL_F32, "config 1 objective, end to end fp32")
+    Hb = gq.gq_fisher_gram(X.to(torch.bfloat16), s)
+    Hb_ref = oracle.fisher_gram(to_np64(X.to(torch.bfloat16)), to_np64(s))
+    _check_objective(W, What, Hb, Hb_ref, spec.G, TOL_BF16, "config 1 values, objective on the bf16-path H")
+
+
+@pytest.mark.parametrize("d_out,d_in,G,ld", [
+    (300, 200, 3, None),     # m = 100 < row tile, ragged column tile
+    (512, 384, 1, None),     # one group, several row blocks
+    (64, 520, 8, 528),       # m = 8, padded pitch
+    (12, 6, 2, 8),           # tiny, d_in not a multiple of 4
+])
+def test_objective_shapes(d_out, d_in, G, ld):
+    say(f"objective d_out={d_out} d_in={d_in} G={G} ld={ld}")
+    X, s = _gram_case(600, d_in, G, torch.float32, 900 + d_in, ld if d_in % 4 else None)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    W = wl.make_w(d_out, d_in, 5, DEV)
+    What = wl.quantize_uniform_per_row(W, 8)
+    if ld:
+        W, What = _pitched(W, ld), _pitched(What, ld)
+    _check_objective(W, What, H, to_np64(H), G, TOL_F32, f"objective {d_out}x{d_in} G={G}")
+
+
+def test_objective_zero_when_nothing_changed():
+    X, s = _gram_case(256, 128, 2, torch.float32, 3)
+    H = gq.gq_fisher_gram(X, s)
+    W = wl.make_w(64, 128, 9, DEV)
+    obj = gq.gq_objective(W, W.clone(), H)
+    torch.cuda.synchronize()
+    assert bool((obj == 0).all())

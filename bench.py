@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the GuidedQuant Fisher-Gram hot path on one MI355X.
+
+A step is one pass of the whole path over one linear layer's calibration batch:
+    gq_group_weights(dZ) -> s,  gq_fisher_gram(X, s) -> H (upper triangle),
+    gq_fisher_mirror(H),        gq_objective(W, What, H) -> obj
+on synthetic tensors of the Llama-2-7B attention-projection shape
+(X[65536,4096] bf16, dZ[65536,4096] fp32, G=4), resident in HBM before timing.
+
+Prints ONE JSON line on stdout.  `value` is the algorithmic Gram work of a step,
+G*n*d_in*(d_in+1) flop (upper triangle only), divided by the whole step time;
+`roofline` is the Gram kernel alone (HIP events around its launches inside the
+timed region) against the bf16 dense MFMA peak; `cpu_baseline` is the fp64
+oracle timed on the host cores on a bounded token sample of the same layer.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published, no sparsity)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gram_flops(G, n, d_in):
+    return float(G) * n * d_in * (d_in + 1)
+
+
+def cpu_baseline(spec, X, dZ, W, What, sample_tokens):
+    """Time the oracle (numpy fp64, as it stands) on the first `sample_tokens` tokens."""
+    import numpy as np
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Xh = X[:sample_tokens].to("cpu").to(__import__("torch").float64).numpy()
+    dZh = dZ[:sample_tokens].to("cpu").numpy()
+    Wh, Whh = W.to("cpu").numpy(), What.to("cpu").numpy()
+    t0 = time.perf_counter()
+    s = oracle.group_weights(dZh, spec.G)
+    H = oracle.fisher_gram(Xh, s)
+    obj, _ = oracle.objective(Wh, Whh, H, spec.G)
+    dt = time.perf_counter() - t0
+    fl = gram_flops(spec.G, sample_tokens, spec.d_in)
+    return {
+        "value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"first {sample_tokens} of {spec.n} tokens, all {spec.G} groups, whole path "
+                  f"(group weights + Gram + objective) in numpy fp64, {dt:.1f} s; "
+                  f"rate = algorithmic Gram flop of the sample / that time",
+    }, H, obj
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama2_7b_attn")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tokens", type=int, default=0, help="override n (debugging only; invalid as a result)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); the path has no multi-GPU part")
+
+    import torch
+    from paper_2505_07004_amd import binding as gq
+    from paper_2505_07004_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU: libgq has no CPU path")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    spec = wl.CONFIGS[args.workload]
+    if args.tokens:
+        spec = wl.scaled(spec, n=args.tokens)
+    log(f"workload {spec.name}: X[{spec.n},{spec.d_in}] {spec.x_dtype}, dZ[{spec.n},{spec.d_out}] f32, G={spec.G}")
+    t0 = time.perf_counter()
+    X = wl.make_x(spec, dev)
+    dZ = wl.make_dz_for(spec, dev)
+    W, What = wl.make_weights(spec, dev)
+    torch.cuda.synchronize()
+    log(f"inputs generated on the GPU in {time.perf_counter() - t0:.1f} s")
+
+    n, d_in, d_out, G = spec.n, spec.d_in, spec.d_out, spec.G
+    s = torch.empty((n, G), dtype=torch.float32, device=dev)
+    H = torch.empty((G, d_in, d_in), dtype=torch.float32, device=dev)
+    ws_g = torch.empty(max(1, gq.gq_fisher_gram_workspace_bytes(X.dtype, n, d_in, G)), dtype=torch.uint8, device=dev)
+    lib = gq.load_library()
+    ws_o = torch.empty(max(1, int(lib.gq_objective_workspace_bytes(d_out, d_in, G))), dtype=torch.uint8, device=dev)
+
+    names = ["group_weights", "fisher_gram", "mirror", "objective"]
+
+    def step(events=None):
+        ev = events
+        if ev is not None:
+            ev[0].record()
+        gq.gq_group_weights(dZ, G, out=s)
+        if ev is not None:
+            ev[1].record()
+        gq.gq_fisher_gram(X, s, H=H, workspace=ws_g)
+        if ev is not None:
+            ev[2].record()
+        gq.gq_fisher_mirror(H)
+        if ev is not None:
+            ev[3].record()
+        obj = gq.gq_objective(W, What, H, workspace=ws_o)
+        if ev is not None:
+            ev[4].record()
+        return obj
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        obj = step(evs[k])
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms_per_step = total_s * 1e3 / args.steps
+    per_kernel = {nm: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, nm in enumerate(names)}
+    log("per-call ms (HIP events, mean over timed steps):", json.dumps(per_kernel))
+
+    fl = gram_flops(G, n, d_in)
+    value = fl / (ms_per_step * 1e-3) / 1e12
+    gram_ms = per_kernel["fisher_gram"]
+    achieved = fl / (gram_ms * 1e-3) / 1e12
+    dz_gbs = (dZ.numel() * 4 + s.numel() * 4) / (per_kernel["group_weights"] * 1e-3) / 1e9
+
+    result = {
+        "metric": "Fisher-Gram TFLOP/s (algorithmic, upper triangle) over one linear layer's whole GuidedQuant pass",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: X[{n},{d_in}] bf16, dZ[{n},{d_out}] f32, G={G}, "
+                               f"W[{d_out},{d_in}] f32 with 3-bit per-row codebook What",
+                   "tokens": n, "d_in": d_in, "d_out": d_out, "G": G},
+        "pct_of_mfma_peak": 100.0 * achieved / PEAK_BF16_TFLOPS,
+        "ms_per_call": per_kernel,
+        "group_weights_GBps": dz_gbs,
+        "roofline": {"bound": "mfma", "kernel": "fisher_gram_bf16", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "flop_per_launch": fl, "ms_per_launch": gram_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+        ns = min(args.cpu_sample_tokens, n)
+        base, H_ref, obj_ref = cpu_baseline(spec, X, dZ, W, What, ns)
+        result["cpu_baseline"] = base
+        # the same sample through the HIP path, compared with what the oracle just computed
+        s2 = gq.gq_group_weights(dZ[:ns], G)
+        H2 = gq.gq_fisher_gram(X[:ns], s2, mirror=True)
+        obj2 = gq.gq_objective(W, What, H2)
+        torch.cuda.synchronize()
+        Hg = H2.to("cpu").to(torch.float64).numpy()
+        eh = max(float(np.linalg.norm(Hg[k] - H_ref[k]) / np.linalg.norm(H_ref[k])) for k in range(G))
+        eo = float(np.max(np.abs(obj2.cpu().numpy() - obj_ref) / obj_ref))
+        result["check"] = {"sample_tokens": ns, "H_rel_fro_max": eh, "obj_rel_max": eo, "tolerance": 3e-3}
+        log(f"check on the oracle's sample: H rel-Frobenius {eh:.2e}, objective {eo:.2e}")
+        if not (eh <= 3e-3 and eo <= 3e-3):
+            log("PARITY CHECK FAILED")
+            print(json.dumps(result))
+            sys.exit(2)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -11,6 +11,17 @@
 // token-major MFMA operands are produced by the CDNA4 transposing LDS read
 // (ds_read_b64_tr_b16).  s[i,k] is applied in registers between that read and the MFMA:
 // bf16 -> fp32, one fp32 multiply, round-to-nearest-even back to bf16.
+//
+// Pipeline.  Tokens are consumed 32 at a time through a ring of LDS stages (7 deep when four
+// groups share a workgroup).  Stages are filled by direct global->LDS loads
+// (global_load_lds_dwordx4: 16 bytes per lane, no VGPR staging), issued 5-6 stages ahead of
+// their use so that HBM/L2 latency is covered by a single wave per SIMD; the swizzle is
+// applied by choosing which global chunk each lane fetches.  Completion is tracked with an
+// explicit s_waitcnt vmcnt(N) per stage followed by the one workgroup barrier of the stage.
+// The loop is free of bounds branches: rows past the last token are clamped to the last row
+// and get weight 0 (the weights are first repacked group-major and zero-padded into the
+// workspace), columns past d_in are clamped into the row pitch and only ever feed outputs
+// that are not stored.
 #include "gq_internal.hpp"
 
 namespace gq {
@@ -18,20 +29,41 @@ namespace {
 
 constexpr int kTN = 256;            // tile columns (raw operand)
 constexpr int kStep = 32;           // tokens per LDS stage
-constexpr int kRowBytes = kTN * 2;  // LDS bytes per token row (both operand tiles use this pitch)
-constexpr int kTileBytes = kStep * kRowBytes;
 constexpr int kNB = kTN / 32;       // raw-operand MFMA fragments per wave
 constexpr int kMA = 2;              // scaled-operand MFMA fragments per wave (64 rows)
+constexpr int kMaxStages = 8;       // upper bound of the ring depth (sizes the weight padding)
+constexpr int kLdsBudget = 150 * 1024;
 
-// Byte offset of 16-byte chunk c of token row r inside a staged tile.  XOR-ing bits 2..3 of
-// the chunk index with r%4 spreads the four token rows of one transposing read over all banks.
-__device__ inline int lds_chunk_off(int r, int c) { return r * kRowBytes + 16 * (c ^ (4 * (r & 3))); }
+// Byte offset of 16-byte chunk c of token row r in a staged tile whose rows hold CHUNKS
+// chunks.  The XOR spreads the four token rows touched by one transposing read (64 bytes
+// each per half-wave) over all 64 banks.  It is an involution in c, so the same function maps
+// a physical slot back to the logical chunk it holds.
+template <int CHUNKS>
+__device__ inline int swizzle(int r, int c) {
+  if (CHUNKS >= 16) return c ^ (4 * (r & 3));
+  return c ^ (4 * ((r >> 1) & 1));
+}
+template <int CHUNKS>
+__device__ inline int lds_chunk_off(int r, int c) {
+  return r * (CHUNKS * 16) + 16 * swizzle<CHUNKS>(r, c);
+}
 
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+typedef char __attribute__((address_space(3))) * lds_char_ptr;
 
-__device__ inline u32x2 lds_read_tr(const char* base, int byte_off) {
-  bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(base + byte_off));
+__device__ inline u32x2 lds_read_tr(const char* p) {
+  bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p);
   return __builtin_bit_cast(u32x2, v);
+}
+
+// Direct global->LDS load: every active lane moves 16 bytes from its own global address to
+// LDS address lds_base + 16*lane (lds_base is wave-uniform and travels in M0).  Tracked by vmcnt.
+__device__ inline void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+template <int N>
+__device__ inline void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 // 8 bf16 (as 4 dwords) of tokens t..t+7 times their 8 fp32 weights, rounded to bf16 (RNE).
@@ -50,37 +82,47 @@ __device__ inline bf16x8 scale_frag(u32x2 lo, u32x2 hi, f32x4 s0, f32x4 s1) {
   return __builtin_bit_cast(bf16x8, out);
 }
 
-__device__ inline u32x4 load_chunk(const __bf16* __restrict__ X, int64_t ld, int64_t n, int64_t d, int64_t i,
-                                   int64_t c) {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (i < n && c < d) {
-    const __bf16* p = X + i * ld + c;
-    if (c + 8 <= d) {
-      v = *reinterpret_cast<const u32x4*>(p);
-    } else {
-      unsigned short h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      for (int e = 0; e < 8; ++e)
-        if (c + e < d) h[e] = __builtin_bit_cast(unsigned short, p[e]);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) v[q] = (unsigned int)h[2 * q] | ((unsigned int)h[2 * q + 1] << 16);
-    }
-  }
-  return v;
+struct Frags {
+  u32x2 a[kMA][2];
+  u32x2 b[kNB][2];
+  f32x4 s[2];
+};
+
+template <int GPC>
+struct Cfg {
+  static constexpr int RB = 4 / GPC;                 // 64-row blocks per workgroup tile
+  static constexpr int TM = 64 * RB;                 // tile rows
+  static constexpr int kAChunks = TM / 8;            // 16-byte chunks per token row, scaled operand
+  static constexpr int kBChunks = kTN / 8;           // 32
+  static constexpr int kALoads = (kStep * kAChunks) / 256;  // wave-level 1 KiB loads per wave and stage
+  static constexpr int kBLoads = (kStep * kBChunks) / 256;  // 4
+  static constexpr int kLoads = kALoads + kBLoads + 1;      // + one (8-lane) load of the wave's weights
+  static constexpr int kABytes = kStep * kAChunks * 16;
+  static constexpr int kBBytes = kStep * kBChunks * 16;
+  static constexpr int kSBytes = 4 * kStep * 4;      // one 32-float row per wave
+  static constexpr int kStageBytes = kABytes + kBBytes + kSBytes;
+  static constexpr int kStages = (kLdsBudget / kStageBytes) < kMaxStages ? (kLdsBudget / kStageBytes) : kMaxStages;
+  static_assert(kStages >= 4, "ring too shallow");
+  static_assert((kStages - 3) * kLoads <= 63, "vmcnt is a 6-bit counter");
+};
+
+// Weights repacked group-major with zero padding: sp[g][i] = s[i][g] for i < n, 0 for n <= i < n_pad.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ s, int64_t n, int G,
+                                                           int64_t n_pad, float* __restrict__ sp) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_pad) return;
+  for (int g = 0; g < G; ++g) sp[(int64_t)g * n_pad + i] = (i < n) ? s[i * G + g] : 0.f;
 }
 
 template <int GPC>
 __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __restrict__ X, int64_t n, int64_t d,
-                                                               int64_t ld, const float* __restrict__ s, int G,
-                                                               float* __restrict__ H, int accumulate) {
-  constexpr int RB = 4 / GPC;          // 64-row blocks per workgroup tile
-  constexpr int TM = 64 * RB;          // tile rows
-  constexpr int kAChunks = TM / 8;     // 16-byte chunks per token row of the scaled operand
-  constexpr int kALoads = (kStep * kAChunks) / 256;  // per thread: 1, 2 or 4
-  constexpr int kBLoads = (kStep * (kTN / 8)) / 256; // 4
+                                                               int64_t ld, const float* __restrict__ sp,
+                                                               int64_t n_pad, float* __restrict__ H, int accumulate) {
+  using C = Cfg<GPC>;
+  constexpr int TM = C::TM, kAChunks = C::kAChunks, kBChunks = C::kBChunks;
+  constexpr int kABytes = C::kABytes, kBBytes = C::kBBytes, kStageBytes = C::kStageBytes, NS = C::kStages;
 
-  __shared__ __attribute__((aligned(16))) char As[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) char Bs[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) float Ss[2][GPC][kStep];
+  __shared__ __attribute__((aligned(1024))) char smem[NS * kStageBytes];
 
   // ---- which tile --------------------------------------------------------------------
   int I, J;
@@ -95,14 +137,11 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   const int gbase = blockIdx.y * GPC;
 
   const int tid = threadIdx.x;
-  const int lane = tid % kWave, wave = tid / kWave;
+  const int lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int g_local = wave % GPC;
   const int sub = wave / GPC;
   const int64_t row_w = row_t + 64 * sub;  // first row of this wave's block
-  // fragments of 32 columns that lie entirely below the diagonal are never needed
-  int y_first = 0;
-  if (row_w > col_t) y_first = (int)((row_w - col_t) / 32);
-  const bool wave_active = row_w < d;
 
   // ---- per-lane LDS read offsets (loop invariant) ---------------------------------------
   const int t16 = lane % 16;
@@ -111,10 +150,10 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   const int boff = ((4 * (t16 % 4)) % 8) * 2;                 // byte inside the chunk
   int offA[kMA], offB[kNB];
 #pragma unroll
-  for (int x = 0; x < kMA; ++x) offA[x] = lds_chunk_off(krl, 8 * sub + 4 * x + clane) + boff;
+  for (int x = 0; x < kMA; ++x) offA[x] = lds_chunk_off<kAChunks>(krl, 8 * sub + 4 * x + clane) + boff;
 #pragma unroll
-  for (int y = 0; y < kNB; ++y) offB[y] = lds_chunk_off(krl, 4 * y + clane) + boff;
-  const int offS = (8 * (lane / 32)) * 4;
+  for (int y = 0; y < kNB; ++y) offB[y] = kABytes + lds_chunk_off<kBChunks>(krl, 4 * y + clane) + boff;
+  const int offS = kABytes + kBBytes + wave * (kStep * 4) + (8 * (lane / 32)) * 4;
 
   f32x16 acc[kMA][kNB];
 #pragma unroll
@@ -124,89 +163,131 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // ---- staging ------------------------------------------------------------------------------
-  u32x4 ra[kALoads], rb[kBLoads];
-  float rs = 0.f;
-  auto fetch = [&](int64_t step) {
-    const int64_t i0 = step * kStep;
+  // ---- direct global->LDS staging -------------------------------------------------------------
+  // Wave w issues, per stage, kALoads + kBLoads loads of 1 KiB (64 lanes x 16 B) plus one
+  // 8-lane load of its own 32 weights.  LDS slot q (16 B units) of a tile holds token row
+  // q / CHUNKS and physical chunk q % CHUNKS; the lane fetches the logical chunk that the
+  // swizzle stores there.
+  const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
+  const int64_t last_row = n - 1;
+  const int64_t full_steps = n / kStep;          // stages below this index need no row clamp
+  const char* pa[C::kALoads];                    // running global address, stage 0 .. (valid while unclamped)
+  const char* pb[C::kBLoads];
+  int ra_[C::kALoads], rb_[C::kBLoads];          // token row inside the stage
+  int64_t ca_[C::kALoads], cb_[C::kBLoads];      // clamped first column of the lane's chunk
 #pragma unroll
-    for (int h = 0; h < kALoads; ++h) {
-      const int q = tid + 256 * h;
-      ra[h] = load_chunk(X, ld, n, d, i0 + q / kAChunks, row_t + 8 * (q % kAChunks));
-    }
-#pragma unroll
-    for (int h = 0; h < kBLoads; ++h) {
-      const int q = tid + 256 * h;
-      rb[h] = load_chunk(X, ld, n, d, i0 + q / (kTN / 8), col_t + 8 * (q % (kTN / 8)));
-    }
-    if (tid < GPC * kStep) {
-      const int64_t i = i0 + tid % kStep;
-      rs = (i < n) ? s[i * G + gbase + tid / kStep] : 0.f;
-    }
-  };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int h = 0; h < kALoads; ++h) {
-      const int q = tid + 256 * h;
-      *reinterpret_cast<u32x4*>(&As[buf][lds_chunk_off(q / kAChunks, q % kAChunks)]) = ra[h];
-    }
-#pragma unroll
-    for (int h = 0; h < kBLoads; ++h) {
-      const int q = tid + 256 * h;
-      *reinterpret_cast<u32x4*>(&Bs[buf][lds_chunk_off(q / (kTN / 8), q % (kTN / 8))]) = rb[h];
-    }
-    if (tid < GPC * kStep) Ss[buf][tid / kStep][tid % kStep] = rs;
-  };
-
-  const int64_t steps = (n + kStep - 1) / kStep;
-  if (steps > 0) {
-    fetch(0);
-    stash(0);
+  for (int h = 0; h < C::kALoads; ++h) {
+    const int q = (wave * C::kALoads + h) * 64 + lane;
+    const int r = q / kAChunks;
+    int64_t c = row_t + 8 * swizzle<kAChunks>(r, q % kAChunks);
+    if (c + 8 > ld) c = ld - 8;                  // stays inside the row pitch; feeds only unstored outputs
+    ra_[h] = r;
+    ca_[h] = c;
+    pa[h] = reinterpret_cast<const char*>(X + (int64_t)r * ld + c);
   }
-  __syncthreads();
-  for (int64_t step = 0; step < steps; ++step) {
-    const int buf = (int)(step & 1);
-    if (step + 1 < steps) fetch(step + 1);
-    if (wave_active) {
-      const char* Ab = As[buf];
-      const char* Bb = Bs[buf];
-      const char* Sb = reinterpret_cast<const char*>(&Ss[buf][g_local][0]);
 #pragma unroll
-      for (int ks = 0; ks < kStep / 16; ++ks) {
-        const int roff = ks * 16 * kRowBytes;
-        const f32x4 s0 = *reinterpret_cast<const f32x4*>(Sb + offS + ks * 64);
-        const f32x4 s1 = *reinterpret_cast<const f32x4*>(Sb + offS + ks * 64 + 16);
-        bf16x8 a[kMA];
+  for (int h = 0; h < C::kBLoads; ++h) {
+    const int q = (wave * C::kBLoads + h) * 64 + lane;
+    const int r = q / kBChunks;
+    int64_t c = col_t + 8 * swizzle<kBChunks>(r, q % kBChunks);
+    if (c + 8 > ld) c = ld - 8;
+    rb_[h] = r;
+    cb_[h] = c;
+    pb[h] = reinterpret_cast<const char*>(X + (int64_t)r * ld + c);
+  }
+  const int64_t step_bytes = (int64_t)kStep * ld * 2;
+  // weights: lanes 0..7 of every wave fetch the wave's 32 floats of the stage (16 B each)
+  const char* ps = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad + 4 * (lane % 8));
+
+  auto issue = [&](int64_t step, int slot) {
+    const unsigned stage = smem_base + (unsigned)slot * kStageBytes;
+    if (step < full_steps) {
 #pragma unroll
-        for (int x = 0; x < kMA; ++x) {
-          u32x2 lo = lds_read_tr(Ab, offA[x] + roff);
-          u32x2 hi = lds_read_tr(Ab, offA[x] + roff + 4 * kRowBytes);
-          a[x] = scale_frag(lo, hi, s0, s1);
-        }
+      for (int h = 0; h < C::kALoads; ++h) dma16(pa[h], stage + (wave * C::kALoads + h) * 1024);
 #pragma unroll
-        for (int y = 0; y < kNB; ++y) {
-          if (y >= y_first) {
-            u32x2 lo = lds_read_tr(Bb, offB[y] + roff);
-            u32x2 hi = lds_read_tr(Bb, offB[y] + roff + 4 * kRowBytes);
-            u32x4 bw = {lo[0], lo[1], hi[0], hi[1]};
-            bf16x8 b = __builtin_bit_cast(bf16x8, bw);
+      for (int h = 0; h < C::kBLoads; ++h) dma16(pb[h], stage + kABytes + (wave * C::kBLoads + h) * 1024);
+    } else {  // the ragged last stage and the stages prefetched past the end: clamp rows to the last token
+      const int64_t i0 = step * kStep;
 #pragma unroll
-            for (int x = 0; x < kMA; ++x)
-              acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b, acc[x][y], 0, 0, 0);
-          }
-        }
+      for (int h = 0; h < C::kALoads; ++h) {
+        int64_t i = i0 + ra_[h];
+        i = i < last_row ? i : last_row;
+        dma16(X + i * ld + ca_[h], stage + (wave * C::kALoads + h) * 1024);
+      }
+#pragma unroll
+      for (int h = 0; h < C::kBLoads; ++h) {
+        int64_t i = i0 + rb_[h];
+        i = i < last_row ? i : last_row;
+        dma16(X + i * ld + cb_[h], stage + kABytes + (wave * C::kBLoads + h) * 1024);
       }
     }
-    if (step + 1 < steps) stash(buf ^ 1);
-    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < C::kALoads; ++h) pa[h] += step_bytes;
+#pragma unroll
+    for (int h = 0; h < C::kBLoads; ++h) pb[h] += step_bytes;
+    if (lane < 8) dma16(ps, stage + kABytes + kBBytes + wave * (kStep * 4));
+    ps += kStep * 4;
+  };
+  auto load_frags = [&](Frags& f, const char* stage, int ks) {
+    f.s[0] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64);
+    f.s[1] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64 + 16);
+#pragma unroll
+    for (int x = 0; x < kMA; ++x) {
+      f.a[x][0] = lds_read_tr(stage + offA[x] + ks * 16 * (kAChunks * 16));
+      f.a[x][1] = lds_read_tr(stage + offA[x] + (ks * 16 + 4) * (kAChunks * 16));
+    }
+#pragma unroll
+    for (int y = 0; y < kNB; ++y) {
+      f.b[y][0] = lds_read_tr(stage + offB[y] + ks * 16 * (kBChunks * 16));
+      f.b[y][1] = lds_read_tr(stage + offB[y] + (ks * 16 + 4) * (kBChunks * 16));
+    }
+  };
+  auto multiply = [&](const Frags& f) {
+    bf16x8 a[kMA];
+#pragma unroll
+    for (int x = 0; x < kMA; ++x) a[x] = scale_frag(f.a[x][0], f.a[x][1], f.s[0], f.s[1]);
+#pragma unroll
+    for (int y = 0; y < kNB; ++y) {
+      u32x4 bw = {f.b[y][0][0], f.b[y][0][1], f.b[y][1][0], f.b[y][1][1]};
+      bf16x8 b = __builtin_bit_cast(bf16x8, bw);
+#pragma unroll
+      for (int x = 0; x < kMA; ++x) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b, acc[x][y], 0, 0, 0);
+    }
+  };
+
+  // Stage t lives in ring slot t % NS.  Loads of stages 0 .. NS-2 are issued up front; in
+  // iteration t the wave first waits until its own loads of stage t+1 have landed (at most
+  // NS-3 younger stages may still be in flight), the barrier then makes every wave's part of
+  // stage t+1 visible and proves that stage t-1 is no longer being read, so its slot is
+  // refilled with stage t+NS-1.
+  const int64_t steps = (n + kStep - 1) / kStep;
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) issue(t, t);
+  wait_vmcnt<(NS - 3) * C::kLoads>();
+  __builtin_amdgcn_s_barrier();
+  int slot_cur = 0, slot_nxt = 1, slot_fill = NS - 1;
+  Frags f0, f1;
+  load_frags(f0, smem, 0);
+  for (int64_t step = 0; step < steps; ++step) {
+    wait_vmcnt<(NS - 3) * C::kLoads>();
+    __builtin_amdgcn_s_barrier();
+    issue(step + NS - 1, slot_fill);   // past the end this re-reads the last row with weight 0: harmless
+    const char* st_cur = smem + slot_cur * kStageBytes;
+    const char* st_nxt = smem + slot_nxt * kStageBytes;
+    load_frags(f1, st_cur, 1);
+    multiply(f0);
+    load_frags(f0, st_nxt, 0);
+    multiply(f1);
+    slot_fill = slot_cur;
+    slot_cur = slot_nxt;
+    slot_nxt = (slot_nxt + 1 == NS) ? 0 : slot_nxt + 1;
   }
+  wait_vmcnt<0>();   // no load may still be writing this workgroup's LDS when it is released
 
   // ---- epilogue: register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32 ------
-  if (!wave_active) return;
   float* Hk = H + (int64_t)(gbase + g_local) * d * d;
 #pragma unroll
   for (int y = 0; y < kNB; ++y) {
-    if (y < y_first) continue;
     const int64_t col = col_t + 32 * y + lane % 32;
 #pragma unroll
     for (int x = 0; x < kMA; ++x) {
@@ -234,22 +315,31 @@ int64_t tile_count(int64_t d, int gpc) {
   return (int64_t)gpc * tri_count(last) + rows_last;
 }
 
+int64_t padded_tokens(int64_t n) { return (n + kStep - 1) / kStep * kStep + (int64_t)kStep * kMaxStages; }
+
 }  // namespace
 
-size_t fisher_gram_bf16_workspace(int64_t, int64_t, int) { return 0; }
+size_t fisher_gram_bf16_workspace(int64_t n, int64_t, int G) {
+  return (size_t)(padded_tokens(n) * G) * sizeof(float);
+}
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                   float* H, bool accumulate, void*, size_t, hipStream_t st) {
+                                   float* H, bool accumulate, void* ws, size_t, hipStream_t st) {
+  const int64_t n_pad = padded_tokens(n);
+  float* sp = (float*)ws;
+  pack_weights_kernel<<<dim3((unsigned)((n_pad + 255) / 256)), dim3(256), 0, st>>>(s, n, G, n_pad, sp);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   const int gpc = groups_per_workgroup(G);
   const dim3 grid((unsigned)tile_count(d_in, gpc), (unsigned)(G / gpc));
   const __bf16* Xb = (const __bf16*)X;
   const int acc = accumulate ? 1 : 0;
   if (gpc == 4)
-    fisher_gram_bf16_kernel<4><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, s, G, H, acc);
+    fisher_gram_bf16_kernel<4><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc);
   else if (gpc == 2)
-    fisher_gram_bf16_kernel<2><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, s, G, H, acc);
+    fisher_gram_bf16_kernel<2><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc);
   else
-    fisher_gram_bf16_kernel<1><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, s, G, H, acc);
+    fisher_gram_bf16_kernel<1><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc);
   return hipGetLastError();
 }
 

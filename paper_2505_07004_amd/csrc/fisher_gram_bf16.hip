@@ -61,6 +61,10 @@ __device__ inline u32x2 lds_read_tr(const char* p) {
 __device__ inline void dma16(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
+// Same with 4 bytes per lane (LDS address lds_base + 4*lane).
+__device__ inline void dma4(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
 template <int N>
 __device__ inline void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -82,9 +86,14 @@ __device__ inline bf16x8 scale_frag(u32x2 lo, u32x2 hi, f32x4 s0, f32x4 s1) {
   return __builtin_bit_cast(bf16x8, out);
 }
 
-struct Frags {
-  u32x2 a[kMA][2];
+// Operands of one 16-token sub-step of a wave: the two 64-row fragments already scaled, the
+// eight raw 32-column fragments as read.
+struct Operands {
+  bf16x8 a[kMA];
   u32x2 b[kNB][2];
+};
+struct RawA {
+  u32x2 a[kMA][2];
   f32x4 s[2];
 };
 
@@ -96,10 +105,10 @@ struct Cfg {
   static constexpr int kBChunks = kTN / 8;           // 32
   static constexpr int kALoads = (kStep * kAChunks) / 256;  // wave-level 1 KiB loads per wave and stage
   static constexpr int kBLoads = (kStep * kBChunks) / 256;  // 4
-  static constexpr int kLoads = kALoads + kBLoads + 1;      // + one (8-lane) load of the wave's weights
+  static constexpr int kLoads = kALoads + kBLoads + 1;      // + one 4-byte-per-lane load of the wave's weights
   static constexpr int kABytes = kStep * kAChunks * 16;
   static constexpr int kBBytes = kStep * kBChunks * 16;
-  static constexpr int kSBytes = 4 * kStep * 4;      // one 32-float row per wave
+  static constexpr int kSBytes = 4 * 64 * 4;         // per wave 64 floats: its 32 weights + 32 of the next stage (unused)
   static constexpr int kStageBytes = kABytes + kBBytes + kSBytes;
   static constexpr int kStages = (kLdsBudget / kStageBytes) < kMaxStages ? (kLdsBudget / kStageBytes) : kMaxStages;
   static_assert(kStages >= 4, "ring too shallow");
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
 template <int GPC>
 __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __restrict__ X, int64_t n, int64_t d,
                                                                int64_t ld, const float* __restrict__ sp,
-                                                               int64_t n_pad, float* __restrict__ H, int accumulate) {
+                                                               int64_t n_pad, float* __restrict__ H, int accumulate, int n_gsets) {
   using C = Cfg<GPC>;
   constexpr int TM = C::TM, kAChunks = C::kAChunks, kBChunks = C::kBChunks;
   constexpr int kABytes = C::kABytes, kBBytes = C::kBBytes, kStageBytes = C::kStageBytes, NS = C::kStages;
@@ -125,16 +134,28 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   __shared__ __attribute__((aligned(1024))) char smem[NS * kStageBytes];
 
   // ---- which tile --------------------------------------------------------------------
-  int I, J;
+  // Workgroups are handed to the 8 XCDs round-robin by their linear id, and every XCD has its
+  // own L2.  The id is therefore remapped so that each XCD walks one contiguous range of the
+  // work list (ordered by tile column J, then tile row I, then group set): workgroups that are
+  // resident on an XCD at the same time share the 256-column raw panel, and both group sets of
+  // a tile read identical data.
+  int I, J, gset;
   {
-    const int64_t t = blockIdx.x;
+    constexpr int kXcd = 8;
+    const int64_t total = gridDim.x;
+    const int64_t id = blockIdx.x;
+    const int64_t x = id % kXcd, idx = id / kXcd;
+    const int64_t q = total / kXcd, r = total % kXcd;
+    const int64_t logical = x * q + (x < r ? x : r) + idx;
+    gset = (int)(logical % n_gsets);
+    const int64_t t = logical / n_gsets;
     int dummy;
     tri_decode(t / GPC, dummy, J);
     I = (int)(t - (int64_t)GPC * tri_count(J));
   }
   const int64_t row_t = (int64_t)I * TM;   // first row of the tile
   const int64_t col_t = (int64_t)J * kTN;  // first column of the tile
-  const int gbase = blockIdx.y * GPC;
+  const int gbase = gset * GPC;
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
@@ -148,12 +169,15 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   const int krl = 8 * (lane / 32) + t16 / 4;                  // token row inside a 16-token sub-step
   const int clane = 2 * ((lane / 16) % 2) + (t16 % 4) / 2;    // chunk bits 0..1
   const int boff = ((4 * (t16 % 4)) % 8) * 2;                 // byte inside the chunk
-  int offA[kMA], offB[kNB];
+  // Fragment y of the raw operand sits at chunk 4*(y ^ q) + clane of its token row, q = krl & 3
+  // (the swizzle); only the two low bits of y interact with q, so four per-lane bases plus
+  // immediate offsets (256 B per unit of y/4, whole rows per sub-step) address all of them.
+  int offA[kMA], offB[4];
 #pragma unroll
   for (int x = 0; x < kMA; ++x) offA[x] = lds_chunk_off<kAChunks>(krl, 8 * sub + 4 * x + clane) + boff;
 #pragma unroll
-  for (int y = 0; y < kNB; ++y) offB[y] = kABytes + lds_chunk_off<kBChunks>(krl, 4 * y + clane) + boff;
-  const int offS = kABytes + kBBytes + wave * (kStep * 4) + (8 * (lane / 32)) * 4;
+  for (int y = 0; y < 4; ++y) offB[y] = kABytes + lds_chunk_off<kBChunks>(krl, 4 * y + clane) + boff;
+  const int offS = kABytes + kBBytes + wave * 256 + (8 * (lane / 32)) * 4;
 
   f32x16 acc[kMA][kNB];
 #pragma unroll
@@ -196,39 +220,47 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     pb[h] = reinterpret_cast<const char*>(X + (int64_t)r * ld + c);
   }
   const int64_t step_bytes = (int64_t)kStep * ld * 2;
-  // weights: lanes 0..7 of every wave fetch the wave's 32 floats of the stage (16 B each)
-  const char* ps = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad + 4 * (lane % 8));
+  // weights: lane l of every wave fetches float l of the wave's group from the current stage on
+  // (64 floats: the second half belongs to the next stage and is never read from this slot)
+  const char* ps = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad + lane);
 
-  auto issue = [&](int64_t step, int slot) {
-    const unsigned stage = smem_base + (unsigned)slot * kStageBytes;
-    if (step < full_steps) {
+  // Addresses of the loads of one stage, fixed at the top of the step that issues them.
+  const char* cur_ptr[C::kLoads];
+  auto prepare = [&](int64_t step) {
+    const bool full = step < full_steps;
+    const int64_t i0 = step * kStep;
 #pragma unroll
-      for (int h = 0; h < C::kALoads; ++h) dma16(pa[h], stage + (wave * C::kALoads + h) * 1024);
-#pragma unroll
-      for (int h = 0; h < C::kBLoads; ++h) dma16(pb[h], stage + kABytes + (wave * C::kBLoads + h) * 1024);
-    } else {  // the ragged last stage and the stages prefetched past the end: clamp rows to the last token
-      const int64_t i0 = step * kStep;
-#pragma unroll
-      for (int h = 0; h < C::kALoads; ++h) {
-        int64_t i = i0 + ra_[h];
-        i = i < last_row ? i : last_row;
-        dma16(X + i * ld + ca_[h], stage + (wave * C::kALoads + h) * 1024);
-      }
-#pragma unroll
-      for (int h = 0; h < C::kBLoads; ++h) {
-        int64_t i = i0 + rb_[h];
-        i = i < last_row ? i : last_row;
-        dma16(X + i * ld + cb_[h], stage + kABytes + (wave * C::kBLoads + h) * 1024);
-      }
+    for (int h = 0; h < C::kALoads; ++h) {
+      int64_t i = i0 + ra_[h];
+      i = i < last_row ? i : last_row;       // only the ragged last stage and stages past the end clamp
+      cur_ptr[h] = full ? pa[h] : reinterpret_cast<const char*>(X + i * ld + ca_[h]);
+      pa[h] += step_bytes;
     }
 #pragma unroll
-    for (int h = 0; h < C::kALoads; ++h) pa[h] += step_bytes;
-#pragma unroll
-    for (int h = 0; h < C::kBLoads; ++h) pb[h] += step_bytes;
-    if (lane < 8) dma16(ps, stage + kABytes + kBBytes + wave * (kStep * 4));
+    for (int h = 0; h < C::kBLoads; ++h) {
+      int64_t i = i0 + rb_[h];
+      i = i < last_row ? i : last_row;
+      cur_ptr[C::kALoads + h] = full ? pb[h] : reinterpret_cast<const char*>(X + i * ld + cb_[h]);
+      pb[h] += step_bytes;
+    }
+    cur_ptr[C::kLoads - 1] = ps;
     ps += kStep * 4;
   };
-  auto load_frags = [&](Frags& f, const char* stage, int ks) {
+  auto issue_one = [&](int k, int slot) {     // k-th load of the prepared stage into ring slot `slot`
+    const unsigned stage = smem_base + (unsigned)slot * kStageBytes;
+    if (k < C::kALoads)
+      dma16(cur_ptr[k], stage + (wave * C::kALoads + k) * 1024);
+    else if (k < C::kALoads + C::kBLoads)
+      dma16(cur_ptr[k], stage + kABytes + (wave * C::kBLoads + (k - C::kALoads)) * 1024);
+    else
+      dma4(cur_ptr[k], stage + kABytes + kBBytes + wave * 256);
+  };
+  auto issue = [&](int64_t step, int slot) {
+    prepare(step);
+#pragma unroll
+    for (int k = 0; k < C::kLoads; ++k) issue_one(k, slot);
+  };
+  auto read_raw_a = [&](RawA& f, const char* stage, int ks) {
     f.s[0] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64);
     f.s[1] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64 + 16);
 #pragma unroll
@@ -236,23 +268,64 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
       f.a[x][0] = lds_read_tr(stage + offA[x] + ks * 16 * (kAChunks * 16));
       f.a[x][1] = lds_read_tr(stage + offA[x] + (ks * 16 + 4) * (kAChunks * 16));
     }
-#pragma unroll
-    for (int y = 0; y < kNB; ++y) {
-      f.b[y][0] = lds_read_tr(stage + offB[y] + ks * 16 * (kBChunks * 16));
-      f.b[y][1] = lds_read_tr(stage + offB[y] + (ks * 16 + 4) * (kBChunks * 16));
-    }
   };
-  auto multiply = [&](const Frags& f) {
-    bf16x8 a[kMA];
+  auto read_b1 = [&](Operands& o, const char* stage, int ks, int y) {
+    const char* p = stage + offB[y % 4] + (y / 4) * 256;
+    o.b[y][0] = lds_read_tr(p + ks * 16 * (kBChunks * 16));
+    o.b[y][1] = lds_read_tr(p + (ks * 16 + 4) * (kBChunks * 16));
+  };
+  // One dword (two tokens) of a scaled fragment: bf16 -> fp32, times the token weights, RNE -> bf16.
+  auto scale1 = [&](const RawA& f, int x, int q) -> unsigned int {
+    const unsigned int w = f.a[x][q / 2][q % 2];
+    const f32x4 sv = f.s[q / 2];
+    f32x2 v;
+    v[0] = __builtin_bit_cast(float, w << 16) * sv[2 * (q % 2)];
+    v[1] = __builtin_bit_cast(float, w & 0xffff0000u) * sv[2 * (q % 2) + 1];
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));
+  };
+  auto mfma1 = [&](const Operands& o, int i) {   // MFMA number i of a sub-step: fragment pair (x, y) = (i%2, i/2)
+    const int x = i % 2, y = i / 2;
+    u32x4 bw = {o.b[y][0][0], o.b[y][0][1], o.b[y][1][0], o.b[y][1][1]};
+    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[x], __builtin_bit_cast(bf16x8, bw), acc[x][y], 0, 0, 0);
+  };
+  // One 16-token sub-step in its exact issue order (scheduling fences keep the compiler from
+  // regrouping it): the 16 MFMAs on the current operands, each occupying the matrix core for
+  // 32 cycles, with the next sub-step's work slotted in between them: after MFMA 0 the six LDS
+  // reads of the next scaled operand and its weights, after MFMAs 1..8 the reads of one raw
+  // fragment each, after MFMAs 8..15 one eighth of the scaling (5 VALU operations) each.
+  // The direct loads of the stage NS-1 ahead are spread over the two sub-steps (one after every
+  // third MFMA or so): issued back to back they would fill the address queue of the memory
+  // pipeline and hold the wave, and with it its MFMAs, at the issue stage.
+  auto sub_step = [&](const Operands& cur, Operands& nxt, RawA& raw, const char* stage, int ks, int dma_first,
+                      int dma_count, int slot) {
+    u32x4 an[kMA];
+    mfma1(cur, 0);
+    read_raw_a(raw, stage, ks);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int x = 0; x < kMA; ++x) a[x] = scale_frag(f.a[x][0], f.a[x][1], f.s[0], f.s[1]);
-#pragma unroll
-    for (int y = 0; y < kNB; ++y) {
-      u32x4 bw = {f.b[y][0][0], f.b[y][0][1], f.b[y][1][0], f.b[y][1][1]};
-      bf16x8 b = __builtin_bit_cast(bf16x8, bw);
-#pragma unroll
-      for (int x = 0; x < kMA; ++x) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b, acc[x][y], 0, 0, 0);
+    for (int i = 1; i <= 8; ++i) {
+      mfma1(cur, i);
+      read_b1(nxt, stage, ks, i - 1);
+      if (i == 8) {
+        an[0][0] = scale1(raw, 0, 0);
+        asm volatile("" : "+v"(an[0][0]));           // keeps the scaling where it is written (see below)
+      }
+      if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
+      __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int i = 9; i <= 15; ++i) {
+      mfma1(cur, i);
+      const int piece = i - 8;                       // 1..7
+      an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
+      // an empty asm that "uses" the value: without it the optimiser sinks all the scaling
+      // below the last MFMA of the sub-step, where nothing hides it
+      asm volatile("" : "+v"(an[piece / 4][piece % 4]));
+      if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int x = 0; x < kMA; ++x) nxt.a[x] = __builtin_bit_cast(bf16x8, an[x]);
   };
 
   // Stage t lives in ring slot t % NS.  Loads of stages 0 .. NS-2 are issued up front; in
@@ -266,18 +339,25 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   wait_vmcnt<(NS - 3) * C::kLoads>();
   __builtin_amdgcn_s_barrier();
   int slot_cur = 0, slot_nxt = 1, slot_fill = NS - 1;
-  Frags f0, f1;
-  load_frags(f0, smem, 0);
+  Operands o0, o1;
+  RawA raw;
+  read_raw_a(raw, smem, 0);
+#pragma unroll
+  for (int y = 0; y < kNB; ++y) read_b1(o0, smem, 0, y);
+#pragma unroll
+  for (int x = 0; x < kMA; ++x) o0.a[x] = scale_frag(raw.a[x][0], raw.a[x][1], raw.s[0], raw.s[1]);
   for (int64_t step = 0; step < steps; ++step) {
     wait_vmcnt<(NS - 3) * C::kLoads>();
     __builtin_amdgcn_s_barrier();
-    issue(step + NS - 1, slot_fill);   // past the end this re-reads the last row with weight 0: harmless
+    prepare(step + NS - 1);            // past the end this re-reads the last row with weight 0: harmless
     const char* st_cur = smem + slot_cur * kStageBytes;
     const char* st_nxt = smem + slot_nxt * kStageBytes;
-    load_frags(f1, st_cur, 1);
-    multiply(f0);
-    load_frags(f0, st_nxt, 0);
-    multiply(f1);
+    constexpr int kFirstHalf = (C::kLoads + 1) / 2;
+    __builtin_amdgcn_sched_barrier(0);
+    // tokens 0..15 of the stage; fetches tokens 16..31
+    sub_step(o0, o1, raw, st_cur, 1, 0, kFirstHalf, slot_fill);
+    // tokens 16..31; fetches tokens 0..15 of the next stage (complete since the barrier)
+    sub_step(o1, o0, raw, st_nxt, 0, kFirstHalf, C::kLoads - kFirstHalf, slot_fill);
     slot_fill = slot_cur;
     slot_cur = slot_nxt;
     slot_nxt = (slot_nxt + 1 == NS) ? 0 : slot_nxt + 1;
@@ -331,15 +411,16 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int gpc = groups_per_workgroup(G);
-  const dim3 grid((unsigned)tile_count(d_in, gpc), (unsigned)(G / gpc));
+  const int n_gsets = G / gpc;
+  const dim3 grid((unsigned)(tile_count(d_in, gpc) * n_gsets));
   const __bf16* Xb = (const __bf16*)X;
   const int acc = accumulate ? 1 : 0;
   if (gpc == 4)
-    fisher_gram_bf16_kernel<4><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc);
+    fisher_gram_bf16_kernel<4><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc, n_gsets);
   else if (gpc == 2)
-    fisher_gram_bf16_kernel<2><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc);
+    fisher_gram_bf16_kernel<2><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc, n_gsets);
   else
-    fisher_gram_bf16_kernel<1><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc);
+    fisher_gram_bf16_kernel<1><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc, n_gsets);
   return hipGetLastError();
 }
 

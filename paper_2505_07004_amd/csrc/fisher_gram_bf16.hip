@@ -123,48 +123,77 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
   for (int g = 0; g < G; ++g) sp[(int64_t)g * n_pad + i] = (i < n) ? s[i * G + g] : 0.f;
 }
 
+// A work item is one tile (TM rows x 256 columns of the upper triangle) for one set of GPC
+// groups.  Items are ordered by tile column J, then tile row I, then group set, so that
+// neighbours in the list share the 256-column raw panel.
+struct Item {
+  int64_t row_t, col_t;
+  int gbase;
+};
+template <int GPC>
+__device__ inline Item decode_item(int64_t item, int n_gsets) {
+  const int gset = (int)(item % n_gsets);
+  const int64_t t = item / n_gsets;
+  int dummy, J;
+  tri_decode(t / GPC, dummy, J);
+  const int I = (int)(t - (int64_t)GPC * tri_count(J));
+  Item it;
+  it.row_t = (int64_t)I * (64 * (4 / GPC));
+  it.col_t = (int64_t)J * kTN;
+  it.gbase = gset * GPC;
+  return it;
+}
+
+// First unit of persistent workgroup p when `units` units are dealt evenly to P workgroups.
+__host__ __device__ inline int64_t first_unit(int64_t p, int64_t units, int64_t P) { return p * units / P; }
+
+constexpr int kTileFloats = 4 * kMA * kNB * 16 * 64;   // accumulators of one workgroup tile (256 KiB)
+
+// Persistent kernel with a hybrid work split.  P workgroups are resident (one per compute unit).
+// With T items of `steps` token steps each, every workgroup first computes floor(T/P) whole
+// items, all starting at token 0 at the same time: workgroups that share column panels then
+// sweep the tokens in lockstep and find each other's rows in L2.  The T mod P left-over items
+// are cut stream-K fashion: their items x steps "units" are dealt out as one contiguous run
+// per workgroup, so every compute unit stays busy to the end.  A run that covers all steps of
+// an item goes straight into H; a partial run is parked in the workspace and a second small
+// kernel adds the parts of every split item in a fixed order.  No workgroup ever waits for
+// another one.
 template <int GPC>
 __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __restrict__ X, int64_t n, int64_t d,
                                                                int64_t ld, const float* __restrict__ sp,
-                                                               int64_t n_pad, float* __restrict__ H, int accumulate, int n_gsets) {
+                                                               int64_t n_pad, float* __restrict__ H, int accumulate,
+                                                               int n_gsets, int64_t n_items, float* __restrict__ partial) {
   using C = Cfg<GPC>;
-  constexpr int TM = C::TM, kAChunks = C::kAChunks, kBChunks = C::kBChunks;
+  constexpr int kAChunks = C::kAChunks, kBChunks = C::kBChunks;
   constexpr int kABytes = C::kABytes, kBBytes = C::kBBytes, kStageBytes = C::kStageBytes, NS = C::kStages;
 
   __shared__ __attribute__((aligned(1024))) char smem[NS * kStageBytes];
 
-  // ---- which tile --------------------------------------------------------------------
-  // Workgroups are handed to the 8 XCDs round-robin by their linear id, and every XCD has its
-  // own L2.  The id is therefore remapped so that each XCD walks one contiguous range of the
-  // work list (ordered by tile column J, then tile row I, then group set): workgroups that are
-  // resident on an XCD at the same time share the 256-column raw panel, and both group sets of
-  // a tile read identical data.
-  int I, J, gset;
+  // Workgroups are handed to the 8 XCDs round-robin by their id, and every XCD has its own L2.
+  // The id is remapped so that each XCD owns one contiguous eighth of the unit range:
+  // workgroups resident on an XCD then share raw panels (and both group sets of a tile read
+  // identical data).
+  const int64_t P = gridDim.x;
+  int64_t p;
   {
     constexpr int kXcd = 8;
-    const int64_t total = gridDim.x;
     const int64_t id = blockIdx.x;
     const int64_t x = id % kXcd, idx = id / kXcd;
-    const int64_t q = total / kXcd, r = total % kXcd;
-    const int64_t logical = x * q + (x < r ? x : r) + idx;
-    gset = (int)(logical % n_gsets);
-    const int64_t t = logical / n_gsets;
-    int dummy;
-    tri_decode(t / GPC, dummy, J);
-    I = (int)(t - (int64_t)GPC * tri_count(J));
+    const int64_t q = P / kXcd, r = P % kXcd;
+    p = x * q + (x < r ? x : r) + idx;
   }
-  const int64_t row_t = (int64_t)I * TM;   // first row of the tile
-  const int64_t col_t = (int64_t)J * kTN;  // first column of the tile
-  const int gbase = gset * GPC;
+  const int64_t steps = (n + kStep - 1) / kStep;
+  const int64_t rounds = n_items / P;                        // whole items per workgroup
+  const int64_t units = (n_items - rounds * P) * steps;      // left-over work, dealt out in runs
+  const int64_t u_begin = first_unit(p, units, P), u_end = first_unit(p + 1, units, P);
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int g_local = wave % GPC;
   const int sub = wave / GPC;
-  const int64_t row_w = row_t + 64 * sub;  // first row of this wave's block
 
-  // ---- per-lane LDS read offsets (loop invariant) ---------------------------------------
+  // ---- per-lane LDS read offsets (invariant) ----------------------------------------------
   const int t16 = lane % 16;
   const int krl = 8 * (lane / 32) + t16 / 4;                  // token row inside a 16-token sub-step
   const int clane = 2 * ((lane / 16) % 2) + (t16 % 4) / 2;    // chunk bits 0..1
@@ -179,208 +208,275 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   for (int y = 0; y < 4; ++y) offB[y] = kABytes + lds_chunk_off<kBChunks>(krl, 4 * y + clane) + boff;
   const int offS = kABytes + kBBytes + wave * 256 + (8 * (lane / 32)) * 4;
 
-  f32x16 acc[kMA][kNB];
-#pragma unroll
-  for (int x = 0; x < kMA; ++x)
-#pragma unroll
-    for (int y = 0; y < kNB; ++y)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
-
-  // ---- direct global->LDS staging -------------------------------------------------------------
-  // Wave w issues, per stage, kALoads + kBLoads loads of 1 KiB (64 lanes x 16 B) plus one
-  // 8-lane load of its own 32 weights.  LDS slot q (16 B units) of a tile holds token row
-  // q / CHUNKS and physical chunk q % CHUNKS; the lane fetches the logical chunk that the
-  // swizzle stores there.
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
   const int64_t last_row = n - 1;
-  const int64_t full_steps = n / kStep;          // stages below this index need no row clamp
-  const char* pa[C::kALoads];                    // running global address, stage 0 .. (valid while unclamped)
-  const char* pb[C::kBLoads];
-  int ra_[C::kALoads], rb_[C::kBLoads];          // token row inside the stage
-  int64_t ca_[C::kALoads], cb_[C::kBLoads];      // clamped first column of the lane's chunk
-#pragma unroll
-  for (int h = 0; h < C::kALoads; ++h) {
-    const int q = (wave * C::kALoads + h) * 64 + lane;
-    const int r = q / kAChunks;
-    int64_t c = row_t + 8 * swizzle<kAChunks>(r, q % kAChunks);
-    if (c + 8 > ld) c = ld - 8;                  // stays inside the row pitch; feeds only unstored outputs
-    ra_[h] = r;
-    ca_[h] = c;
-    pa[h] = reinterpret_cast<const char*>(X + (int64_t)r * ld + c);
-  }
-#pragma unroll
-  for (int h = 0; h < C::kBLoads; ++h) {
-    const int q = (wave * C::kBLoads + h) * 64 + lane;
-    const int r = q / kBChunks;
-    int64_t c = col_t + 8 * swizzle<kBChunks>(r, q % kBChunks);
-    if (c + 8 > ld) c = ld - 8;
-    rb_[h] = r;
-    cb_[h] = c;
-    pb[h] = reinterpret_cast<const char*>(X + (int64_t)r * ld + c);
-  }
   const int64_t step_bytes = (int64_t)kStep * ld * 2;
-  // weights: lane l of every wave fetches float l of the wave's group from the current stage on
-  // (64 floats: the second half belongs to the next stage and is never read from this slot)
-  const char* ps = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad + lane);
 
-  // Addresses of the loads of one stage, fixed at the top of the step that issues them.
-  const char* cur_ptr[C::kLoads];
-  auto prepare = [&](int64_t step) {
-    const bool full = step < full_steps;
-    const int64_t i0 = step * kStep;
+  f32x16 acc[kMA][kNB];
+
+  int64_t round = 0;
+  for (int64_t u = u_begin; round < rounds || u < u_end;) {
+    int64_t item, k0, k1;
+    if (round < rounds) {            // a whole item, in step with every other workgroup
+      item = round * P + p;
+      k0 = 0;
+      k1 = steps;
+    } else {                         // (part of) a left-over item
+      item = rounds * P + u / steps;
+      k0 = u - (u / steps) * steps;
+      const int64_t len = (steps - k0) < (u_end - u) ? (steps - k0) : (u_end - u);
+      k1 = k0 + len;
+    }
+    const Item it = decode_item<GPC>(item, n_gsets);
+    const int64_t row_t = it.row_t, col_t = it.col_t;
+    const int gbase = it.gbase;
+    const int64_t row_w = row_t + 64 * sub;      // first row of this wave's block
+
+#pragma unroll
+    for (int x = 0; x < kMA; ++x)
+#pragma unroll
+      for (int y = 0; y < kNB; ++y)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+    // ---- direct global->LDS staging -----------------------------------------------------------
+    // Wave w issues, per stage, kALoads + kBLoads loads of 1 KiB (64 lanes x 16 B) plus one
+    // 4-byte-per-lane load of its group's weights.  LDS slot q (16 B units) of a tile holds
+    // token row q / CHUNKS and physical chunk q % CHUNKS; the lane fetches the logical chunk
+    // that the swizzle stores there.
+    // Per load: the running global address (advancing one stage per issue) and the address of the
+    // same columns in the last token row.  Rows past the last token are read from that row
+    // instead (their weight is 0), which for a fixed column is simply min(running, last).
+    const char* prun[C::kLoads];
+    const char* plast[C::kLoads];
 #pragma unroll
     for (int h = 0; h < C::kALoads; ++h) {
-      int64_t i = i0 + ra_[h];
-      i = i < last_row ? i : last_row;       // only the ragged last stage and stages past the end clamp
-      cur_ptr[h] = full ? pa[h] : reinterpret_cast<const char*>(X + i * ld + ca_[h]);
-      pa[h] += step_bytes;
+      const int q = (wave * C::kALoads + h) * 64 + lane;
+      const int r = q / kAChunks;
+      int64_t c = row_t + 8 * swizzle<kAChunks>(r, q % kAChunks);
+      if (c + 8 > ld) c = ld - 8;                  // stays inside the row pitch; feeds only unstored outputs
+      prun[h] = reinterpret_cast<const char*>(X + (k0 * kStep + r) * ld + c);
+      plast[h] = reinterpret_cast<const char*>(X + last_row * ld + c);
     }
 #pragma unroll
     for (int h = 0; h < C::kBLoads; ++h) {
-      int64_t i = i0 + rb_[h];
-      i = i < last_row ? i : last_row;
-      cur_ptr[C::kALoads + h] = full ? pb[h] : reinterpret_cast<const char*>(X + i * ld + cb_[h]);
-      pb[h] += step_bytes;
+      const int q = (wave * C::kBLoads + h) * 64 + lane;
+      const int r = q / kBChunks;
+      int64_t c = col_t + 8 * swizzle<kBChunks>(r, q % kBChunks);
+      if (c + 8 > ld) c = ld - 8;
+      prun[C::kALoads + h] = reinterpret_cast<const char*>(X + (k0 * kStep + r) * ld + c);
+      plast[C::kALoads + h] = reinterpret_cast<const char*>(X + last_row * ld + c);
     }
-    cur_ptr[C::kLoads - 1] = ps;
-    ps += kStep * 4;
-  };
-  auto issue_one = [&](int k, int slot) {     // k-th load of the prepared stage into ring slot `slot`
-    const unsigned stage = smem_base + (unsigned)slot * kStageBytes;
-    if (k < C::kALoads)
-      dma16(cur_ptr[k], stage + (wave * C::kALoads + k) * 1024);
-    else if (k < C::kALoads + C::kBLoads)
-      dma16(cur_ptr[k], stage + kABytes + (wave * C::kBLoads + (k - C::kALoads)) * 1024);
-    else
-      dma4(cur_ptr[k], stage + kABytes + kBBytes + wave * 256);
-  };
-  auto issue = [&](int64_t step, int slot) {
-    prepare(step);
-#pragma unroll
-    for (int k = 0; k < C::kLoads; ++k) issue_one(k, slot);
-  };
-  auto read_raw_a = [&](RawA& f, const char* stage, int ks) {
-    f.s[0] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64);
-    f.s[1] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64 + 16);
-#pragma unroll
-    for (int x = 0; x < kMA; ++x) {
-      f.a[x][0] = lds_read_tr(stage + offA[x] + ks * 16 * (kAChunks * 16));
-      f.a[x][1] = lds_read_tr(stage + offA[x] + (ks * 16 + 4) * (kAChunks * 16));
-    }
-  };
-  auto read_b1 = [&](Operands& o, const char* stage, int ks, int y) {
-    const char* p = stage + offB[y % 4] + (y / 4) * 256;
-    o.b[y][0] = lds_read_tr(p + ks * 16 * (kBChunks * 16));
-    o.b[y][1] = lds_read_tr(p + (ks * 16 + 4) * (kBChunks * 16));
-  };
-  // One dword (two tokens) of a scaled fragment: bf16 -> fp32, times the token weights, RNE -> bf16.
-  auto scale1 = [&](const RawA& f, int x, int q) -> unsigned int {
-    const unsigned int w = f.a[x][q / 2][q % 2];
-    const f32x4 sv = f.s[q / 2];
-    f32x2 v;
-    v[0] = __builtin_bit_cast(float, w << 16) * sv[2 * (q % 2)];
-    v[1] = __builtin_bit_cast(float, w & 0xffff0000u) * sv[2 * (q % 2) + 1];
-    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));
-  };
-  auto mfma1 = [&](const Operands& o, int i) {   // MFMA number i of a sub-step: fragment pair (x, y) = (i%2, i/2)
-    const int x = i % 2, y = i / 2;
-    u32x4 bw = {o.b[y][0][0], o.b[y][0][1], o.b[y][1][0], o.b[y][1][1]};
-    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[x], __builtin_bit_cast(bf16x8, bw), acc[x][y], 0, 0, 0);
-  };
-  // One 16-token sub-step in its exact issue order (scheduling fences keep the compiler from
-  // regrouping it): the 16 MFMAs on the current operands, each occupying the matrix core for
-  // 32 cycles, with the next sub-step's work slotted in between them: after MFMA 0 the six LDS
-  // reads of the next scaled operand and its weights, after MFMAs 1..8 the reads of one raw
-  // fragment each, after MFMAs 8..15 one eighth of the scaling (5 VALU operations) each.
-  // The direct loads of the stage NS-1 ahead are spread over the two sub-steps (one after every
-  // third MFMA or so): issued back to back they would fill the address queue of the memory
-  // pipeline and hold the wave, and with it its MFMAs, at the issue stage.
-  auto sub_step = [&](const Operands& cur, Operands& nxt, RawA& raw, const char* stage, int ks, int dma_first,
-                      int dma_count, int slot) {
-    u32x4 an[kMA];
-    mfma1(cur, 0);
-    read_raw_a(raw, stage, ks);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 1; i <= 8; ++i) {
-      mfma1(cur, i);
-      read_b1(nxt, stage, ks, i - 1);
-      if (i == 8) {
-        an[0][0] = scale1(raw, 0, 0);
-        asm volatile("" : "+v"(an[0][0]));           // keeps the scaling where it is written (see below)
-      }
-      if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int i = 9; i <= 15; ++i) {
-      mfma1(cur, i);
-      const int piece = i - 8;                       // 1..7
-      an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
-      // an empty asm that "uses" the value: without it the optimiser sinks all the scaling
-      // below the last MFMA of the sub-step, where nothing hides it
-      asm volatile("" : "+v"(an[piece / 4][piece % 4]));
-      if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int x = 0; x < kMA; ++x) nxt.a[x] = __builtin_bit_cast(bf16x8, an[x]);
-  };
+    // weights: lane l of every wave fetches float l of the wave's group from the current stage on
+    // (64 floats: the second half belongs to the next stage and is never read from this slot);
+    // the padding of the repacked weights makes every such read valid
+    prun[C::kLoads - 1] = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad + k0 * kStep + lane);
+    plast[C::kLoads - 1] = nullptr;
 
-  // Stage t lives in ring slot t % NS.  Loads of stages 0 .. NS-2 are issued up front; in
-  // iteration t the wave first waits until its own loads of stage t+1 have landed (at most
-  // NS-3 younger stages may still be in flight), the barrier then makes every wave's part of
-  // stage t+1 visible and proves that stage t-1 is no longer being read, so its slot is
-  // refilled with stage t+NS-1.
-  const int64_t steps = (n + kStep - 1) / kStep;
+    // k-th load of the next stage to fetch, into ring slot `slot`; a handful of VALU operations
+    // and one memory instruction, small enough to sit between two MFMAs
+    auto issue_one = [&](int k, int slot) {
+      const unsigned stage = smem_base + (unsigned)slot * kStageBytes;
+      if (k < C::kLoads - 1) {
+        const char* ptr = prun[k] < plast[k] ? prun[k] : plast[k];
+        if (k < C::kALoads)
+          dma16(ptr, stage + (wave * C::kALoads + k) * 1024);
+        else
+          dma16(ptr, stage + kABytes + (wave * C::kBLoads + (k - C::kALoads)) * 1024);
+        prun[k] += step_bytes;
+      } else {
+        dma4(prun[k], stage + kABytes + kBBytes + wave * 256);
+        prun[k] += kStep * 4;
+      }
+    };
+    auto issue = [&](int slot) {
 #pragma unroll
-  for (int t = 0; t < NS - 1; ++t) issue(t, t);
-  wait_vmcnt<(NS - 3) * C::kLoads>();
-  __builtin_amdgcn_s_barrier();
-  int slot_cur = 0, slot_nxt = 1, slot_fill = NS - 1;
-  Operands o0, o1;
-  RawA raw;
-  read_raw_a(raw, smem, 0);
+      for (int k = 0; k < C::kLoads; ++k) issue_one(k, slot);
+    };
+    auto read_raw_a = [&](RawA& f, const char* stage, int ks) {
+      f.s[0] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64);
+      f.s[1] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64 + 16);
 #pragma unroll
-  for (int y = 0; y < kNB; ++y) read_b1(o0, smem, 0, y);
+      for (int x = 0; x < kMA; ++x) {
+        f.a[x][0] = lds_read_tr(stage + offA[x] + ks * 16 * (kAChunks * 16));
+        f.a[x][1] = lds_read_tr(stage + offA[x] + (ks * 16 + 4) * (kAChunks * 16));
+      }
+    };
+    auto read_b1 = [&](Operands& o, const char* stage, int ks, int y) {
+      const char* pp = stage + offB[y % 4] + (y / 4) * 256;
+      o.b[y][0] = lds_read_tr(pp + ks * 16 * (kBChunks * 16));
+      o.b[y][1] = lds_read_tr(pp + (ks * 16 + 4) * (kBChunks * 16));
+    };
+    // One dword (two tokens) of a scaled fragment: bf16 -> fp32, times the token weights, RNE -> bf16.
+    auto scale1 = [&](const RawA& f, int x, int q) -> unsigned int {
+      const unsigned int w = f.a[x][q / 2][q % 2];
+      const f32x4 sv = f.s[q / 2];
+      f32x2 v;
+      v[0] = __builtin_bit_cast(float, w << 16) * sv[2 * (q % 2)];
+      v[1] = __builtin_bit_cast(float, w & 0xffff0000u) * sv[2 * (q % 2) + 1];
+      return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));
+    };
+    auto mfma1 = [&](const Operands& o, int i) {   // MFMA number i of a sub-step: fragment pair (x, y) = (i%2, i/2)
+      const int x = i % 2, y = i / 2;
+      u32x4 bw = {o.b[y][0][0], o.b[y][0][1], o.b[y][1][0], o.b[y][1][1]};
+      acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[x], __builtin_bit_cast(bf16x8, bw), acc[x][y], 0, 0, 0);
+    };
+    // One 16-token sub-step in its exact issue order (scheduling fences keep the compiler from
+    // regrouping it): the 16 MFMAs on the current operands, each occupying the matrix core for
+    // 32 cycles, with the next sub-step's work slotted in between them: after MFMA 0 the six LDS
+    // reads of the next scaled operand and its weights, after MFMAs 1..8 the reads of one raw
+    // fragment each, after MFMAs 8..15 one eighth of the scaling (5 VALU operations) each.
+    // The direct loads of the stage NS-1 ahead are spread over the two sub-steps (one after
+    // every third MFMA): issued back to back they would queue up in the memory pipeline.
+    auto sub_step = [&](const Operands& cur, Operands& nxt, RawA& raw, const char* stage, int ks, int dma_first,
+                        int dma_count, int slot) {
+      u32x4 an[kMA];
+      mfma1(cur, 0);
+      read_raw_a(raw, stage, ks);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int x = 0; x < kMA; ++x) o0.a[x] = scale_frag(raw.a[x][0], raw.a[x][1], raw.s[0], raw.s[1]);
-  for (int64_t step = 0; step < steps; ++step) {
+      for (int i = 1; i <= 8; ++i) {
+        mfma1(cur, i);
+        read_b1(nxt, stage, ks, i - 1);
+        if (i == 8) {
+          an[0][0] = scale1(raw, 0, 0);
+          asm volatile("" : "+v"(an[0][0]));           // keeps the scaling where it is written (see below)
+        }
+        if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = 9; i <= 15; ++i) {
+        mfma1(cur, i);
+        const int piece = i - 8;                       // 1..7
+        an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
+        // an empty asm that "uses" the value: without it the optimiser sinks all the scaling
+        // below the last MFMA of the sub-step, where nothing hides it
+        asm volatile("" : "+v"(an[piece / 4][piece % 4]));
+        if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int x = 0; x < kMA; ++x) nxt.a[x] = __builtin_bit_cast(bf16x8, an[x]);
+    };
+
+    // Token step k0 + t of the run lives in ring slot t % NS.  Loads of the first NS-1 stages are
+    // issued up front; in iteration t the wave first waits until its own loads of stage t+1
+    // have landed (at most NS-3 younger stages may still be in flight), the barrier then makes
+    // every wave's part of stage t+1 visible and proves that stage t-1 is no longer being
+    // read, so its slot is refilled with stage t+NS-1.
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) issue(t);
     wait_vmcnt<(NS - 3) * C::kLoads>();
     __builtin_amdgcn_s_barrier();
-    prepare(step + NS - 1);            // past the end this re-reads the last row with weight 0: harmless
-    const char* st_cur = smem + slot_cur * kStageBytes;
-    const char* st_nxt = smem + slot_nxt * kStageBytes;
-    constexpr int kFirstHalf = (C::kLoads + 1) / 2;
-    __builtin_amdgcn_sched_barrier(0);
-    // tokens 0..15 of the stage; fetches tokens 16..31
-    sub_step(o0, o1, raw, st_cur, 1, 0, kFirstHalf, slot_fill);
-    // tokens 16..31; fetches tokens 0..15 of the next stage (complete since the barrier)
-    sub_step(o1, o0, raw, st_nxt, 0, kFirstHalf, C::kLoads - kFirstHalf, slot_fill);
-    slot_fill = slot_cur;
-    slot_cur = slot_nxt;
-    slot_nxt = (slot_nxt + 1 == NS) ? 0 : slot_nxt + 1;
-  }
-  wait_vmcnt<0>();   // no load may still be writing this workgroup's LDS when it is released
+    int slot_cur = 0, slot_nxt = 1, slot_fill = NS - 1;
+    Operands o0, o1;
+    RawA raw;
+    read_raw_a(raw, smem, 0);
+#pragma unroll
+    for (int y = 0; y < kNB; ++y) read_b1(o0, smem, 0, y);
+#pragma unroll
+    for (int x = 0; x < kMA; ++x) o0.a[x] = scale_frag(raw.a[x][0], raw.a[x][1], raw.s[0], raw.s[1]);
+    for (int64_t step = k0; step < k1; ++step) {
+      wait_vmcnt<(NS - 3) * C::kLoads>();
+      __builtin_amdgcn_s_barrier();
+      const char* st_cur = smem + slot_cur * kStageBytes;
+      const char* st_nxt = smem + slot_nxt * kStageBytes;
+      constexpr int kFirstHalf = (C::kLoads + 1) / 2;
+      __builtin_amdgcn_sched_barrier(0);
+      // tokens 0..15 of the stage; fetches tokens 16..31
+      sub_step(o0, o1, raw, st_cur, 1, 0, kFirstHalf, slot_fill);
+      // tokens 16..31; fetches tokens 0..15 of the next stage (complete since the barrier)
+      sub_step(o1, o0, raw, st_nxt, 0, kFirstHalf, C::kLoads - kFirstHalf, slot_fill);
+      slot_fill = slot_cur;
+      slot_cur = slot_nxt;
+      slot_nxt = (slot_nxt + 1 == NS) ? 0 : slot_nxt + 1;
+    }
+    wait_vmcnt<0>();   // no load may still be writing the ring when it is reused or released
 
-  // ---- epilogue: register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32 ------
-  float* Hk = H + (int64_t)(gbase + g_local) * d * d;
+    // ---- epilogue: register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32 ------
+    if (k0 == 0 && k1 == steps) {
+      float* Hk = H + (int64_t)(gbase + g_local) * d * d;
 #pragma unroll
-  for (int y = 0; y < kNB; ++y) {
-    const int64_t col = col_t + 32 * y + lane % 32;
+      for (int y = 0; y < kNB; ++y) {
+        const int64_t col = col_t + 32 * y + lane % 32;
 #pragma unroll
-    for (int x = 0; x < kMA; ++x) {
+        for (int x = 0; x < kMA; ++x) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = row_w + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-        if (row < d && col < d && row <= col) {
-          float v = acc[x][y][r];
-          float* p = Hk + row * d + col;
-          if (accumulate) v += *p;
-          *p = v;
+          for (int r = 0; r < 16; ++r) {
+            const int64_t row = row_w + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+            if (row < d && col < d && row <= col) {
+              float v = acc[x][y][r];
+              float* ph = Hk + row * d + col;
+              if (accumulate) v += *ph;
+              *ph = v;
+            }
+          }
         }
       }
+    } else {
+      // the first run of a workgroup parks in slot 2p, a later (necessarily last) one in 2p+1
+      float* slot = partial + (size_t)(2 * p + (u == u_begin ? 0 : 1)) * kTileFloats + (size_t)wave * (kTileFloats / 4);
+#pragma unroll
+      for (int x = 0; x < kMA; ++x)
+#pragma unroll
+        for (int y = 0; y < kNB; ++y)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) slot[((x * kNB + y) * 16 + r) * 64 + lane] = acc[x][y][r];
+    }
+    __syncthreads();   // every wave is done with the ring before the next run refills it
+    if (round < rounds)
+      ++round;
+    else
+      u += k1 - k0;
+  }
+}
+
+// Adds the parked parts of every left-over item that was split between workgroups, in
+// workgroup order, and stores the sum into H.  One workgroup per left-over item.
+template <int GPC>
+__global__ __launch_bounds__(256) void fisher_gram_fixup_kernel(int64_t n, int64_t d, float* __restrict__ H,
+                                                                int accumulate, int n_gsets, int64_t n_items, int64_t P,
+                                                                const float* __restrict__ partial) {
+  const int64_t steps = (n + kStep - 1) / kStep;
+  const int64_t rounds = n_items / P;
+  const int64_t units = (n_items - rounds * P) * steps;
+  const int64_t j = blockIdx.x;                                    // index among the left-over items
+  const int64_t lo = j * steps, hi = lo + steps;                   // its units
+  // first workgroup whose run reaches into the item
+  int64_t q0 = lo * P / units;
+  if (q0 >= P) q0 = P - 1;
+  while (q0 > 0 && first_unit(q0, units, P) > lo) --q0;
+  while (q0 + 1 < P && first_unit(q0 + 1, units, P) <= lo) ++q0;
+  if (first_unit(q0, units, P) <= lo && first_unit(q0 + 1, units, P) >= hi) return;   // one run covers the item: already in H
+  const Item it = decode_item<GPC>(rounds * P + j, n_gsets);
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int g_local = wave % GPC, sub = wave / GPC;
+  const int64_t row_w = it.row_t + 64 * sub;
+  float* Hk = H + (int64_t)(it.gbase + g_local) * d * d;
+  const size_t in_tile = (size_t)wave * (kTileFloats / 4) + lane;
+  // blockIdx.y picks one 32x32 accumulator fragment (x, y) of every wave
+  const int x = blockIdx.y / kNB, y = blockIdx.y % kNB;
+  const int64_t col = it.col_t + 32 * y + lane % 32;
+  float v[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = 0.f;
+  for (int64_t q = q0; q < P; ++q) {
+    const int64_t b0 = first_unit(q, units, P), b1 = first_unit(q + 1, units, P);
+    if (b0 >= hi) break;
+    if (b1 == b0) continue;                                        // this workgroup had no left-over run
+    // a run parks its first part in slot 2q and a later (necessarily last) part in 2q+1
+    const float* part = partial + (size_t)(2 * q + (b0 >= lo ? 0 : 1)) * kTileFloats + in_tile +
+                        (size_t)((x * kNB + y) * 16) * 64;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] += part[r * 64];
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int64_t row = row_w + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+    if (row < d && col < d && row <= col) {
+      float* ph = Hk + row * d + col;
+      *ph = accumulate ? *ph + v[r] : v[r];
     }
   }
 }
@@ -397,31 +493,68 @@ int64_t tile_count(int64_t d, int gpc) {
 
 int64_t padded_tokens(int64_t n) { return (n + kStep - 1) / kStep * kStep + (int64_t)kStep * kMaxStages; }
 
+constexpr int kMaxWorkgroups = 256;   // one persistent workgroup per compute unit of an MI355X
+constexpr int kMinUnitsPerWorkgroup = 32;
+
+struct Plan {
+  int gpc, n_gsets;
+  int64_t n_pad, n_items, P;
+  size_t sp_bytes, partial_bytes;
+};
+Plan make_plan(int64_t n, int64_t d_in, int G) {
+  Plan pl;
+  pl.gpc = groups_per_workgroup(G);
+  pl.n_gsets = G / pl.gpc;
+  pl.n_pad = padded_tokens(n);
+  const int64_t steps = (n + kStep - 1) / kStep;
+  pl.n_items = tile_count(d_in, pl.gpc) * pl.n_gsets;
+  int64_t P = pl.n_items * steps / kMinUnitsPerWorkgroup;
+  if (P < 1) P = 1;
+  if (P > kMaxWorkgroups) P = kMaxWorkgroups;
+  pl.P = P;
+  pl.sp_bytes = ((size_t)(pl.n_pad * G) * sizeof(float) + 255) / 256 * 256;
+  pl.partial_bytes = (size_t)(2 * P) * kTileFloats * sizeof(float);
+  return pl;
+}
+
 }  // namespace
 
-size_t fisher_gram_bf16_workspace(int64_t n, int64_t, int G) {
-  return (size_t)(padded_tokens(n) * G) * sizeof(float);
+size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
+  if (n <= 0) return 0;
+  const Plan pl = make_plan(n, d_in, G);
+  return pl.sp_bytes + pl.partial_bytes;
 }
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                    float* H, bool accumulate, void* ws, size_t, hipStream_t st) {
-  const int64_t n_pad = padded_tokens(n);
+  const Plan pl = make_plan(n, d_in, G);
   float* sp = (float*)ws;
-  pack_weights_kernel<<<dim3((unsigned)((n_pad + 255) / 256)), dim3(256), 0, st>>>(s, n, G, n_pad, sp);
+  float* partial = (float*)((char*)ws + pl.sp_bytes);
+  pack_weights_kernel<<<dim3((unsigned)((pl.n_pad + 255) / 256)), dim3(256), 0, st>>>(s, n, G, pl.n_pad, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int gpc = groups_per_workgroup(G);
-  const int n_gsets = G / gpc;
-  const dim3 grid((unsigned)(tile_count(d_in, gpc) * n_gsets));
+  const int64_t left_over = pl.n_items % pl.P;
+  const dim3 grid((unsigned)pl.P), fix((unsigned)left_over, (unsigned)(kMA * kNB));
   const __bf16* Xb = (const __bf16*)X;
   const int acc = accumulate ? 1 : 0;
-  if (gpc == 4)
-    fisher_gram_bf16_kernel<4><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc, n_gsets);
-  else if (gpc == 2)
-    fisher_gram_bf16_kernel<2><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc, n_gsets);
-  else
-    fisher_gram_bf16_kernel<1><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, n_pad, H, acc, n_gsets);
-  return hipGetLastError();
+#define GQ_LAUNCH_GRAM(GPC)                                                                                     \
+  fisher_gram_bf16_kernel<GPC><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc, pl.n_gsets,  \
+                                                           pl.n_items, partial);                                 \
+  e = hipGetLastError();                                                                                        \
+  if (e == hipSuccess && left_over > 0) {                                                                            \
+    fisher_gram_fixup_kernel<GPC><<<fix, dim3(256), 0, st>>>(n, d_in, H, acc, pl.n_gsets, pl.n_items, pl.P,      \
+                                                             partial);                                         \
+    e = hipGetLastError();                                                                                      \
+  }
+  if (pl.gpc == 4) {
+    GQ_LAUNCH_GRAM(4)
+  } else if (pl.gpc == 2) {
+    GQ_LAUNCH_GRAM(2)
+  } else {
+    GQ_LAUNCH_GRAM(1)
+  }
+#undef GQ_LAUNCH_GRAM
+  return e;
 }
 
 }  // namespace gq

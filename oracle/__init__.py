@@ -12,4 +12,5 @@ from .gq_oracle import (  # noqa: F401
     per_channel_hessian,
     unaveraged_objective,
     objective_from_tokens,
+    objective_rows_from_tokens,
 )

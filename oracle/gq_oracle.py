@@ -168,3 +168,15 @@ def objective_from_tokens(X, s_k, delta_j) -> float:
         t = float(np.dot(X[i], delta_j))
         total += s_k[i] * t * t
     return total
+
+
+def objective_rows_from_tokens(X, s_k, delta_rows) -> np.ndarray:
+    """sum_i s_k[i] * (x_i . delta_j)^2 for several channels j at once (rows of
+    `delta_rows`), i.e. `objective_from_tokens` with the token loop written as
+    one matrix product.  Used to sample the objective at sizes where Hbar_k is
+    too large to form on the host."""
+    X = np.asarray(X, dtype=_F64)
+    s_k = np.asarray(s_k, dtype=_F64)
+    D = np.asarray(delta_rows, dtype=_F64)
+    T = X @ D.T                      # [n, rows]: x_i . delta_j
+    return (s_k[:, None] * T * T).sum(axis=0)

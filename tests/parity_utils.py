@@ -23,3 +23,101 @@ def upper(a: np.ndarray) -> np.ndarray:
 
 def say(msg: str) -> None:
     print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ sampled oracle for full-size shapes
+def _host_cols(X: torch.Tensor, idx) -> np.ndarray:
+    """Columns idx of a (GPU) matrix as fp64 on the host (exact for bf16/fp32 values)."""
+    return X[:, torch.as_tensor(idx, device=X.device)].to(torch.float64).cpu().numpy()
+
+
+def sampled_gram_check(oracle, X, s, H, tol, n_random=24, block=128, n_probe=4, seed=0, what=""):
+    """Compare a (mirrored, full-square) GPU result H[G,d,d] with the fp64 oracle on
+    (i) blocks of `block` x `block` entries: random ones, a run along the diagonal, the last
+    block row/column and the blocks holding the largest-norm (outlier) columns, and
+    (ii) probe vectors: H[k] v against X^T (s_k * (X v)), evaluated chunk-wise in fp64 on the host.
+    Returns (rel-Frobenius over the sampled entries, max probe rel error, entries compared)."""
+    rng = np.random.default_rng(seed)
+    n, d = X.shape
+    G = s.shape[1]
+    nb = (d + block - 1) // block
+    s64 = s.to(torch.float64).cpu().numpy()
+    col_norm = X.to(torch.float32).pow(2).sum(0)
+    hot = int(torch.argmax(col_norm).item()) // block
+    pairs = {(nb - 1, nb - 1), (0, nb - 1), (0, 0), (hot, hot), (min(hot, nb - 1), nb - 1), (0, hot)}
+    for t in range(min(3, nb)):
+        b = int(rng.integers(0, nb))
+        pairs.add((b, b))
+        if b + 1 < nb:
+            pairs.add((b, b + 1))
+    while len(pairs) < n_random + 8 and len(pairs) < nb * (nb + 1) // 2:
+        a, b = sorted(int(v) for v in rng.integers(0, nb, size=2))
+        pairs.add((a, b))
+    worst, entries = 0.0, 0
+    num, den = np.zeros(G), np.zeros(G)
+    for (bi, bj) in sorted(pairs):
+        rows = np.arange(bi * block, min(d, (bi + 1) * block))
+        cols = np.arange(bj * block, min(d, (bj + 1) * block))
+        Xs = np.concatenate([_host_cols(X, rows), _host_cols(X, cols)], axis=1)
+        for k in range(G):
+            ref = oracle.fisher_gram_block(Xs, s64[:, k], slice(0, len(rows)), slice(len(rows), len(rows) + len(cols)))
+            got = H[k][bi * block:bi * block + len(rows), bj * block:bj * block + len(cols)].to(torch.float64).cpu().numpy()
+            err = rel_fro(got, ref)
+            worst = max(worst, err)
+            num[k] += float(np.sum((got - ref) ** 2))
+            den[k] += float(np.sum(ref ** 2))
+            entries += ref.size
+            # the mirrored entry must be the same number
+            if bi != bj:
+                low = H[k][bj * block:bj * block + len(cols), bi * block:bi * block + len(rows)].to(torch.float64).cpu().numpy()
+                assert np.array_equal(low, got.T)
+    # probe vectors
+    V = rng.standard_normal((d, n_probe))
+    V[hot * block:min(d, (hot + 1) * block), 0] += 1.0
+    Y = np.zeros((G, d, n_probe))
+    chunk = 4096
+    for r0 in range(0, n, chunk):
+        Xc = X[r0:r0 + chunk].to(torch.float64).cpu().numpy()
+        T = Xc @ V
+        for k in range(G):
+            Y[k] += Xc.T @ (s64[r0:r0 + chunk, k][:, None] * T)
+    Vg = torch.as_tensor(V, device=H.device)
+    worst_probe = 0.0
+    for k in range(G):
+        got = (H[k].to(torch.float64) @ Vg).cpu().numpy()
+        worst_probe = max(worst_probe, rel_fro(got, Y[k]))
+    pooled = float(np.max(np.sqrt(num / den)))     # rel-Frobenius over all sampled entries of a group (max over groups)
+    say(f"{what}: sampled H check: {len(pairs)} blocks x {G} groups ({entries} entries): rel-Frobenius over the "
+        f"sampled entries {pooled:.2e} (worst single block {worst:.2e}); {n_probe} probe vectors worst "
+        f"{worst_probe:.2e} (tol {tol:g})")
+    # the verdict is the relative Frobenius error over what was sampled (per group) and the
+    # whole-matrix probes; a single small-norm off-diagonal block may sit a little above it,
+    # but a localized indexing mistake would put it near 1
+    assert pooled <= tol and worst_probe <= tol and worst <= 5 * tol
+    return pooled, worst_probe, entries
+
+
+def sampled_objective_check(oracle, X, s, W, What, obj, obj_row, G, tol, rows_per_group=32, seed=0, what=""):
+    """obj_row[j] for sampled channels against sum_i s_k[i] (x_i . delta_j)^2 computed from X in
+    fp64 on the host, and obj[k] against the fp64 sum of the GPU's own obj_row."""
+    rng = np.random.default_rng(seed)
+    n, d = X.shape
+    d_out = W.shape[0]
+    m = d_out // G
+    s64 = s.to(torch.float64).cpu().numpy()
+    rows = np.concatenate([k * m + np.sort(rng.choice(m, size=min(rows_per_group, m), replace=False)) for k in range(G)])
+    D = (W[torch.as_tensor(rows, device=W.device)].to(torch.float64) - What[torch.as_tensor(rows, device=W.device)].to(torch.float64)).cpu().numpy()
+    ref = np.zeros(len(rows))
+    chunk = 4096
+    for r0 in range(0, n, chunk):
+        Xc = X[r0:r0 + chunk].to(torch.float64).cpu().numpy()
+        for k in range(G):
+            sel = (rows // m) == k
+            ref[sel] += oracle.objective_rows_from_tokens(Xc, s64[r0:r0 + chunk, k], D[sel])
+    got = obj_row.to(torch.float64).cpu().numpy()
+    e_rows = rel_fro(got[rows], ref)
+    sums = got.reshape(G, m).sum(1)
+    e_sum = float(np.max(np.abs(obj.cpu().numpy() - sums) / sums))
+    say(f"{what}: objective on {len(rows)} sampled channels rel-Frobenius {e_rows:.2e}; obj vs sum of rows {e_sum:.2e} (tol {tol:g})")
+    assert e_rows <= tol and e_sum <= 1e-6
+    return e_rows

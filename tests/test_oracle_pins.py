@@ -189,3 +189,15 @@ def test_objective_zero_nonneg_single_perturbation_and_group_routing():
     assert obj[0] == 0 and obj[2] == 0 and row[j] == obj[1]
     objr, _ = oracle.objective(W, r.standard_normal((d_out, d_in)), H, G)
     assert np.all(objr > 0)
+
+
+def test_objective_rows_from_tokens_matches_the_token_loop_and_the_hessian_form():
+    r = _rng(15)
+    n, d_in = 33, 5
+    X, s_k = r.standard_normal((n, d_in)), r.random(n)
+    D = r.standard_normal((4, d_in))
+    got = oracle.objective_rows_from_tokens(X, s_k, D)
+    H = oracle.fisher_gram(X, s_k[:, None])[0]
+    for j in range(4):
+        assert abs(got[j] - oracle.objective_from_tokens(X, s_k, D[j])) <= 1e-12 * got[j]
+        assert abs(got[j] - D[j] @ H @ D[j]) <= 1e-11 * got[j]

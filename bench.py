@@ -36,6 +36,18 @@ def gram_flops(G, n, d_in):
     return float(G) * n * d_in * (d_in + 1)
 
 
+def load_traffic(workload):
+    """HBM bytes per Gram launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs of
+    this script, scaled by a plain copy of known size); the committed summary under profiles/
+    holds the figures and the commands.  None when no measurement is on file."""
+    path = os.path.join(ROOT, "profiles", f"fisher_gram_bf16_{workload}.traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)["hbm_bytes_per_launch"]
+    except Exception:
+        return None
+
+
 def cpu_baseline(spec, X, dZ, W, What, sample_tokens):
     """Time the oracle (numpy fp64, as it stands) on the first `sample_tokens` tokens."""
     import numpy as np
@@ -68,7 +80,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama2_7b_attn")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override n (debugging only; invalid as a result)")
     args = ap.parse_args()
@@ -121,6 +135,13 @@ def main():
             ev[4].record()
         return obj
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -153,7 +174,7 @@ def main():
         "ms_per_call": per_kernel,
         "group_weights_GBps": dz_gbs,
         "roofline": {"bound": "mfma", "kernel": "fisher_gram_bf16", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": load_traffic(spec.name),
                      "flop_per_launch": fl, "ms_per_launch": gram_ms},
     }
 

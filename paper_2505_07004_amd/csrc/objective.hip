@@ -1,40 +1,120 @@
 // GuidedQuant layer objective (Eq. "ours2", Section 3.2):
 //   obj_row[j] = delta_j^T H[k(j)] delta_j,  delta_j = W[j,:] - What[j,:],  obj[k] = sum_{j in J_k} obj_row[j].
 //
-// Only the upper triangle of H is read:  delta^T H delta = sum_{a<=b in tile terms} ... =
-//   2 * sum_{tiles ta < tb} delta_a^T H[ta,tb] delta_b + sum_{tb} delta_b^T H[tb,tb] delta_b,
-// where the diagonal tile is completed to a full symmetric tile while it is staged.
-// A workgroup owns 128 channels (rows j) x one 128-wide column tile tb of one group and
-// contracts over all tiles ta <= tb on the fp32 matrix cores (v_mfma_f32_32x32x2_f32):
-//   Y[j,b] = 2 * sum_{a in tiles < tb} delta[j,a] H[a,b] + sum_{a in tile tb} delta[j,a] Hsym[a,b]
-// then partial[tb][j] = sum_b Y[j,b] * delta[j,b].  A second kernel adds the partials of a
-// row in fixed order (fp32 obj_row) and the rows of a group in fp64 (obj): deterministic.
+// The contraction Y = Delta_k H_k (2 d_out d_in^2 flop) runs on the bf16 matrix cores at
+// fp32-grade accuracy by splitting both operands into two bf16 terms, x = hi + lo with
+// hi = bf16(x), lo = bf16(x - hi) (together 16 mantissa bits), and summing the three products
+// hi*hi + hi*lo + lo*hi in fp32 accumulators (the dropped lo*lo term is below 2^-16 relative).
+// Only the upper triangle of H is read.  In tile terms
+//   delta^T H delta = 2 * sum_{ta < tb} delta_a^T H[ta,tb] delta_b + sum_tb delta_b^T H[tb,tb] delta_b,
+// so a workgroup that owns 128 channels (rows j) and one 128-wide column tile tb contracts only
+// over a < (tb+1)*128, doubles its accumulators before the diagonal tile, and finishes with
+// partial[tb][j] = sum_b Y[j,b] * delta[j,b] in fp32.
+//
+// Kernels: (1) split delta into hi/lo bf16 [d_out, d_in]; (2) split H into hi/lo bf16 written
+// TRANSPOSED (Hs[k][b][a] = H[k][a][b] for a <= b, the diagonal 128-tiles completed to full
+// squares), which makes both MFMA operands contiguous along the contraction index a;
+// (3) the MFMA kernel; (4) a reduction that adds the partials of a row in fixed order (fp32
+// obj_row) and the rows of a group in fp64 (obj).  Everything is deterministic.
 #include "gq_internal.hpp"
 
 namespace gq {
 namespace {
 
-constexpr int kTile = 128;
-constexpr int kStep = 16;
-constexpr int kDPitch = kStep + 1;    // delta tile [128 rows j][16 a], odd pitch: column reads hit distinct banks
-constexpr int kHPitch = kTile + 32;   // H tile [16 a][128 b]
+constexpr int kTile = 128;            // rows j and columns b per workgroup
+constexpr int kKS = 64;               // contraction elements per LDS stage
+constexpr int kPitch = kKS * 2 + 16;  // LDS bytes per tile row: 9 sixteen-byte granules, odd => conflict-free b128 reads
+constexpr int kTileBytes = kTile * kPitch;
 
-__global__ __launch_bounds__(256) void objective_partial_kernel(const float* __restrict__ W,
-                                                                const float* __restrict__ What, int64_t d_out,
-                                                                int64_t d, int64_t ld, const float* __restrict__ H,
-                                                                int G, int n_tb, int n_rb, float* __restrict__ partial) {
-  __shared__ float Ds[2][kTile][kDPitch];
-  __shared__ __attribute__((aligned(16))) float Hs[2][kStep][kHPitch];
+__device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
+  const __bf16 h = (__bf16)x;
+  const __bf16 l = (__bf16)(x - (float)h);
+  hi = __builtin_bit_cast(unsigned short, h);
+  lo = __builtin_bit_cast(unsigned short, l);
+}
+
+// Dh/Dl[j, a] = hi/lo of W[j,a] - What[j,a]; row pitch ldp (multiple of kKS, zero padded).
+__global__ __launch_bounds__(256) void split_delta_kernel(const float* __restrict__ W, const float* __restrict__ What,
+                                                          int64_t d_out, int64_t d, int64_t ld, int64_t ldp,
+                                                          unsigned short* __restrict__ Dh,
+                                                          unsigned short* __restrict__ Dl) {
+  const int64_t j = blockIdx.y;
+  for (int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x; a < ldp; a += (int64_t)gridDim.x * 256) {
+    const float v = a < d ? W[j * ld + a] - What[j * ld + a] : 0.f;
+    unsigned short h, l;
+    split_bf16(v, h, l);
+    Dh[j * ldp + a] = h;
+    Dl[j * ldp + a] = l;
+  }
+}
+
+// Hh/Hl[k][b][a] = hi/lo of H[k][a][b] for a <= b; inside a diagonal 128-tile also [a][b].
+// One workgroup per 64x64 tile (ti <= tj) of the upper triangle, transposed through LDS.
+__global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ H, int64_t d, int64_t ldp,
+                                                      unsigned short* __restrict__ Hh,
+                                                      unsigned short* __restrict__ Hl) {
+  __shared__ float tile[64][65];
+  const int k = blockIdx.y;
+  const float* Hk = H + (int64_t)k * d * d;
+  unsigned short* Hhk = Hh + (int64_t)k * ldp * ldp;
+  unsigned short* Hlk = Hl + (int64_t)k * ldp * ldp;
+  int ti, tj;
+  tri_decode(blockIdx.x, ti, tj);
+  const int64_t r0 = (int64_t)ti * 64, c0 = (int64_t)tj * 64;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  for (int r = ty; r < 64; r += 4) {
+    const int64_t a = r0 + r, b = c0 + tx;
+    tile[r][tx] = (a < d && b < d && a <= b) ? Hk[a * d + b] : 0.f;
+  }
+  __syncthreads();
+  const bool same128 = (ti / 2 == tj / 2);
+  for (int r = ty; r < 64; r += 4) {
+    // transposed position: row b = c0 + r, column a = r0 + tx
+    const int64_t b = c0 + r, a = r0 + tx;
+    if (a < ldp && b < ldp) {
+      float v = 0.f;
+      if (a <= b) v = tile[tx][r];
+      else if (ti == tj) v = tile[r][tx];          // below the diagonal inside a diagonal 64-tile: the mirror image
+      if (a <= b || ti == tj) {
+        unsigned short h, l;
+        split_bf16(v, h, l);
+        Hhk[b * ldp + a] = h;
+        Hlk[b * ldp + a] = l;
+      }
+    }
+    // the upper off-diagonal 64-tile of a diagonal 128-tile is needed as well (untransposed)
+    if (same128 && ti != tj) {
+      const int64_t a2 = r0 + r, b2 = c0 + tx;
+      if (a2 < ldp && b2 < ldp) {
+        unsigned short h, l;
+        split_bf16(tile[r][tx], h, l);
+        Hhk[a2 * ldp + b2] = h;
+        Hlk[a2 * ldp + b2] = l;
+      }
+    }
+  }
+}
+
+// Y tile [128 j][128 b] over a < (tb+1)*128 on bf16 MFMA with split operands, then the row dot.
+__global__ __launch_bounds__(256) void objective_mfma_kernel(const unsigned short* __restrict__ Dh,
+                                                             const unsigned short* __restrict__ Dl,
+                                                             const unsigned short* __restrict__ Hh,
+                                                             const unsigned short* __restrict__ Hl,
+                                                             const float* __restrict__ W, const float* __restrict__ What,
+                                                             int64_t d_out, int64_t d, int64_t ld, int64_t ldp, int G,
+                                                             int n_tb, float* __restrict__ partial) {
+  __shared__ __attribute__((aligned(16))) char smem[2][4][kTileBytes];   // stage x {Dh, Dl, Hh, Hl}
   __shared__ float red[2][kTile];
 
-  const int tb = n_tb - 1 - (int)(blockIdx.x % n_tb);  // heavy column tiles first
+  const int tb = n_tb - 1 - (int)(blockIdx.x % n_tb);   // heavy column tiles first
   const int rb = (int)(blockIdx.x / n_tb);
   const int k = blockIdx.y;
   const int64_t m = d_out / G;
   const int64_t j0 = (int64_t)k * m + (int64_t)rb * kTile;  // first channel of this block
   const int64_t j_end = (int64_t)(k + 1) * m;               // rows >= j_end belong to another group
   const int64_t b0 = (int64_t)tb * kTile;
-  const float* Hk = H + (int64_t)k * d * d;
+  const unsigned short* Hhk = Hh + (int64_t)k * ldp * ldp;
+  const unsigned short* Hlk = Hl + (int64_t)k * ldp * ldp;
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave, wave = tid / kWave;
@@ -48,96 +128,80 @@ __global__ __launch_bounds__(256) void objective_partial_kernel(const float* __r
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // staging assignment.  delta: 128 rows x 16 a = 512 float4 -> 2 per thread (row = q/4, a4 = q%4).
-  // H: 16 a x 128 b = 512 float4 -> 2 per thread (row = q/32, b4 = q%32).
-  f32x4 rd[2], rh[2];
-  auto fetch = [&](int ta, int kk) {  // kk: a-offset inside tile ta
-    const int64_t abase = (int64_t)ta * kTile + kk;
+  // staging: every tile is 128 rows x 8 chunks of 16 B; thread -> (row q/8, chunk q%8), q = tid + 256 h
+  u32x4 rg[4][4];
+  auto fetch = [&](int64_t a0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < 4; ++h) {
       const int q = tid + 256 * h;
-      {  // delta
-        const int64_t j = j0 + q / 4;
-        const int64_t a = abase + 4 * (q % 4);
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (j < j_end) {
-          const float* pw = W + j * ld + a;
-          const float* ph = What + j * ld + a;
-          if (a + 4 <= d) {
-            f32x4 w4 = *reinterpret_cast<const f32x4*>(pw);
-            f32x4 h4 = *reinterpret_cast<const f32x4*>(ph);
-            v = w4 - h4;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (a + e < d) v[e] = pw[e] - ph[e];
-          }
-        }
-        rd[h] = v;
-      }
-      {  // H rows a, columns b0.. ; on the diagonal tile entries below the diagonal come from the transpose
-        const int64_t a = abase + q / 32;
-        const int64_t b = b0 + 4 * (q % 32);
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (a < d) {
-          if (ta != tb && b + 4 <= d && (d & 3) == 0) {
-            v = *reinterpret_cast<const f32x4*>(Hk + a * d + b);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int64_t bb = b + e;
-              if (bb < d) v[e] = (a <= bb) ? Hk[a * d + bb] : Hk[bb * d + a];
-            }
-          }
-        }
-        rh[h] = v;
-      }
+      const int r = q / 8, c = q % 8;
+      const int64_t a = a0 + 8 * c;                       // a0 + 64 <= ldp always (ldp is padded)
+      int64_t j = j0 + r;
+      j = j < d_out ? j : d_out - 1;                      // rows past the group are masked at the end
+      int64_t b = b0 + r;
+      b = b < ldp ? b : ldp - 1;
+      rg[0][h] = *reinterpret_cast<const u32x4*>(Dh + j * ldp + a);
+      rg[1][h] = *reinterpret_cast<const u32x4*>(Dl + j * ldp + a);
+      rg[2][h] = *reinterpret_cast<const u32x4*>(Hhk + b * ldp + a);
+      rg[3][h] = *reinterpret_cast<const u32x4*>(Hlk + b * ldp + a);
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int q = tid + 256 * h;
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) Ds[buf][q / 4][4 * (q % 4) + e] = rd[h][e];
-      *reinterpret_cast<f32x4*>(&Hs[buf][q / 32][4 * (q % 32)]) = rh[h];
-    }
+      for (int h = 0; h < 4; ++h) {
+        const int q = tid + 256 * h;
+        *reinterpret_cast<u32x4*>(&smem[buf][t][(q / 8) * kPitch + (q % 8) * 16]) = rg[t][h];
+      }
+  };
+  auto frag = [&](int buf, int t, int row0, int ks) -> bf16x8 {   // rows row0 + lane%32, k = 16 ks + 8 (lane/32) ..
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[buf][t][(row0 + lane % 32) * kPitch + (2 * ks + lane / 32) * 16]);
+    return __builtin_bit_cast(bf16x8, v);
   };
 
-  constexpr int kSub = kTile / kStep;  // 8 stages per a-tile
-  const int total = (tb + 1) * kSub;
-  fetch(0, 0);
+  const int64_t stages = (int64_t)(tb + 1) * (kTile / kKS);
+  const int64_t first_diag = (int64_t)tb * (kTile / kKS);
+  fetch(0);
   stash(0);
   __syncthreads();
-  for (int it = 0; it < total; ++it) {
-    const int buf = it & 1;
-    const int ta = it / kSub;
-    if (it + 1 < total) fetch((it + 1) / kSub, ((it + 1) % kSub) * kStep);
-#pragma unroll
-    for (int kk = 0; kk < kStep; kk += 2) {
-      float av[2], bv[2];
-#pragma unroll
-      for (int x = 0; x < 2; ++x) av[x] = Ds[buf][wm * 64 + x * 32 + lane % 32][kk + lane / 32];
-#pragma unroll
-      for (int y = 0; y < 2; ++y) bv[y] = Hs[buf][kk + lane / 32][wn * 64 + y * 32 + lane % 32];
-#pragma unroll
-      for (int x = 0; x < 2; ++x)
-#pragma unroll
-        for (int y = 0; y < 2; ++y)
-          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
-    }
-    // all strictly-upper tiles are done: they count twice (their mirror images are never visited)
-    if (ta < tb && (it + 1) / kSub == tb) {
+  for (int64_t it = 0; it < stages; ++it) {
+    const int buf = (int)(it & 1);
+    if (it + 1 < stages) fetch((it + 1) * kKS);
+    if (it == first_diag && tb > 0) {
+      // all strictly-upper tiles are done: they count twice (their mirror images are never visited)
 #pragma unroll
       for (int x = 0; x < 2; ++x)
 #pragma unroll
         for (int y = 0; y < 2; ++y) acc[x][y] *= 2.f;
     }
-    if (it + 1 < total) stash(buf ^ 1);
+#pragma unroll
+    for (int ks = 0; ks < kKS / 16; ++ks) {
+      bf16x8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        ah[x] = frag(buf, 0, wm * 64 + x * 32, ks);
+        al[x] = frag(buf, 1, wm * 64 + x * 32, ks);
+      }
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        bh[y] = frag(buf, 2, wn * 64 + y * 32, ks);
+        bl[y] = frag(buf, 3, wn * 64 + y * 32, ks);
+      }
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y) {
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[x], bh[y], acc[x][y], 0, 0, 0);
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[x], bl[y], acc[x][y], 0, 0, 0);
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[x], bh[y], acc[x][y], 0, 0, 0);
+        }
+    }
+    if (it + 1 < stages) stash(buf ^ 1);
     __syncthreads();
   }
 
-  // row dot with delta[j, b]: register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32
+  // row dot with delta[j, b] (fp32): register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32
   float rowsum[2][16];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
@@ -192,24 +256,59 @@ __global__ __launch_bounds__(256) void objective_reduce_kernel(const float* __re
   if (threadIdx.x == 0) obj[k] = red[0];
 }
 
+struct Layout {
+  int64_t ldp, n_tb;
+  size_t partial_bytes, delta_bytes, h_bytes;   // delta_bytes / h_bytes: one of the hi/lo arrays
+};
+Layout make_layout(int64_t d_out, int64_t d_in, int G) {
+  Layout L;
+  L.n_tb = (d_in + kTile - 1) / kTile;
+  L.ldp = L.n_tb * kTile;                       // padded so that every 128 x 64 operand tile is in range
+  L.partial_bytes = ((size_t)(L.n_tb * d_out) * sizeof(float) + 255) / 256 * 256;
+  L.delta_bytes = ((size_t)(d_out * L.ldp) * 2 + 255) / 256 * 256;
+  L.h_bytes = ((size_t)((int64_t)G * L.ldp * L.ldp) * 2 + 255) / 256 * 256;
+  return L;
+}
+
 }  // namespace
 
 size_t objective_workspace(int64_t d_out, int64_t d_in, int G) {
-  (void)G;
-  const int64_t n_tb = (d_in + kTile - 1) / kTile;
-  return (size_t)(n_tb * d_out) * sizeof(float);
+  const Layout L = make_layout(d_out, d_in, G);
+  return L.partial_bytes + 2 * L.delta_bytes + 2 * L.h_bytes;
 }
 
 hipError_t launch_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld,
                             const float* H, int G, double* obj, float* obj_row, void* ws, hipStream_t st) {
+  const Layout L = make_layout(d_out, d_in, G);
+  char* p = (char*)ws;
+  float* partial = (float*)p;
+  p += L.partial_bytes;
+  unsigned short* Dh = (unsigned short*)p;
+  p += L.delta_bytes;
+  unsigned short* Dl = (unsigned short*)p;
+  p += L.delta_bytes;
+  unsigned short* Hh = (unsigned short*)p;
+  p += L.h_bytes;
+  unsigned short* Hl = (unsigned short*)p;
+
   const int64_t m = d_out / G;
-  const int n_tb = (int)((d_in + kTile - 1) / kTile);
+  const int n_tb = (int)L.n_tb;
   const int n_rb = (int)((m + kTile - 1) / kTile);
-  float* partial = (float*)ws;
-  objective_partial_kernel<<<dim3((unsigned)(n_tb * n_rb), (unsigned)G), dim3(256), 0, st>>>(
-      W, What, d_out, d_in, ld, H, G, n_tb, n_rb, partial);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e;
+  {
+    int64_t bx = (L.ldp + 255) / 256;
+    if (bx > 64) bx = 64;
+    split_delta_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(W, What, d_out, d_in, ld, L.ldp, Dh, Dl);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
+    const int64_t T = L.ldp / 64;
+    split_h_kernel<<<dim3((unsigned)tri_count(T), (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hh, Hl);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  objective_mfma_kernel<<<dim3((unsigned)(n_tb * n_rb), (unsigned)G), dim3(256), 0, st>>>(
+      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_tb, partial);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   objective_reduce_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, n_tb, obj_row, obj);
   return hipGetLastError();
 }

@@ -48,6 +48,21 @@ def load_traffic(workload):
         return None
 
 
+def mfma_ceiling():
+    """What a loop of nothing but bf16 MFMAs sustains on this GPU (constant and random operands),
+    measured by the small stand-alone program built next to the library, as a child process."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2505_07004_amd", "mfma_ceiling")
+    if not os.path.exists(exe):
+        return None
+    try:
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        return json.loads(out.stdout.strip().splitlines()[-1])
+    except Exception as e:
+        log("mfma_ceiling failed:", e)
+        return None
+
+
 def cpu_baseline(spec, X, dZ, W, What, sample_tokens):
     """Time the oracle (numpy fp64, as it stands) on the first `sample_tokens` tokens."""
     import numpy as np
@@ -82,8 +97,9 @@ def main():
     ap.add_argument("--workload", default="llama2_7b_attn")
     ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+                    help="also run one plain 1 GiB elementwise copy kernel (reference point for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the pure-MFMA ceiling measurement")
     ap.add_argument("--tokens", type=int, default=0, help="override n (debugging only; invalid as a result)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -138,7 +154,7 @@ def main():
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
-        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.mul(src, 1.0, out=dst)        # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
 
@@ -177,6 +193,12 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": load_traffic(spec.name),
                      "flop_per_launch": fl, "ms_per_launch": gram_ms},
     }
+
+    if not args.no_ceiling:
+        ceil = mfma_ceiling()
+        if ceil:
+            result["mfma_ceiling"] = ceil
+            result["roofline"]["frac_of_measured_ceiling"] = achieved / ceil["random_operands_tflops"]
 
     if not args.no_cpu_baseline:
         import numpy as np

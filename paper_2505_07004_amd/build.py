@@ -13,6 +13,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libgq.so")
+CEILING_PATH = os.path.join(PKG_DIR, "mfma_ceiling")
 
 SOURCES = [
     "gq_api.hip",
@@ -69,6 +70,10 @@ def build(verbose: bool = False, save_temps: bool = False) -> str:
             if verbose and out.strip():
                 print(out)
     out = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs)
+    if verbose and out.strip():
+        print(out)
+    # stand-alone measurement of the bf16 MFMA ceiling (run by bench.py as a child process)
+    out = _run([hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, "mfma_ceiling.hip"), "-o", CEILING_PATH])
     if verbose and out.strip():
         print(out)
     return LIB_PATH

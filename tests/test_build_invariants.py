@@ -1,0 +1,34 @@
+"""Static checks on the generated gfx950 code of the bf16 Gram kernel (CPU only: hipcc
+cross-compiles).  The hot loop is written in an exact issue order around its 32 MFMAs per
+32-token stage; it must not have been duplicated or peeled by the compiler, and no register
+spill (scratch access) may sit inside it."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2505_07004_amd", "csrc")
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="needs hipcc")
+def test_hot_loop_of_the_gram_kernel_is_compact_and_spill_free():
+    from paper_2505_07004_amd import build as b
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    cmd = [hipcc] + b.HIPCC_FLAGS + ["-I", b.INCLUDE, "-I", CSRC, "-S", "--cuda-device-only",
+                                      os.path.join(CSRC, "fisher_gram_bf16.hip"), "-o", "-"]
+    asm = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, check=True).stdout
+    kernels = re.findall(r"^(_ZN2gq\S*fisher_gram_bf16_kernel\S*):[^\n]*\n(.*?)s_endpgm", asm, flags=re.S | re.M)
+    assert len(kernels) == 3                      # one instantiation per groups-per-workgroup (4, 2, 1)
+    for name, body in kernels:
+        lines = body.splitlines()
+        mfma = [i for i, l in enumerate(lines) if "v_mfma_f32_32x32x16_bf16" in l]
+        # 2 sub-steps x 16 MFMAs, exactly once: the loop was neither unrolled further nor peeled
+        assert len(mfma) == 32, (name, len(mfma))
+        loop = lines[mfma[0]:mfma[-1] + 1]
+        assert not [l for l in loop if "scratch_" in l], f"{name}: register spill inside the hot loop"
+        # the direct loads of one stage and the single barrier per stage are in there too
+        assert sum("global_load_lds_dword" in l for l in loop) >= 5, name
+        assert sum("s_barrier" in l for l in lines[mfma[0] - 80:mfma[-1]]) == 1, name

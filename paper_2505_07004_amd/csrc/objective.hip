@@ -22,8 +22,10 @@ namespace gq {
 namespace {
 
 constexpr int kTile = 128;            // rows j and columns b per workgroup
-constexpr int kKS = 64;               // contraction elements per LDS stage
-constexpr int kPitch = kKS * 2 + 16;  // LDS bytes per tile row: 9 sixteen-byte granules, odd => conflict-free b128 reads
+constexpr int kKS = 32;               // contraction elements per LDS stage (2 stages x 4 tiles = 80 KiB: two workgroups per CU)
+constexpr int kPitch = kKS * 2 + 16;  // LDS bytes per tile row: an odd number (5) of 16-byte granules => conflict-free b128 reads
+constexpr int kChunks = kKS / 8;      // 16-byte chunks per tile row
+constexpr int kTileLoads = kTile * kChunks / 256;   // chunks per thread and tile
 constexpr int kTileBytes = kTile * kPitch;
 
 __device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ 
 }
 
 // Y tile [128 j][128 b] over a < (tb+1)*128 on bf16 MFMA with split operands, then the row dot.
-__global__ __launch_bounds__(256) void objective_mfma_kernel(const unsigned short* __restrict__ Dh,
+__global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned short* __restrict__ Dh,
                                                              const unsigned short* __restrict__ Dl,
                                                              const unsigned short* __restrict__ Hh,
                                                              const unsigned short* __restrict__ Hl,
@@ -104,7 +106,9 @@ __global__ __launch_bounds__(256) void objective_mfma_kernel(const unsigned shor
                                                              int64_t d_out, int64_t d, int64_t ld, int64_t ldp, int G,
                                                              int n_tb, float* __restrict__ partial) {
   __shared__ __attribute__((aligned(16))) char smem[2][4][kTileBytes];   // stage x {Dh, Dl, Hh, Hl}
-  __shared__ float red[2][kTile];
+  // the row-sum exchange at the end reuses the staging memory (all waves are past the last
+  // barrier of the main loop by then), which keeps the workgroup at exactly 80 KiB
+  float (*red)[kTile] = reinterpret_cast<float (*)[kTile]>(&smem[0][0][0]);
 
   const int tb = n_tb - 1 - (int)(blockIdx.x % n_tb);   // heavy column tiles first
   const int rb = (int)(blockIdx.x / n_tb);
@@ -128,14 +132,14 @@ __global__ __launch_bounds__(256) void objective_mfma_kernel(const unsigned shor
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // staging: every tile is 128 rows x 8 chunks of 16 B; thread -> (row q/8, chunk q%8), q = tid + 256 h
-  u32x4 rg[4][4];
+  // staging: every tile is 128 rows x kChunks chunks of 16 B; thread -> (row q/kChunks, chunk q%kChunks), q = tid + 256 h
+  u32x4 rg[4][kTileLoads];
   auto fetch = [&](int64_t a0) {
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
+    for (int h = 0; h < kTileLoads; ++h) {
       const int q = tid + 256 * h;
-      const int r = q / 8, c = q % 8;
-      const int64_t a = a0 + 8 * c;                       // a0 + 64 <= ldp always (ldp is padded)
+      const int r = q / kChunks, c = q % kChunks;
+      const int64_t a = a0 + 8 * c;                       // a0 + kKS <= ldp always (ldp is padded to 128)
       int64_t j = j0 + r;
       j = j < d_out ? j : d_out - 1;                      // rows past the group are masked at the end
       int64_t b = b0 + r;
@@ -150,9 +154,9 @@ __global__ __launch_bounds__(256) void objective_mfma_kernel(const unsigned shor
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int h = 0; h < 4; ++h) {
+      for (int h = 0; h < kTileLoads; ++h) {
         const int q = tid + 256 * h;
-        *reinterpret_cast<u32x4*>(&smem[buf][t][(q / 8) * kPitch + (q % 8) * 16]) = rg[t][h];
+        *reinterpret_cast<u32x4*>(&smem[buf][t][(q / kChunks) * kPitch + (q % kChunks) * 16]) = rg[t][h];
       }
   };
   auto frag = [&](int buf, int t, int row0, int ks) -> bf16x8 {   // rows row0 + lane%32, k = 16 ks + 8 (lane/32) ..

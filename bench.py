@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the pure-MFMA ceiling measurement")
     ap.add_argument("--tokens", type=int, default=0, help="override n (debugging only; invalid as a result)")
+    ap.add_argument("--groups", type=int, default=0, help="override G (the 13B sweep runs G in 1, 2, 4, 8)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); the path has no multi-GPU part")
@@ -116,6 +117,8 @@ def main():
     spec = wl.CONFIGS[args.workload]
     if args.tokens:
         spec = wl.scaled(spec, n=args.tokens)
+    if args.groups:
+        spec = wl.scaled(spec, G=args.groups)
     log(f"workload {spec.name}: X[{spec.n},{spec.d_in}] {spec.x_dtype}, dZ[{spec.n},{spec.d_out}] f32, G={spec.G}")
     t0 = time.perf_counter()
     X = wl.make_x(spec, dev)
@@ -125,6 +128,7 @@ def main():
     log(f"inputs generated on the GPU in {time.perf_counter() - t0:.1f} s")
 
     n, d_in, d_out, G = spec.n, spec.d_in, spec.d_out, spec.G
+    chunks = max(1, spec.chunks)
     s = torch.empty((n, G), dtype=torch.float32, device=dev)
     H = torch.empty((G, d_in, d_in), dtype=torch.float32, device=dev)
     ws_g = torch.empty(max(1, gq.gq_fisher_gram_workspace_bytes(X.dtype, n, d_in, G)), dtype=torch.uint8, device=dev)
@@ -140,7 +144,12 @@ def main():
         gq.gq_group_weights(dZ, G, out=s)
         if ev is not None:
             ev[1].record()
-        gq.gq_fisher_gram(X, s, H=H, workspace=ws_g)
+        if chunks == 1:
+            gq.gq_fisher_gram(X, s, H=H, workspace=ws_g)
+        else:                                   # streamed over token chunks: overwrite, then accumulate
+            c = n // chunks
+            for i in range(chunks):
+                gq.gq_fisher_gram(X[i * c:(i + 1) * c], s[i * c:(i + 1) * c], H=H, accumulate=i > 0, workspace=ws_g)
         if ev is not None:
             ev[2].record()
         gq.gq_fisher_mirror(H)
@@ -185,7 +194,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{spec.name}: X[{n},{d_in}] bf16, dZ[{n},{d_out}] f32, G={G}, "
                                f"W[{d_out},{d_in}] f32 with 3-bit per-row codebook What",
-                   "tokens": n, "d_in": d_in, "d_out": d_out, "G": G},
+                   "tokens": n, "d_in": d_in, "d_out": d_out, "G": G, "token_chunks": chunks},
         "pct_of_mfma_peak": 100.0 * achieved / PEAK_BF16_TFLOPS,
         "ms_per_call": per_kernel,
         "group_weights_GBps": dz_gbs,

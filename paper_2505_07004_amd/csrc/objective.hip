@@ -14,8 +14,8 @@
 // Kernels: (1) split delta into hi/lo bf16 [d_out, d_in]; (2) split H into hi/lo bf16 written
 // TRANSPOSED (Hs[k][b][a] = H[k][a][b] for a <= b, the diagonal 128-tiles completed to full
 // squares), which makes both MFMA operands contiguous along the contraction index a;
-// (3) the MFMA kernel; (4) a reduction that adds the partials of a row in fixed order (fp32
-// obj_row) and the rows of a group in fp64 (obj).  Everything is deterministic.
+// (3) the MFMA kernel; (4) a two-step reduction that adds the partials of a row in fixed order
+// (fp32 obj_row) and the rows of a group in fp64 (obj).  Everything is deterministic.
 #include "gq_internal.hpp"
 
 namespace gq {
@@ -104,15 +104,28 @@ __global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned s
                                                              const unsigned short* __restrict__ Hl,
                                                              const float* __restrict__ W, const float* __restrict__ What,
                                                              int64_t d_out, int64_t d, int64_t ld, int64_t ldp, int G,
-                                                             int n_tb, float* __restrict__ partial) {
+                                                             int n_tb, int n_rb, float* __restrict__ partial) {
   __shared__ __attribute__((aligned(16))) char smem[2][4][kTileBytes];   // stage x {Dh, Dl, Hh, Hl}
   // the row-sum exchange at the end reuses the staging memory (all waves are past the last
   // barrier of the main loop by then), which keeps the workgroup at exactly 80 KiB
   float (*red)[kTile] = reinterpret_cast<float (*)[kTile]>(&smem[0][0][0]);
 
-  const int tb = n_tb - 1 - (int)(blockIdx.x % n_tb);   // heavy column tiles first
-  const int rb = (int)(blockIdx.x / n_tb);
-  const int k = blockIdx.y;
+  // Work order: group, then column tile (heavy ones first), then row block, so that the row
+  // blocks that read the same H tiles run side by side; workgroup ids are dealt round-robin to
+  // the 8 XCDs (each with its own L2), so the id is first remapped to give every XCD one
+  // contiguous stretch of that order.
+  int k, tb, rb;
+  {
+    constexpr int kXcd = 8;
+    const int64_t total = gridDim.x, id = blockIdx.x;
+    const int64_t x = id % kXcd, idx = id / kXcd, q = total / kXcd, r = total % kXcd;
+    const int64_t logical = x * q + (x < r ? x : r) + idx;
+    const int64_t per_group = (int64_t)n_tb * n_rb;
+    k = (int)(logical / per_group);
+    const int64_t rem = logical - (int64_t)k * per_group;
+    tb = n_tb - 1 - (int)(rem / n_rb);
+    rb = (int)(rem % n_rb);
+  }
   const int64_t m = d_out / G;
   const int64_t j0 = (int64_t)k * m + (int64_t)rb * kTile;  // first channel of this block
   const int64_t j_end = (int64_t)(k + 1) * m;               // rows >= j_end belong to another group
@@ -236,20 +249,22 @@ __global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned s
   }
 }
 
-// obj_row[j] = sum_tb partial[tb][j] (fixed order); obj[k] = fp64 sum over the group's rows.
-__global__ __launch_bounds__(256) void objective_reduce_kernel(const float* __restrict__ partial, int64_t d_out,
-                                                               int G, int n_tb, float* __restrict__ obj_row,
-                                                               double* __restrict__ obj) {
+// obj_row[j] = sum_tb partial[tb][j] (fixed order) for 256 rows per workgroup, and the fp64 sum
+// of those rows (fixed tree) into block_sum[k][block].
+__global__ __launch_bounds__(256) void objective_rows_kernel(const float* __restrict__ partial, int64_t d_out, int G,
+                                                             int n_tb, float* __restrict__ obj_row,
+                                                             double* __restrict__ block_sum) {
   __shared__ double red[256];
-  const int k = blockIdx.x;
+  const int k = blockIdx.y;
   const int64_t m = d_out / G;
+  const int64_t jj = (int64_t)blockIdx.x * 256 + threadIdx.x;
   double acc = 0.0;
-  for (int64_t jj = threadIdx.x; jj < m; jj += 256) {
+  if (jj < m) {
     const int64_t j = (int64_t)k * m + jj;
     float v = 0.f;
     for (int tb = 0; tb < n_tb; ++tb) v += partial[(int64_t)tb * d_out + j];
     if (obj_row) obj_row[j] = v;
-    acc += (double)v;
+    acc = (double)v;
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -257,18 +272,30 @@ __global__ __launch_bounds__(256) void objective_reduce_kernel(const float* __re
     if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
-  if (threadIdx.x == 0) obj[k] = red[0];
+  if (threadIdx.x == 0) block_sum[(int64_t)k * gridDim.x + blockIdx.x] = red[0];
+}
+
+// obj[k] = sum of the group's block sums, in block order.
+__global__ void objective_groups_kernel(const double* __restrict__ block_sum, int n_blocks, double* __restrict__ obj) {
+  const int k = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  double acc = 0.0;
+  for (int b = 0; b < n_blocks; ++b) acc += block_sum[(int64_t)k * n_blocks + b];
+  obj[k] = acc;
 }
 
 struct Layout {
   int64_t ldp, n_tb;
-  size_t partial_bytes, delta_bytes, h_bytes;   // delta_bytes / h_bytes: one of the hi/lo arrays
+  int64_t n_blocks;                             // 256-row blocks per group in the final reduction
+  size_t partial_bytes, sums_bytes, delta_bytes, h_bytes;   // delta_bytes / h_bytes: one of the hi/lo arrays
 };
 Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   Layout L;
   L.n_tb = (d_in + kTile - 1) / kTile;
   L.ldp = L.n_tb * kTile;                       // padded so that every 128 x 64 operand tile is in range
   L.partial_bytes = ((size_t)(L.n_tb * d_out) * sizeof(float) + 255) / 256 * 256;
+  L.n_blocks = (d_out / G + 255) / 256;
+  L.sums_bytes = ((size_t)(L.n_blocks * G) * sizeof(double) + 255) / 256 * 256;
   L.delta_bytes = ((size_t)(d_out * L.ldp) * 2 + 255) / 256 * 256;
   L.h_bytes = ((size_t)((int64_t)G * L.ldp * L.ldp) * 2 + 255) / 256 * 256;
   return L;
@@ -278,7 +305,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
 
 size_t objective_workspace(int64_t d_out, int64_t d_in, int G) {
   const Layout L = make_layout(d_out, d_in, G);
-  return L.partial_bytes + 2 * L.delta_bytes + 2 * L.h_bytes;
+  return L.partial_bytes + L.sums_bytes + 2 * L.delta_bytes + 2 * L.h_bytes;
 }
 
 hipError_t launch_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld,
@@ -287,6 +314,8 @@ hipError_t launch_objective(const float* W, const float* What, int64_t d_out, in
   char* p = (char*)ws;
   float* partial = (float*)p;
   p += L.partial_bytes;
+  double* block_sum = (double*)p;
+  p += L.sums_bytes;
   unsigned short* Dh = (unsigned short*)p;
   p += L.delta_bytes;
   unsigned short* Dl = (unsigned short*)p;
@@ -310,10 +339,13 @@ hipError_t launch_objective(const float* W, const float* What, int64_t d_out, in
     split_h_kernel<<<dim3((unsigned)tri_count(T), (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hh, Hl);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  objective_mfma_kernel<<<dim3((unsigned)(n_tb * n_rb), (unsigned)G), dim3(256), 0, st>>>(
-      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_tb, partial);
+  objective_mfma_kernel<<<dim3((unsigned)((int64_t)n_tb * n_rb * G)), dim3(256), 0, st>>>(
+      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_tb, n_rb, partial);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  objective_reduce_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, n_tb, obj_row, obj);
+  objective_rows_kernel<<<dim3((unsigned)L.n_blocks, (unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, n_tb, obj_row,
+                                                                                       block_sum);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  objective_groups_kernel<<<dim3((unsigned)G), dim3(64), 0, st>>>(block_sum, (int)L.n_blocks, obj);
   return hipGetLastError();
 }
 

@@ -124,19 +124,18 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
 }
 
 // A work item is one tile (TM rows x 256 columns of the upper triangle) for one set of GPC
-// groups.  Items are ordered by tile column J, then tile row I, then group set, so that
-// neighbours in the list share the 256-column raw panel.
+// groups.  The group set is the fastest index (both sets of a tile read identical data), the
+// tiles follow the banded order of band_decode.
 struct Item {
   int64_t row_t, col_t;
   int gbase;
 };
 template <int GPC>
-__device__ inline Item decode_item(int64_t item, int n_gsets) {
+__device__ inline Item decode_item(int64_t item, int n_gsets, int64_t d) {
   const int gset = (int)(item % n_gsets);
   const int64_t t = item / n_gsets;
-  int dummy, J;
-  tri_decode(t / GPC, dummy, J);
-  const int I = (int)(t - (int64_t)GPC * tri_count(J));
+  int I, J;
+  band_decode(t, GPC, (d + kTN - 1) / kTN, I, J);
   Item it;
   it.row_t = (int64_t)I * (64 * (4 / GPC));
   it.col_t = (int64_t)J * kTN;
@@ -146,6 +145,11 @@ __device__ inline Item decode_item(int64_t item, int n_gsets) {
 
 // First unit of persistent workgroup p when `units` units are dealt evenly to P workgroups.
 __host__ __device__ inline int64_t first_unit(int64_t p, int64_t units, int64_t P) { return p * units / P; }
+
+// Word 3 of a gfx950 raw buffer resource (32-bit untyped data), and a byte offset that lies
+// outside every resource built here (each spans at most 64 rows of H).
+constexpr int kBufferWord3 = 0x00020000;
+constexpr unsigned kBufferOutside = 0x7ffffff0u;
 
 constexpr int kTileFloats = 4 * kMA * kNB * 16 * 64;   // accumulators of one workgroup tile (256 KiB)
 
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
       const int64_t len = (steps - k0) < (u_end - u) ? (steps - k0) : (u_end - u);
       k1 = k0 + len;
     }
-    const Item it = decode_item<GPC>(item, n_gsets);
+    const Item it = decode_item<GPC>(item, n_gsets, d);
     const int64_t row_t = it.row_t, col_t = it.col_t;
     const int gbase = it.gbase;
     const int64_t row_w = row_t + 64 * sub;      // first row of this wave's block
@@ -396,21 +400,42 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
 
     // ---- epilogue: register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32 ------
     if (k0 == 0 && k1 == steps) {
-      float* Hk = H + (int64_t)(gbase + g_local) * d * d;
+      // Straight-line code with every lane active: H is addressed through a buffer resource
+      // that spans exactly the valid rows of this wave's 64-row block, and a lane whose entry
+      // lies below the diagonal or right of column d gets an offset outside it (the hardware
+      // returns 0 for such a load and drops such a store).  No branch depends on the lane.
+      const int64_t rows_valid = (d - row_w) < 64 ? (d - row_w) : 64;
+      float* base = H + (int64_t)(gbase + g_local) * d * d + row_w * d;
+      const int records = rows_valid > 0 ? (int)(rows_valid * d * (int64_t)sizeof(float)) : 0;
+      const __amdgpu_buffer_rsrc_t hres = __builtin_amdgcn_make_buffer_rsrc(base, 0, records, kBufferWord3);
+      const int lrow = 4 * (lane / 32), lcol = lane % 32;
+      const int delta = lrow - lcol + (int)(row_w - col_t);        // row <= col  <=>  delta + c <= 32 y
+      const int cols_left = (int)(d - col_t) - lcol;               // col < d     <=>  32 y < cols_left
+      const unsigned off0 = (unsigned)(((int64_t)lrow * d + col_t + lcol) * (int64_t)sizeof(float));
+      const unsigned dbytes = (unsigned)(d * (int64_t)sizeof(float));
 #pragma unroll
       for (int y = 0; y < kNB; ++y) {
-        const int64_t col = col_t + 32 * y + lane % 32;
 #pragma unroll
         for (int x = 0; x < kMA; ++x) {
+          unsigned off[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int64_t row = row_w + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-            if (row < d && col < d && row <= col) {
-              float v = acc[x][y][r];
-              float* ph = Hk + row * d + col;
-              if (accumulate) v += *ph;
-              *ph = v;
-            }
+            const int c = 32 * x + 8 * (r / 4) + (r % 4);          // row inside the block, less lrow
+            const bool keep = (delta + c <= 32 * y) && (32 * y < cols_left);
+            off[r] = keep ? off0 + (unsigned)c * dbytes + (unsigned)(32 * y * (int)sizeof(float)) : kBufferOutside;
+          }
+          if (accumulate) {
+            float old[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              old[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(hres, off[r], 0, 0));
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[x][y][r] += old[r];
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float v = acc[x][y][r];   // a scalar copy: a bit cast applied to the vector element itself reads element 0
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), hres, off[r], 0, 0);
           }
         }
       }
@@ -449,7 +474,7 @@ __global__ __launch_bounds__(256) void fisher_gram_fixup_kernel(int64_t n, int64
   while (q0 > 0 && first_unit(q0, units, P) > lo) --q0;
   while (q0 + 1 < P && first_unit(q0 + 1, units, P) <= lo) ++q0;
   if (first_unit(q0, units, P) <= lo && first_unit(q0 + 1, units, P) >= hi) return;   // one run covers the item: already in H
-  const Item it = decode_item<GPC>(rounds * P + j, n_gsets);
+  const Item it = decode_item<GPC>(rounds * P + j, n_gsets, d);
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int g_local = wave % GPC, sub = wave / GPC;
   const int64_t row_w = it.row_t + 64 * sub;

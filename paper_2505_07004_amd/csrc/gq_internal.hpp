@@ -36,6 +36,43 @@ __host__ __device__ inline void tri_decode(int64_t t, int& i, int& j) {
   i = (int)(t - jj * (jj + 1) / 2);
 }
 
+// Order of the Gram kernel's tiles.  The upper triangle of a grid of NT tile columns (256 wide),
+// tile column J holding R(J) = rpt * (J + 1) row blocks, is walked in bands of kTileBand tile
+// columns; inside a band the row block is the slow index and the tile column the fast one, so a
+// run of consecutive tiles (the workgroups resident on one XCD take such a run and share its
+// panels through that XCD's L2) covers few distinct row blocks and few distinct tile columns.
+// Measured at d = 4096, G = 4: bands of 2 fetch 26 % fewer bytes into L2 than single columns,
+// bands of 4 fetch 70 % more.  Decodes t in [0, rpt * tri_count(NT)) into row block I and tile
+// column J; the row blocks of the last tile column come last, in increasing order, so a
+// truncated count drops exactly the row blocks past the end of a ragged matrix.
+constexpr int kTileBand = 2;
+__host__ __device__ inline void band_decode(int64_t t, int rpt, int64_t NT, int& I, int& J) {
+  int dummy, j_col;
+  tri_decode(t / rpt, dummy, j_col);                 // the tile column whose column-major range holds t
+  const int64_t J0 = (int64_t)(j_col / kTileBand) * kTileBand;
+  const int Kb = (int)((NT - J0) < kTileBand ? (NT - J0) : kTileBand);
+  int64_t off = t - (int64_t)rpt * tri_count(J0);
+  const int64_t R0 = (int64_t)rpt * (J0 + 1);        // row blocks that every tile column of the band has
+  if (off < R0 * Kb) {
+    I = (int)(off / Kb);
+    J = (int)(J0 + off % Kb);
+    return;
+  }
+  off -= R0 * Kb;
+  for (int jj = 1; jj < Kb; ++jj) {                  // the staircase under the band's diagonal tiles
+    const int w = Kb - jj;
+    const int64_t seg = (int64_t)rpt * w;
+    if (off < seg || jj == Kb - 1) {
+      I = (int)(R0 + (int64_t)rpt * (jj - 1) + off / w);
+      J = (int)(J0 + jj + off % w);
+      return;
+    }
+    off -= seg;
+  }
+  I = 0;                                             // not reached for t in range
+  J = (int)J0;
+}
+
 // ---- launchers (each validates nothing; the C ABI layer has done that) -----
 hipError_t launch_group_weights(const void* dZ, gq_dtype dt, int64_t n, int64_t d_out, int64_t ld,
                                 int G, float grad_scale, float* s, hipStream_t st);

@@ -1,7 +1,11 @@
 """Static checks on the generated gfx950 code of the bf16 Gram kernel (CPU only: hipcc
 cross-compiles).  The hot loop is written in an exact issue order around its 32 MFMAs per
 32-token stage; it must not have been duplicated or peeled by the compiler, and no register
-spill (scratch access) may sit inside it."""
+spill (scratch access) may sit inside it.  Outside the loop the kernel does spill, so it
+must never run with some lanes switched off: spill code that the compiler places inside a
+lane-masked region saves only the active lanes (this dropped accumulator lanes in an earlier
+form of the epilogue that branched per element); the kernel therefore masks H accesses
+through out-of-range buffer offsets and contains no write to EXEC at all."""
 import os
 import re
 import shutil
@@ -32,3 +36,10 @@ def test_hot_loop_of_the_gram_kernel_is_compact_and_spill_free():
         # the direct loads of one stage and the single barrier per stage are in there too
         assert sum("global_load_lds_dword" in l for l in loop) >= 5, name
         assert sum("s_barrier" in l for l in lines[mfma[0] - 80:mfma[-1]]) == 1, name
+        writes_exec = [l for l in lines if re.search(r"saveexec|\bs_\w+\s+exec(_lo|_hi)?\s*,", l)]
+        assert not writes_exec, (name, writes_exec[:3])
+    # the second-pass kernels do mask lanes with branches, so they must not spill at all
+    fixups = re.findall(r"^(_ZN2gq\S*fisher_gram_fixup_kernel\S*):[^\n]*\n(.*?)s_endpgm", asm, flags=re.S | re.M)
+    assert len(fixups) == 3
+    for name, body in fixups:
+        assert "scratch_" not in body, name

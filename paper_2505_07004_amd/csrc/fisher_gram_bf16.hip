@@ -49,25 +49,9 @@ __device__ inline int lds_chunk_off(int r, int c) {
 }
 
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
-typedef char __attribute__((address_space(3))) * lds_char_ptr;
-
 __device__ inline u32x2 lds_read_tr(const char* p) {
   bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p);
   return __builtin_bit_cast(u32x2, v);
-}
-
-// Direct global->LDS load: every active lane moves 16 bytes from its own global address to
-// LDS address lds_base + 16*lane (lds_base is wave-uniform and travels in M0).  Tracked by vmcnt.
-__device__ inline void dma16(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
-// Same with 4 bytes per lane (LDS address lds_base + 4*lane).
-__device__ inline void dma4(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
-template <int N>
-__device__ inline void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 // 8 bf16 (as 4 dwords) of tokens t..t+7 times their 8 fp32 weights, rounded to bf16 (RNE).

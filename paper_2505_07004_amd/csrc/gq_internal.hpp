@@ -22,6 +22,23 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kWave = 64;
 
+// ---- direct global->LDS loads (CDNA4) ---------------------------------------
+typedef char __attribute__((address_space(3))) * lds_char_ptr;
+
+// Direct global->LDS load: every active lane moves 16 bytes from its own global address to
+// LDS address lds_base + 16*lane (lds_base is wave-uniform and travels in M0).  Tracked by vmcnt.
+__device__ inline void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+// Same with 4 bytes per lane (LDS address lds_base + 4*lane).
+__device__ inline void dma4(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+template <int N>
+__device__ inline void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Number of tiles on or above the diagonal of a T x T tile grid.
 __host__ __device__ inline int64_t tri_count(int64_t T) { return T * (T + 1) / 2; }
 

@@ -7,9 +7,11 @@
 // hi*hi + hi*lo + lo*hi in fp32 accumulators (the dropped lo*lo term is below 2^-16 relative).
 // Only the upper triangle of H is read.  In tile terms
 //   delta^T H delta = 2 * sum_{ta < tb} delta_a^T H[ta,tb] delta_b + sum_tb delta_b^T H[tb,tb] delta_b,
-// so a workgroup that owns 128 channels (rows j) and one 128-wide column tile tb contracts only
-// over a < (tb+1)*128, doubles its accumulators before the diagonal tile, and finishes with
-// partial[tb][j] = sum_b Y[j,b] * delta[j,b] in fp32.
+// so a workgroup that owns 256 channels (rows j) and a pair of 128-wide column tiles
+// (tb = 2P, 2P+1) contracts over a < (2P+2)*128; the accumulators of a column tile are doubled
+// once the contraction reaches that tile's diagonal block (everything before it lies strictly
+// above the diagonal), the first tile of the pair reads zeros past its diagonal block, and the
+// workgroup finishes with partial[P][j] = sum_b Y[j,b] * delta[j,b] in fp32.
 //
 // Kernels: (1) split delta into hi/lo bf16; (2) split H into hi/lo bf16, TRANSPOSED
 // (Hs[k][b][a] = H[k][a][b] for a <= b, the diagonal 128-tiles completed to full squares), so
@@ -23,13 +25,16 @@
 namespace gq {
 namespace {
 
-constexpr int kTile = 128;            // rows j and columns b per workgroup
+constexpr int kTile = 128;            // rows of a staged tile (channels j, or columns b of H)
 constexpr int kKS = 16;               // contraction elements per LDS stage (one MFMA deep)
 constexpr int kRowBytes = kKS * 2;    // a staged tile row: two 16-byte chunks
 constexpr int kTileBytes = kTile * kRowBytes;       // 4 KiB
-constexpr int kStageBytes = 4 * kTileBytes;         // {Dh, Dl, Hh, Hl}: 16 KiB
-constexpr int kStages = 5;                          // ring depth: 80 KiB, two workgroups per CU
+constexpr int kStageTiles = 8;                      // {Dh, Dl} x 2 row blocks, {Hh, Hl} x 2 column tiles
+constexpr int kStageBytes = kStageTiles * kTileBytes;   // 32 KiB
+constexpr int kStages = 5;                          // ring depth: 160 KiB, all of a CU
 constexpr int kLoadsPerStage = kTileBytes / 1024;   // 1 KiB direct loads per wave and stage (wave w fills tile w)
+constexpr int kPairStages = 2 * kTile / kKS;        // stages per pair of 128-tiles along the contraction (16)
+constexpr int kOrderP = 4, kOrderR = 8;             // workgroups are ordered in blocks of 4 tile pairs x 8 row blocks
 constexpr int kTileElems = kTile * kKS;             // bf16 elements of one staged tile
 
 // Element offset, inside a staged tile, of contraction element e (0..15) of row r (0..127): a row
@@ -88,9 +93,10 @@ __global__ __launch_bounds__(256) void split_delta_kernel(const float* __restric
 }
 
 // Staged tiles of the transposed H: column tile tb holds columns b = 128 tb + r as its rows,
-// stage st the contraction elements a = 16 st .. 16 st + 15, for st < 8 (tb + 1):
+// stage st the contraction elements a = 16 st .. 16 st + 15, for st < 16 (tb / 2 + 1):
 //   Hh/Hl[k][(tb * n_st + st) * kTileElems + tile_pos(r, e)] = hi/lo of H[k][a][b]  (a <= b),
-// of H[k][b][a] below the diagonal of the diagonal 128-tile, 0 past d.  One workgroup turns a
+// of H[k][b][a] below the diagonal of the diagonal 128-tile, 0 past d; an even tile tb also
+// gets eight stages of zeros after its diagonal block.  One workgroup turns a
 // block of 64 a x 128 b (four stages) through LDS: coalesced reads along b, 1 KiB contiguous
 // writes per wave.
 __global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ H, int64_t d, int64_t ldp, int64_t n_st,
@@ -101,8 +107,16 @@ __global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ 
   const float* Hk = H + (int64_t)k * d * d;
   unsigned short* Hhk = Hh + (int64_t)k * ldp * ldp;
   unsigned short* Hlk = Hl + (int64_t)k * ldp * ldp;
+  // 128-tiles (ta, tb) with ta/2 <= tb/2: the tile below the diagonal of a pair (ta = tb + 1) is
+  // written as zeros, the MFMA kernel runs both column tiles of a pair over the same range
   int ta, tb;
-  tri_decode(blockIdx.x / 2, ta, tb);                       // 128-tiles, ta <= tb
+  {
+    int pa, pb;
+    tri_decode(blockIdx.x / 8, pa, pb);
+    const int sub = (blockIdx.x / 2) % 4;
+    ta = 2 * pa + (sub & 1);
+    tb = 2 * pb + (sub >> 1);
+  }
   const int64_t a0 = (int64_t)ta * kTile + 64 * (blockIdx.x % 2), b0 = (int64_t)tb * kTile;
   const int t = threadIdx.x;
 #pragma unroll 4
@@ -111,7 +125,7 @@ __global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ 
     const int ar = idx / kTile, bc = idx % kTile;
     const int64_t a = a0 + ar, b = b0 + bc;
     float v = 0.f;
-    if (a < d && b < d) v = a <= b ? Hk[a * d + b] : Hk[b * d + a];   // a > b only inside a diagonal tile
+    if (a < d && b < d && ta <= tb) v = a <= b ? Hk[a * d + b] : Hk[b * d + a];   // a > b: inside a diagonal tile
     tile[ar][bc] = v;
   }
   __syncthreads();
@@ -134,43 +148,61 @@ __global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ 
   }
 }
 
-// Y tile [128 j][128 b] over a < (tb+1)*128 on bf16 MFMA with split operands, then the row dot.
+// Y tile [256 j][256 b] for one pair P of column tiles, on bf16 MFMA with split operands, then
+// the row dot.  8 waves: wave (wm, wn) owns rows 64 wm .. 64 wm + 63 and column tile 2P + wn.
 //
-// Staging.  The four operand tiles of a stage (128 rows x 16 contraction elements each, 4 KiB
+// Staging.  The eight operand tiles of a stage (128 rows x 16 contraction elements each, 4 KiB
 // contiguous in the split arrays and already in LDS order) go from global memory straight into
 // LDS (global_load_lds_dwordx4: wave w copies tile w with four 1 KiB loads), kStages - 1 stages
 // ahead of their use, tracked by an explicit vmcnt wait and one workgroup barrier per stage.
-__global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned short* __restrict__ Dh,
+__global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned short* __restrict__ Dh,
                                                              const unsigned short* __restrict__ Dl,
                                                              const unsigned short* __restrict__ Hh,
                                                              const unsigned short* __restrict__ Hl,
                                                              const float* __restrict__ W, const float* __restrict__ What,
                                                              int64_t d_out, int64_t d, int64_t ld, int64_t ldp, int G,
-                                                             int n_tb, int n_rb, float* __restrict__ partial) {
+                                                             int n_pairs, int n_rb2, float* __restrict__ partial) {
   __shared__ __attribute__((aligned(1024))) char smem[kStages * kStageBytes];
-  // the row-sum exchange at the end reuses the staging memory (after a barrier)
-  float (*red)[kTile] = reinterpret_cast<float (*)[kTile]>(&smem[0]);
+  // (the row-sum exchange at the end reuses the staging memory, after a barrier)
 
-  // Work order: group, then column tile (heavy ones first), then row block, so that the row
-  // blocks that read the same H tiles run side by side; workgroup ids are dealt round-robin to
-  // the 8 XCDs (each with its own L2), so the id is first remapped to give every XCD one
-  // contiguous stretch of that order.
-  int k, tb, rb;
+  // Work order.  Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so
+  // the id is first remapped to give every XCD one contiguous stretch of the logical order.
+  // That order walks, per group, blocks of kOrderP tile pairs x kOrderR row blocks (heavy pairs
+  // first): the workgroups resident on an XCD then share both their H tiles and their delta
+  // tiles through its L2.
+  int k, P, rb2;
   {
     constexpr int kXcd = 8;
     const int64_t total = gridDim.x, id = blockIdx.x;
     const int64_t x = id % kXcd, idx = id / kXcd, q = total / kXcd, r = total % kXcd;
     const int64_t logical = x * q + (x < r ? x : r) + idx;
-    const int64_t per_group = (int64_t)n_tb * n_rb;
+    const int64_t per_group = (int64_t)n_pairs * n_rb2;
     k = (int)(logical / per_group);
-    const int64_t rem = logical - (int64_t)k * per_group;
-    tb = n_tb - 1 - (int)(rem / n_rb);
-    rb = (int)(rem % n_rb);
+    int64_t rem = logical - (int64_t)k * per_group;
+    // bands of kOrderP pairs from the top; the first band holds the remainder
+    const int n_bands = (n_pairs + kOrderP - 1) / kOrderP;
+    const int first_w = n_pairs - (n_bands - 1) * kOrderP;
+    int band, pw;
+    if (rem < (int64_t)first_w * n_rb2) {
+      band = 0;
+      pw = first_w;
+    } else {
+      rem -= (int64_t)first_w * n_rb2;
+      band = 1 + (int)(rem / ((int64_t)kOrderP * n_rb2));
+      rem = rem % ((int64_t)kOrderP * n_rb2);
+      pw = kOrderP;
+    }
+    const int p_hi = n_pairs - 1 - (band == 0 ? 0 : first_w + (band - 1) * kOrderP);   // heaviest pair of the band
+    const int rblk = (int)(rem / ((int64_t)pw * kOrderR));
+    const int off = (int)(rem % ((int64_t)pw * kOrderR));
+    const int rw = (n_rb2 - rblk * kOrderR) < kOrderR ? (n_rb2 - rblk * kOrderR) : kOrderR;
+    P = p_hi - off / rw;
+    rb2 = rblk * kOrderR + off % rw;
   }
   const int64_t m = d_out / G;
-  const int64_t j0 = (int64_t)k * m + (int64_t)rb * kTile;  // first channel of this block
-  const int64_t j_end = (int64_t)(k + 1) * m;               // rows >= j_end belong to another group
-  const int64_t b0 = (int64_t)tb * kTile;
+  const int64_t j0 = (int64_t)k * m + (int64_t)rb2 * 2 * kTile;   // first channel of this block
+  const int64_t j_end = (int64_t)(k + 1) * m;                     // rows >= j_end belong to another group
+  const int64_t b0 = (int64_t)P * 2 * kTile;
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
@@ -181,9 +213,10 @@ __global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned s
   const int64_t n_st = ldp / kKS;
   const unsigned short* gp[kLoadsPerStage];
   {
+    const int which = (wave % 4) / 2;                       // row block / column tile of the pair
     const unsigned short* src =
-        wave < 2 ? (wave == 0 ? Dh : Dl) + ((int64_t)k * n_rb + rb) * n_st * kTileElems
-                 : (wave == 2 ? Hh : Hl) + (int64_t)k * ldp * ldp + (int64_t)tb * n_st * kTileElems;
+        wave < 4 ? (wave % 2 == 0 ? Dh : Dl) + (((int64_t)k * n_rb2 + rb2) * 2 + which) * n_st * kTileElems
+                 : (wave % 2 == 0 ? Hh : Hl) + (int64_t)k * ldp * ldp + ((int64_t)P * 2 + which) * n_st * kTileElems;
 #pragma unroll
     for (int i = 0; i < kLoadsPerStage; ++i) gp[i] = src + i * 512 + lane * 8;
   }
@@ -203,65 +236,96 @@ __global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned s
   // ---- fragment addresses: row l % 32 of a 32-row block, chunk l / 32 -----------------------
   const int lrow = lane % 32;
   const int frag_off = lrow * kRowBytes + (((lane / 32) ^ ((lrow >> 3) & 1)) * 16);
-  auto frag = [&](int slot, int t, int row0) -> bf16x8 {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kStageBytes + t * kTileBytes + row0 * kRowBytes + frag_off]);
+  const int a_off = (wm / 2) * 2 * kTileBytes + (wm % 2) * 64 * kRowBytes + frag_off;   // Dh tile; Dl follows it
+  const int b_off = (4 + 2 * wn) * kTileBytes + frag_off;                               // Hh tile; Hl follows it
+  auto frag = [&](int slot, int off) -> bf16x8 {
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kStageBytes + off]);
     return __builtin_bit_cast(bf16x8, v);
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][4];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < 4; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   // Fragments of one stage: rows of delta (hi, lo) and of the transposed H tile (hi, lo).
   struct Frags {
-    bf16x8 ah[2], al[2], bh[2], bl[2];
+    bf16x8 ah[2], al[2], bh[4], bl[4];
   };
-  auto read = [&](Frags& f, int slot) {
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      f.ah[x] = frag(slot, 0, wm * 64 + x * 32);
-      f.al[x] = frag(slot, 1, wm * 64 + x * 32);
-    }
-#pragma unroll
-    for (int y = 0; y < 2; ++y) {
-      f.bh[y] = frag(slot, 2, wn * 64 + y * 32);
-      f.bl[y] = frag(slot, 3, wn * 64 + y * 32);
-    }
+  // The three products of the two 32 x 32 blocks of column block y, interleaved so that
+  // consecutive MFMAs never update the same accumulator.
+  auto mma = [&](const Frags& f, int y) {
+    acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[0], f.bh[y], acc[0][y], 0, 0, 0);
+    acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[1], f.bh[y], acc[1][y], 0, 0, 0);
+    acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[0], f.bl[y], acc[0][y], 0, 0, 0);
+    acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[1], f.bl[y], acc[1][y], 0, 0, 0);
+    acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[0], f.bh[y], acc[0][y], 0, 0, 0);
+    acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[1], f.bh[y], acc[1][y], 0, 0, 0);
   };
-  auto mma = [&](const Frags& f) {
+  auto read_a = [&](Frags& f, int slot, int x) {
+    f.ah[x] = frag(slot, a_off + x * 32 * kRowBytes);
+    f.al[x] = frag(slot, a_off + kTileBytes + x * 32 * kRowBytes);
+  };
+  auto read_b = [&](Frags& f, int slot, int y) {
+    f.bh[y] = frag(slot, b_off + y * 32 * kRowBytes);
+    f.bl[y] = frag(slot, b_off + kTileBytes + y * 32 * kRowBytes);
+  };
+  auto read_all = [&](Frags& f, int slot) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) read_a(f, slot, x);
+#pragma unroll
+    for (int y = 0; y < 4; ++y) read_b(f, slot, y);
+  };
+  auto twice = [&]() {
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
-      for (int y = 0; y < 2; ++y) {
-        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[x], f.bh[y], acc[x][y], 0, 0, 0);
-        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[x], f.bl[y], acc[x][y], 0, 0, 0);
-        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[x], f.bh[y], acc[x][y], 0, 0, 0);
-      }
+      for (int y = 0; y < 4; ++y) acc[x][y] *= 2.f;
   };
 
-  const int stages = (tb + 1) * (kTile / kKS);              // a multiple of 8, > kStages
-  const int first_diag = tb * (kTile / kKS);
+  // Every kernel argument the epilogue needs is pulled into registers here: a scalar load left
+  // pending across the loops would turn the partial LDS-counter waits inside them into full ones.
+  asm volatile("" ::"s"(partial), "s"(W), "s"(What), "s"(ld), "s"(d), "s"(d_out), "s"(j_end));
+
+  const int stages = (P + 1) * kPairStages;                 // a multiple of 16, > kStages
 #pragma unroll
   for (int t = 0; t < kStages - 1; ++t) issue(t, true);
   int slot_next = 1, slot_fill = kStages - 1;               // ring slots of stage it + 1 and of stage it - 1
 
   // One step: the MFMAs of stage `it` run on fragments read during the previous step, while
   // the fragments of stage it + 1 are read and stage it + kStages - 1 is requested.  The step
-  // is branch-free (past the end it reads a stale slot and requests the last stage again), so
-  // the LDS reads of the next stage stay in flight behind the MFMAs.
+  // is branch-free (past the end it reads a stale slot and requests the last stage again).
+  // All eight waves leave the barrier together, so every wave first queues MFMAs and then
+  // slips its loads and LDS reads in between groups of six MFMAs, in the order in which the
+  // next step consumes them: the matrix pipe has work while the LDS serves the reads, and at
+  // most 12 LDS reads are in flight (the counter that tracks them has 4 bits).
+  auto fence = [&]() { __builtin_amdgcn_sched_barrier(0); };
   auto step = [&](const Frags& cur, Frags& nxt, int it) {
     wait_vmcnt<(kStages - 3) * kLoadsPerStage>();   // this wave's loads of stage it + 1 have landed
     // everyone's have; and everyone has issued the MFMAs of stage it - 1, so its slot is free
     __builtin_amdgcn_s_barrier();
+    fence();
+    mma(cur, 0);
+    fence();
     issue(slot_fill, it + kStages < stages);
-    read(nxt, slot_next);
-    __builtin_amdgcn_sched_barrier(0);              // keep the reads ahead of the MFMAs they overlap with
-    mma(cur);
-    __builtin_amdgcn_sched_barrier(0);
+    read_a(nxt, slot_next, 0);
+    read_a(nxt, slot_next, 1);
+    fence();
+    mma(cur, 1);
+    fence();
+    read_b(nxt, slot_next, 0);
+    read_b(nxt, slot_next, 1);
+    fence();
+    mma(cur, 2);
+    fence();
+    read_b(nxt, slot_next, 2);
+    read_b(nxt, slot_next, 3);
+    fence();
+    mma(cur, 3);
+    fence();
     slot_fill = slot_fill + 1 == kStages ? 0 : slot_fill + 1;
     slot_next = slot_next + 1 == kStages ? 0 : slot_next + 1;
   };
@@ -269,54 +333,68 @@ __global__ __launch_bounds__(256, 2) void objective_mfma_kernel(const unsigned s
   Frags f0, f1;
   wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
   __builtin_amdgcn_s_barrier();
-  read(f0, 0);
+  read_all(f0, 0);
   int it = 0;
-  for (; it < first_diag; it += 2) {     // strictly-upper tiles
+  const int diag0 = P * kPairStages, diag1 = diag0 + kPairStages / 2;
+  for (; it < diag0; it += 2) {          // strictly above the diagonal for both column tiles
     step(f0, f1, it);
     step(f1, f0, it + 1);
   }
-  if (tb > 0) {
-    // they count twice (their mirror images are never visited)
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int y = 0; y < 2; ++y) acc[x][y] *= 2.f;
+  if (wn == 0 && P > 0) twice();         // what came before counts twice (its mirror image is never visited)
+  for (; it < diag1; it += 2) {          // diagonal block of the first tile, still above the second's
+    step(f0, f1, it);
+    step(f1, f0, it + 1);
   }
-  for (; it < stages; it += 2) {         // the diagonal tile
+  if (wn == 1) twice();
+  for (; it < stages; it += 2) {         // diagonal block of the second tile (zeros for the first)
     step(f0, f1, it);
     step(f1, f0, it + 1);
   }
   wait_vmcnt<0>();   // the repeated requests of the last stage
   __syncthreads();   // the ring is idle: `red` may reuse it
 
-  // row dot with delta[j, b] (fp32): register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32
-  float rowsum[2][16];
+  // Row dot with delta[j, b] (fp32).  Register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4),
+  // column l%32 of a 32 x 32 block.  Branch-free: addresses are clamped into the matrix, which
+  // is harmless because Y is exactly 0 in columns b >= d (the padded rows of the transposed H
+  // are zeros) and rows j >= j_end are dropped at the final store.
+  float v[2][16];
+  {
+    const int64_t bl = b0 + wn * kTile + lane % 32;
+    int64_t bcol[4];
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int64_t j = j0 + wm * 64 + x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-      float v = 0.f;
-#pragma unroll
-      for (int y = 0; y < 2; ++y) {
-        const int64_t b = b0 + wn * 64 + y * 32 + lane % 32;
-        if (j < j_end && b < d) v += acc[x][y][r] * (W[j * ld + b] - What[j * ld + b]);
-      }
-#pragma unroll
-      for (int off = 16; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-      rowsum[x][r] = v;
-    }
-  if (lane % 32 == 0) {
+    for (int y = 0; y < 4; ++y) bcol[y] = (bl + 32 * y) < d ? (bl + 32 * y) : d - 1;
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        red[wn][wm * 64 + x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] = rowsum[x][r];
+      for (int r = 0; r < 16; ++r) {
+        int64_t j = j0 + wm * 64 + x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        j = j < j_end ? j : j_end - 1;
+        float t = 0.f;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) t += acc[x][y][r] * (W[j * ld + bcol[y]] - What[j * ld + bcol[y]]);
+        v[x][r] = t;
+      }
+  }
+  // Sum over the 32 lanes of each half-wave, for all 32 rows at once: every lane parks its 32
+  // values as a column of a 32 x 32 array (pitch 33 floats), then adds up one row of it.
+  constexpr int kPitch = 33;
+  float* park = reinterpret_cast<float*>(&smem[0]) + (wave * 2 + lane / 32) * 32 * kPitch;
+  float (*red)[2 * kTile] = reinterpret_cast<float (*)[2 * kTile]>(&smem[8 * 2 * 32 * kPitch * sizeof(float)]);
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) park[(x * 16 + r) * kPitch + lane % 32] = v[x][r];
+  float sum = 0.f;   // no barrier: a wave reads back only what it wrote itself, and its LDS accesses stay in order
+#pragma unroll
+  for (int c = 0; c < 32; ++c) sum += park[(lane % 32) * kPitch + c];
+  {
+    const int xr = lane % 32;   // this lane now owns block x = xr / 16, register r = xr % 16 of its half-wave
+    red[wn][wm * 64 + (xr / 16) * 32 + 8 * ((xr % 16) / 4) + 4 * (lane / 32) + (xr % 4)] = sum;
   }
   __syncthreads();
-  if (tid < kTile) {
+  if (tid < 2 * kTile) {
     const int64_t j = j0 + tid;
-    if (j < j_end) partial[(int64_t)tb * d_out + j] = red[0][tid] + red[1][tid];
+    if (j < j_end) partial[(int64_t)P * d_out + j] = red[0][tid] + red[1][tid];
   }
 }
 
@@ -356,19 +434,19 @@ __global__ void objective_groups_kernel(const double* __restrict__ block_sum, in
 }
 
 struct Layout {
-  int64_t ldp, n_tb;
+  int64_t ldp, n_pairs, n_rb2;
   int64_t n_blocks;                             // 256-row blocks per group in the final reduction
   size_t partial_bytes, sums_bytes, delta_bytes, h_bytes;   // delta_bytes / h_bytes: one of the hi/lo arrays
 };
 Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   Layout L;
-  L.n_tb = (d_in + kTile - 1) / kTile;
-  L.ldp = L.n_tb * kTile;                       // padded so that every 128 x 64 operand tile is in range
-  L.partial_bytes = ((size_t)(L.n_tb * d_out) * sizeof(float) + 255) / 256 * 256;
+  L.n_pairs = (d_in + 2 * kTile - 1) / (2 * kTile);
+  L.ldp = L.n_pairs * 2 * kTile;                // contraction length padded to whole tile pairs
+  L.n_rb2 = (d_out / G + 2 * kTile - 1) / (2 * kTile);
+  L.partial_bytes = ((size_t)(L.n_pairs * d_out) * sizeof(float) + 255) / 256 * 256;
   L.n_blocks = (d_out / G + 255) / 256;
   L.sums_bytes = ((size_t)(L.n_blocks * G) * sizeof(double) + 255) / 256 * 256;
-  const int64_t n_rb = (d_out / G + kTile - 1) / kTile;
-  L.delta_bytes = ((size_t)((int64_t)G * n_rb * kTile * L.ldp) * 2 + 255) / 256 * 256;
+  L.delta_bytes = ((size_t)((int64_t)G * L.n_rb2 * 2 * kTile * L.ldp) * 2 + 255) / 256 * 256;
   L.h_bytes = ((size_t)((int64_t)G * L.ldp * L.ldp) * 2 + 255) / 256 * 256;
   return L;
 }
@@ -396,24 +474,18 @@ hipError_t launch_objective(const float* W, const float* What, int64_t d_out, in
   p += L.h_bytes;
   unsigned short* Hl = (unsigned short*)p;
 
-  const int64_t m = d_out / G;
-  const int n_tb = (int)L.n_tb;
-  const int n_rb = (int)((m + kTile - 1) / kTile);
+  const int n_pairs = (int)L.n_pairs, n_rb2 = (int)L.n_rb2;
   hipError_t e;
   const int64_t n_st = L.ldp / kKS;
-  {
-    split_delta_kernel<<<dim3((unsigned)(n_st / 4), (unsigned)(G * n_rb)), dim3(256), 0, st>>>(W, What, d_out, d_in, ld, G,
-                                                                                              n_rb, n_st, Dh, Dl);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
-  {
-    split_h_kernel<<<dim3((unsigned)(2 * tri_count(n_tb)), (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, n_st, Hh, Hl);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
-  objective_mfma_kernel<<<dim3((unsigned)((int64_t)n_tb * n_rb * G)), dim3(256), 0, st>>>(
-      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_tb, n_rb, partial);
+  split_delta_kernel<<<dim3((unsigned)(n_st / 4), (unsigned)(G * n_rb2 * 2)), dim3(256), 0, st>>>(W, What, d_out, d_in, ld, G,
+                                                                                                 n_rb2 * 2, n_st, Dh, Dl);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  objective_rows_kernel<<<dim3((unsigned)L.n_blocks, (unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, n_tb, obj_row,
+  split_h_kernel<<<dim3((unsigned)(8 * tri_count(n_pairs)), (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, n_st, Hh, Hl);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  objective_mfma_kernel<<<dim3((unsigned)((int64_t)n_pairs * n_rb2 * G)), dim3(512), 0, st>>>(
+      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_pairs, n_rb2, partial);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  objective_rows_kernel<<<dim3((unsigned)L.n_blocks, (unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, n_pairs, obj_row,
                                                                                        block_sum);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   objective_groups_kernel<<<dim3((unsigned)G), dim3(64), 0, st>>>(block_sum, (int)L.n_blocks, obj);

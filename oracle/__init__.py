@@ -13,4 +13,6 @@ from .gq_oracle import (  # noqa: F401
     unaveraged_objective,
     objective_from_tokens,
     objective_rows_from_tokens,
+    cd_coordinate_target,
+    cd_assign,
 )

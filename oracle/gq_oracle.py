@@ -20,6 +20,11 @@ Notation (paper, Section 3 "GuidedQuant", Algorithm 1):
                      [d_out, d_in] (row j = output channel j), i.e. the
                      transpose of the paper's [d_in, d_out] layout.
 
+The assignment step that consumes Hbar_k (Section 4.2, Algorithm 2 lines 6-12 with
+the closed form of Eq. "cd_closed") is `cd_assign`; being an iterative heuristic it
+follows the algorithm's steps in the paper's order: cycles, then coordinates in
+increasing order, one closed-form minimisation each.
+
 Pins (tests/test_oracle_pins.py) check every function against closed forms,
 a hand-worked example, an independent BLAS routine (dsyrk), and brute-force
 evaluation of the paper's *un-averaged* definitions (per-channel Hessians,
@@ -180,3 +185,60 @@ def objective_rows_from_tokens(X, s_k, delta_rows) -> np.ndarray:
     D = np.asarray(delta_rows, dtype=_F64)
     T = X @ D.T                      # [n, rows]: x_i . delta_j
     return (s_k[:, None] * T * T).sum(axis=0)
+
+
+
+def cd_coordinate_target(w_j, what_j, H_k, i: int) -> float:
+    """Eq. "cd_closed" (Section 4.2): the unconstrained minimiser of
+    (what - w)^T H (what - w) over coordinate i alone, all others fixed:
+        t = w[i] - sum_{i' != i} H[i, i'] / H[i, i] * (what[i'] - w[i']).
+    """
+    w_j = np.asarray(w_j, dtype=_F64)
+    delta = np.asarray(what_j, dtype=_F64) - w_j
+    H_k = np.asarray(H_k, dtype=_F64)
+    off = H_k[i] @ delta - H_k[i, i] * delta[i]
+    return float(w_j[i] - off / H_k[i, i])
+
+
+def cd_assign(W, What, codebook, H, G: int | None = None, n_cycles: int = 1):
+    """Cyclic coordinate descent on the assignments (Algorithm 2, lines 6-12, with the
+    closed-form coordinate update of Eq. "cd_closed_par"), every output channel of
+    group k against that group's Hbar_k.
+
+    W, What   [d_out, d_in]  original weights and the current feasible quantized weights
+    codebook  [d_out, m]     the grid {c_1..c_m} of every output channel
+    H         [G, d_in, d_in] full symmetric matrices with positive diagonals
+
+    For cycle = 1..n_cycles, for i = 0..d_in-1 (in this order): every channel j replaces
+    What[j, i] by the point of its grid nearest to the coordinate target t of Eq.
+    "cd_closed", computed from the current What (coordinates < i already updated in
+    this cycle).  Among equally near grid points the one with the lowest index wins.
+    Returns (Q [d_out, d_in] int64 grid indices, What_new [d_out, d_in] float64); a
+    coordinate's index is that of its last update.
+    """
+    W = np.asarray(W, dtype=_F64)
+    What = np.array(What, dtype=_F64, copy=True)
+    C = np.asarray(codebook, dtype=_F64)
+    H = np.asarray(H, dtype=_F64)
+    if H.ndim == 2:
+        H = H[None]
+    G = H.shape[0] if G is None else G
+    d_out, d_in = W.shape
+    Q = np.zeros((d_out, d_in), dtype=np.int64)
+    for k, (j0, j1) in enumerate(group_partition(d_out, G)):
+        Hk = H[k]
+        diag = np.diag(Hk)
+        if np.any(diag <= 0):
+            raise ValueError("H must have a positive diagonal")
+        Wk, Ck = W[j0:j1], C[j0:j1]
+        delta = What[j0:j1] - Wk                       # [rows, d_in]
+        rows = np.arange(j1 - j0)
+        for _ in range(n_cycles):
+            for i in range(d_in):
+                off = delta @ Hk[i] - Hk[i, i] * delta[:, i]     # sum over i' != i
+                t = Wk[:, i] - off / Hk[i, i]
+                q = np.argmin(np.abs(Ck - t[:, None]), axis=1)   # first minimum = lowest index
+                Q[j0:j1, i] = q
+                What[j0:j1, i] = Ck[rows, q]               # the grid value itself, not w + (c - w)
+                delta[:, i] = What[j0:j1, i] - Wk[:, i]
+    return Q, What

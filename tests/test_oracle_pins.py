@@ -201,3 +201,95 @@ def test_objective_rows_from_tokens_matches_the_token_loop_and_the_hessian_form(
     for j in range(4):
         assert abs(got[j] - oracle.objective_from_tokens(X, s_k, D[j])) <= 1e-12 * got[j]
         assert abs(got[j] - D[j] @ H @ D[j]) <= 1e-11 * got[j]
+
+
+# ---------------------------------------------------------------- cyclic CD assignment step
+def _cd_case(seed, d_out=6, d_in=7, G=2, m=4, n=40):
+    r = _rng(seed)
+    X = r.standard_normal((n, d_in))
+    s = r.random((n, G)) + 0.1
+    H = oracle.fisher_gram(X, s)
+    W = r.standard_normal((d_out, d_in))
+    C = np.sort(r.standard_normal((d_out, m)), axis=1)
+    q0 = r.integers(0, m, size=(d_out, d_in))
+    What0 = C[np.arange(d_out)[:, None], q0]
+    return W, What0, C, H
+
+
+def test_cd_worked_example():
+    # Worked by hand from Eq. (cd_closed): H = [[2,1],[1,2]], w = (0.4, 0.6), grid {0, 1}, start (0, 0).
+    # i=0: t = 0.4 - (1/2)(0 - 0.6) = 0.7 -> 1;   i=1: t = 0.6 - (1/2)(1 - 0.4) = 0.3 -> 0.
+    H = np.array([[[2.0, 1.0], [1.0, 2.0]]])
+    W = np.array([[0.4, 0.6]])
+    C = np.array([[0.0, 1.0]])
+    assert abs(oracle.cd_coordinate_target(W[0], [0.0, 0.0], H[0], 0) - 0.7) < 1e-15
+    assert abs(oracle.cd_coordinate_target(W[0], [1.0, 0.0], H[0], 1) - 0.3) < 1e-15
+    Q, What = oracle.cd_assign(W, np.zeros((1, 2)), C, H)
+    assert Q.tolist() == [[1, 0]] and What.tolist() == [[1.0, 0.0]]
+    # the objective went from 1.52 to 0.72 (hand-computed delta^T H delta)
+    assert abs(oracle.objective(W, np.zeros((1, 2)), H)[0][0] - 1.52) < 1e-14
+    assert abs(oracle.objective(W, What, H)[0][0] - 0.72) < 1e-14
+
+
+def test_cd_each_update_is_the_exhaustive_argmin_of_the_objective():
+    # Algorithm 2, line 8 defines the update as the grid point that minimises the layer objective;
+    # replay the cycle with that definition evaluated exhaustively and compare the assignments.
+    W, What0, C, H = _cd_case(20)
+    d_out, d_in = W.shape
+    G = H.shape[0]
+    Q, What = oracle.cd_assign(W, What0, C, H, G, n_cycles=2)
+    cur = What0.copy()
+    for _ in range(2):
+        for i in range(d_in):
+            for j in range(d_out):
+                best, best_q = None, None
+                for q in range(C.shape[1]):
+                    trial = cur.copy()
+                    trial[j, i] = C[j, q]
+                    val = oracle.objective(W, trial, H, G)[1][j]
+                    if best is None or val < best - 1e-12 * abs(best):
+                        best, best_q = val, q
+                cur[j, i] = C[j, best_q]
+                last = best_q
+                if _ == 1:
+                    assert Q[j, i] == last
+    np.testing.assert_array_equal(What, cur)
+
+
+def test_cd_is_a_descent_method_and_reaches_a_fixed_point():
+    W, What0, C, H = _cd_case(21, d_out=8, d_in=12, G=2, m=8)
+    prev = oracle.objective(W, What0, H, 2)[1]
+    cur = What0
+    for cycle in range(30):
+        Q, nxt = oracle.cd_assign(W, cur, C, H, 2, n_cycles=1)
+        val = oracle.objective(W, nxt, H, 2)[1]
+        assert np.all(val <= prev * (1 + 1e-12))          # Prop. 4.1: feasible start => monotone descent, per channel
+        if np.array_equal(nxt, cur):
+            break
+        prev, cur = val, nxt
+    else:
+        raise AssertionError("no fixed point within 30 cycles")
+    # several cycles in one call are the same as the calls chained
+    Qk, Wk = oracle.cd_assign(W, What0, C, H, 2, n_cycles=cycle + 1)
+    np.testing.assert_array_equal(Wk, cur)
+    assert np.all(C[np.arange(8)[:, None], Qk] == Wk)
+
+
+def test_cd_with_diagonal_hessian_is_round_to_nearest_and_groups_use_their_own_matrix():
+    W, What0, C, H = _cd_case(22, d_out=6, d_in=9, G=2, m=4)
+    H = H.copy()
+    H[1] = np.diag(np.diag(H[1]))                                  # group 1: no coupling between coordinates
+    Q, What = oracle.cd_assign(W, What0, C, H, 2)
+    rtn = np.argmin(np.abs(C[3:, None, :] - W[3:, :, None]), axis=2)
+    np.testing.assert_array_equal(Q[3:], rtn)
+    assert not np.array_equal(Q[:3], np.argmin(np.abs(C[:3, None, :] - W[:3, :, None]), axis=2))   # group 0 is coupled
+
+
+def test_cd_tie_goes_to_the_lower_index_and_rejects_nonpositive_diagonal():
+    H = np.array([[[1.0, 0.0], [0.0, 1.0]]])
+    W = np.array([[0.5, 0.25]])
+    C = np.array([[0.0, 1.0, 0.5]])                                # 0.25 is equally far from 0 (index 0) and 0.5 (index 2)
+    Q, What = oracle.cd_assign(W, np.zeros((1, 2)), C, H)
+    assert Q.tolist() == [[2, 0]] and What.tolist() == [[0.5, 0.0]]
+    with pytest.raises(ValueError):
+        oracle.cd_assign(W, np.zeros((1, 2)), C, np.zeros((1, 2, 2)))

@@ -10,6 +10,7 @@
  *   gq_fisher_gram    H[k]   (+)= X^T Diag(s[:,k]) X                      (Algorithm 1, line 4)
  *   gq_fisher_mirror  H[k][b,a] = H[k][a,b]  for a < b                    (storage of the full square)
  *   gq_objective      obj[k]  = sum_{j in J_k} (w_j-what_j)^T H[k] (w_j-what_j)   (Eq. "ours2", Section 3.2)
+ *   gq_cd_assign      cyclic coordinate descent on the assignments against H[k]   (Section 4.2, Eq. "cd_closed")
  *
  * Conventions shared by every call
  *   - Every data pointer is DEVICE memory on the current HIP device, allocated
@@ -92,7 +93,8 @@ size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in,
  *
  *   H[k][a,b] (+)= sum_{i<n} s[i,k] * X[i,a] * X[i,b]      for a <= b, k < G
  *
- *   X    [n, d_in]        device, x_dtype, row pitch ld_x elements
+ *   X    [n, d_in]        device, x_dtype, row pitch ld_x elements; all n*ld_x elements must be
+ *                         readable (whole 16-byte chunks are loaded, never past the pitch of a row)
  *   s    [n, G]           device fp32 (as written by gq_group_weights)
  *   H    [G, d_in, d_in]  device fp32, dense.  Only the upper triangle (incl.
  *                         diagonal) of each H[k] is read and written; the strictly
@@ -147,6 +149,45 @@ size_t gq_objective_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G);
  */
 int gq_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld_w,
                  const float* H, int32_t G, double* obj, float* obj_row,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace gq_cd_assign needs (never 0 for valid sizes). */
+size_t gq_cd_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G);
+
+/*
+ * The assignment step of layer-wise non-uniform quantization run against the group
+ * Hessians (Section 4.2: Algorithm 2, lines 6-12, with the closed-form coordinate update
+ * of Eq. "cd_closed"; coordinates are processed in blocks of 128 as in Algorithm 4).
+ *
+ * For cycle = 1..n_cycles, for i = 0..d_in-1 in this order, every output channel j
+ * (group k = j / (d_out/G)) replaces What[j,i] by the point of its grid nearest to
+ *
+ *   t = W[j,i] - sum_{i' != i} H[k][i,i'] / H[k][i,i] * (What[j,i'] - W[j,i']),
+ *
+ * computed from the current What (coordinates < i already updated in this cycle).
+ * Among equally near grid points the one with the lowest index wins.  The sums are
+ * evaluated in fp32-grade arithmetic, so a target that lies within rounding distance
+ * of the midpoint of two grid points may go to either of them.
+ *
+ *   W         [d_out, d_in]    device fp32, row pitch ld_w elements (row j = output channel j)
+ *   What      [d_out, d_in]    device fp32, same pitch; in: the current quantized weights
+ *                              (every entry a point of its channel's grid); out: the new ones
+ *   codebook  [d_out, n_levels] device fp32, dense: the grid of every output channel,
+ *                              1 <= n_levels <= 16, in any order
+ *   H         [G, d_in, d_in]  device fp32 with positive diagonals; only the upper triangle
+ *                              (incl. diagonal) of each H[k] is read
+ *   Q         [d_out, d_in]    device bytes, dense, or NULL: the grid index chosen at the
+ *                              last update of every coordinate
+ *   workspace  at least gq_cd_workspace_bytes() bytes, 256-byte aligned
+ *
+ * n_cycles == 0 is a valid no-op.  Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_out <= 0,
+ * d_in <= 0, G <= 0, d_out % G != 0, ld_w < d_in, n_cycles < 0, n_levels <= 0),
+ * GQ_ERR_UNSUPPORTED (n_levels > 16), GQ_ERR_ALIGN (W/What/H not 16-byte aligned or
+ * ld_w*4 not a multiple of 16), GQ_ERR_WORKSPACE, GQ_ERR_HIP.
+ */
+int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_levels,
+                 int64_t d_out, int64_t d_in, int64_t ld_w, const float* H, int32_t G,
+                 int32_t n_cycles, uint8_t* Q,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus

@@ -57,6 +57,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_objective.restype = c.c_int
     lib.gq_objective.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
                                  c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.gq_cd_workspace_bytes.restype = c.c_size_t
+    lib.gq_cd_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
+    lib.gq_cd_assign.restype = c.c_int
+    lib.gq_cd_assign.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int64, c.c_int64,
+                                 c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -183,3 +188,29 @@ def gq_objective(W: torch.Tensor, What: torch.Tensor, H: torch.Tensor, want_rows
                           obj.data_ptr(), rows.data_ptr() if want_rows else None, ws_ptr, ws_bytes, _stream())
     _check(st, "gq_objective")
     return (obj, rows) if want_rows else obj
+
+
+def gq_cd_assign(W: torch.Tensor, What: torch.Tensor, codebook: torch.Tensor, H: torch.Tensor, n_cycles: int = 1,
+                 want_codes: bool = True, workspace: Optional[torch.Tensor] = None):
+    """Cyclic coordinate descent on the assignments against H[k] (Section 4.2, Eq. "cd_closed").
+    `What` [d_out, d_in] (every entry a point of its row's grid `codebook` [d_out, m]) is updated
+    IN PLACE; returns the grid indices [d_out, d_in] uint8 of the last update (or None)."""
+    _require_gpu(W, What, codebook, H, workspace)
+    d_out, d_in = W.shape
+    G = int(H.shape[0])
+    assert W.dtype == torch.float32 and What.dtype == torch.float32 and H.dtype == torch.float32
+    assert codebook.dtype == torch.float32 and codebook.is_contiguous() and codebook.shape[0] == d_out
+    assert What.shape == W.shape and _rows(W) == _rows(What) and H.is_contiguous()
+    lib = load_library()
+    need = int(lib.gq_cd_workspace_bytes(d_out, d_in, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(max(need, 1), W.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    Q = torch.empty((d_out, d_in), dtype=torch.uint8, device=W.device) if want_codes else None
+    st = lib.gq_cd_assign(W.data_ptr(), What.data_ptr(), codebook.data_ptr(), int(codebook.shape[1]), d_out, d_in,
+                          _rows(W), H.data_ptr(), G, int(n_cycles), Q.data_ptr() if want_codes else None,
+                          ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_cd_assign")
+    return Q

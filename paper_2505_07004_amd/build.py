@@ -22,6 +22,7 @@ SOURCES = [
     "fisher_gram_bf16.hip",
     "mirror.hip",
     "objective.hip",
+    "cd_assign.hip",
 ]
 
 HIPCC_FLAGS = [

@@ -1,0 +1,402 @@
+// Cyclic coordinate descent on the assignments against the group Hessians (Section 4.2:
+// Algorithm 2 lines 6-12, coordinate update of Eq. "cd_closed_par"; evaluated block-wise in
+// the spirit of Algorithms 3 and 4).
+//
+// For output channel j of group k, with delta = what_j - w_j and Ht[i][i'] = H[k][i][i'] / H[k][i][i]
+// (zero diagonal), coordinate i is replaced by the grid point nearest to
+//     t = w[i] - sum_{i' != i} Ht[i][i'] * delta[i'],
+// coordinates in increasing order, every channel independently.
+//
+// The coordinates are processed in blocks of 128.  For a block, one GEMM gives
+//     B0[j][i] = sum_{i'} delta[j][i'] * Ht[i][i']            (all i', current delta)
+// for its 128 coordinates at once (bf16 matrix cores at fp32-grade accuracy: both operands
+// split into hi + lo bf16 terms, three products), and a second kernel walks the block
+// sequentially, one thread per channel with its 128 targets in registers: after coordinate i
+// changes by eps, the targets of the later coordinates i'' of the block move by
+// -eps * Ht[i''][i].  The block's new delta is written back (split) for the next block's GEMM.
+// Compared with Algorithm 4 the bookkeeping differs (the part of the sum that lies outside
+// the block is recomputed per block from the current weights instead of being carried along
+// and corrected after each block; the flop count is the same), the update rule does not.
+#include "gq_internal.hpp"
+
+namespace gq {
+namespace {
+
+constexpr int kBlk = 128;             // coordinates per block
+constexpr int kRows = 64;             // channels per workgroup row tile (GEMM) / per wave (sequential kernel)
+constexpr int kMaxLevels = 16;        // grid points per channel (4 bits)
+
+__device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
+  const __bf16 h = (__bf16)x;
+  const __bf16 l = (__bf16)(x - (float)h);
+  hi = __builtin_bit_cast(unsigned short, h);
+  lo = __builtin_bit_cast(unsigned short, l);
+}
+
+// Ht (hi/lo bf16, [G][ldp][ldp], row i contiguous over i', zero diagonal and zero padding) and
+// the fp32 coefficients of every diagonal block in both orientations,
+//   Cd[k][blk][b][a] = CdT[k][blk][a][b] = Ht[blk*128 + b][blk*128 + a]
+// (what the target of coordinate b moves by, per unit change of coordinate a).
+// Only the upper triangle of H is read.  One workgroup per 64 x 64 tile.
+__global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ H, int64_t d, int64_t ldp,
+                                                      unsigned short* __restrict__ Hth,
+                                                      unsigned short* __restrict__ Htl, float* __restrict__ Cd,
+                                                      float* __restrict__ CdT) {
+  __shared__ float tile[64][65];
+  __shared__ float diag[64];
+  const int k = blockIdx.z;
+  const int ti = blockIdx.y, tj = blockIdx.x;              // tile of rows i, of columns i'
+  const float* Hk = H + (int64_t)k * d * d;
+  const int tmin = ti < tj ? ti : tj, tmax = ti < tj ? tj : ti;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  for (int r = ty; r < 64; r += 4) {                       // the tile on or above the diagonal
+    const int64_t a = (int64_t)tmin * 64 + r, b = (int64_t)tmax * 64 + tx;
+    tile[r][tx] = (a < d && b < d) ? Hk[a * d + b] : 0.f;
+  }
+  if (threadIdx.x < 64) {
+    const int64_t i = (int64_t)ti * 64 + threadIdx.x;
+    diag[threadIdx.x] = i < d ? Hk[i * d + i] : 1.f;
+  }
+  __syncthreads();
+  const int64_t n_blk = ldp / kBlk;
+  for (int r = ty; r < 64; r += 4) {
+    const int li = r, lj = tx;                             // local row i, local column i'
+    const int64_t i = (int64_t)ti * 64 + li, ip = (int64_t)tj * 64 + lj;
+    float h;
+    if (ti < tj) h = tile[li][lj];
+    else if (ti > tj) h = tile[lj][li];
+    else h = li <= lj ? tile[li][lj] : tile[lj][li];
+    const float v = (i < d && ip < d && i != ip) ? h / diag[li] : 0.f;
+    unsigned short hi, lo;
+    split_bf16(v, hi, lo);
+    const int64_t off = (int64_t)k * ldp * ldp + i * ldp + ip;
+    Hth[off] = hi;
+    Htl[off] = lo;
+    if (i / kBlk == ip / kBlk) {
+      const int64_t blk = i / kBlk;
+      const int64_t base = ((int64_t)k * n_blk + blk) * kBlk * kBlk;
+      Cd[base + (i % kBlk) * kBlk + (ip % kBlk)] = v;
+      CdT[base + (ip % kBlk) * kBlk + (i % kBlk)] = v;
+    }
+  }
+}
+
+// Dh/Dl[j][a] = hi/lo of What[j][a] - W[j][a], row pitch ldp, zero padded.
+__global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__ W, const float* __restrict__ What,
+                                                       int64_t d, int64_t ld, int64_t ldp,
+                                                       unsigned short* __restrict__ Dh,
+                                                       unsigned short* __restrict__ Dl) {
+  const int64_t j = blockIdx.y;
+  for (int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x; a < ldp; a += (int64_t)gridDim.x * 256) {
+    const float v = a < d ? What[j * ld + a] - W[j * ld + a] : 0.f;
+    unsigned short h, l;
+    split_bf16(v, h, l);
+    Dh[j * ldp + a] = h;
+    Dl[j * ldp + a] = l;
+  }
+}
+
+// Partial sums of B0 for block `blk`:  C[part][i][j] = sum over this part's contraction range
+// of delta[j][i'] * Ht[blk*128 + i][i'],  i < 128, j a channel (j contiguous, pitch d_out).
+// Both operands are contiguous along the contraction index, so every MFMA fragment (8 bf16
+// of one row per lane) is a 16-byte global load; nothing is staged in LDS.  A workgroup owns
+// 64 channels of one group; its 4 waves take different quarters of the part's contraction
+// range and are added up through LDS.  The parts (gridDim.y) are added by the sequential
+// kernel in a fixed order.
+__global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short* __restrict__ Dh,
+                                                            const unsigned short* __restrict__ Dl,
+                                                            const unsigned short* __restrict__ Hth,
+                                                            const unsigned short* __restrict__ Htl, int64_t d_out,
+                                                            int64_t ldp, int G, int n_rt, int blk,
+                                                            float* __restrict__ C) {
+  __shared__ float red[4][kBlk][kRows + 1];
+  const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
+  const int64_t m = d_out / G;
+  const int64_t j0 = (int64_t)k * m + (int64_t)rt * kRows, j_last = (int64_t)(k + 1) * m - 1;
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+
+  // contraction range of this wave, in steps of 16
+  const int64_t n_steps = ldp / 16, n_chunks = 4 * (int64_t)gridDim.y, chunk = (int64_t)blockIdx.y * 4 + wave;
+  const int64_t s0 = chunk * n_steps / n_chunks, s1 = (chunk + 1) * n_steps / n_chunks;
+
+  const unsigned short *pa_h[2], *pa_l[2], *pb_h[4], *pb_l[4];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    int64_t j = j0 + 32 * x + lane % 32;
+    j = j < j_last ? j : j_last;                           // rows past the group: repeat its last row (never stored)
+    pa_h[x] = Dh + j * ldp + 8 * (lane / 32) + 16 * s0;
+    pa_l[x] = Dl + j * ldp + 8 * (lane / 32) + 16 * s0;
+  }
+#pragma unroll
+  for (int y = 0; y < 4; ++y) {
+    const int64_t i = (int64_t)blk * kBlk + 32 * y + lane % 32;
+    pb_h[y] = Hth + (int64_t)k * ldp * ldp + i * ldp + 8 * (lane / 32) + 16 * s0;
+    pb_l[y] = Htl + (int64_t)k * ldp * ldp + i * ldp + 8 * (lane / 32) + 16 * s0;
+  }
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 4; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+  // The fragments of step s + 1 are requested before the MFMAs of step s (past the end the
+  // last step is fetched again), so a single wave per SIMD hides most of the load latency.
+  struct Frags {
+    bf16x8 ah[2], al[2], bh[4], bl[4];
+  };
+  auto fetch = [&](Frags& f, bool advance) {
+    const int step = advance ? 16 : 0;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      f.ah[x] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pa_h[x]));
+      f.al[x] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pa_l[x]));
+      pa_h[x] += step;
+      pa_l[x] += step;
+    }
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+      f.bh[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pb_h[y]));
+      f.bl[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pb_l[y]));
+      pb_h[y] += step;
+      pb_l[y] += step;
+    }
+  };
+  auto mma = [&](const Frags& f) {
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+      acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[0], f.bh[y], acc[0][y], 0, 0, 0);
+      acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[1], f.bh[y], acc[1][y], 0, 0, 0);
+      acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[0], f.bl[y], acc[0][y], 0, 0, 0);
+      acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[1], f.bl[y], acc[1][y], 0, 0, 0);
+      acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[0], f.bh[y], acc[0][y], 0, 0, 0);
+      acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[1], f.bh[y], acc[1][y], 0, 0, 0);
+    }
+  };
+  if (s1 > s0) {
+    Frags f0, f1;
+    fetch(f0, s0 + 1 < s1);
+    int64_t s = s0;
+    for (; s + 1 < s1; s += 2) {
+      fetch(f1, s + 2 < s1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(f0);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(f0, s + 3 < s1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(f1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (s < s1) mma(f0);
+  }
+
+  // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4) (channel), column l%32 (coordinate)
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 4; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        red[wave][32 * y + lane % 32][32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] = acc[x][y][r];
+  __syncthreads();
+  float* Cp = C + (int64_t)blockIdx.y * kBlk * d_out;
+  for (int idx = threadIdx.x; idx < kBlk * kRows; idx += 256) {
+    const int i = idx / kRows, r = idx % kRows;
+    const int64_t j = j0 + r;
+    if (j <= j_last) Cp[(int64_t)i * d_out + j] = (red[0][i][r] + red[1][i][r]) + (red[2][i][r] + red[3][i][r]);
+  }
+}
+
+// The sequential walk through block `blk`: one wave per 64 channels of a group, one thread per
+// channel.  The block of W and What is moved between global memory and LDS row by row
+// (coalesced); a lane works on column `lane` of the LDS arrays.  The 128 targets of a channel
+// live in LDS; the block is walked in four runs of 32 coordinates whose targets sit in
+// registers: inside a run every update corrects the later targets of the run at once, the
+// targets after the run are corrected when the run is over (32 changes at a time).  Lanes past
+// the end of the group repeat its last channel, so the whole wave stays active throughout.
+constexpr int kRun = 32;
+__global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __restrict__ C, int n_parts,
+                                                             const float* __restrict__ W, float* __restrict__ What,
+                                                             const float* __restrict__ codebook, int n_levels,
+                                                             const float* __restrict__ Cd,
+                                                             const float* __restrict__ CdT, int64_t d_out, int64_t d,
+                                                             int64_t ld, int64_t ldp, int G, int n_rt, int blk,
+                                                             unsigned char* __restrict__ Q,
+                                                             unsigned short* __restrict__ Dh,
+                                                             unsigned short* __restrict__ Dl) {
+  __shared__ float wblk[kBlk][kRows + 1];                  // the block of W
+  __shared__ float cur[kBlk][kRows + 1];                   // the block of What, old values then new ones
+  __shared__ float tgt[kBlk][kRows];                       // the targets t[i] of every channel
+  __shared__ unsigned char code[kBlk][kRows + 4];
+  const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
+  const int64_t m = d_out / G;
+  const int lane = threadIdx.x;
+  const int64_t j0 = (int64_t)k * m + (int64_t)rt * kRows, j_last = (int64_t)(k + 1) * m - 1;
+  const int64_t j = (j0 + lane) < j_last ? (j0 + lane) : j_last;
+  const int n_rows = (int)((j_last - j0 + 1) < kRows ? (j_last - j0 + 1) : kRows);
+  const int64_t i0 = (int64_t)blk * kBlk;
+  const int n_valid = (int)((d - i0) < kBlk ? (d - i0) : kBlk);   // coordinates of this block inside the matrix
+  const int64_t cbase = (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk;
+  const float* coef_b = Cd + cbase;                        // [b][a]
+  const float* coef_a = CdT + cbase;                       // [a][b]
+
+  for (int r = 0; r < kRows; ++r) {
+    const int64_t jr = r < n_rows ? j0 + r : j_last;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int i = lane + 64 * half;
+      const int64_t a = (i0 + i) < d ? (i0 + i) : d - 1;
+      wblk[i][r] = W[jr * ld + a];
+      cur[i][r] = What[jr * ld + a];
+    }
+  }
+  __syncthreads();
+
+  float grid[kMaxLevels];
+#pragma unroll
+  for (int q = 0; q < kMaxLevels; ++q) grid[q] = codebook[j * n_levels + (q < n_levels ? q : n_levels - 1)];
+
+  // targets t[i] = w[i] - B0[i]; B0 = sum of the parts in order
+  for (int i = 0; i < kBlk; ++i) {
+    float b = 0.f;
+    for (int p = 0; p < n_parts; ++p) b += C[((int64_t)p * kBlk + i) * d_out + j];
+    tgt[i][lane] = wblk[i][lane] - b;
+  }
+
+  for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
+    float t[kRun], eps[kRun];
+#pragma unroll
+    for (int ii = 0; ii < kRun; ++ii) t[ii] = tgt[c0 + ii][lane];
+#pragma unroll
+    for (int ii = 0; ii < kRun; ++ii) {
+      eps[ii] = 0.f;
+      if (c0 + ii < n_valid) {                              // uniform
+        const float ti = t[ii];
+        float best = fabsf(grid[0] - ti), val = grid[0];
+        int bq = 0;
+#pragma unroll
+        for (int q = 1; q < kMaxLevels; ++q) {
+          const float dist = fabsf(grid[q] - ti);
+          const bool better = (q < n_levels) && (dist < best);   // equally near: the lower index stays
+          best = better ? dist : best;
+          val = better ? grid[q] : val;
+          bq = better ? q : bq;
+        }
+        const float e = val - cur[c0 + ii][lane];
+        cur[c0 + ii][lane] = val;
+        code[c0 + ii][lane] = (unsigned char)bq;
+        eps[ii] = e;
+        const float* row = coef_a + (int64_t)(c0 + ii) * kBlk + c0;   // Ht[c0 + ii2][c0 + ii] over ii2
+#pragma unroll
+        for (int ii2 = ii + 1; ii2 < kRun; ++ii2) t[ii2] -= e * row[ii2];
+      }
+    }
+    for (int i2 = c0 + kRun; i2 < n_valid; ++i2) {          // the targets after the run
+      const float* row = coef_b + (int64_t)i2 * kBlk + c0;  // Ht[i2][c0 + ii] over ii
+      float a = 0.f;
+#pragma unroll
+      for (int ii = 0; ii < kRun; ++ii) a += eps[ii] * row[ii];
+      tgt[i2][lane] -= a;
+    }
+  }
+  __syncthreads();
+
+  // write the block back row by row: What, the codes, and the split delta for the next block's GEMM
+  for (int r = 0; r < n_rows; ++r) {
+    const int64_t jr = j0 + r;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int i = lane + 64 * half;
+      if (i < n_valid) {
+        const int64_t a = i0 + i;
+        const float v = cur[i][r];
+        What[jr * ld + a] = v;
+        if (Q) Q[jr * d + a] = code[i][r];
+        unsigned short h, l;
+        split_bf16(v - wblk[i][r], h, l);
+        Dh[jr * ldp + a] = h;
+        Dl[jr * ldp + a] = l;
+      }
+    }
+  }
+}
+
+struct Layout {
+  int64_t ldp, n_blk;
+  int n_rt, n_parts;
+  size_t ht_bytes, cdt_bytes, delta_bytes, c_bytes;
+};
+Layout make_layout(int64_t d_out, int64_t d_in, int G) {
+  Layout L;
+  L.n_blk = (d_in + kBlk - 1) / kBlk;
+  L.ldp = L.n_blk * kBlk;
+  const int64_t m = d_out / G;
+  L.n_rt = (int)((m + kRows - 1) / kRows);
+  // enough workgroups to fill the chip, at least one 16-step stage per wave
+  int parts = (int)(512 / ((int64_t)L.n_rt * G));
+  const int max_parts = (int)(L.ldp / 16 / 4);
+  if (parts > max_parts) parts = max_parts;
+  if (parts > 8) parts = 8;
+  if (parts < 1) parts = 1;
+  L.n_parts = parts;
+  auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+  L.ht_bytes = up((size_t)G * L.ldp * L.ldp * 2);
+  L.cdt_bytes = up((size_t)G * L.n_blk * kBlk * kBlk * sizeof(float));
+  L.delta_bytes = up((size_t)d_out * L.ldp * 2);
+  L.c_bytes = up((size_t)L.n_parts * kBlk * d_out * sizeof(float));
+  return L;
+}
+
+}  // namespace
+
+size_t cd_workspace(int64_t d_out, int64_t d_in, int G) {
+  const Layout L = make_layout(d_out, d_in, G);
+  return 2 * L.ht_bytes + 2 * L.cdt_bytes + 2 * L.delta_bytes + L.c_bytes;
+}
+
+hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
+                            int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q,
+                            void* ws, hipStream_t st) {
+  const Layout L = make_layout(d_out, d_in, G);
+  char* p = (char*)ws;
+  unsigned short* Hth = (unsigned short*)p;
+  p += L.ht_bytes;
+  unsigned short* Htl = (unsigned short*)p;
+  p += L.ht_bytes;
+  float* Cd = (float*)p;
+  p += L.cdt_bytes;
+  float* CdT = (float*)p;
+  p += L.cdt_bytes;
+  unsigned short* Dh = (unsigned short*)p;
+  p += L.delta_bytes;
+  unsigned short* Dl = (unsigned short*)p;
+  p += L.delta_bytes;
+  float* C = (float*)p;
+
+  hipError_t e;
+  const unsigned t64 = (unsigned)(L.ldp / 64);
+  cd_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd, CdT);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  {
+    int64_t bx = (L.ldp + 255) / 256;
+    if (bx > 64) bx = 64;
+    cd_delta_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(W, What, d_in, ld, L.ldp, Dh, Dl);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  const unsigned n_tiles = (unsigned)(L.n_rt * G);
+  for (int cycle = 0; cycle < n_cycles; ++cycle)
+    for (int blk = 0; blk < (int)L.n_blk; ++blk) {
+      cd_block_gemm_kernel<<<dim3(n_tiles, (unsigned)L.n_parts), dim3(256), 0, st>>>(Dh, Dl, Hth, Htl, d_out, L.ldp, G, L.n_rt,
+                                                                                    blk, C);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      cd_block_seq_kernel<<<dim3(n_tiles), dim3(kRows), 0, st>>>(C, L.n_parts, W, What, codebook, n_levels, Cd, CdT, d_out, d_in,
+                                                                  ld, L.ldp, G, L.n_rt, blk, Q, Dh, Dl);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+  return hipSuccess;
+}
+
+}  // namespace gq

@@ -96,4 +96,24 @@ int gq_objective(const float* W, const float* What, int64_t d_out, int64_t d_in,
                                        (hipStream_t)hip_stream));
 }
 
+size_t gq_cd_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G) {
+  if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0) return 0;
+  return gq::cd_workspace(d_out, d_in, G);
+}
+
+int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_levels, int64_t d_out, int64_t d_in,
+                 int64_t ld_w, const float* H, int32_t G, int32_t n_cycles, uint8_t* Q, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_cycles < 0 || n_levels <= 0)
+    return GQ_ERR_SHAPE;
+  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (!W || !What || !codebook || !H) return GQ_ERR_NULLPTR;
+  if (!aligned16(W) || !aligned16(What) || !aligned16(H) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;
+  const size_t need = gq_cd_workspace_bytes(d_out, d_in, G);
+  if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
+  if (n_cycles == 0) return GQ_OK;
+  return from_hip(gq::launch_cd_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, H, G, n_cycles, Q, workspace,
+                                       (hipStream_t)hip_stream));
+}
+
 }  // extern "C"

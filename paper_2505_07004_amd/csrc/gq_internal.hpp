@@ -110,4 +110,9 @@ hipError_t launch_objective(const float* W, const float* What, int64_t d_out, in
                             hipStream_t st);
 size_t objective_workspace(int64_t d_out, int64_t d_in, int G);
 
+hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
+                            int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q,
+                            void* ws, hipStream_t st);
+size_t cd_workspace(int64_t d_out, int64_t d_in, int G);
+
 }  // namespace gq

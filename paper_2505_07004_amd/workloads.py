@@ -86,10 +86,11 @@ def quantize_uniform_per_row(W: torch.Tensor, levels: int = 16) -> torch.Tensor:
     return (lo + q * step).to(torch.float32).contiguous()
 
 
-def quantize_codebook_per_row(W: torch.Tensor, bits: int = 3, iters: int = 5) -> torch.Tensor:
+def quantize_codebook_per_row(W: torch.Tensor, bits: int = 3, iters: int = 5, return_codebook: bool = False):
     """Assign every entry of a row to the nearest of 2**bits per-row codebook
     values: codebook initialised at the (2q+1)/2^(bits+1) quantiles of the row
-    and refined by `iters` unweighted 1-D Lloyd iterations (ties -> lower index)."""
+    and refined by `iters` unweighted 1-D Lloyd iterations (ties -> lower index).
+    With return_codebook also returns that codebook, [d_out, 2**bits] fp32."""
     m = 1 << bits
     d_out, d_in = W.shape
     qs = (2 * torch.arange(m, device=W.device, dtype=torch.float32) + 1) / (2 * m)
@@ -110,7 +111,9 @@ def quantize_codebook_per_row(W: torch.Tensor, bits: int = 3, iters: int = 5) ->
             c = torch.where(cnt > 0, tot / cnt.clamp(min=1), c)
         idx = torch.argmin((w[:, :, None] - c[:, None, :]).abs(), dim=2)
         out[r0:r1] = torch.gather(c, 1, idx)
-    return out.to(torch.float32).contiguous()
+        code[r0:r1] = c
+    out = out.to(torch.float32).contiguous()
+    return (out, code.to(torch.float32).contiguous()) if return_codebook else out
 
 
 @dataclass

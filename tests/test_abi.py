@@ -21,7 +21,7 @@ def test_header_declares_the_expected_calls():
     syms = _declared_symbols()
     for name in ("gq_group_weights", "gq_fisher_gram", "gq_objective", "gq_fisher_mirror",
                  "gq_fisher_gram_workspace_bytes", "gq_objective_workspace_bytes",
-                 "gq_version", "gq_status_string"):
+                 "gq_cd_assign", "gq_cd_workspace_bytes", "gq_version", "gq_status_string"):
         assert name in syms
 
 
@@ -69,6 +69,18 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_objective(a16, a16, 8, 6, 6, a16, 4, a16, None, P(0x1100), 1 << 20, None) == -4
     assert lib.gq_objective_workspace_bytes(8, 8, 4) > 0
     assert lib.gq_objective_workspace_bytes(10, 8, 4) == 0
+    # coordinate-descent assignment step
+    big = 1 << 30
+    assert lib.gq_cd_assign(a16, a16, a16, 8, 10, 8, 8, a16, 4, 1, None, P(0x1100), big, None) == -2     # G does not divide d_out
+    assert lib.gq_cd_assign(a16, a16, a16, 0, 8, 8, 8, a16, 4, 1, None, P(0x1100), big, None) == -2      # no grid points
+    assert lib.gq_cd_assign(a16, a16, a16, 8, 8, 8, 8, a16, 4, -1, None, P(0x1100), big, None) == -2     # negative cycles
+    assert lib.gq_cd_assign(a16, a16, a16, 17, 8, 8, 8, a16, 4, 1, None, P(0x1100), big, None) == -7     # more than 16 grid points
+    assert lib.gq_cd_assign(a16, a16, None, 8, 8, 8, 8, a16, 4, 1, None, P(0x1100), big, None) == -1
+    assert lib.gq_cd_assign(a16, a16, a16, 8, 8, 6, 6, a16, 4, 1, None, P(0x1100), big, None) == -4      # pitch not a multiple of 16 bytes
+    assert lib.gq_cd_assign(a16, a16, a16, 8, 8, 8, 8, a16, 4, 1, None, P(0x1100), 16, None) == -5
+    assert lib.gq_cd_assign(a16, a16, a16, 8, 8, 8, 8, a16, 4, 0, None, P(0x1100), big, None) == 0       # zero cycles: nothing to do
+    assert lib.gq_cd_workspace_bytes(8, 8, 4) > 0
+    assert lib.gq_cd_workspace_bytes(10, 8, 4) == 0
 
 
 def test_binding_refuses_cpu_tensors():

@@ -1,0 +1,133 @@
+"""The coordinate-descent assignment step on the GPU (through the C ABI) against the fp64 oracle.
+
+The step is a sequence of rounding decisions, each depending on all earlier ones, and the GPU
+evaluates the sums in fp32-grade arithmetic: a target within rounding distance of the midpoint
+of two grid points may legitimately go either way, after which the two trajectories differ.
+So the tests compare what is unique and check that the rest is valid:
+  * every decision the GPU took is re-derived in fp64 FROM THE GPU'S OWN TRAJECTORY (one cycle
+    per call, so the state at every coordinate is known from the call's input and output): the
+    chosen grid point must be the nearest one up to a small slack, and where it is not the
+    oracle's choice the target must sit at a midpoint up to that slack;
+  * the codes agree with the oracle's for all but a tiny fraction of the entries;
+  * the layer objective never increases (Prop. 4.1) and ends within 1e-3 of the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_07004_amd import binding as gq
+from paper_2505_07004_amd import workloads as wl
+from parity_utils import say, to_np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _case(n, d_in, d_out, G, bits, seed, ld=None):
+    X = wl.make_x_outlier(n, d_in, max(1, d_in // 64), 20.0, seed, DEV, torch.float32)
+    dZ = wl.make_dz(n, d_out, 1.0, 1.5, seed + 1, DEV)
+    s = gq.gq_group_weights(dZ, G)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))   # damping, as every user of H adds
+    W = wl.make_w(d_out, d_in, seed + 2, DEV)
+    What, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
+    if ld:
+        buf = torch.zeros((2, d_out, ld), device=DEV)
+        buf[0, :, :d_in], buf[1, :, :d_in] = W, What
+        W, What = buf[0, :, :d_in], buf[1, :, :d_in]
+    return W, What, C.contiguous(), H
+
+
+def _targets_along(Wn, old, new, Hn, G):
+    """t[j, i] of Eq. (cd_closed) for the state in which coordinate i was updated during one cycle
+    that turned `old` into `new`: coordinates < i new, coordinates > i old."""
+    d_out, d_in = Wn.shape
+    m = d_out // G
+    T = np.empty_like(Wn)
+    for k in range(G):
+        r = slice(k * m, (k + 1) * m)
+        Ht = Hn[k] / np.diag(Hn[k])[:, None]
+        lower, upper = np.tril(Ht, -1), np.triu(Ht, 1)
+        T[r] = Wn[r] - (new[r] - Wn[r]) @ lower.T - (old[r] - Wn[r]) @ upper.T
+    return T
+
+
+def _check_cycle(Wn, old, new, Qg, Cn, Hn, G, what):
+    d_out, d_in = Wn.shape
+    T = _targets_along(Wn, old, new, Hn, G)
+    dist = np.abs(Cn[:, None, :] - T[:, :, None])                     # [d_out, d_in, m]
+    chosen = np.take_along_axis(dist, Qg[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    best = dist.min(axis=2)
+    # slack: fp32-grade evaluation of a sum whose terms are ~ |Ht| |delta|
+    scale = np.abs(Wn) + np.abs(T) + 1e-30
+    slack = 2e-5 * scale + 1e-6 * np.abs(Cn).max(axis=1)[:, None]
+    bad = chosen > best + 2 * slack
+    say(f"{what}: decisions off the nearest grid point by more than the slack: {int(bad.sum())} of {bad.size}; "
+        f"max excess {float((chosen - best).max()):.2e}")
+    assert not bad.any()
+    assert np.array_equal(new, np.take_along_axis(Cn, Qg.astype(np.int64), axis=1))   # What is the grid value of its code, exactly
+
+
+@pytest.mark.parametrize("n,d_in,d_out,G,bits,ld", [
+    (512, 256, 128, 2, 3, None),        # two blocks, one row tile per group
+    (400, 200, 96, 4, 2, 208),          # ragged last block, 24 channels per group, padded pitch
+    (600, 384, 192, 1, 4, None),        # 16 grid points, three row tiles
+    (300, 132, 40, 2, 3, 136),          # last block of 4 coordinates
+])
+def test_cd_one_cycle_decisions_are_valid_and_match_the_oracle(n, d_in, d_out, G, bits, ld):
+    say(f"cd n={n} d_in={d_in} d_out={d_out} G={G} bits={bits} ld={ld}")
+    W, What, C, H = _case(n, d_in, d_out, G, bits, 31 + d_in, ld)
+    Wn, old, Cn, Hn = to_np64(W), to_np64(What), to_np64(C), to_np64(H)
+    Qg = gq.gq_cd_assign(W, What, C, H, n_cycles=1)
+    torch.cuda.synchronize()
+    new = to_np64(What)
+    Qg = Qg.cpu().numpy()
+    _check_cycle(Wn, old, new, Qg, Cn, Hn, G, "one cycle")
+    Qo, ref = oracle.cd_assign(Wn, old, Cn, Hn, G, n_cycles=1)
+    differ = float(np.mean(Qo != Qg))
+    o0 = oracle.objective(Wn, old, Hn, G)[0]
+    og, oo = oracle.objective(Wn, new, Hn, G)[0], oracle.objective(Wn, ref, Hn, G)[0]
+    say(f"  codes that differ from the oracle's: {100 * differ:.3f} %; objective {o0} -> gpu {og}, oracle {oo}")
+    assert differ <= 5e-3
+    assert np.all(og <= o0 * (1 + 1e-9)) and np.all(np.abs(og - oo) <= 1e-3 * oo)
+
+
+def test_cd_cycles_in_one_call_equal_chained_calls_and_descend_to_the_oracle_level():
+    W, What, C, H = _case(512, 256, 128, 2, 3, 77)
+    Wn, Cn, Hn = to_np64(W), to_np64(C), to_np64(H)
+    chained = What.clone()
+    prev = oracle.objective(Wn, to_np64(chained), Hn, 2)[0]
+    for cycle in range(3):
+        old = to_np64(chained)
+        Qc = gq.gq_cd_assign(W, chained, C, H, n_cycles=1)
+        torch.cuda.synchronize()
+        _check_cycle(Wn, old, to_np64(chained), Qc.cpu().numpy(), Cn, Hn, 2, f"cycle {cycle}")
+        val = oracle.objective(Wn, to_np64(chained), Hn, 2)[0]
+        assert np.all(val <= prev * (1 + 1e-9))
+        prev = val
+    once = What.clone()
+    Q3 = gq.gq_cd_assign(W, once, C, H, n_cycles=3)
+    torch.cuda.synchronize()
+    assert torch.equal(once, chained) and torch.equal(Q3, Qc)          # same kernels, same order: bit-identical
+    _, ref = oracle.cd_assign(Wn, to_np64(What), Cn, Hn, 2, n_cycles=3)
+    oo = oracle.objective(Wn, ref, Hn, 2)[0]
+    say(f"3 cycles: objective gpu {prev}, oracle {oo}")
+    assert np.all(np.abs(prev - oo) <= 2e-3 * oo)
+
+
+def test_cd_diagonal_hessian_is_round_to_nearest_and_zero_cycles_is_a_no_op():
+    d_out, d_in = 64, 160
+    W = wl.make_w(d_out, d_in, 5, DEV)
+    What, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)
+    C = C.contiguous()
+    start = What[:, torch.randperm(d_in, device=DEV)].contiguous()      # a feasible but poor start
+    start = torch.gather(C, 1, torch.randint(0, 8, (d_out, d_in), device=DEV))
+    H = torch.diag_embed(torch.rand(2, d_in, device=DEV) + 0.5)
+    keep = start.clone()
+    assert gq.gq_cd_assign(W, start, C, H, n_cycles=0) is not None
+    assert torch.equal(start, keep)
+    Q = gq.gq_cd_assign(W, start, C, H, n_cycles=1)
+    torch.cuda.synchronize()
+    rtn = torch.argmin((C[:, None, :] - W[:, :, None]).abs(), dim=2)
+    assert torch.equal(Q.long(), rtn)
+    assert torch.equal(start, torch.gather(C, 1, rtn))

@@ -24,7 +24,7 @@ namespace {
 
 constexpr int kBlk = 128;             // coordinates per block
 constexpr int kRows = 64;             // channels per workgroup row tile (GEMM) / per wave (sequential kernel)
-constexpr int kMaxLevels = 16;        // grid points per channel (4 bits)
+constexpr int kMaxLevels = 16;        // most grid points per channel (4 bits)
 
 __device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
   const __bf16 h = (__bf16)x;
@@ -34,14 +34,13 @@ __device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& l
 }
 
 // Ht (hi/lo bf16, [G][ldp][ldp], row i contiguous over i', zero diagonal and zero padding) and
-// the fp32 coefficients of every diagonal block in both orientations,
-//   Cd[k][blk][b][a] = CdT[k][blk][a][b] = Ht[blk*128 + b][blk*128 + a]
+// the fp32 coefficients of every diagonal block,
+//   Cd[k][blk][b][a] = Ht[blk*128 + b][blk*128 + a]
 // (what the target of coordinate b moves by, per unit change of coordinate a).
 // Only the upper triangle of H is read.  One workgroup per 64 x 64 tile.
 __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ H, int64_t d, int64_t ldp,
                                                       unsigned short* __restrict__ Hth,
-                                                      unsigned short* __restrict__ Htl, float* __restrict__ Cd,
-                                                      float* __restrict__ CdT) {
+                                                      unsigned short* __restrict__ Htl, float* __restrict__ Cd) {
   __shared__ float tile[64][65];
   __shared__ float diag[64];
   const int k = blockIdx.z;
@@ -76,7 +75,6 @@ __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ 
       const int64_t blk = i / kBlk;
       const int64_t base = ((int64_t)k * n_blk + blk) * kBlk * kBlk;
       Cd[base + (i % kBlk) * kBlk + (ip % kBlk)] = v;
-      CdT[base + (ip % kBlk) * kBlk + (i % kBlk)] = v;
     }
   }
 }
@@ -212,24 +210,26 @@ __global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short
 
 // The sequential walk through block `blk`: one wave per 64 channels of a group, one thread per
 // channel.  The block of W and What is moved between global memory and LDS row by row
-// (coalesced); a lane works on column `lane` of the LDS arrays.  The 128 targets of a channel
-// live in LDS; the block is walked in four runs of 32 coordinates whose targets sit in
-// registers: inside a run every update corrects the later targets of the run at once, the
-// targets after the run are corrected when the run is over (32 changes at a time).  Lanes past
-// the end of the group repeat its last channel, so the whole wave stays active throughout.
+// (coalesced); a lane works on column `lane` of the LDS arrays.  The block's 128 x 128
+// coefficients sit in LDS too (every lane reads the same one: a broadcast).  The 128 targets
+// of a channel live in LDS; the block is walked in four runs of 32 coordinates whose targets
+// sit in registers: inside a run every update corrects the later targets of the run at once,
+// the targets after the run are corrected when the run is over (32 changes at a time).  Lanes
+// past the end of the group repeat its last channel, so the whole wave stays active throughout.
+// LV = 4, 8 or 16 bounds the number of grid points (the search is unrolled over it).
 constexpr int kRun = 32;
+template <int LV>
 __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __restrict__ C, int n_parts,
                                                              const float* __restrict__ W, float* __restrict__ What,
                                                              const float* __restrict__ codebook, int n_levels,
-                                                             const float* __restrict__ Cd,
-                                                             const float* __restrict__ CdT, int64_t d_out, int64_t d,
+                                                             const float* __restrict__ Cd, int64_t d_out, int64_t d,
                                                              int64_t ld, int64_t ldp, int G, int n_rt, int blk,
                                                              unsigned char* __restrict__ Q,
                                                              unsigned short* __restrict__ Dh,
                                                              unsigned short* __restrict__ Dl) {
-  __shared__ float wblk[kBlk][kRows + 1];                  // the block of W
+  __shared__ float tw[kBlk][kRows + 1];                    // the block of W; then the targets; then W again
   __shared__ float cur[kBlk][kRows + 1];                   // the block of What, old values then new ones
-  __shared__ float tgt[kBlk][kRows];                       // the targets t[i] of every channel
+  __shared__ __attribute__((aligned(16))) float coef[kBlk][kBlk];   // coef[b][a] = Ht[i0 + b][i0 + a]
   __shared__ unsigned char code[kBlk][kRows + 4];
   const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
   const int64_t m = d_out / G;
@@ -239,37 +239,61 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
   const int n_rows = (int)((j_last - j0 + 1) < kRows ? (j_last - j0 + 1) : kRows);
   const int64_t i0 = (int64_t)blk * kBlk;
   const int n_valid = (int)((d - i0) < kBlk ? (d - i0) : kBlk);   // coordinates of this block inside the matrix
-  const int64_t cbase = (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk;
-  const float* coef_b = Cd + cbase;                        // [b][a]
-  const float* coef_a = CdT + cbase;                       // [a][b]
 
-  for (int r = 0; r < kRows; ++r) {
-    const int64_t jr = r < n_rows ? j0 + r : j_last;
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int i = lane + 64 * half;
-      const int64_t a = (i0 + i) < d ? (i0 + i) : d - 1;
-      wblk[i][r] = W[jr * ld + a];
-      cur[i][r] = What[jr * ld + a];
-    }
+  {
+    const f32x4* src = reinterpret_cast<const f32x4*>(Cd + (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk);
+    f32x4* dst = reinterpret_cast<f32x4*>(&coef[0][0]);
+#pragma unroll 8
+    for (int q = lane; q < kBlk * kBlk / 4; q += kRows) dst[q] = src[q];
   }
+  // rows of W (and What) in batches of 8, all loads of a batch in flight together
+  auto load_rows = [&](bool with_what) {
+    for (int r0 = 0; r0 < kRows; r0 += 8) {
+      float wv[8][2], cv[8][2];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int64_t jr = (r0 + u) < n_rows ? j0 + r0 + u : j_last;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int i = lane + 64 * half;
+          const int64_t a = (i0 + i) < d ? (i0 + i) : d - 1;
+          wv[u][half] = W[jr * ld + a];
+          if (with_what) cv[u][half] = What[jr * ld + a];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          tw[lane + 64 * half][r0 + u] = wv[u][half];
+          if (with_what) cur[lane + 64 * half][r0 + u] = cv[u][half];
+        }
+    }
+  };
+  load_rows(true);
   __syncthreads();
 
-  float grid[kMaxLevels];
+  float grid[LV];
 #pragma unroll
-  for (int q = 0; q < kMaxLevels; ++q) grid[q] = codebook[j * n_levels + (q < n_levels ? q : n_levels - 1)];
+  for (int q = 0; q < LV; ++q) grid[q] = codebook[j * n_levels + (q < n_levels ? q : n_levels - 1)];
 
-  // targets t[i] = w[i] - B0[i]; B0 = sum of the parts in order
-  for (int i = 0; i < kBlk; ++i) {
-    float b = 0.f;
-    for (int p = 0; p < n_parts; ++p) b += C[((int64_t)p * kBlk + i) * d_out + j];
-    tgt[i][lane] = wblk[i][lane] - b;
+  // targets t[i] = w[i] - B0[i], in place; B0 = sum of the parts in order (16 coordinates in flight)
+  for (int ib = 0; ib < kBlk; ib += 16) {
+    float b[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) b[u] = 0.f;
+    for (int p = 0; p < n_parts; ++p) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) b[u] += C[((int64_t)p * kBlk + ib + u) * d_out + j];
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) tw[ib + u][lane] -= b[u];
   }
 
   for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
     float t[kRun], eps[kRun];
 #pragma unroll
-    for (int ii = 0; ii < kRun; ++ii) t[ii] = tgt[c0 + ii][lane];
+    for (int ii = 0; ii < kRun; ++ii) t[ii] = tw[c0 + ii][lane];
 #pragma unroll
     for (int ii = 0; ii < kRun; ++ii) {
       eps[ii] = 0.f;
@@ -278,7 +302,7 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
         float best = fabsf(grid[0] - ti), val = grid[0];
         int bq = 0;
 #pragma unroll
-        for (int q = 1; q < kMaxLevels; ++q) {
+        for (int q = 1; q < LV; ++q) {
           const float dist = fabsf(grid[q] - ti);
           const bool better = (q < n_levels) && (dist < best);   // equally near: the lower index stays
           best = better ? dist : best;
@@ -289,19 +313,23 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
         cur[c0 + ii][lane] = val;
         code[c0 + ii][lane] = (unsigned char)bq;
         eps[ii] = e;
-        const float* row = coef_a + (int64_t)(c0 + ii) * kBlk + c0;   // Ht[c0 + ii2][c0 + ii] over ii2
 #pragma unroll
-        for (int ii2 = ii + 1; ii2 < kRun; ++ii2) t[ii2] -= e * row[ii2];
+        for (int ii2 = ii + 1; ii2 < kRun; ++ii2) t[ii2] -= e * coef[c0 + ii2][c0 + ii];
       }
     }
     for (int i2 = c0 + kRun; i2 < n_valid; ++i2) {          // the targets after the run
-      const float* row = coef_b + (int64_t)i2 * kBlk + c0;  // Ht[i2][c0 + ii] over ii
+      const f32x4* row = reinterpret_cast<const f32x4*>(&coef[i2][c0]);
       float a = 0.f;
 #pragma unroll
-      for (int ii = 0; ii < kRun; ++ii) a += eps[ii] * row[ii];
-      tgt[i2][lane] -= a;
+      for (int q4 = 0; q4 < kRun / 4; ++q4) {
+        const f32x4 cf = row[q4];
+        a += eps[4 * q4] * cf[0] + eps[4 * q4 + 1] * cf[1] + eps[4 * q4 + 2] * cf[2] + eps[4 * q4 + 3] * cf[3];
+      }
+      tw[i2][lane] -= a;
     }
   }
+  __syncthreads();
+  load_rows(false);                                         // W again, for the new delta
   __syncthreads();
 
   // write the block back row by row: What, the codes, and the split delta for the next block's GEMM
@@ -316,7 +344,7 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
         What[jr * ld + a] = v;
         if (Q) Q[jr * d + a] = code[i][r];
         unsigned short h, l;
-        split_bf16(v - wblk[i][r], h, l);
+        split_bf16(v - tw[i][r], h, l);
         Dh[jr * ldp + a] = h;
         Dl[jr * ldp + a] = l;
       }
@@ -354,7 +382,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
 
 size_t cd_workspace(int64_t d_out, int64_t d_in, int G) {
   const Layout L = make_layout(d_out, d_in, G);
-  return 2 * L.ht_bytes + 2 * L.cdt_bytes + 2 * L.delta_bytes + L.c_bytes;
+  return 2 * L.ht_bytes + L.cdt_bytes + 2 * L.delta_bytes + L.c_bytes;
 }
 
 hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
@@ -368,8 +396,6 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
   p += L.ht_bytes;
   float* Cd = (float*)p;
   p += L.cdt_bytes;
-  float* CdT = (float*)p;
-  p += L.cdt_bytes;
   unsigned short* Dh = (unsigned short*)p;
   p += L.delta_bytes;
   unsigned short* Dl = (unsigned short*)p;
@@ -378,7 +404,7 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
 
   hipError_t e;
   const unsigned t64 = (unsigned)(L.ldp / 64);
-  cd_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd, CdT);
+  cd_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
     int64_t bx = (L.ldp + 255) / 256;
@@ -392,8 +418,17 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
       cd_block_gemm_kernel<<<dim3(n_tiles, (unsigned)L.n_parts), dim3(256), 0, st>>>(Dh, Dl, Hth, Htl, d_out, L.ldp, G, L.n_rt,
                                                                                     blk, C);
       if ((e = hipGetLastError()) != hipSuccess) return e;
-      cd_block_seq_kernel<<<dim3(n_tiles), dim3(kRows), 0, st>>>(C, L.n_parts, W, What, codebook, n_levels, Cd, CdT, d_out, d_in,
-                                                                  ld, L.ldp, G, L.n_rt, blk, Q, Dh, Dl);
+#define GQ_LAUNCH_SEQ(LV)                                                                                              \
+  cd_block_seq_kernel<LV><<<dim3(n_tiles), dim3(kRows), 0, st>>>(C, L.n_parts, W, What, codebook, n_levels, Cd, d_out,      \
+                                                                 d_in, ld, L.ldp, G, L.n_rt, blk, Q, Dh, Dl)
+      if (n_levels <= 4) {
+        GQ_LAUNCH_SEQ(4);
+      } else if (n_levels <= 8) {
+        GQ_LAUNCH_SEQ(8);
+      } else {
+        GQ_LAUNCH_SEQ(kMaxLevels);
+      }
+#undef GQ_LAUNCH_SEQ
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
   return hipSuccess;

@@ -100,6 +100,8 @@ def main():
                     help="also run one plain 1 GiB elementwise copy kernel (reference point for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the pure-MFMA ceiling measurement")
+    ap.add_argument("--cd-cycles", type=int, default=1,
+                    help="cycles of the coordinate-descent assignment step timed after the main loop (0: skip)")
     ap.add_argument("--tokens", type=int, default=0, help="override n (debugging only; invalid as a result)")
     ap.add_argument("--groups", type=int, default=0, help="override G (the 13B sweep runs G in 1, 2, 4, 8)")
     args = ap.parse_args()
@@ -202,6 +204,36 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": load_traffic(spec.name),
                      "flop_per_launch": fl, "ms_per_launch": gram_ms},
     }
+
+    if args.cd_cycles > 0:
+        # The step that consumes H (Section 4.2): timed on its own, after the hot path, on the H just
+        # built (diagonal damped by 1 % of its mean, as every user of H does) and the 3-bit grids.
+        Hd = H + 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+        _, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)
+        ws_c = torch.empty(int(lib.gq_cd_workspace_bytes(d_out, d_in, G)), dtype=torch.uint8, device=dev)
+        Wq = What.clone()
+        gq.gq_cd_assign(W, Wq, C, Hd, n_cycles=1, want_codes=False, workspace=ws_c)      # warm-up
+        Wq = What.clone()
+        o_before = gq.gq_objective(W, Wq, Hd, workspace=ws_o)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        gq.gq_cd_assign(W, Wq, C, Hd, n_cycles=args.cd_cycles, want_codes=False, workspace=ws_c)
+        e1.record()
+        o_after = gq.gq_objective(W, Wq, Hd, workspace=ws_o)
+        torch.cuda.synchronize()
+        cd_ms = e0.elapsed_time(e1)
+        cd_fl = 2.0 * d_out * d_in * d_in * args.cd_cycles          # the sums of Eq. (cd_closed), once per coordinate and cycle
+        result["cd_assign"] = {
+            "cycles": args.cd_cycles, "ms": cd_ms, "ms_per_cycle": cd_ms / args.cd_cycles, "levels": 8,
+            "objective_before": [float(v) for v in o_before.tolist()], "objective_after": [float(v) for v in o_after.tolist()],
+            "roofline": {"bound": "mfma", "achieved": cd_fl / (cd_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS / 3,
+                         "unit": "TFLOP/s", "frac": cd_fl / (cd_ms * 1e-3) / 1e12 / (PEAK_BF16_TFLOPS / 3), "traffic": None,
+                         "note": "fp32-grade multiply-adds (three bf16 MFMA products each), 2*d_out*d_in^2 per cycle; "
+                                 "the walk inside a block of 128 coordinates is sequential"},
+        }
+        log(f"cd_assign: {cd_ms / args.cd_cycles:.2f} ms per cycle; objective {result['cd_assign']['objective_before']} -> "
+            f"{result['cd_assign']['objective_after']}")
+        del Hd, Wq, ws_c
 
     if not args.no_ceiling:
         ceil = mfma_ceiling()

@@ -40,31 +40,39 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
 
 def _targets_along(Wn, old, new, Hn, G):
     """t[j, i] of Eq. (cd_closed) for the state in which coordinate i was updated during one cycle
-    that turned `old` into `new`: coordinates < i new, coordinates > i old."""
+    that turned `old` into `new` (coordinates < i new, coordinates > i old), and the sum of the
+    absolute values of the terms of its sum, S[j, i] = sum_i' |Ht[i, i']| |delta[j, i']|."""
     d_out, d_in = Wn.shape
     m = d_out // G
-    T = np.empty_like(Wn)
+    T, S = np.empty_like(Wn), np.empty_like(Wn)
     for k in range(G):
         r = slice(k * m, (k + 1) * m)
         Ht = Hn[k] / np.diag(Hn[k])[:, None]
         lower, upper = np.tril(Ht, -1), np.triu(Ht, 1)
-        T[r] = Wn[r] - (new[r] - Wn[r]) @ lower.T - (old[r] - Wn[r]) @ upper.T
-    return T
+        dn, do = new[r] - Wn[r], old[r] - Wn[r]
+        T[r] = Wn[r] - dn @ lower.T - do @ upper.T
+        S[r] = np.abs(dn) @ np.abs(lower).T + np.abs(do) @ np.abs(upper).T
+    return T, S
 
 
 def _check_cycle(Wn, old, new, Qg, Cn, Hn, G, what):
-    d_out, d_in = Wn.shape
-    T = _targets_along(Wn, old, new, Hn, G)
+    """Slack of a decision: the GPU forms every product of the sum from two-term bf16 splits of both
+    factors and drops the lo*lo product, a relative error below 2^-15 per term in the worst case, and
+    adds the terms in fp32; so its target is within 2^-14 * S + 2^-20 * |t| of the exact one, and the
+    grid point it picks can be farther from the exact target than the nearest one by at most twice that."""
+    T, S = _targets_along(Wn, old, new, Hn, G)
     dist = np.abs(Cn[:, None, :] - T[:, :, None])                     # [d_out, d_in, m]
     chosen = np.take_along_axis(dist, Qg[:, :, None].astype(np.int64), axis=2)[:, :, 0]
     best = dist.min(axis=2)
-    # slack: fp32-grade evaluation of a sum whose terms are ~ |Ht| |delta|
-    scale = np.abs(Wn) + np.abs(T) + 1e-30
-    slack = 2e-5 * scale + 1e-6 * np.abs(Cn).max(axis=1)[:, None]
-    bad = chosen > best + 2 * slack
+    slack = 2.0 ** -14 * S + 2.0 ** -20 * np.abs(T)
+    excess = chosen - best
+    bad = excess > 2 * slack
+    spacing = np.median(np.diff(np.sort(Cn, axis=1), axis=1))
     say(f"{what}: decisions off the nearest grid point by more than the slack: {int(bad.sum())} of {bad.size}; "
-        f"max excess {float((chosen - best).max()):.2e}")
+        f"max excess {float(excess.max()):.2e}, largest slack {float(2 * slack.max()):.2e}, median grid spacing {spacing:.2e}")
     assert not bad.any()
+    assert 2 * slack.max() <= 0.1 * spacing                            # the bound is small against the grid itself,
+    assert np.mean(excess > 0) <= 2e-3                                 # and almost every decision IS the exact nearest point
     assert np.array_equal(new, np.take_along_axis(Cn, Qg.astype(np.int64), axis=1))   # What is the grid value of its code, exactly
 
 
@@ -131,3 +139,44 @@ def test_cd_diagonal_hessian_is_round_to_nearest_and_zero_cycles_is_a_no_op():
     rtn = torch.argmin((C[:, None, :] - W[:, :, None]).abs(), dim=2)
     assert torch.equal(Q.long(), rtn)
     assert torch.equal(start, torch.gather(C, 1, rtn))
+
+
+def test_cd_at_the_llama2_7b_shape_on_sampled_channels():
+    """Full size of workload configuration 2 (d_out = d_in = 4096, G = 4, 3-bit grids), one cycle.
+    The fp64 replay along the GPU's trajectory needs, for a channel, only that channel's rows of
+    W / What and its group's H, so it is run for 48 sampled channels of every group."""
+    spec = wl.CONFIGS["llama2_7b_attn"]
+    say(f"cd at {spec.name}: W[{spec.d_out},{spec.d_in}] G={spec.G}")
+    X = wl.make_x(spec, DEV)
+    s = gq.gq_group_weights(wl.make_dz_for(spec, DEV), spec.G)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    del X, s
+    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, spec.d_in))
+    W = wl.make_w(spec.d_out, spec.d_in, 7, DEV)
+    What, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)
+    old = What.clone()
+    before = gq.gq_objective(W, What, H)
+    Q = gq.gq_cd_assign(W, What, C, H, n_cycles=1)
+    after = gq.gq_objective(W, What, H)
+    torch.cuda.synchronize()
+    say(f"  objective {before.tolist()} -> {after.tolist()}")
+    assert torch.all(after < before)
+    assert torch.equal(What, torch.gather(C, 1, Q.long()))
+    m = spec.d_out // spec.G
+    g = torch.Generator().manual_seed(5)
+    for k in range(spec.G):
+        rows = (k * m + torch.randperm(m, generator=g)[:48]).to(DEV)
+        Hk = to_np64(H[k])[None]
+        _check_cycle(to_np64(W[rows]), to_np64(old[rows]), to_np64(What[rows]), Q[rows].cpu().numpy(), to_np64(C[rows]),
+                     Hk, 1, f"config 2 shape, group {k}, 48 sampled channels")
+        # the oracle's own cycle on 4 of them: one flipped near-tie early in a channel changes many later
+        # decisions of that channel, so at this length only the quality of the result is comparable
+        r4 = rows[:4]
+        Qo, ref = oracle.cd_assign(to_np64(W[r4]), to_np64(old[r4]), to_np64(C[r4]), Hk, 1, n_cycles=1)
+        differ = float(np.mean(Qo != Q[r4].cpu().numpy()))
+        o_start = oracle.objective(to_np64(W[r4]), to_np64(old[r4]), Hk, 1)[1]
+        o_gpu = oracle.objective(to_np64(W[r4]), to_np64(What[r4]), Hk, 1)[1]
+        o_ref = oracle.objective(to_np64(W[r4]), ref, Hk, 1)[1]
+        say(f"  group {k}: 4 channels, codes that differ from the oracle's {100 * differ:.2f} %; "
+            f"objective start {o_start.sum():.5f}, gpu {o_gpu.sum():.5f}, oracle {o_ref.sum():.5f}")
+        assert np.all(o_gpu < o_start) and abs(o_gpu.sum() - o_ref.sum()) <= 1e-2 * o_ref.sum()

@@ -1,6 +1,9 @@
 """Pins for the CPU oracle: closed forms, a hand-worked example, an independent
 BLAS routine, and brute force through the paper's *un-averaged* definitions.
 None of these tests touches the HIP path."""
+import json
+import os
+
 import numpy as np
 import pytest
 import scipy.linalg.blas as blas
@@ -14,14 +17,15 @@ def _rng(seed):
 
 # ---------------------------------------------------------------- worked example
 # Worked by hand from Algorithm 1 (lines 1, 2, 4) and Eq. (ours2); n=3, d_in=2,
-# d_out=4, G=2 so J_0={0,1}, J_1={2,3}.
-X_EX = np.array([[1.0, 2.0], [3.0, 4.0], [0.0, -1.0]])
-DZ_EX = np.array([[1.0, -1.0, 2.0, 0.0], [0.0, 2.0, 1.0, 1.0], [3.0, 0.0, 0.0, 1.0]])
-S_EX = np.array([[1.0, 2.0], [2.0, 1.0], [4.5, 0.5]])
-H_EX = np.array([[[19.0, 26.0], [26.0, 40.5]], [[11.0, 16.0], [16.0, 24.5]]])
-DELTA_EX = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0], [1.0, -1.0]])
-OBJ_ROW_EX = np.array([19.0, 40.5, 67.5, 3.5])
-OBJ_EX = np.array([59.5, 71.0])
+# d_out=4, G=2 so J_0={0,1}, J_1={2,3}.  The numbers live in tests/golden/.
+def _golden(name):
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)) as f:
+        return json.load(f)
+
+
+_EX = _golden("alg1_worked_example.json")
+X_EX, DZ_EX, S_EX, H_EX = (np.array(_EX[k]) for k in ("X", "dZ", "s", "H"))
+DELTA_EX, OBJ_ROW_EX, OBJ_EX = (np.array(_EX[k]) for k in ("delta", "obj_row", "obj"))
 
 
 def test_worked_example_group_weights():
@@ -217,18 +221,14 @@ def _cd_case(seed, d_out=6, d_in=7, G=2, m=4, n=40):
 
 
 def test_cd_worked_example():
-    # Worked by hand from Eq. (cd_closed): H = [[2,1],[1,2]], w = (0.4, 0.6), grid {0, 1}, start (0, 0).
-    # i=0: t = 0.4 - (1/2)(0 - 0.6) = 0.7 -> 1;   i=1: t = 0.6 - (1/2)(1 - 0.4) = 0.3 -> 0.
-    H = np.array([[[2.0, 1.0], [1.0, 2.0]]])
-    W = np.array([[0.4, 0.6]])
-    C = np.array([[0.0, 1.0]])
-    assert abs(oracle.cd_coordinate_target(W[0], [0.0, 0.0], H[0], 0) - 0.7) < 1e-15
-    assert abs(oracle.cd_coordinate_target(W[0], [1.0, 0.0], H[0], 1) - 0.3) < 1e-15
-    Q, What = oracle.cd_assign(W, np.zeros((1, 2)), C, H)
-    assert Q.tolist() == [[1, 0]] and What.tolist() == [[1.0, 0.0]]
-    # the objective went from 1.52 to 0.72 (hand-computed delta^T H delta)
-    assert abs(oracle.objective(W, np.zeros((1, 2)), H)[0][0] - 1.52) < 1e-14
-    assert abs(oracle.objective(W, What, H)[0][0] - 0.72) < 1e-14
+    ex = _golden("cd_worked_example.json")          # worked by hand from Eq. (cd_closed)
+    H, W, C, start = (np.array(ex[k]) for k in ("H", "W", "grid", "start"))
+    assert abs(oracle.cd_coordinate_target(W[0], start[0], H[0], 0) - ex["targets"][0]) < 1e-15
+    assert abs(oracle.cd_coordinate_target(W[0], [1.0, 0.0], H[0], 1) - ex["targets"][1]) < 1e-15
+    Q, What = oracle.cd_assign(W, start, C, H)
+    assert Q.tolist() == ex["codes"] and What.tolist() == ex["What"]
+    assert abs(oracle.objective(W, start, H)[0][0] - ex["objective_before"]) < 1e-14
+    assert abs(oracle.objective(W, What, H)[0][0] - ex["objective_after"]) < 1e-14
 
 
 def test_cd_each_update_is_the_exhaustive_argmin_of_the_objective():

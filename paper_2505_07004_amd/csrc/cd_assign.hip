@@ -35,8 +35,8 @@ __device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& l
 
 // Ht (hi/lo bf16, [G][ldp][ldp], row i contiguous over i', zero diagonal and zero padding) and
 // the fp32 coefficients of every diagonal block,
-//   Cd[k][blk][b][a] = Ht[blk*128 + b][blk*128 + a]
-// (what the target of coordinate b moves by, per unit change of coordinate a).
+//   Cd[k][blk][a][b] = Ht[blk*128 + b][blk*128 + a]
+// (what the target of coordinate b moves by, per unit change of coordinate a; row a contiguous over b).
 // Only the upper triangle of H is read.  One workgroup per 64 x 64 tile.
 __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ H, int64_t d, int64_t ldp,
                                                       unsigned short* __restrict__ Hth,
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ 
     if (i / kBlk == ip / kBlk) {
       const int64_t blk = i / kBlk;
       const int64_t base = ((int64_t)k * n_blk + blk) * kBlk * kBlk;
-      Cd[base + (i % kBlk) * kBlk + (ip % kBlk)] = v;
+      Cd[base + (ip % kBlk) * kBlk + (i % kBlk)] = v;
     }
   }
 }
@@ -208,34 +208,44 @@ __global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short
   }
 }
 
-// The sequential walk through block `blk`: one wave per 64 channels of a group, one thread per
-// channel.  The block of W and What is moved between global memory and LDS row by row
-// (coalesced); a lane works on column `lane` of the LDS arrays.  The block's 128 x 128
-// coefficients sit in LDS too (every lane reads the same one: a broadcast).  The 128 targets
-// of a channel live in LDS; the block is walked in four runs of 32 coordinates whose targets
-// sit in registers: inside a run every update corrects the later targets of the run at once,
-// the targets after the run are corrected when the run is over (32 changes at a time).  Lanes
-// past the end of the group repeat its last channel, so the whole wave stays active throughout.
+// The sequential walk through block `blk`: a workgroup of 4 waves per 64 channels of a group,
+// FOUR LANES PER CHANNEL.  The block of W and What is moved between global memory and LDS row
+// by row (coalesced); the block's 128 x 128 coefficients sit in LDS too.  The 128 targets of a
+// channel live in LDS; the block is walked in four runs of 32 coordinates.  Inside a run every
+// lane of the quad keeps 8 of the 32 targets in registers: the owner broadcasts the target of
+// the current coordinate to its quad (DPP), every lane tries a quarter of the grid, two DPP
+// exchanges settle the nearest point (lowest index among equals), and every lane corrects its
+// own 8 targets.  The targets after the run are corrected when the run is over (32 changes at
+// a time, each lane again its own 8 per run).  Channels past the end of the group repeat its
+// last channel, and all four lanes of a quad store the same values, so no lane is ever masked.
 // LV = 4, 8 or 16 bounds the number of grid points (the search is unrolled over it).
 constexpr int kRun = 32;
+constexpr int kQuadSwap1 = 0xB1, kQuadSwap2 = 0x4E;        // DPP quad_perm [1,0,3,2] and [2,3,0,1]
+template <int CTRL>
+__device__ inline float quad_dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ inline int quad_dpp(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
 template <int LV>
-__global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __restrict__ C, int n_parts,
-                                                             const float* __restrict__ W, float* __restrict__ What,
-                                                             const float* __restrict__ codebook, int n_levels,
-                                                             const float* __restrict__ Cd, int64_t d_out, int64_t d,
-                                                             int64_t ld, int64_t ldp, int G, int n_rt, int blk,
-                                                             unsigned char* __restrict__ Q,
-                                                             unsigned short* __restrict__ Dh,
-                                                             unsigned short* __restrict__ Dl) {
+__global__ __launch_bounds__(256) void cd_block_seq_kernel(const float* __restrict__ C, int n_parts,
+                                                           const float* __restrict__ W, float* __restrict__ What,
+                                                           const float* __restrict__ codebook, int n_levels,
+                                                           const float* __restrict__ Cd, int64_t d_out, int64_t d,
+                                                           int64_t ld, int64_t ldp, int G, int n_rt, int blk,
+                                                           unsigned char* __restrict__ Q,
+                                                           unsigned short* __restrict__ Dh,
+                                                           unsigned short* __restrict__ Dl) {
   __shared__ float tw[kBlk][kRows + 1];                    // the block of W; then the targets; then W again
   __shared__ float cur[kBlk][kRows + 1];                   // the block of What, old values then new ones
-  __shared__ __attribute__((aligned(16))) float coef[kBlk][kBlk];   // coef[b][a] = Ht[i0 + b][i0 + a]
+  __shared__ __attribute__((aligned(16))) float coef[kBlk][kBlk];   // coef[a][b] = Ht[i0 + b][i0 + a]
   __shared__ unsigned char code[kBlk][kRows + 4];
   const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
   const int64_t m = d_out / G;
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int64_t j0 = (int64_t)k * m + (int64_t)rt * kRows, j_last = (int64_t)(k + 1) * m - 1;
-  const int64_t j = (j0 + lane) < j_last ? (j0 + lane) : j_last;
   const int n_rows = (int)((j_last - j0 + 1) < kRows ? (j_last - j0 + 1) : kRows);
   const int64_t i0 = (int64_t)blk * kBlk;
   const int n_valid = (int)((d - i0) < kBlk ? (d - i0) : kBlk);   // coordinates of this block inside the matrix
@@ -244,11 +254,11 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
     const f32x4* src = reinterpret_cast<const f32x4*>(Cd + (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk);
     f32x4* dst = reinterpret_cast<f32x4*>(&coef[0][0]);
 #pragma unroll 8
-    for (int q = lane; q < kBlk * kBlk / 4; q += kRows) dst[q] = src[q];
+    for (int q4 = tid; q4 < kBlk * kBlk / 4; q4 += 256) dst[q4] = src[q4];
   }
-  // rows of W (and What) in batches of 8, all loads of a batch in flight together
+  // rows of W (and What): wave w moves rows 16 w .. 16 w + 15, 8 at a time with all loads in flight together
   auto load_rows = [&](bool with_what) {
-    for (int r0 = 0; r0 < kRows; r0 += 8) {
+    for (int r0 = 16 * wave; r0 < 16 * wave + 16; r0 += 8) {
       float wv[8][2], cv[8][2];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
@@ -273,59 +283,110 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
   load_rows(true);
   __syncthreads();
 
-  float grid[LV];
+  // targets t[i] = w[i] - B0[i], in place; B0 = sum of the parts in order.  Thread: channel tid % 64,
+  // coordinates 32 (tid / 64) .. + 31, 16 in flight.
+  {
+    const int r = tid % kRows;
+    const int64_t jr = r < n_rows ? j0 + r : j_last;
+    for (int ib = 32 * (tid / kRows); ib < 32 * (tid / kRows) + 32; ib += 16) {
+      float b[16];
 #pragma unroll
-  for (int q = 0; q < LV; ++q) grid[q] = codebook[j * n_levels + (q < n_levels ? q : n_levels - 1)];
-
-  // targets t[i] = w[i] - B0[i], in place; B0 = sum of the parts in order (16 coordinates in flight)
-  for (int ib = 0; ib < kBlk; ib += 16) {
-    float b[16];
+      for (int u = 0; u < 16; ++u) b[u] = 0.f;
+      for (int p = 0; p < n_parts; ++p) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) b[u] = 0.f;
-    for (int p = 0; p < n_parts; ++p) {
+        for (int u = 0; u < 16; ++u) b[u] += C[((int64_t)p * kBlk + ib + u) * d_out + jr];
+      }
 #pragma unroll
-      for (int u = 0; u < 16; ++u) b[u] += C[((int64_t)p * kBlk + ib + u) * d_out + j];
+      for (int u = 0; u < 16; ++u) tw[ib + u][r] -= b[u];
     }
+  }
+  __syncthreads();
+
+  // ---- the walk: channel ch of the tile, lane q of its quad ----------------------------------
+  const int ch = 16 * wave + lane / 4, q = lane % 4;
+  const int64_t j = ch < n_rows ? j0 + ch : j_last;
+  float grid[LV / 4];
+  bool usable[LV / 4];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) tw[ib + u][lane] -= b[u];
+  for (int u = 0; u < LV / 4; ++u) {
+    const int lvl = q + 4 * u;
+    usable[u] = lvl < n_levels;
+    grid[u] = codebook[j * n_levels + (usable[u] ? lvl : n_levels - 1)];
   }
 
   for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
-    float t[kRun], eps[kRun];
+    float own[8], eps[kRun];
 #pragma unroll
-    for (int ii = 0; ii < kRun; ++ii) t[ii] = tw[c0 + ii][lane];
+    for (int kk = 0; kk < 8; ++kk) own[kk] = tw[c0 + 8 * q + kk][ch];
 #pragma unroll
     for (int ii = 0; ii < kRun; ++ii) {
       eps[ii] = 0.f;
       if (c0 + ii < n_valid) {                              // uniform
-        const float ti = t[ii];
-        float best = fabsf(grid[0] - ti), val = grid[0];
-        int bq = 0;
-#pragma unroll
-        for (int q = 1; q < LV; ++q) {
-          const float dist = fabsf(grid[q] - ti);
-          const bool better = (q < n_levels) && (dist < best);   // equally near: the lower index stays
-          best = better ? dist : best;
-          val = better ? grid[q] : val;
-          bq = better ? q : bq;
+        constexpr int kBroadcast[4] = {0x00, 0x55, 0xAA, 0xFF};
+        float ti;                                           // target of coordinate c0 + ii: lane ii / 8 of the quad owns it
+        switch (ii / 8) {
+          case 0: ti = quad_dpp<kBroadcast[0]>(own[ii % 8]); break;
+          case 1: ti = quad_dpp<kBroadcast[1]>(own[ii % 8]); break;
+          case 2: ti = quad_dpp<kBroadcast[2]>(own[ii % 8]); break;
+          default: ti = quad_dpp<kBroadcast[3]>(own[ii % 8]); break;
         }
-        const float e = val - cur[c0 + ii][lane];
-        cur[c0 + ii][lane] = val;
-        code[c0 + ii][lane] = (unsigned char)bq;
-        eps[ii] = e;
+        // this lane's quarter of the grid (levels q, q + 4, ...: increasing, so '<' keeps the lower index)
+        float best = usable[0] ? fabsf(grid[0] - ti) : __builtin_inff(), val = grid[0];
+        int bq = q;
 #pragma unroll
-        for (int ii2 = ii + 1; ii2 < kRun; ++ii2) t[ii2] -= e * coef[c0 + ii2][c0 + ii];
+        for (int u = 1; u < LV / 4; ++u) {
+          const float dist = fabsf(grid[u] - ti);
+          const bool better = usable[u] && (dist < best);
+          best = better ? dist : best;
+          val = better ? grid[u] : val;
+          bq = better ? q + 4 * u : bq;
+        }
+        // settle it inside the quad: nearest point, lowest index among equally near ones
+        {
+          const float ob = quad_dpp<kQuadSwap1>(best), ov = quad_dpp<kQuadSwap1>(val);
+          const int oq = quad_dpp<kQuadSwap1>(bq);
+          const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
+          best = take ? ob : best;
+          val = take ? ov : val;
+          bq = take ? oq : bq;
+        }
+        {
+          const float ob = quad_dpp<kQuadSwap2>(best), ov = quad_dpp<kQuadSwap2>(val);
+          const int oq = quad_dpp<kQuadSwap2>(bq);
+          const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
+          best = take ? ob : best;
+          val = take ? ov : val;
+          bq = take ? oq : bq;
+        }
+        const float e = val - cur[c0 + ii][ch];
+        cur[c0 + ii][ch] = val;                             // all four lanes of the quad store the same value
+        code[c0 + ii][ch] = (unsigned char)bq;
+        eps[ii] = e;
+        const f32x4* row = reinterpret_cast<const f32x4*>(&coef[c0 + ii][c0 + 8 * q]);   // Ht[c0 + 8q + kk][c0 + ii] over kk
+        const f32x4 c_lo = row[0], c_hi = row[1];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          own[kk] -= e * c_lo[kk];                          // (targets already used are corrected too: harmless)
+          own[4 + kk] -= e * c_hi[kk];
+        }
       }
     }
-    for (int i2 = c0 + kRun; i2 < n_valid; ++i2) {          // the targets after the run
-      const f32x4* row = reinterpret_cast<const f32x4*>(&coef[i2][c0]);
-      float a = 0.f;
+    for (int c1 = c0 + kRun; c1 < n_valid; c1 += kRun) {    // the targets after the run, a run at a time
+      float a[8];
 #pragma unroll
-      for (int q4 = 0; q4 < kRun / 4; ++q4) {
-        const f32x4 cf = row[q4];
-        a += eps[4 * q4] * cf[0] + eps[4 * q4 + 1] * cf[1] + eps[4 * q4 + 2] * cf[2] + eps[4 * q4 + 3] * cf[3];
+      for (int kk = 0; kk < 8; ++kk) a[kk] = 0.f;
+#pragma unroll
+      for (int ii = 0; ii < kRun; ++ii) {
+        const f32x4* row = reinterpret_cast<const f32x4*>(&coef[c0 + ii][c1 + 8 * q]);
+        const f32x4 c_lo = row[0], c_hi = row[1];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          a[kk] += eps[ii] * c_lo[kk];
+          a[4 + kk] += eps[ii] * c_hi[kk];
+        }
       }
-      tw[i2][lane] -= a;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) tw[c1 + 8 * q + kk][ch] -= a[kk];
     }
   }
   __syncthreads();
@@ -333,7 +394,7 @@ __global__ __launch_bounds__(kRows) void cd_block_seq_kernel(const float* __rest
   __syncthreads();
 
   // write the block back row by row: What, the codes, and the split delta for the next block's GEMM
-  for (int r = 0; r < n_rows; ++r) {
+  for (int r = 16 * wave; r < 16 * wave + 16 && r < n_rows; ++r) {
     const int64_t jr = j0 + r;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
@@ -419,7 +480,7 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
                                                                                     blk, C);
       if ((e = hipGetLastError()) != hipSuccess) return e;
 #define GQ_LAUNCH_SEQ(LV)                                                                                              \
-  cd_block_seq_kernel<LV><<<dim3(n_tiles), dim3(kRows), 0, st>>>(C, L.n_parts, W, What, codebook, n_levels, Cd, d_out,      \
+  cd_block_seq_kernel<LV><<<dim3(n_tiles), dim3(256), 0, st>>>(C, L.n_parts, W, What, codebook, n_levels, Cd, d_out,      \
                                                                  d_in, ld, L.ldp, G, L.n_rt, blk, Q, Dh, Dl)
       if (n_levels <= 4) {
         GQ_LAUNCH_SEQ(4);

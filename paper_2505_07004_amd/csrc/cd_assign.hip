@@ -96,115 +96,116 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
 
 // Partial sums of B0 for block `blk`:  C[part][i][j] = sum over this part's contraction range
 // of delta[j][i'] * Ht[blk*128 + i][i'],  i < 128, j a channel (j contiguous, pitch d_out).
-// Both operands are contiguous along the contraction index, so every MFMA fragment (8 bf16
-// of one row per lane) is a 16-byte global load; nothing is staged in LDS.  A workgroup owns
-// 64 channels of one group; its 4 waves take different quarters of the part's contraction
-// range and are added up through LDS.  The parts (gridDim.y) are added by the sequential
-// kernel in a fixed order.
+// A workgroup owns 128 channels of one group and all 128 coordinates of the block; its 4
+// waves compute 64 x 64 each.  Both operands are contraction-major in memory; a stage is 64
+// contraction elements = one whole 128-byte line of each of the 4 x 128 operand rows
+// ({delta, Ht} x {hi, lo}), copied straight into LDS (global_load_lds_dwordx4: 8 lanes per row,
+// wave w copies operand w) into a ring of two stages, one barrier per stage.  A row of a staged
+// tile holds eight 16-byte chunks; chunk c of row r sits at position c ^ ((r >> 1) & 7), which
+// makes the 16-byte fragment reads of 16 consecutive rows conflict-free (the loading lane
+// applies the same XOR when it picks its global chunk).  The parts (gridDim.y) split the
+// contraction; the sequential kernel adds them in a fixed order.
+constexpr int kGemmRows = 128;                       // channels per workgroup
+constexpr int kGemmK = 64;                           // contraction elements per stage
+constexpr int kGemmTile = 128 * kGemmK * 2;          // bytes of one staged operand tile (16 KiB)
+constexpr int kGemmStage = 4 * kGemmTile;            // 64 KiB
 __global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short* __restrict__ Dh,
                                                             const unsigned short* __restrict__ Dl,
                                                             const unsigned short* __restrict__ Hth,
                                                             const unsigned short* __restrict__ Htl, int64_t d_out,
-                                                            int64_t ldp, int G, int n_rt, int blk,
+                                                            int64_t ldp, int G, int n_gt, int blk,
                                                             float* __restrict__ C) {
-  __shared__ float red[4][kBlk][kRows + 1];
-  const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * kGemmStage];
+  const int k = blockIdx.x / n_gt, gt = blockIdx.x % n_gt;
   const int64_t m = d_out / G;
-  const int64_t j0 = (int64_t)k * m + (int64_t)rt * kRows, j_last = (int64_t)(k + 1) * m - 1;
-  const int lane = threadIdx.x % kWave;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int64_t j0 = (int64_t)k * m + (int64_t)gt * kGemmRows, j_last = (int64_t)(k + 1) * m - 1;
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int wm = wave / 2, wn = wave % 2;
 
-  // contraction range of this wave, in steps of 16
-  const int64_t n_steps = ldp / 16, n_chunks = 4 * (int64_t)gridDim.y, chunk = (int64_t)blockIdx.y * 4 + wave;
-  const int64_t s0 = chunk * n_steps / n_chunks, s1 = (chunk + 1) * n_steps / n_chunks;
+  // contraction range of this part, in stages of 64
+  const int64_t n_stages = ldp / kGemmK;
+  const int64_t s0 = (int64_t)blockIdx.y * n_stages / gridDim.y, s1 = ((int64_t)blockIdx.y + 1) * n_stages / gridDim.y;
 
-  const unsigned short *pa_h[2], *pa_l[2], *pb_h[4], *pb_l[4];
+  // ---- staging: wave w copies operand w (0: delta hi, 1: delta lo, 2: Ht hi, 3: Ht lo); load
+  // number i moves rows 8 i .. 8 i + 7, lane -> (row 8 i + lane / 8, position lane % 8)
+  const unsigned short* src = wave == 0 ? Dh : wave == 1 ? Dl : (wave == 2 ? Hth : Htl) + (int64_t)k * ldp * ldp;
+  const int64_t row_first = wave < 2 ? j0 : (int64_t)blk * kBlk, row_last = wave < 2 ? j_last : ldp - 1;
+  const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
+  auto issue = [&](int64_t stage, int slot) {
 #pragma unroll
-  for (int x = 0; x < 2; ++x) {
-    int64_t j = j0 + 32 * x + lane % 32;
-    j = j < j_last ? j : j_last;                           // rows past the group: repeat its last row (never stored)
-    pa_h[x] = Dh + j * ldp + 8 * (lane / 32) + 16 * s0;
-    pa_l[x] = Dl + j * ldp + 8 * (lane / 32) + 16 * s0;
-  }
-#pragma unroll
-  for (int y = 0; y < 4; ++y) {
-    const int64_t i = (int64_t)blk * kBlk + 32 * y + lane % 32;
-    pb_h[y] = Hth + (int64_t)k * ldp * ldp + i * ldp + 8 * (lane / 32) + 16 * s0;
-    pb_l[y] = Htl + (int64_t)k * ldp * ldp + i * ldp + 8 * (lane / 32) + 16 * s0;
-  }
+    for (int i = 0; i < 16; ++i) {
+      const int r = 8 * i + lane / 8;
+      const int c = (lane % 8) ^ ((r >> 1) & 7);
+      int64_t row = row_first + r;
+      row = row < row_last ? row : row_last;             // rows past the group: repeat its last row (never stored)
+      dma16(src + row * ldp + stage * kGemmK + 8 * c, smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
+    }
+  };
 
-  f32x16 acc[2][4];
+  // ---- fragments: row l % 32 of a 32-row block, chunk 2 t + l / 32 of its 64 contraction elements
+  const int lrow = lane % 32;
+  auto frag = [&](int slot, int tile, int row0, int t) -> bf16x8 {
+    const int pos = (2 * t + lane / 32) ^ ((lrow >> 1) & 7);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kGemmStage + tile * kGemmTile + (row0 + lrow) * 128 + pos * 16]);
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
+  f32x16 acc[2][2];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 4; ++y)
+    for (int y = 0; y < 2; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // The fragments of step s + 1 are requested before the MFMAs of step s (past the end the
-  // last step is fetched again), so a single wave per SIMD hides most of the load latency.
-  struct Frags {
-    bf16x8 ah[2], al[2], bh[4], bl[4];
-  };
-  auto fetch = [&](Frags& f, bool advance) {
-    const int step = advance ? 16 : 0;
+  if (s0 < s1) issue(s0, 0);
+  for (int64_t s = s0; s < s1; ++s) {
+    const int slot = (int)((s - s0) & 1);
+    wait_vmcnt<0>();                                      // this wave's loads of stage s have landed
+    __builtin_amdgcn_s_barrier();                         // everyone's have; and everyone is done with the other slot
+    if (s + 1 < s1) issue(s + 1, slot ^ 1);
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      f.ah[x] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pa_h[x]));
-      f.al[x] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pa_l[x]));
-      pa_h[x] += step;
-      pa_l[x] += step;
-    }
+    for (int t = 0; t < kGemmK / 16; ++t) {
+      bf16x8 ah[2], al[2], bh[2], bl[2];
 #pragma unroll
-    for (int y = 0; y < 4; ++y) {
-      f.bh[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pb_h[y]));
-      f.bl[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pb_l[y]));
-      pb_h[y] += step;
-      pb_l[y] += step;
-    }
-  };
-  auto mma = [&](const Frags& f) {
+      for (int x = 0; x < 2; ++x) {
+        ah[x] = frag(slot, 0, wm * 64 + x * 32, t);
+        al[x] = frag(slot, 1, wm * 64 + x * 32, t);
+      }
 #pragma unroll
-    for (int y = 0; y < 4; ++y) {
-      acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[0], f.bh[y], acc[0][y], 0, 0, 0);
-      acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[1], f.bh[y], acc[1][y], 0, 0, 0);
-      acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[0], f.bl[y], acc[0][y], 0, 0, 0);
-      acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[1], f.bl[y], acc[1][y], 0, 0, 0);
-      acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[0], f.bh[y], acc[0][y], 0, 0, 0);
-      acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[1], f.bh[y], acc[1][y], 0, 0, 0);
+      for (int y = 0; y < 2; ++y) {
+        bh[y] = frag(slot, 2, wn * 64 + y * 32, t);
+        bl[y] = frag(slot, 3, wn * 64 + y * 32, t);
+      }
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[0], bh[y], acc[0][y], 0, 0, 0);
+        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[1], bh[y], acc[1][y], 0, 0, 0);
+        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[0], bl[y], acc[0][y], 0, 0, 0);
+        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[1], bl[y], acc[1][y], 0, 0, 0);
+        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[0], bh[y], acc[0][y], 0, 0, 0);
+        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[1], bh[y], acc[1][y], 0, 0, 0);
+      }
     }
-  };
-  if (s1 > s0) {
-    Frags f0, f1;
-    fetch(f0, s0 + 1 < s1);
-    int64_t s = s0;
-    for (; s + 1 < s1; s += 2) {
-      fetch(f1, s + 2 < s1);
-      __builtin_amdgcn_sched_barrier(0);
-      mma(f0);
-      __builtin_amdgcn_sched_barrier(0);
-      fetch(f0, s + 3 < s1);
-      __builtin_amdgcn_sched_barrier(0);
-      mma(f1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (s < s1) mma(f0);
   }
+  __syncthreads();                                        // the ring is idle: the output tile may reuse it
 
   // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4) (channel), column l%32 (coordinate)
+  float (*out)[kGemmRows + 1] = reinterpret_cast<float (*)[kGemmRows + 1]>(&smem[0]);   // [coordinate][channel]
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 4; ++y)
+    for (int y = 0; y < 2; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        red[wave][32 * y + lane % 32][32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] = acc[x][y][r];
+        out[wn * 64 + 32 * y + lane % 32][wm * 64 + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] = acc[x][y][r];
   __syncthreads();
   float* Cp = C + (int64_t)blockIdx.y * kBlk * d_out;
-  for (int idx = threadIdx.x; idx < kBlk * kRows; idx += 256) {
-    const int i = idx / kRows, r = idx % kRows;
+  for (int idx = tid; idx < kBlk * kGemmRows; idx += 256) {
+    const int i = idx / kGemmRows, r = idx % kGemmRows;
     const int64_t j = j0 + r;
-    if (j <= j_last) Cp[(int64_t)i * d_out + j] = (red[0][i][r] + red[1][i][r]) + (red[2][i][r] + red[3][i][r]);
+    if (j <= j_last) Cp[(int64_t)i * d_out + j] = out[i][r];
   }
 }
 
@@ -415,7 +416,7 @@ __global__ __launch_bounds__(256) void cd_block_seq_kernel(const float* __restri
 
 struct Layout {
   int64_t ldp, n_blk;
-  int n_rt, n_parts;
+  int n_rt, n_gt, n_parts;
   size_t ht_bytes, cdt_bytes, delta_bytes, c_bytes;
 };
 Layout make_layout(int64_t d_out, int64_t d_in, int G) {
@@ -424,11 +425,12 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   L.ldp = L.n_blk * kBlk;
   const int64_t m = d_out / G;
   L.n_rt = (int)((m + kRows - 1) / kRows);
-  // enough workgroups to fill the chip, at least one 16-step stage per wave
-  int parts = (int)(512 / ((int64_t)L.n_rt * G));
-  const int max_parts = (int)(L.ldp / 16 / 4);
+  L.n_gt = (int)((m + kGemmRows - 1) / kGemmRows);
+  // enough GEMM workgroups to fill the chip, at least two 64-deep stages each
+  int parts = (int)(256 / ((int64_t)L.n_gt * G));
+  const int max_parts = (int)(L.ldp / kGemmK / 2);
   if (parts > max_parts) parts = max_parts;
-  if (parts > 8) parts = 8;
+  if (parts > 16) parts = 16;
   if (parts < 1) parts = 1;
   L.n_parts = parts;
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
@@ -476,7 +478,7 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
   const unsigned n_tiles = (unsigned)(L.n_rt * G);
   for (int cycle = 0; cycle < n_cycles; ++cycle)
     for (int blk = 0; blk < (int)L.n_blk; ++blk) {
-      cd_block_gemm_kernel<<<dim3(n_tiles, (unsigned)L.n_parts), dim3(256), 0, st>>>(Dh, Dl, Hth, Htl, d_out, L.ldp, G, L.n_rt,
+      cd_block_gemm_kernel<<<dim3((unsigned)(L.n_gt * G), (unsigned)L.n_parts), dim3(256), 0, st>>>(Dh, Dl, Hth, Htl, d_out, L.ldp, G, L.n_gt,
                                                                                     blk, C);
       if ((e = hipGetLastError()) != hipSuccess) return e;
 #define GQ_LAUNCH_SEQ(LV)                                                                                              \

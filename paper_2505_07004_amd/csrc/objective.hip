@@ -161,7 +161,8 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
                                                              const unsigned short* __restrict__ Hl,
                                                              const float* __restrict__ W, const float* __restrict__ What,
                                                              int64_t d_out, int64_t d, int64_t ld, int64_t ldp, int G,
-                                                             int n_pairs, int n_rb2, float* __restrict__ partial) {
+                                                             int n_pairs, int n_rb2, int chunk, int n_slots,
+                                                             float* __restrict__ partial) {
   __shared__ __attribute__((aligned(1024))) char smem[kStages * kStageBytes];
   // (the row-sum exchange at the end reuses the staging memory, after a barrier)
 
@@ -170,18 +171,21 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
   // That order walks, per group, blocks of kOrderP tile pairs x kOrderR row blocks (heavy pairs
   // first): the workgroups resident on an XCD then share both their H tiles and their delta
   // tiles through its L2.
-  int k, P, rb2;
+  // The contraction of pair P (P + 1 pair blocks of 16 stages) is cut into slots of at most
+  // `chunk` pair blocks, so that small problems still give every CU several workgroups of
+  // similar length; slot 0 is the last (diagonal) part of the heaviest pair.
+  int k, sl, rb2;
   {
     constexpr int kXcd = 8;
     const int64_t total = gridDim.x, id = blockIdx.x;
     const int64_t x = id % kXcd, idx = id / kXcd, q = total / kXcd, r = total % kXcd;
     const int64_t logical = x * q + (x < r ? x : r) + idx;
-    const int64_t per_group = (int64_t)n_pairs * n_rb2;
+    const int64_t per_group = (int64_t)n_slots * n_rb2;
     k = (int)(logical / per_group);
     int64_t rem = logical - (int64_t)k * per_group;
-    // bands of kOrderP pairs from the top; the first band holds the remainder
-    const int n_bands = (n_pairs + kOrderP - 1) / kOrderP;
-    const int first_w = n_pairs - (n_bands - 1) * kOrderP;
+    // bands of kOrderP slots; the first band holds the remainder
+    const int n_bands = (n_slots + kOrderP - 1) / kOrderP;
+    const int first_w = n_slots - (n_bands - 1) * kOrderP;
     int band, pw;
     if (rem < (int64_t)first_w * n_rb2) {
       band = 0;
@@ -192,13 +196,25 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
       rem = rem % ((int64_t)kOrderP * n_rb2);
       pw = kOrderP;
     }
-    const int p_hi = n_pairs - 1 - (band == 0 ? 0 : first_w + (band - 1) * kOrderP);   // heaviest pair of the band
+    const int s_lo = band == 0 ? 0 : first_w + (band - 1) * kOrderP;   // first slot of the band
     const int rblk = (int)(rem / ((int64_t)pw * kOrderR));
     const int off = (int)(rem % ((int64_t)pw * kOrderR));
     const int rw = (n_rb2 - rblk * kOrderR) < kOrderR ? (n_rb2 - rblk * kOrderR) : kOrderR;
-    P = p_hi - off / rw;
+    sl = s_lo + off / rw;
     rb2 = rblk * kOrderR + off % rw;
   }
+  // slot -> (pair, part): pairs from the heaviest down, the parts of a pair from its diagonal end down
+  int P = n_pairs - 1, part;
+  {
+    int rem = sl;
+    while (rem >= (P + chunk) / chunk) {                   // number of parts of pair P = ceil((P + 1) / chunk)
+      rem -= (P + chunk) / chunk;
+      --P;
+    }
+    part = (P + chunk) / chunk - 1 - rem;
+  }
+  const int pb_begin = part * chunk;                                        // first pair block of this part
+  const bool last_part = (part + 1) * chunk >= P + 1;                       // it ends with the diagonal pair block
   const int64_t m = d_out / G;
   const int64_t j0 = (int64_t)k * m + (int64_t)rb2 * 2 * kTile;   // first channel of this block
   const int64_t j_end = (int64_t)(k + 1) * m;                     // rows >= j_end belong to another group
@@ -218,7 +234,7 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
         wave < 4 ? (wave % 2 == 0 ? Dh : Dl) + (((int64_t)k * n_rb2 + rb2) * 2 + which) * n_st * kTileElems
                  : (wave % 2 == 0 ? Hh : Hl) + (int64_t)k * ldp * ldp + ((int64_t)P * 2 + which) * n_st * kTileElems;
 #pragma unroll
-    for (int i = 0; i < kLoadsPerStage; ++i) gp[i] = src + i * 512 + lane * 8;
+    for (int i = 0; i < kLoadsPerStage; ++i) gp[i] = src + (int64_t)pb_begin * kPairStages * kTileElems + i * 512 + lane * 8;
   }
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
   // Requests the next stage of the contraction into ring slot `slot`; `advance` is false once
@@ -290,7 +306,7 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
   // pending across the loops would turn the partial LDS-counter waits inside them into full ones.
   asm volatile("" ::"s"(partial), "s"(W), "s"(What), "s"(ld), "s"(d), "s"(d_out), "s"(j_end));
 
-  const int stages = (P + 1) * kPairStages;                 // a multiple of 16, > kStages
+  const int stages = (last_part ? P + 1 : (part + 1) * chunk) * kPairStages;   // end of this part; it has >= 16 stages
 #pragma unroll
   for (int t = 0; t < kStages - 1; ++t) issue(t, true);
   int slot_next = 1, slot_fill = kStages - 1;               // ring slots of stage it + 1 and of stage it - 1
@@ -334,21 +350,25 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
   wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
   __builtin_amdgcn_s_barrier();
   read_all(f0, 0);
-  int it = 0;
+  int it = pb_begin * kPairStages;
   const int diag0 = P * kPairStages, diag1 = diag0 + kPairStages / 2;
-  for (; it < diag0; it += 2) {          // strictly above the diagonal for both column tiles
+  const int upper_end = last_part ? diag0 : stages;
+  for (; it < upper_end; it += 2) {      // strictly above the diagonal for both column tiles
     step(f0, f1, it);
     step(f1, f0, it + 1);
   }
-  if (wn == 0 && P > 0) twice();         // what came before counts twice (its mirror image is never visited)
-  for (; it < diag1; it += 2) {          // diagonal block of the first tile, still above the second's
-    step(f0, f1, it);
-    step(f1, f0, it + 1);
-  }
-  if (wn == 1) twice();
-  for (; it < stages; it += 2) {         // diagonal block of the second tile (zeros for the first)
-    step(f0, f1, it);
-    step(f1, f0, it + 1);
+  // what came before counts twice (its mirror image is never visited)
+  if (!last_part || (wn == 0 && P > 0)) twice();
+  if (last_part) {
+    for (; it < diag1; it += 2) {        // diagonal block of the first tile, still above the second's
+      step(f0, f1, it);
+      step(f1, f0, it + 1);
+    }
+    if (wn == 1) twice();
+    for (; it < stages; it += 2) {       // diagonal block of the second tile (zeros for the first)
+      step(f0, f1, it);
+      step(f1, f0, it + 1);
+    }
   }
   wait_vmcnt<0>();   // the repeated requests of the last stage
   __syncthreads();   // the ring is idle: `red` may reuse it
@@ -394,7 +414,7 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
   __syncthreads();
   if (tid < 2 * kTile) {
     const int64_t j = j0 + tid;
-    if (j < j_end) partial[(int64_t)P * d_out + j] = red[0][tid] + red[1][tid];
+    if (j < j_end) partial[(int64_t)sl * d_out + j] = red[0][tid] + red[1][tid];
   }
 }
 
@@ -435,6 +455,7 @@ __global__ void objective_groups_kernel(const double* __restrict__ block_sum, in
 
 struct Layout {
   int64_t ldp, n_pairs, n_rb2;
+  int chunk, n_slots;                           // pair blocks per workgroup, workgroups per (group, row block)
   int64_t n_blocks;                             // 256-row blocks per group in the final reduction
   size_t partial_bytes, sums_bytes, delta_bytes, h_bytes;   // delta_bytes / h_bytes: one of the hi/lo arrays
 };
@@ -443,7 +464,12 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   L.n_pairs = (d_in + 2 * kTile - 1) / (2 * kTile);
   L.ldp = L.n_pairs * 2 * kTile;                // contraction length padded to whole tile pairs
   L.n_rb2 = (d_out / G + 2 * kTile - 1) / (2 * kTile);
-  L.partial_bytes = ((size_t)(L.n_pairs * d_out) * sizeof(float) + 255) / 256 * 256;
+  // cut the heavy pairs while the grid would give a CU fewer than ~4 workgroups
+  L.chunk = (int)L.n_pairs;
+  while (L.chunk > 2 && L.n_pairs * L.n_rb2 * G * (L.n_pairs / L.chunk) < 1024) L.chunk = (L.chunk + 1) / 2;
+  L.n_slots = 0;
+  for (int64_t P = 0; P < L.n_pairs; ++P) L.n_slots += (int)((P + L.chunk) / L.chunk);
+  L.partial_bytes = ((size_t)((int64_t)L.n_slots * d_out) * sizeof(float) + 255) / 256 * 256;
   L.n_blocks = (d_out / G + 255) / 256;
   L.sums_bytes = ((size_t)(L.n_blocks * G) * sizeof(double) + 255) / 256 * 256;
   L.delta_bytes = ((size_t)((int64_t)G * L.n_rb2 * 2 * kTile * L.ldp) * 2 + 255) / 256 * 256;
@@ -482,10 +508,10 @@ hipError_t launch_objective(const float* W, const float* What, int64_t d_out, in
   if ((e = hipGetLastError()) != hipSuccess) return e;
   split_h_kernel<<<dim3((unsigned)(8 * tri_count(n_pairs)), (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, n_st, Hh, Hl);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  objective_mfma_kernel<<<dim3((unsigned)((int64_t)n_pairs * n_rb2 * G)), dim3(512), 0, st>>>(
-      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_pairs, n_rb2, partial);
+  objective_mfma_kernel<<<dim3((unsigned)((int64_t)L.n_slots * n_rb2 * G)), dim3(512), 0, st>>>(
+      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_pairs, n_rb2, L.chunk, L.n_slots, partial);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  objective_rows_kernel<<<dim3((unsigned)L.n_blocks, (unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, n_pairs, obj_row,
+  objective_rows_kernel<<<dim3((unsigned)L.n_blocks, (unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, L.n_slots, obj_row,
                                                                                        block_sum);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   objective_groups_kernel<<<dim3((unsigned)G), dim3(64), 0, st>>>(block_sum, (int)L.n_blocks, obj);

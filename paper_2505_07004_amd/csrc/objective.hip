@@ -65,12 +65,15 @@ __global__ __launch_bounds__(256) void split_delta_kernel(const float* __restric
   const int64_t j0 = (int64_t)k * m + (int64_t)rb * kTile, j_end = (int64_t)(k + 1) * m;
   const int64_t a0 = (int64_t)blockIdx.x * 64;
   const int t = threadIdx.x;
-#pragma unroll 4
+  // branch-free (clamped addresses, values selected afterwards) so that all 32 x 2 loads of a thread are in flight together
+#pragma unroll
   for (int i = 0; i < 32; ++i) {
     const int idx = t + 256 * i;
     const int r = idx / 64, ac = idx % 64;
     const int64_t j = j0 + r, a = a0 + ac;
-    tile[r][ac] = (j < j_end && a < d) ? W[j * ld + a] - What[j * ld + a] : 0.f;
+    const int64_t jc = j < j_end ? j : j_end - 1, acl = a < d ? a : d - 1;
+    const float v = W[jc * ld + acl] - What[jc * ld + acl];
+    tile[r][ac] = (j < j_end && a < d) ? v : 0.f;
   }
   __syncthreads();
   const int r = t / 2, c = t % 2;
@@ -119,14 +122,21 @@ __global__ __launch_bounds__(256) void split_h_kernel(const float* __restrict__ 
   }
   const int64_t a0 = (int64_t)ta * kTile + 64 * (blockIdx.x % 2), b0 = (int64_t)tb * kTile;
   const int t = threadIdx.x;
-#pragma unroll 4
-  for (int i = 0; i < 32; ++i) {
-    const int idx = t + 256 * i;
-    const int ar = idx / kTile, bc = idx % kTile;
-    const int64_t a = a0 + ar, b = b0 + bc;
-    float v = 0.f;
-    if (a < d && b < d && ta <= tb) v = a <= b ? Hk[a * d + b] : Hk[b * d + a];   // a > b: inside a diagonal tile
-    tile[ar][bc] = v;
+  // branch-free inside (clamped addresses, values selected afterwards): all 32 loads of a thread in flight together
+  if (ta <= tb) {                                           // uniform; the tile below a pair's diagonal is all zeros
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const int idx = t + 256 * i;
+      const int ar = idx / kTile, bc = idx % kTile;
+      const int64_t a = a0 + ar, b = b0 + bc;
+      const int64_t lo = a < b ? a : b, hi = a < b ? b : a;   // below the diagonal of a diagonal tile: the mirror image
+      const int64_t lc = lo < d ? lo : d - 1, hc = hi < d ? hi : d - 1;
+      const float v = Hk[lc * d + hc];
+      tile[ar][bc] = (hi < d) ? v : 0.f;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) tile[(t + 256 * i) / kTile][(t + 256 * i) % kTile] = 0.f;
   }
   __syncthreads();
 #pragma unroll

@@ -18,9 +18,13 @@ __global__ __launch_bounds__(256) void mirror_kernel(float* __restrict__ H, int6
   tri_decode(blockIdx.x, ti, tj);  // ti <= tj
   const int64_t r0 = (int64_t)ti * kT, c0 = (int64_t)tj * kT;
   const int tx = threadIdx.x % kT, ty = threadIdx.x / kT;  // 64 x 4
-  for (int r = ty; r < kT; r += 4) {
+  // branch-free (clamped addresses): the 16 loads of a thread are in flight together
+#pragma unroll
+  for (int u = 0; u < kT / 4; ++u) {
+    const int r = ty + 4 * u;
     const int64_t a = r0 + r, b = c0 + tx;
-    tile[r][tx] = (a < d && b < d) ? Hk[a * d + b] : 0.f;
+    const int64_t ac = a < d ? a : d - 1, bc = b < d ? b : d - 1;
+    tile[r][tx] = Hk[ac * d + bc];
   }
   __syncthreads();
   // write the transposed tile: rows b in tile tj, columns a in tile ti

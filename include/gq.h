@@ -83,6 +83,19 @@ int gq_group_weights(const void* dZ, gq_dtype dz_dtype, int64_t n, int64_t d_out
                      int32_t G, float grad_scale, float* s, void* hip_stream);
 
 /*
+ * The same, written into G columns of a wider array: s[i*ld_s + k], k < G, ld_s >= G.
+ * Linear layers that read the same input X (q/k/v, gate/up: the paper quantizes a block's
+ * layers from one cached input) can put their weights side by side in one
+ * [n, G_1 + G_2 + ...] array, each layer calling this with `s` pointing at its first
+ * column, and then make ONE gq_fisher_gram call with G = G_1 + G_2 + ...: the result
+ * H[G_1 + G_2 + ..., d_in, d_in] is the layers' group Hessians one after the other
+ * (Algorithm 1, line 4, for every layer of the block in a single pass over X).
+ * Additional error: GQ_ERR_SHAPE if ld_s < G.
+ */
+int gq_group_weights_strided(const void* dZ, gq_dtype dz_dtype, int64_t n, int64_t d_out, int64_t ld_dz,
+                             int32_t G, float grad_scale, float* s, int64_t ld_s, void* hip_stream);
+
+/*
  * Bytes of device workspace gq_fisher_gram needs for these sizes (may be 0).
  * Returns 0 for invalid arguments as well; gq_fisher_gram reports those.
  */

@@ -45,6 +45,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_group_weights.restype = c.c_int
     lib.gq_group_weights.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_int32,
                                      c.c_float, c.c_void_p, c.c_void_p]
+    lib.gq_group_weights_strided.restype = c.c_int
+    lib.gq_group_weights_strided.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_int32,
+                                             c.c_float, c.c_void_p, c.c_int64, c.c_void_p]
     lib.gq_fisher_gram_workspace_bytes.restype = c.c_size_t
     lib.gq_fisher_gram_workspace_bytes.argtypes = [c.c_int, c.c_int64, c.c_int64, c.c_int32]
     lib.gq_fisher_gram.restype = c.c_int
@@ -113,14 +116,21 @@ def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
 
 
 def gq_group_weights(dZ: torch.Tensor, G: int, grad_scale: float = 1.0,
-                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """s[i,k] = grad_scale^2/(d_out/G) * sum_{j in J_k} dZ[i,j]^2 -> fp32 [n, G]."""
+                     out: Optional[torch.Tensor] = None, out_col: int = 0) -> torch.Tensor:
+    """s[i,k] = grad_scale^2/(d_out/G) * sum_{j in J_k} dZ[i,j]^2 -> fp32 [n, G].
+    With a wider contiguous `out` [n, G_total] the G columns starting at `out_col` are written
+    (layers that share their input X stack their weights for one gq_fisher_gram call)."""
     _require_gpu(dZ, out)
     n, d_out = dZ.shape
     s = out if out is not None else torch.empty((n, G), dtype=torch.float32, device=dZ.device)
-    assert s.dtype == torch.float32 and s.is_contiguous() and tuple(s.shape) == (n, G)
-    st = load_library().gq_group_weights(dZ.data_ptr(), _dtype_code(dZ), n, d_out, _rows(dZ), G,
-                                         float(grad_scale), s.data_ptr(), _stream())
+    assert s.dtype == torch.float32 and s.is_contiguous() and s.shape[0] == n and 0 <= out_col and out_col + G <= s.shape[1]
+    lib = load_library()
+    if s.shape[1] == G:
+        st = lib.gq_group_weights(dZ.data_ptr(), _dtype_code(dZ), n, d_out, _rows(dZ), G,
+                                  float(grad_scale), s.data_ptr(), _stream())
+    else:
+        st = lib.gq_group_weights_strided(dZ.data_ptr(), _dtype_code(dZ), n, d_out, _rows(dZ), G, float(grad_scale),
+                                          s.data_ptr() + 4 * out_col, int(s.shape[1]), _stream())
     _check(st, "gq_group_weights")
     return s
 

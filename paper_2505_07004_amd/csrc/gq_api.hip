@@ -38,7 +38,17 @@ int gq_group_weights(const void* dZ, gq_dtype dz_dtype, int64_t n, int64_t d_out
   if (n == 0) return GQ_OK;
   if (!dZ || !s) return GQ_ERR_NULLPTR;
   if (!aligned16(dZ) || ((size_t)ld_dz * elem_size(dz_dtype)) % 16 != 0) return GQ_ERR_ALIGN;
-  return from_hip(gq::launch_group_weights(dZ, dz_dtype, n, d_out, ld_dz, G, grad_scale, s, (hipStream_t)hip_stream));
+  return from_hip(gq::launch_group_weights(dZ, dz_dtype, n, d_out, ld_dz, G, grad_scale, s, G, (hipStream_t)hip_stream));
+}
+
+int gq_group_weights_strided(const void* dZ, gq_dtype dz_dtype, int64_t n, int64_t d_out, int64_t ld_dz, int32_t G,
+                             float grad_scale, float* s, int64_t ld_s, void* hip_stream) {
+  if (!valid_dtype((int)dz_dtype)) return GQ_ERR_DTYPE;
+  if (n < 0 || d_out <= 0 || G <= 0 || d_out % G != 0 || ld_dz < d_out || ld_s < G) return GQ_ERR_SHAPE;
+  if (n == 0) return GQ_OK;
+  if (!dZ || !s) return GQ_ERR_NULLPTR;
+  if (!aligned16(dZ) || ((size_t)ld_dz * elem_size(dz_dtype)) % 16 != 0) return GQ_ERR_ALIGN;
+  return from_hip(gq::launch_group_weights(dZ, dz_dtype, n, d_out, ld_dz, G, grad_scale, s, ld_s, (hipStream_t)hip_stream));
 }
 
 size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in, int32_t G) {

@@ -92,7 +92,7 @@ __host__ __device__ inline void band_decode(int64_t t, int rpt, int64_t NT, int&
 
 // ---- launchers (each validates nothing; the C ABI layer has done that) -----
 hipError_t launch_group_weights(const void* dZ, gq_dtype dt, int64_t n, int64_t d_out, int64_t ld,
-                                int G, float grad_scale, float* s, hipStream_t st);
+                                int G, float grad_scale, float* s, int64_t ld_s, hipStream_t st);
 
 hipError_t launch_fisher_gram_f32(const float* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
                                   int G, float* H, bool accumulate, hipStream_t st);

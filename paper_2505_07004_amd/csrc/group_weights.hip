@@ -36,7 +36,7 @@ template <> struct Elems<__bf16> {
 template <typename T, int LPP, bool VEC>
 __global__ __launch_bounds__(256) void group_weights_kernel(const T* __restrict__ dZ, int64_t n_pairs,
                                                             int G, int64_t m, int64_t ld, float coef,
-                                                            float* __restrict__ s) {
+                                                            float* __restrict__ s, int64_t ld_s) {
   constexpr int kTeams = 256 / LPP;
   const int team = threadIdx.x / LPP;
   const int lane = threadIdx.x % LPP;
@@ -65,12 +65,12 @@ __global__ __launch_bounds__(256) void group_weights_kernel(const T* __restrict_
     float acc = (a0 + a1) + (a2 + a3);
 #pragma unroll
     for (int off = LPP / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-    if (lane == 0) s[p] = coef * acc;
+    if (lane == 0) s[i * ld_s + k] = coef * acc;
   }
 }
 
 template <typename T, int LPP>
-hipError_t launch_t(const T* dZ, int64_t n, int64_t m, int64_t ld, int G, float coef, float* s, bool vec,
+hipError_t launch_t(const T* dZ, int64_t n, int64_t m, int64_t ld, int G, float coef, float* s, int64_t ld_s, bool vec,
                     hipStream_t st) {
   const int64_t n_pairs = n * G;
   const int64_t teams = 256 / LPP;
@@ -78,33 +78,33 @@ hipError_t launch_t(const T* dZ, int64_t n, int64_t m, int64_t ld, int G, float 
   const int64_t cap = 256 * 16;  // 16 resident blocks per CU is more than enough to saturate HBM
   if (blocks > cap) blocks = cap;
   if (vec)
-    group_weights_kernel<T, LPP, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dZ, n_pairs, G, m, ld, coef, s);
+    group_weights_kernel<T, LPP, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dZ, n_pairs, G, m, ld, coef, s, ld_s);
   else
-    group_weights_kernel<T, LPP, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dZ, n_pairs, G, m, ld, coef, s);
+    group_weights_kernel<T, LPP, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dZ, n_pairs, G, m, ld, coef, s, ld_s);
   return hipGetLastError();
 }
 
 template <typename T>
 hipError_t launch_dt(const T* dZ, int64_t n, int64_t d_out, int64_t ld, int G, float grad_scale, float* s,
-                     hipStream_t st) {
+                     int64_t ld_s, hipStream_t st) {
   const int64_t m = d_out / G;
   const float coef = (float)((double)grad_scale * (double)grad_scale / (double)m);
   constexpr int V = Elems<T>::kPerVec;
   const bool vec = (m % V == 0);  // with a 16-byte aligned base and pitch every segment start is aligned
   const int64_t work = vec ? m / V : m;  // loads per segment
-  if (work >= 64) return launch_t<T, 64>(dZ, n, m, ld, G, coef, s, vec, st);
-  if (work >= 16) return launch_t<T, 16>(dZ, n, m, ld, G, coef, s, vec, st);
-  if (work >= 4) return launch_t<T, 4>(dZ, n, m, ld, G, coef, s, vec, st);
-  return launch_t<T, 1>(dZ, n, m, ld, G, coef, s, vec, st);
+  if (work >= 64) return launch_t<T, 64>(dZ, n, m, ld, G, coef, s, ld_s, vec, st);
+  if (work >= 16) return launch_t<T, 16>(dZ, n, m, ld, G, coef, s, ld_s, vec, st);
+  if (work >= 4) return launch_t<T, 4>(dZ, n, m, ld, G, coef, s, ld_s, vec, st);
+  return launch_t<T, 1>(dZ, n, m, ld, G, coef, s, ld_s, vec, st);
 }
 
 }  // namespace
 
 hipError_t launch_group_weights(const void* dZ, gq_dtype dt, int64_t n, int64_t d_out, int64_t ld, int G,
-                                float grad_scale, float* s, hipStream_t st) {
+                                float grad_scale, float* s, int64_t ld_s, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  if (dt == GQ_F32) return launch_dt<float>((const float*)dZ, n, d_out, ld, G, grad_scale, s, st);
-  return launch_dt<__bf16>((const __bf16*)dZ, n, d_out, ld, G, grad_scale, s, st);
+  if (dt == GQ_F32) return launch_dt<float>((const float*)dZ, n, d_out, ld, G, grad_scale, s, ld_s, st);
+  return launch_dt<__bf16>((const __bf16*)dZ, n, d_out, ld, G, grad_scale, s, ld_s, st);
 }
 
 }  // namespace gq

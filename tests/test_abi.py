@@ -21,7 +21,7 @@ def test_header_declares_the_expected_calls():
     syms = _declared_symbols()
     for name in ("gq_group_weights", "gq_fisher_gram", "gq_objective", "gq_fisher_mirror",
                  "gq_fisher_gram_workspace_bytes", "gq_objective_workspace_bytes",
-                 "gq_cd_assign", "gq_cd_workspace_bytes", "gq_version", "gq_status_string"):
+                 "gq_cd_assign", "gq_cd_workspace_bytes", "gq_group_weights_strided", "gq_version", "gq_status_string"):
         assert name in syms
 
 
@@ -58,6 +58,8 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_fisher_gram(odd, 1, 4, 8, 8, a16, 2, a16, 0, None, 0, None) == -4
     assert lib.gq_fisher_gram(a16, 1, 4, 12, 12, a16, 2, a16, 0, None, 0, None) == -4  # bf16 pitch 24 B
     assert lib.gq_fisher_gram(a16, 1, 4, 8, 8, a16, 2, a16, 64, None, 0, None) == -7   # unknown flag
+    assert lib.gq_group_weights_strided(a16, 0, 4, 8, 8, 2, 1.0, a16, 1, None) == -2      # output pitch smaller than G
+    assert lib.gq_group_weights_strided(a16, 0, 0, 8, 8, 2, 1.0, a16, 6, None) == 0       # no tokens: nothing to do
     # mirror
     assert lib.gq_fisher_mirror(None, 8, 2, None) == -1
     assert lib.gq_fisher_mirror(a16, 0, 2, None) == -2

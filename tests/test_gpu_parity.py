@@ -237,3 +237,30 @@ def test_objective_zero_when_nothing_changed():
     obj = gq.gq_objective(W, W.clone(), H)
     torch.cuda.synchronize()
     assert bool((obj == 0).all())
+
+
+# ------------------------------------------------------------------ layers that share X
+def test_stacked_group_weights_and_one_gram_call_for_three_layers():
+    n, d_in = 700, 320
+    X = wl.make_x_outlier(n, d_in, 5, 20.0, 91, DEV, torch.bfloat16)
+    layers = [(wl.make_dz(n, 96, 1.0, 1.5, 92, DEV), 4), (wl.make_dz(n, 64, 1.0, 1.5, 93, DEV).to(torch.bfloat16), 2),
+              (wl.make_dz(n, 40, 1.0, 1.5, 94, DEV), 1)]
+    G_total = sum(G for _, G in layers)
+    s_all = torch.full((n, G_total), float("nan"), device=DEV)
+    col = 0
+    for dZ, G in layers:
+        gq.gq_group_weights(dZ, G, out=s_all, out_col=col)
+        assert torch.equal(s_all[:, col:col + G], gq.gq_group_weights(dZ, G))      # same kernel, same order: bit-identical
+        col += G
+    assert not torch.isnan(s_all).any()
+    H = gq.gq_fisher_gram(X, s_all, mirror=True)
+    torch.cuda.synchronize()
+    X64 = to_np64(X)
+    col = 0
+    for dZ, G in layers:
+        ref = oracle.fisher_gram(X64, oracle.group_weights(to_np64(dZ), G))
+        for k in range(G):
+            err = rel_fro(to_np64(H[col + k]), ref[k])
+            say(f"stacked layers: H[{col + k}] rel-Frobenius {err:.2e}")
+            assert err <= TOL_BF16
+        col += G

@@ -293,3 +293,14 @@ def test_cd_tie_goes_to_the_lower_index_and_rejects_nonpositive_diagonal():
     assert Q.tolist() == [[2, 0]] and What.tolist() == [[0.5, 0.0]]
     with pytest.raises(ValueError):
         oracle.cd_assign(W, np.zeros((1, 2)), C, np.zeros((1, 2, 2)))
+
+
+def test_gram_of_stacked_layer_weights_is_the_layers_grams_one_after_the_other():
+    # layers that read the same X: Algorithm 1, line 4 is linear in s column by column
+    r = _rng(40)
+    X = r.standard_normal((30, 6))
+    dZa, dZb = r.standard_normal((30, 8)), r.standard_normal((30, 12))
+    sa, sb = oracle.group_weights(dZa, 2), oracle.group_weights(dZb, 3)
+    H = oracle.fisher_gram(X, np.concatenate([sa, sb], axis=1))
+    np.testing.assert_array_equal(H[:2], oracle.fisher_gram(X, sa))
+    np.testing.assert_array_equal(H[2:], oracle.fisher_gram(X, sb))

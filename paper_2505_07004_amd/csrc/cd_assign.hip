@@ -11,9 +11,9 @@
 //     B0[j][i] = sum_{i'} delta[j][i'] * Ht[i][i']            (all i', current delta)
 // for its 128 coordinates at once (bf16 matrix cores at fp32-grade accuracy: both operands
 // split into hi + lo bf16 terms, three products), and a second kernel walks the block
-// sequentially, one thread per channel with its 128 targets in registers: after coordinate i
-// changes by eps, the targets of the later coordinates i'' of the block move by
-// -eps * Ht[i''][i].  The block's new delta is written back (split) for the next block's GEMM.
+// sequentially, four lanes per channel: after coordinate i changes by eps, the targets of the
+// later coordinates i'' of the block move by -eps * Ht[i''][i].  The block's new delta is
+// written back (split) for the next block's GEMM.
 // Compared with Algorithm 4 the bookkeeping differs (the part of the sum that lies outside
 // the block is recomputed per block from the current weights instead of being carried along
 // and corrected after each block; the flop count is the same), the update rule does not.

@@ -15,4 +15,5 @@ from .gq_oracle import (  # noqa: F401
     objective_rows_from_tokens,
     cd_coordinate_target,
     cd_assign,
+    lnq_codebook,
 )

@@ -242,3 +242,37 @@ def cd_assign(W, What, codebook, H, G: int | None = None, n_cycles: int = 1):
                 What[j0:j1, i] = Ck[rows, q]               # the grid value itself, not w + (c - w)
                 delta[:, i] = What[j0:j1, i] - Wk[:, i]
     return Q, What
+
+
+def lnq_codebook(W, Q, H, n_levels: int, G: int | None = None, lam: float = 1e-7):
+    """Closed-form codebook update of LNQ for fixed assignments (Section 4.2, Eq. "conti-sol",
+    Algorithm 2 lines 4 and 14), every output channel j of group k against that group's Hbar_k:
+
+        c^(j) = (P^T H P + lam I)^-1 P^T H w_j,     P[i, q] = 1 if Q[j, i] == q else 0,
+
+    with the small constant lam (1e-7 in the paper) on the diagonal, which also settles grid
+    points that no coordinate is assigned to (their value becomes 0).
+    W [d_out, d_in], Q [d_out, d_in] integer grid indices in [0, n_levels), H [G, d_in, d_in].
+    Returns (codebook [d_out, n_levels] float64, What [d_out, d_in] = P c).
+    """
+    W = np.asarray(W, dtype=_F64)
+    Q = np.asarray(Q)
+    H = np.asarray(H, dtype=_F64)
+    if H.ndim == 2:
+        H = H[None]
+    G = H.shape[0] if G is None else G
+    d_out, d_in = W.shape
+    if Q.shape != W.shape or Q.min() < 0 or Q.max() >= n_levels:
+        raise ValueError("Q must hold grid indices in [0, n_levels) for every weight")
+    C = np.zeros((d_out, n_levels), dtype=_F64)
+    What = np.empty_like(W)
+    for k, (j0, j1) in enumerate(group_partition(d_out, G)):
+        Hk = H[k]
+        for j in range(j0, j1):
+            P = np.zeros((d_in, n_levels), dtype=_F64)
+            P[np.arange(d_in), Q[j]] = 1.0
+            A = P.T @ Hk @ P + lam * np.eye(n_levels)
+            b = P.T @ (Hk @ W[j])
+            C[j] = np.linalg.solve(A, b)
+            What[j] = P @ C[j]
+    return C, What

@@ -304,3 +304,65 @@ def test_gram_of_stacked_layer_weights_is_the_layers_grams_one_after_the_other()
     H = oracle.fisher_gram(X, np.concatenate([sa, sb], axis=1))
     np.testing.assert_array_equal(H[:2], oracle.fisher_gram(X, sa))
     np.testing.assert_array_equal(H[2:], oracle.fisher_gram(X, sb))
+
+
+# ---------------------------------------------------------------- LNQ codebook step
+def test_lnq_codebook_worked_example():
+    ex = _golden("lnq_codebook_worked_example.json")      # worked by hand from Eq. (conti-sol)
+    C, What = oracle.lnq_codebook(np.array(ex["W"]), np.array(ex["Q"]), np.array(ex["H"]), 2, lam=0.0)
+    np.testing.assert_allclose(C, ex["codebook"], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(What, ex["What"], rtol=0, atol=1e-14)
+
+
+def test_lnq_codebook_with_identity_hessian_is_the_cluster_mean_and_empty_clusters_get_zero():
+    # H = I: the problem is 1-D k-means' centroid step (textbook): c_q = mean of the weights assigned to q
+    r = _rng(50)
+    d_out, d_in, m = 5, 40, 4
+    W = r.standard_normal((d_out, d_in))
+    Q = r.integers(0, 3, size=(d_out, d_in))                 # grid point 3 is never used
+    C, What = oracle.lnq_codebook(W, Q, np.eye(d_in)[None], m, lam=1e-12)
+    for j in range(d_out):
+        for q in range(3):
+            np.testing.assert_allclose(C[j, q], W[j, Q[j] == q].mean(), rtol=1e-9)
+        assert C[j, 3] == 0.0
+    np.testing.assert_array_equal(What, np.take_along_axis(C, Q, axis=1))
+
+
+def test_lnq_codebook_is_the_minimiser_of_the_layer_objective_over_the_grid_values():
+    W, What0, C0, H = _cd_case(51, d_out=6, d_in=14, G=2, m=4)
+    Q = np.argmin(np.abs(C0[:, None, :] - What0[:, :, None]), axis=2)
+    lam = 1e-9
+    C, What = oracle.lnq_codebook(W, Q, H, 4, 2, lam=lam)
+    base = oracle.objective(W, What, H, 2)[1]
+    # Prop. 4.1, first inequality: the update cannot increase any channel's objective
+    assert np.all(base <= oracle.objective(W, What0, H, 2)[1] * (1 + 1e-12))
+    # stationarity (normal equations of Eq. (conti-sol)): P^T H (w - P c) = lam c
+    for j in range(6):
+        P = np.eye(4)[Q[j]]
+        g = P.T @ H[j // 3] @ (W[j] - What[j])
+        np.testing.assert_allclose(g, lam * C[j], atol=1e-9 * np.abs(H).max())
+    # and brute force: moving any grid value of any channel either way does not help
+    r = _rng(52)
+    for _ in range(200):
+        j, q = r.integers(0, 6), r.integers(0, 4)
+        C2 = C.copy()
+        C2[j, q] += r.choice([-1, 1]) * 10.0 ** r.uniform(-4, -1)
+        trial = np.take_along_axis(C2, Q, axis=1)
+        assert oracle.objective(W, trial, H, 2)[1][j] >= base[j] * (1 - 1e-9)
+
+
+def test_lnq_codebook_recovers_an_exactly_representable_weight_and_is_relabeling_invariant():
+    r = _rng(53)
+    d_in, m = 20, 4
+    H = oracle.fisher_gram(r.standard_normal((50, d_in)), r.random((50, 1)) + 0.1)
+    c_true = np.array([[-1.5, -0.25, 0.5, 2.0]])
+    Q = r.integers(0, m, size=(1, d_in))
+    W = np.take_along_axis(c_true, Q, axis=1)
+    C, What = oracle.lnq_codebook(W, Q, H, m, lam=0.0)
+    np.testing.assert_allclose(C, c_true, rtol=1e-9)
+    perm = np.array([2, 0, 3, 1])
+    C2, What2 = oracle.lnq_codebook(W, perm[Q], H, m, lam=0.0)
+    np.testing.assert_allclose(C2[0, perm], C[0], rtol=1e-9)
+    np.testing.assert_allclose(What2, What, rtol=1e-9)
+    with pytest.raises(ValueError):
+        oracle.lnq_codebook(W, Q + 1, H, m)

@@ -11,6 +11,7 @@
  *   gq_fisher_mirror  H[k][b,a] = H[k][a,b]  for a < b                    (storage of the full square)
  *   gq_objective      obj[k]  = sum_{j in J_k} (w_j-what_j)^T H[k] (w_j-what_j)   (Eq. "ours2", Section 3.2)
  *   gq_cd_assign      cyclic coordinate descent on the assignments against H[k]   (Section 4.2, Eq. "cd_closed")
+ *   gq_lnq_codebook   closed-form grids for fixed assignments against H[k]        (Section 4.2, Eq. "conti-sol")
  *
  * Conventions shared by every call
  *   - Every data pointer is DEVICE memory on the current HIP device, allocated
@@ -202,6 +203,40 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
                  int64_t d_out, int64_t d_in, int64_t ld_w, const float* H, int32_t G,
                  int32_t n_cycles, uint8_t* Q,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace gq_lnq_codebook needs (0 for invalid sizes). */
+size_t gq_lnq_codebook_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G, int32_t n_levels);
+
+/*
+ * The codebook step of layer-wise non-uniform quantization run against the group
+ * Hessians (Section 4.2: Algorithm 2, lines 4 and 14; the closed form of Eq. "conti-sol").
+ * For fixed assignments Q, every output channel j (group k = j / (d_out/G)) gets the grid
+ *
+ *   codebook[j,:] = (P^T H[k] P + lam I)^-1 P^T H[k] W[j,:],   P[i,q] = 1 if Q[j,i] == q else 0,
+ *
+ * the minimiser of (W[j,:] - P c)^T H[k] (W[j,:] - P c) + lam |c|^2 over c.  P^T H[k] is
+ * accumulated in fp32 from exact products (H enters as three bf16 terms), the n_levels x
+ * n_levels system is solved in fp64 by Gaussian elimination with partial pivoting.  A grid
+ * point no coordinate is assigned to gets the value 0 (lam > 0).
+ *
+ *   W         [d_out, d_in]     device fp32, row pitch ld_w elements (row j = output channel j)
+ *   Q         [d_out, d_in]     device bytes, dense; every entry < n_levels
+ *   H         [G, d_in, d_in]   device fp32; only the upper triangle (incl. diagonal) is read
+ *   lam       >= 0              the paper's value is 1e-7
+ *   codebook  [d_out, n_levels] device fp32, dense, written
+ *   What      [d_out, d_in]     device fp32, pitch ld_w, or NULL: What[j,i] = codebook[j,Q[j,i]]
+ *   workspace  at least gq_lnq_codebook_workspace_bytes() bytes, 256-byte aligned
+ *
+ * Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_out <= 0, d_in <= 0, G <= 0, d_out % G != 0,
+ * ld_w < d_in, n_levels <= 0, lam < 0 or NaN), GQ_ERR_UNSUPPORTED (n_levels > 16),
+ * GQ_ERR_ALIGN (W/What/H not 16-byte aligned or ld_w*4 not a multiple of 16),
+ * GQ_ERR_WORKSPACE, GQ_ERR_HIP.  An entry of Q >= n_levels is not detected: its
+ * coordinate is left out of every sum and its What is 0.
+ */
+int gq_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld_w, const uint8_t* Q,
+                    const float* H, int32_t G, int32_t n_levels, double lam,
+                    float* codebook, float* What,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

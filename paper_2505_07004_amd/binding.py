@@ -62,6 +62,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                  c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_cd_workspace_bytes.restype = c.c_size_t
     lib.gq_cd_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
+    lib.gq_lnq_codebook_workspace_bytes.restype = c.c_size_t
+    lib.gq_lnq_codebook_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32, c.c_int32]
+    lib.gq_lnq_codebook.restype = c.c_int
+    lib.gq_lnq_codebook.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32,
+                                    c.c_int32, c.c_double, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_cd_assign.restype = c.c_int
     lib.gq_cd_assign.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int64, c.c_int64,
                                  c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -224,3 +229,30 @@ def gq_cd_assign(W: torch.Tensor, What: torch.Tensor, codebook: torch.Tensor, H:
                           ws_ptr, ws_bytes, _stream())
     _check(st, "gq_cd_assign")
     return Q
+
+
+def gq_lnq_codebook(W: torch.Tensor, Q: torch.Tensor, H: torch.Tensor, n_levels: int, lam: float = 1e-7,
+                    What: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Closed-form grids for fixed assignments against H[k] (Section 4.2, Eq. "conti-sol").
+    `Q` [d_out, d_in] uint8; returns the codebook [d_out, n_levels] fp32.  If `What` (same shape and
+    pitch as W) is given it is overwritten with codebook[j, Q[j, i]]."""
+    _require_gpu(W, Q, H, What, workspace)
+    d_out, d_in = W.shape
+    G = int(H.shape[0])
+    assert W.dtype == torch.float32 and H.dtype == torch.float32 and H.is_contiguous()
+    assert Q.dtype == torch.uint8 and Q.is_contiguous() and tuple(Q.shape) == (d_out, d_in)
+    if What is not None:
+        assert What.dtype == torch.float32 and What.shape == W.shape and _rows(W) == _rows(What)
+    lib = load_library()
+    need = int(lib.gq_lnq_codebook_workspace_bytes(d_out, d_in, G, int(n_levels)))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(max(need, 1), W.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    codebook = torch.empty((d_out, int(n_levels)), dtype=torch.float32, device=W.device)
+    st = lib.gq_lnq_codebook(W.data_ptr(), d_out, d_in, _rows(W), Q.data_ptr(), H.data_ptr(), G, int(n_levels),
+                             float(lam), codebook.data_ptr(), What.data_ptr() if What is not None else None,
+                             ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_lnq_codebook")
+    return codebook

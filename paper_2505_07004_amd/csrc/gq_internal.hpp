@@ -115,4 +115,9 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
                             void* ws, hipStream_t st);
 size_t cd_workspace(int64_t d_out, int64_t d_in, int G);
 
+hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld, const unsigned char* Q,
+                               const float* H, int G, int n_levels, double lam, float* codebook, float* What,
+                               void* ws, hipStream_t st);
+size_t lnq_codebook_workspace(int64_t d_out, int64_t d_in, int G, int n_levels);
+
 }  // namespace gq

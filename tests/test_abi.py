@@ -21,7 +21,8 @@ def test_header_declares_the_expected_calls():
     syms = _declared_symbols()
     for name in ("gq_group_weights", "gq_fisher_gram", "gq_objective", "gq_fisher_mirror",
                  "gq_fisher_gram_workspace_bytes", "gq_objective_workspace_bytes",
-                 "gq_cd_assign", "gq_cd_workspace_bytes", "gq_group_weights_strided", "gq_version", "gq_status_string"):
+                 "gq_cd_assign", "gq_cd_workspace_bytes", "gq_group_weights_strided",
+                 "gq_lnq_codebook", "gq_lnq_codebook_workspace_bytes", "gq_version", "gq_status_string"):
         assert name in syms
 
 
@@ -83,6 +84,21 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_cd_assign(a16, a16, a16, 8, 8, 8, 8, a16, 4, 0, None, P(0x1100), big, None) == 0       # zero cycles: nothing to do
     assert lib.gq_cd_workspace_bytes(8, 8, 4) > 0
     assert lib.gq_cd_workspace_bytes(10, 8, 4) == 0
+    # codebook step
+    lam = 1e-7
+    assert lib.gq_lnq_codebook(a16, 10, 8, 8, a16, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -2   # G does not divide d_out
+    assert lib.gq_lnq_codebook(a16, 8, 8, 4, a16, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -2    # pitch < width
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 0, lam, a16, None, P(0x1100), big, None) == -2    # no grid points
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 4, -1.0, a16, None, P(0x1100), big, None) == -2   # negative damping
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 4, float("nan"), a16, None, P(0x1100), big, None) == -2
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 17, lam, a16, None, P(0x1100), big, None) == -7   # more than 16 grid points
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, None, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -1   # no assignments
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 4, lam, None, None, P(0x1100), big, None) == -1   # no output
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 4, lam, a16, odd, P(0x1100), big, None) == -4
+    assert lib.gq_lnq_codebook(a16, 8, 6, 6, a16, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -4    # pitch 24 B
+    assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 4, lam, a16, None, P(0x1100), 16, None) == -5
+    assert lib.gq_lnq_codebook_workspace_bytes(8, 8, 4, 4) > 0
+    assert lib.gq_lnq_codebook_workspace_bytes(8, 8, 4, 17) == 0
 
 
 def test_binding_refuses_cpu_tensors():

@@ -1,0 +1,164 @@
+"""The closed-form codebook step on the GPU (through the C ABI) against the fp64 oracle.
+
+The solution of a linear system is as accurate as the system is well conditioned, and the
+conditioning of P^T H P is a property of the data, not of the kernel.  So the first check is a
+backward one, independent of conditioning: with the oracle's fp64 A = P^T H P and b = P^T H w, the
+GPU's grid c must satisfy |(A + lam I) c - b| <= 2^-20 (|P|^T |H| |P| |c| + |P|^T |H| |w|) entry by
+entry (the GPU adds exact products in fp32, a relative error of a few 2^-24 of the sum of the
+absolute values of the terms; measured: 3e-8).  The second check is the
+one the method cares about: the channel's objective at the GPU's grid exceeds the minimum (the
+oracle's) by a relative 1e-6 at most.  The third compares the grids directly, the difference
+divided by the condition number of the system (a looser, normwise bound: 1e-5)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_07004_amd import binding as gq
+from paper_2505_07004_amd import workloads as wl
+from parity_utils import say, to_np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+LAM = 1e-7
+
+
+def _case(n, d_in, d_out, G, bits, seed, ld=None):
+    X = wl.make_x_outlier(n, d_in, max(1, d_in // 64), 20.0, seed, DEV, torch.float32)
+    dZ = wl.make_dz(n, d_out, 1.0, 1.5, seed + 1, DEV)
+    s = gq.gq_group_weights(dZ, G)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+    W = wl.make_w(d_out, d_in, seed + 2, DEV)
+    What, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
+    Q = torch.argmin((C[:, None, :] - What[:, :, None]).abs(), dim=2).to(torch.uint8).contiguous()
+    if ld:
+        buf = torch.zeros((d_out, ld), device=DEV)
+        buf[:, :d_in] = W
+        W = buf[:, :d_in]
+    return W, Q, H
+
+
+def _check_channels(Wn, Qn, Hk, Cg, m, lam, what):
+    """Wn, Qn, Cg: the rows of some channels of ONE group; Hk that group's Hessian (fp64)."""
+    d_in = Wn.shape[1]
+    Habs = np.abs(Hk)
+    worst_back, worst_obj, worst_fwd = 0.0, 0.0, 0.0
+    Co, _ = oracle.lnq_codebook(Wn, Qn, Hk[None], m, 1, lam)
+    for j in range(Wn.shape[0]):
+        P = np.zeros((d_in, m))
+        P[np.arange(d_in), Qn[j]] = 1.0
+        A = P.T @ Hk @ P + lam * np.eye(m)
+        b = P.T @ (Hk @ Wn[j])
+        c = Cg[j]
+        scale = (P.T @ Habs @ P) @ np.abs(c) + P.T @ (Habs @ np.abs(Wn[j]))
+        used = P.sum(axis=0) > 0
+        resid = np.abs(A @ c - b)
+        back = float(np.max(resid[used] / scale[used]))
+        worst_back = max(worst_back, back)
+        assert np.all(c[~used] == 0.0), f"{what}: channel {j}: an unused grid point is not 0"
+        e_g, e_o = Wn[j] - P @ c, Wn[j] - P @ Co[j]
+        o_g, o_o = e_g @ Hk @ e_g, e_o @ Hk @ e_o
+        worst_obj = max(worst_obj, float((o_g - o_o) / o_o))
+        cond = np.linalg.cond(A[np.ix_(used, used)])
+        fwd = float(np.max(np.abs(c - Co[j])) / np.max(np.abs(Co[j])))
+        worst_fwd = max(worst_fwd, fwd / cond)
+    say(f"{what}: backward error {worst_back:.2e} (bound 9.5e-07), objective above the minimum by {worst_obj:.2e} (rel), "
+        f"grid error / condition number {worst_fwd:.2e}")
+    assert worst_back <= 2.0 ** -20
+    assert worst_obj <= 1e-6
+    assert worst_fwd <= 1e-5
+
+
+@pytest.mark.parametrize("n,d_in,d_out,G,bits,ld", [
+    (512, 256, 128, 2, 3, None),        # two column tiles, 64 channels x 8 grid points = 4 row tiles per group
+    (400, 200, 96, 4, 2, 208),          # ragged contraction and columns, 24 x 4 = 96 rows per group (ragged row tile), padded pitch
+    (600, 384, 48, 1, 4, None),         # 16 grid points
+    (300, 132, 40, 2, 3, 136),          # 4 coordinates in the last tile, 160 rows per group
+])
+def test_codebook_step_solves_the_oracles_system(n, d_in, d_out, G, bits, ld):
+    say(f"lnq codebook n={n} d_in={d_in} d_out={d_out} G={G} bits={bits} ld={ld}")
+    W, Q, H = _case(n, d_in, d_out, G, bits, 131 + d_in, ld)
+    m = 1 << bits
+    What = torch.zeros_like(W) if ld is None else torch.zeros((d_out, ld), device=DEV)[:, :d_in]
+    C = gq.gq_lnq_codebook(W, Q, H, m, LAM, What=What)
+    torch.cuda.synchronize()
+    assert torch.equal(What, torch.gather(C, 1, Q.long()))              # What is the grid value of its code, exactly
+    Wn, Qn, Hn, Cg = to_np64(W), Q.cpu().numpy().astype(np.int64), to_np64(H), to_np64(C)
+    per = d_out // G
+    for k in range(G):
+        r = slice(k * per, (k + 1) * per)
+        _check_channels(Wn[r], Qn[r], Hn[k], Cg[r], m, LAM, f"group {k}")
+    # and without the optional output
+    C2 = gq.gq_lnq_codebook(W, Q, H, m, LAM)
+    torch.cuda.synchronize()
+    assert torch.equal(C, C2)                                           # deterministic
+
+
+def test_identity_hessian_gives_cluster_means_and_unused_points_are_zero():
+    d_out, d_in, m = 64, 200, 8
+    W = wl.make_w(d_out, d_in, 3, DEV)
+    g = torch.Generator(device="cpu").manual_seed(11)
+    Q = torch.randint(0, m - 1, (d_out, d_in), generator=g, dtype=torch.uint8).to(DEV)   # grid point m-1 is never used
+    Q[0, :] = 2                                                                            # a channel with a single cluster
+    H = torch.eye(d_in, device=DEV).repeat(2, 1, 1).contiguous()
+    C = gq.gq_lnq_codebook(W, Q, H, m, LAM)
+    torch.cuda.synchronize()
+    Wn, Qn, Cg = to_np64(W), Q.cpu().numpy(), to_np64(C)
+    for j in range(d_out):
+        for q in range(m):
+            sel = Qn[j] == q
+            want = Wn[j][sel].sum() / (sel.sum() + LAM) if sel.any() else 0.0
+            assert abs(Cg[j, q] - want) <= 1e-6 * np.abs(Wn[j]).max(), (j, q, Cg[j, q], want)
+    assert np.all(Cg[:, m - 1] == 0.0)
+
+
+def test_codebook_step_after_a_cd_cycle_does_not_increase_the_objective():
+    """Prop. 4.1: each of the two alternating steps of Algorithm 2 can only lower the objective."""
+    W, Q0, H = _case(512, 256, 128, 2, 3, 977)
+    m = 8
+    What = torch.empty_like(W)
+    C = gq.gq_lnq_codebook(W, Q0, H, m, LAM, What=What)
+    obj = [gq.gq_objective(W, What, H).cpu().numpy()]
+    for it in range(3):
+        Q = gq.gq_cd_assign(W, What, C, H, n_cycles=1)
+        obj.append(gq.gq_objective(W, What, H).cpu().numpy())
+        C = gq.gq_lnq_codebook(W, Q, H, m, LAM, What=What)
+        obj.append(gq.gq_objective(W, What, H).cpu().numpy())
+    torch.cuda.synchronize()
+    say("objective along 3 alternations: " + ", ".join(f"{o.sum():.5f}" for o in obj))
+    for a, b in zip(obj[:-1], obj[1:]):
+        assert np.all(b <= a * (1 + 1e-6))
+    assert obj[-1].sum() < 0.9 * obj[0].sum()
+
+
+def test_codebook_step_at_the_llama2_7b_shape_on_sampled_channels():
+    """Full size of workload configuration 2 (d_out = d_in = 4096, G = 4), 3-bit and 4-bit grids;
+    the oracle's system is formed for 12 sampled channels of every group."""
+    spec = wl.CONFIGS["llama2_7b_attn"]
+    X = wl.make_x(spec, DEV)
+    s = gq.gq_group_weights(wl.make_dz_for(spec, DEV), spec.G)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    del X, s
+    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, spec.d_in))
+    W = wl.make_w(spec.d_out, spec.d_in, 7, DEV)
+    per = spec.d_out // spec.G
+    g = torch.Generator().manual_seed(5)
+    for bits in (3, 4):
+        m = 1 << bits
+        say(f"lnq codebook at {spec.name}: W[{spec.d_out},{spec.d_in}] G={spec.G} grid points {m}")
+        What0, C0 = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
+        Q = torch.argmin((C0[:, None, :] - What0[:, :, None]).abs(), dim=2).to(torch.uint8).contiguous()
+        before = gq.gq_objective(W, What0, H)
+        What = torch.empty_like(W)
+        C = gq.gq_lnq_codebook(W, Q, H, m, LAM, What=What)
+        after = gq.gq_objective(W, What, H)
+        torch.cuda.synchronize()
+        say(f"  objective {before.tolist()} -> {after.tolist()}")
+        assert torch.all(after <= before)
+        assert torch.equal(What, torch.gather(C, 1, Q.long()))
+        for k in range(spec.G):
+            rows = (k * per + torch.randperm(per, generator=g)[:12]).to(DEV)
+            _check_channels(to_np64(W[rows]), Q[rows].cpu().numpy().astype(np.int64), to_np64(H[k]), to_np64(C[rows]),
+                            m, LAM, f"  group {k}, 12 sampled channels")
+        del What, C, What0, C0, Q

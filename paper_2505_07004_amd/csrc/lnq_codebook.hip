@@ -7,19 +7,27 @@
 //     A_j[q][q'] = sum_{i : Q[j][i] == q'} T_j[q][i],      b_j[q] = sum_i T_j[q][i] * w_j[i].
 // T for all channels of a group is ONE contraction (d_out/G * m rows) x d_in x d_in on the bf16
 // matrix cores: the one-hot operand is exact in bf16, H is split into three bf16 terms
-// (24 mantissa bits), so every product is exact and only the fp32 accumulation rounds.  A
-// second kernel bins T into A and b (one workgroup per channel, fixed-order reductions) and
-// solves the m x m system in fp64 by Gaussian elimination with partial pivoting.
+// (24 mantissa bits), so every product is exact and only the fp32 accumulation rounds.  The
+// one-hot operand never exists in memory: every lane builds its fragment from eight code bytes
+// with a few integer operations, so only H travels from L2 to LDS.  A second kernel bins T
+// into A and b (one workgroup per channel, fixed-order reductions) and solves the m x m
+// system in fp64 by Gauss-Jordan elimination with partial pivoting.
 #include "gq_internal.hpp"
 
 namespace gq {
 namespace {
 
-constexpr int kTile = 128;                           // rows (channel, grid point) and columns per workgroup
+constexpr int kRows = 256;                           // rows (channel, grid point) of T per workgroup
+constexpr int kCols = 128;                           // columns of T (= rows of H) per workgroup
 constexpr int kK = 64;                               // contraction elements per stage
-constexpr int kTileBytes = kTile * kK * 2;           // one staged operand tile (16 KiB)
-constexpr int kStageBytes = 4 * kTileBytes;          // {E, H hi, H mid, H lo}: 64 KiB
-constexpr unsigned short kOneBf16 = 0x3F80;
+constexpr int kHTile = kCols * kK * 2;               // one staged term of H (16 KiB)
+constexpr int kHStage = 3 * kHTile;                  // hi, mid, lo: 48 KiB
+constexpr int kMaxCh = 64;                           // channels per workgroup at most
+constexpr int kQStage = kMaxCh * kK;                 // their codes for one stage (4 KiB)
+constexpr int kRing = 3;                             // stages in flight
+constexpr int kLoadsPerStage = 7;                    // per wave: 6 pieces of H, 1 of the codes
+constexpr unsigned kPadCode = 0x7F;                  // a code no grid point has
+constexpr unsigned kNoLevel = 0x7E7E7E7Eu;           // a grid point no code has (rows past the tile's channels)
 
 // x = hi + mid + lo, three bf16 terms (exact for every fp32 x whose exponent leaves room).
 __device__ inline void split3_bf16(float x, unsigned short& hi, unsigned short& mid, unsigned short& lo) {
@@ -70,54 +78,108 @@ __global__ __launch_bounds__(256) void lnq_split_h_kernel(const float* __restric
   }
 }
 
-// E[(j*m + q)][i] = 1 if Q[j][i] == q else 0 (bf16), row pitch ldp, zero padded.
-__global__ __launch_bounds__(256) void lnq_onehot_kernel(const unsigned char* __restrict__ Q, int64_t d, int64_t ldp,
-                                                         int n_levels, unsigned short* __restrict__ E) {
+// Qp[j][i] = Q[j][i] for i < d and Q[j][i] < n_levels, else the pad code; row pitch ldp.
+__global__ __launch_bounds__(256) void lnq_pad_codes_kernel(const unsigned char* __restrict__ Q, int64_t d, int64_t ldp,
+                                                            int n_levels, unsigned char* __restrict__ Qp) {
   const int64_t j = blockIdx.y;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < ldp; i += (int64_t)gridDim.x * 256) {
-    const int code = i < d ? (int)Q[j * d + i] : -1;
-    for (int q = 0; q < n_levels; ++q) E[(j * n_levels + q) * ldp + i] = (q == code) ? kOneBf16 : (unsigned short)0;
+    const int64_t ic = i < d ? i : d - 1;
+    const unsigned code = Q[j * d + ic];
+    Qp[j * ldp + i] = (unsigned char)((i < d && code < (unsigned)n_levels) ? code : kPadCode);
   }
 }
 
-// T[r][i] = sum_{i'} E[r][i'] * H[k(r)][i][i']  for a 128 x 128 tile of (rows r, columns i).
-// Both operands are contraction-major; a stage is 64 contraction elements = one whole
-// 128-byte line of each of the 4 x 128 operand rows (E; H hi, mid, lo), copied straight into
-// LDS (global_load_lds_dwordx4, 8 lanes per row, wave w copies operand w) into a ring of two
-// stages with one barrier per stage; chunk c of row r sits at position c ^ ((r >> 1) & 7).
-// 4 waves of 64 x 64; three MFMAs per fragment pair (E * hi, E * mid, E * lo).
-__global__ __launch_bounds__(256) void lnq_gemm_kernel(const unsigned short* __restrict__ E,
+// Eight bf16 values, 1.0 where the code byte equals the lane's grid point (qrep = that point in
+// every byte), else 0.  All bytes involved are below 0x80, so adding 0x7F to a byte sets its
+// top bit exactly when the byte is non-zero and never carries into the next byte.
+__device__ inline bf16x8 onehot_frag(unsigned c0, unsigned c1, unsigned qrep) {
+  const unsigned m0 = ~((c0 ^ qrep) + 0x7F7F7F7Fu) & 0x80808080u;        // 0x80 in every matching byte
+  const unsigned m1 = ~((c1 ^ qrep) + 0x7F7F7F7Fu) & 0x80808080u;
+  auto one = [](unsigned s) { return (s << 7) - s; };                    // 0x0080 -> 0x3F80 in both halves
+  u32x4 v;
+  v[0] = one(__builtin_amdgcn_perm(0u, m0, 0x0C010C00u));                 // bytes 0, 1 -> the low bytes of the halves
+  v[1] = one(__builtin_amdgcn_perm(0u, m0, 0x0C030C02u));
+  v[2] = one(__builtin_amdgcn_perm(0u, m1, 0x0C010C00u));
+  v[3] = one(__builtin_amdgcn_perm(0u, m1, 0x0C030C02u));
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// T[r][i] = sum_{i'} E[r][i'] * H[k][i][i']  for the rows r = (channel, grid point) of up to 64
+// whole channels (256 rows at most) and 128 columns i.  8 waves of 64 x 64 (4 along the rows,
+// 2 along the columns).  A stage is 64 contraction elements: one whole 128-byte line of each
+// of the 3 x 128 rows of the terms of H, copied straight into LDS (global_load_lds_dwordx4;
+// chunk c of row r at position c ^ ((r >> 1) & 7)), and 64 code bytes of every channel; a ring
+// of three stages, one barrier per stage.  A lane's contraction elements within a stage are
+// the 32 consecutive ones of its half-wave (the matrix cores do not care about the order as
+// long as both operands agree), so its codes are two 16-byte reads.  Three MFMAs per fragment
+// pair (E * lo, E * mid, E * hi).  Workgroups are renumbered so that each XCD works through
+// column blocks of its own: a block of H is fetched into one L2 only.
+__global__ __launch_bounds__(512) void lnq_gemm_kernel(const unsigned char* __restrict__ Qp,
                                                        const unsigned short* __restrict__ Hh,
                                                        const unsigned short* __restrict__ Hm,
-                                                       const unsigned short* __restrict__ Hl, int64_t rows_per_group,
-                                                       int64_t ldp, int n_rt, float* __restrict__ T) {
-  __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
-  const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
-  const int64_t r0 = (int64_t)k * rows_per_group + (int64_t)rt * kTile, r_last = (int64_t)(k + 1) * rows_per_group - 1;
-  const int64_t c0 = (int64_t)blockIdx.y * kTile;
+                                                       const unsigned short* __restrict__ Hl, int64_t per_group,
+                                                       int n_levels, int n_ch, int n_rt, int G, int n_ct, int64_t ldp,
+                                                       float* __restrict__ T) {
+  __shared__ __attribute__((aligned(1024))) char smem[kRing * (kHStage + kQStage)];
+  const int n_blocks = n_rt * G * n_ct;
+  const int per_xcd = (n_blocks + 7) / 8;
+  const int v = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
+  if (v >= n_blocks) return;                                   // the whole workgroup, before any barrier
+  const int ct = v / (n_rt * G), rtg = v % (n_rt * G);
+  const int k = rtg / n_rt, rt = rtg % n_rt;
+  const int64_t j0 = (int64_t)k * per_group + (int64_t)rt * n_ch, j_last = (int64_t)(k + 1) * per_group - 1;
+  const int64_t ch_left = per_group - (int64_t)rt * n_ch;
+  const int rows_here = (int)(ch_left < n_ch ? ch_left : n_ch) * n_levels;   // rows of this tile that exist
+  const int64_t c0 = (int64_t)ct * kCols;
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int wm = wave / 2, wn = wave % 2;
-  const int64_t n_stages = ldp / kK;
-
-  const unsigned short* src = wave == 0 ? E : (wave == 1 ? Hh : wave == 2 ? Hm : Hl) + (int64_t)k * ldp * ldp;
-  const int64_t row_first = wave == 0 ? r0 : c0, row_last = wave == 0 ? r_last : ldp - 1;
+  const int n_stages = (int)(ldp / kK);
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
-  auto issue = [&](int64_t stage, int slot) {
+  const unsigned q_base = smem_base + kRing * kHStage;
+
+  // this lane's six 16-byte pieces of a stage of H and one of the codes
+  const unsigned short* hsrc[6];
+  unsigned hdst[6];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = 8 * i + lane / 8;
-      const int c = (lane % 8) ^ ((r >> 1) & 7);
-      int64_t row = row_first + r;
-      row = row < row_last ? row : row_last;             // rows past the group: repeat its last row (never stored)
-      dma16(src + row * ldp + stage * kK + 8 * c, smem_base + slot * kStageBytes + wave * kTileBytes + i * 1024);
-    }
+  for (int i = 0; i < 6; ++i) {
+    const int g = wave * 6 + i, term = g / 16, i16 = g % 16;
+    const int r = 8 * i16 + lane / 8;
+    const int c = (lane % 8) ^ ((r >> 1) & 7);
+    const unsigned short* base = term == 0 ? Hh : (term == 1 ? Hm : Hl);
+    hsrc[i] = base + (int64_t)k * ldp * ldp + (c0 + r) * ldp + 8 * c;
+    hdst[i] = term * kHTile + i16 * 1024;
+  }
+  const unsigned char* qsrc;
+  {
+    const int piece = tid % 256;
+    int64_t ch = j0 + piece / 4;
+    ch = ch < j_last ? ch : j_last;                            // channels past the group: repeat its last one (never stored)
+    qsrc = Qp + ch * ldp + 16 * (piece % 4);
+  }
+  const unsigned qdst = (wave % 4) * 1024;
+  auto issue = [&](int stage, int slot) {
+#pragma unroll
+    for (int i = 0; i < 6; ++i) dma16(hsrc[i] + (int64_t)stage * kK, smem_base + slot * kHStage + hdst[i]);
+    dma16(qsrc + (int64_t)stage * kK, q_base + slot * kQStage + qdst);
   };
+
+  // the two rows of E this lane supplies: channel and grid point
+  unsigned qrep[2];
+  int qoff[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const int lr = wm * 64 + 32 * x + lane % 32;
+    const bool valid = lr < rows_here;
+    const int ch = valid ? lr / n_levels : 0;
+    qrep[x] = valid ? (unsigned)(lr % n_levels) * 0x01010101u : kNoLevel;
+    qoff[x] = ch * kK + 32 * (lane / 32);
+  }
   const int lrow = lane % 32;
-  auto frag = [&](int slot, int tile, int row0, int t) -> bf16x8 {
-    const int pos = (2 * t + lane / 32) ^ ((lrow >> 1) & 7);
-    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kStageBytes + tile * kTileBytes + (row0 + lrow) * 128 + pos * 16]);
-    return __builtin_bit_cast(bf16x8, v);
+  auto hfrag = [&](int slot, int term, int row0, int t) -> bf16x8 {
+    const int pos = (4 * (lane / 32) + t) ^ ((lrow >> 1) & 7);
+    const u32x4 w = *reinterpret_cast<const u32x4*>(&smem[slot * kHStage + term * kHTile + (row0 + lrow) * 128 + pos * 16]);
+    return __builtin_bit_cast(bf16x8, w);
   };
 
   f32x16 acc[2][2];
@@ -129,21 +191,31 @@ __global__ __launch_bounds__(256) void lnq_gemm_kernel(const unsigned short* __r
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   issue(0, 0);
-  for (int64_t s = 0; s < n_stages; ++s) {
-    const int slot = (int)(s & 1);
-    wait_vmcnt<0>();                                      // this wave's loads of stage s have landed
-    __builtin_amdgcn_s_barrier();                         // everyone's have; and everyone is done with the other slot
-    if (s + 1 < n_stages) issue(s + 1, slot ^ 1);
+  issue(n_stages > 1 ? 1 : 0, 1);
+  for (int s = 0; s < n_stages; ++s) {
+    const int slot = s % kRing;
+    wait_vmcnt<kLoadsPerStage>();                         // all but the youngest stage's loads of this wave have landed
+    __builtin_amdgcn_s_barrier();                         // everyone's have; and everyone is done with stage s - 1
+    issue(s + 2 < n_stages ? s + 2 : n_stages - 1, (s + 2) % kRing);   // past the end: a harmless repeat keeps the count uniform
+    u32x4 codes[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        codes[x][h] = *reinterpret_cast<const u32x4*>(&smem[kRing * kHStage + slot * kQStage + qoff[x] + 16 * h]);
 #pragma unroll
     for (int t = 0; t < kK / 16; ++t) {
       bf16x8 a[2], bh[2], bm[2], bl[2];
 #pragma unroll
-      for (int x = 0; x < 2; ++x) a[x] = frag(slot, 0, wm * 64 + x * 32, t);
+      for (int x = 0; x < 2; ++x) {
+        const unsigned cl = codes[x][t / 2][2 * (t % 2)], chi = codes[x][t / 2][2 * (t % 2) + 1];
+        a[x] = onehot_frag(cl, chi, qrep[x]);
+      }
 #pragma unroll
       for (int y = 0; y < 2; ++y) {
-        bh[y] = frag(slot, 1, wn * 64 + y * 32, t);
-        bm[y] = frag(slot, 2, wn * 64 + y * 32, t);
-        bl[y] = frag(slot, 3, wn * 64 + y * 32, t);
+        bh[y] = hfrag(slot, 0, wn * 64 + y * 32, t);
+        bm[y] = hfrag(slot, 1, wn * 64 + y * 32, t);
+        bl[y] = hfrag(slot, 2, wn * 64 + y * 32, t);
       }
 #pragma unroll
       for (int y = 0; y < 2; ++y) {
@@ -156,16 +228,21 @@ __global__ __launch_bounds__(256) void lnq_gemm_kernel(const unsigned short* __r
       }
     }
   }
+  wait_vmcnt<0>();                                        // the repeats issued past the end
 
   // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32 of a 32 x 32 block
+  const int64_t row0 = j0 * n_levels;
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int64_t row = r0 + wm * 64 + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-      if (row <= r_last) {
+      const int lr = wm * 64 + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+      if (lr < rows_here) {
 #pragma unroll
-        for (int y = 0; y < 2; ++y) T[row * ldp + c0 + wn * 64 + 32 * y + lane % 32] = acc[x][y][r];
+        for (int y = 0; y < 2; ++y) {
+          const float val = acc[x][y][r];
+          T[(row0 + lr) * ldp + c0 + wn * 64 + 32 * y + lane % 32] = val;
+        }
       }
     }
 }
@@ -267,17 +344,18 @@ __global__ __launch_bounds__(256) void lnq_solve_kernel(const float* __restrict_
 
 struct Layout {
   int64_t ldp;
-  int n_rt;
-  size_t h_bytes, e_bytes, t_bytes;
+  int n_ch, n_rt;
+  size_t h_bytes, q_bytes, t_bytes;
 };
 Layout make_layout(int64_t d_out, int64_t d_in, int G, int n_levels) {
   Layout L;
-  L.ldp = (d_in + kTile - 1) / kTile * kTile;
-  const int64_t rows_per_group = d_out / G * n_levels;
-  L.n_rt = (int)((rows_per_group + kTile - 1) / kTile);
+  L.ldp = (d_in + kCols - 1) / kCols * kCols;
+  const int64_t per_group = d_out / G;
+  L.n_ch = kRows / n_levels < kMaxCh ? kRows / n_levels : kMaxCh;          // whole channels per workgroup
+  L.n_rt = (int)((per_group + L.n_ch - 1) / L.n_ch);
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
   L.h_bytes = up((size_t)G * L.ldp * L.ldp * 2);
-  L.e_bytes = up((size_t)d_out * n_levels * L.ldp * 2);
+  L.q_bytes = up((size_t)d_out * L.ldp);
   L.t_bytes = up((size_t)d_out * n_levels * L.ldp * sizeof(float));
   return L;
 }
@@ -286,7 +364,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G, int n_levels) {
 
 size_t lnq_codebook_workspace(int64_t d_out, int64_t d_in, int G, int n_levels) {
   const Layout L = make_layout(d_out, d_in, G, n_levels);
-  return 3 * L.h_bytes + L.e_bytes + L.t_bytes;
+  return 3 * L.h_bytes + L.q_bytes + L.t_bytes;
 }
 
 hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld, const unsigned char* Q,
@@ -300,8 +378,8 @@ hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int6
   p += L.h_bytes;
   unsigned short* Hl = (unsigned short*)p;
   p += L.h_bytes;
-  unsigned short* E = (unsigned short*)p;
-  p += L.e_bytes;
+  unsigned char* Qp = (unsigned char*)p;
+  p += L.q_bytes;
   float* T = (float*)p;
 
   hipError_t e;
@@ -311,12 +389,18 @@ hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int6
   {
     int64_t bx = (L.ldp + 255) / 256;
     if (bx > 64) bx = 64;
-    lnq_onehot_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(Q, d_in, L.ldp, n_levels, E);
+    lnq_pad_codes_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(Q, d_in, L.ldp, n_levels, Qp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  lnq_gemm_kernel<<<dim3((unsigned)(L.n_rt * G), (unsigned)(L.ldp / kTile)), dim3(256), 0, st>>>(
-      E, Hh, Hm, Hl, d_out / G * n_levels, L.ldp, L.n_rt, T);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  {
+    const int n_ct = (int)(L.ldp / kCols);
+    const int64_t n_blocks = (int64_t)L.n_rt * G * n_ct;
+    const int64_t grid = (n_blocks + 7) / 8 * 8;
+    if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    lnq_gemm_kernel<<<dim3((unsigned)grid), dim3(512), 0, st>>>(Qp, Hh, Hm, Hl, d_out / G, n_levels, L.n_ch, L.n_rt, G,
+                                                                n_ct, L.ldp, T);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   if (n_levels <= 4)
     lnq_solve_kernel<4><<<dim3((unsigned)d_out), dim3(256), 0, st>>>(T, Q, W, d_in, ld, L.ldp, n_levels, lam, codebook, What);
   else if (n_levels <= 8)

@@ -101,7 +101,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the pure-MFMA ceiling measurement")
     ap.add_argument("--cd-cycles", type=int, default=1,
-                    help="cycles of the coordinate-descent assignment step timed after the main loop (0: skip)")
+                    help="cycles of the coordinate-descent assignment step timed after the main loop, followed by one "
+                         "codebook step (0: skip both)")
     ap.add_argument("--tokens", type=int, default=0, help="override n (debugging only; invalid as a result)")
     ap.add_argument("--groups", type=int, default=0, help="override G (the 13B sweep runs G in 1, 2, 4, 8)")
     args = ap.parse_args()
@@ -217,7 +218,7 @@ def main():
         o_before = gq.gq_objective(W, Wq, Hd, workspace=ws_o)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        gq.gq_cd_assign(W, Wq, C, Hd, n_cycles=args.cd_cycles, want_codes=False, workspace=ws_c)
+        Qc = gq.gq_cd_assign(W, Wq, C, Hd, n_cycles=args.cd_cycles, want_codes=True, workspace=ws_c)
         e1.record()
         o_after = gq.gq_objective(W, Wq, Hd, workspace=ws_o)
         torch.cuda.synchronize()
@@ -233,7 +234,29 @@ def main():
         }
         log(f"cd_assign: {cd_ms / args.cd_cycles:.2f} ms per cycle; objective {result['cd_assign']['objective_before']} -> "
             f"{result['cd_assign']['objective_after']}")
-        del Hd, Wq, ws_c
+        del ws_c
+        # ... and the other half of the alternation: the closed-form grids for the assignments just made.
+        m = 8
+        ws_l = torch.empty(int(lib.gq_lnq_codebook_workspace_bytes(d_out, d_in, G, m)), dtype=torch.uint8, device=dev)
+        Wl = torch.empty_like(W)
+        gq.gq_lnq_codebook(W, Qc, Hd, m, 1e-7, What=Wl, workspace=ws_l)                  # warm-up
+        e0.record()
+        gq.gq_lnq_codebook(W, Qc, Hd, m, 1e-7, What=Wl, workspace=ws_l)
+        e1.record()
+        o_grid = gq.gq_objective(W, Wl, Hd, workspace=ws_o)
+        torch.cuda.synchronize()
+        lnq_ms = e0.elapsed_time(e1)
+        lnq_fl = 2.0 * d_out * m * d_in * d_in                       # P^T H for every channel: the contraction that dominates
+        result["lnq_codebook"] = {
+            "ms": lnq_ms, "levels": m, "objective_before": [float(v) for v in o_after.tolist()],
+            "objective_after": [float(v) for v in o_grid.tolist()],
+            "roofline": {"bound": "mfma", "achieved": lnq_fl / (lnq_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS / 3,
+                         "unit": "TFLOP/s", "frac": lnq_fl / (lnq_ms * 1e-3) / 1e12 / (PEAK_BF16_TFLOPS / 3), "traffic": None,
+                         "note": "fp32-grade multiply-adds (three bf16 MFMA products each), 2*d_out*levels*d_in^2; "
+                                 "the whole call: split of H, contraction, binning and the fp64 solves"},
+        }
+        log(f"lnq_codebook: {lnq_ms:.2f} ms; objective -> {result['lnq_codebook']['objective_after']}")
+        del Hd, Wq, ws_l, Wl, Qc
 
     if not args.no_ceiling:
         ceil = mfma_ceiling()

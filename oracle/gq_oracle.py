@@ -25,6 +25,9 @@ the closed form of Eq. "cd_closed") is `cd_assign`; being an iterative heuristic
 follows the algorithm's steps in the paper's order: cycles, then coordinates in
 increasing order, one closed-form minimisation each.
 
+`damped_cholesky`, `gptq_assign` and `ldlq_assign` cover the sequential-rounding quantizers the
+paper feeds its Hessians to (GPTQ in SpinQuant, LDLQ in QTIP): published algorithms, restated.
+
 Pins (tests/test_oracle_pins.py) check every function against closed forms,
 a hand-worked example, an independent BLAS routine (dsyrk), and brute-force
 evaluation of the paper's *un-averaged* definitions (per-channel Hessians,
@@ -276,3 +279,111 @@ def lnq_codebook(W, Q, H, n_levels: int, G: int | None = None, lam: float = 1e-7
             C[j] = np.linalg.solve(A, b)
             What[j] = P @ C[j]
     return C, What
+
+
+def damped_cholesky(H, damp_rel: float = 0.01, damp_abs: float = 0.0, reverse: bool = False) -> np.ndarray:
+    """The triangular factor of the damped group Hessians (Algorithm 2, line 1; Section 4.2:
+    a small constant is added to the diagonal so that the matrix is positive definite).
+
+        eps_k = damp_abs + damp_rel * mean_i H[k][i, i]
+        reverse=False:  H[k] + eps_k I = L L^T,  L lower triangular, positive diagonal
+        reverse=True:   H[k] + eps_k I = R R^T,  R UPPER triangular, positive diagonal
+                        (the factorization taken from the last coordinate backwards; it is the one
+                        whose columns give the feedback of sequential rounding in the order
+                        0, 1, ..., d_in-1, see `ldlq_assign`)
+
+    The paper leaves the constant open; the relative form is the convention of the GPTQ line of
+    work it cites (a fraction of the mean diagonal).  H [G, d, d] (or [d, d]) full symmetric.
+    numpy's Cholesky routine is the library step; the reverse form is the same routine applied to
+    the matrix with rows and columns in reverse order.
+    """
+    H = np.asarray(H, dtype=_F64)
+    squeeze = H.ndim == 2
+    if squeeze:
+        H = H[None]
+    out = np.empty_like(H)
+    d = H.shape[1]
+    for k in range(H.shape[0]):
+        A = H[k] + (damp_abs + damp_rel * np.mean(np.diag(H[k]))) * np.eye(d)
+        if reverse:
+            out[k] = np.linalg.cholesky(A[::-1, ::-1])[::-1, ::-1]
+        else:
+            out[k] = np.linalg.cholesky(A)
+    return out[0] if squeeze else out
+
+
+def _nearest(grid_rows, t):
+    """Index of the grid point nearest to t, per row; the lowest index among equals."""
+    return np.argmin(np.abs(grid_rows - t[:, None]), axis=1)
+
+
+def gptq_assign(W, codebook, H, G: int | None = None, damp_rel: float = 0.01, damp_abs: float = 0.0):
+    """Sequential rounding with error feedback as published by Frantar et al. (GPTQ, the weight
+    quantizer the paper plugs its Hessians into for SpinQuant, Appendix "Implementation Details
+    for Different Quantization Types", and the alternative assignment step of its LNQ ablation),
+    without the lazy batching, which does not change the result: with A = H[k] + eps_k I
+    (eps_k as in `damped_cholesky`), A^-1 = T^T T, T upper triangular, for i = 0..d_in-1:
+
+        q_i = nearest grid point of the current w_i;  e = (w_i - q_i) / T[i, i];
+        w_{i'} -= e * T[i, i']   for i' > i.
+
+    W [d_out, d_in], codebook [d_out, m] (the grid of every channel; a uniform grid is a special
+    case), H [G, d_in, d_in].  Returns (Q int64 indices, What float64 grid values).
+    """
+    W = np.asarray(W, dtype=_F64)
+    C = np.asarray(codebook, dtype=_F64)
+    H = np.asarray(H, dtype=_F64)
+    if H.ndim == 2:
+        H = H[None]
+    G = H.shape[0] if G is None else G
+    d_out, d_in = W.shape
+    Q = np.zeros((d_out, d_in), dtype=np.int64)
+    What = np.empty_like(W)
+    for k, (j0, j1) in enumerate(group_partition(d_out, G)):
+        A = H[k] + (damp_abs + damp_rel * np.mean(np.diag(H[k]))) * np.eye(d_in)
+        T = np.linalg.cholesky(np.linalg.inv(A)).T          # A^-1 = T^T T, T upper
+        Wk = W[j0:j1].copy()
+        Ck = C[j0:j1]
+        rows = np.arange(j1 - j0)
+        for i in range(d_in):
+            q = _nearest(Ck, Wk[:, i])
+            Q[j0:j1, i] = q
+            What[j0:j1, i] = Ck[rows, q]
+            e = (Wk[:, i] - What[j0:j1, i]) / T[i, i]
+            Wk[:, i + 1:] -= e[:, None] * T[i, i + 1:][None, :]
+    return Q, What
+
+
+def ldlq_assign(W, codebook, R, G: int | None = None):
+    """The same rounding written with the factor of the matrix itself instead of its inverse
+    (the LDLQ form of Chee et al., which the QTIP quantizer the paper also builds on uses
+    block-wise): with A = R R^T, R upper triangular (`damped_cholesky(..., reverse=True)`),
+    for i = 0..d_in-1
+
+        What[j, i] = nearest grid point of  W[j, i] - sum_{i' < i} (What[j, i'] - W[j, i']) * R[i', i] / R[i, i].
+
+    R [G, d_in, d_in].  Returns (Q, What, Tgt) with Tgt the targets that were rounded.
+    """
+    W = np.asarray(W, dtype=_F64)
+    C = np.asarray(codebook, dtype=_F64)
+    R = np.asarray(R, dtype=_F64)
+    if R.ndim == 2:
+        R = R[None]
+    G = R.shape[0] if G is None else G
+    d_out, d_in = W.shape
+    Q = np.zeros((d_out, d_in), dtype=np.int64)
+    What = np.empty_like(W)
+    Tgt = np.empty_like(W)
+    for k, (j0, j1) in enumerate(group_partition(d_out, G)):
+        Rk = R[k]
+        Wk, Ck = W[j0:j1], C[j0:j1]
+        rows = np.arange(j1 - j0)
+        delta = np.zeros_like(Wk)
+        for i in range(d_in):
+            t = Wk[:, i] - delta[:, :i] @ (Rk[:i, i] / Rk[i, i])
+            q = _nearest(Ck, t)
+            Q[j0:j1, i] = q
+            What[j0:j1, i] = Ck[rows, q]
+            Tgt[j0:j1, i] = t
+            delta[:, i] = What[j0:j1, i] - Wk[:, i]
+    return Q, What, Tgt

@@ -366,3 +366,106 @@ def test_lnq_codebook_recovers_an_exactly_representable_weight_and_is_relabeling
     np.testing.assert_allclose(What2, What, rtol=1e-9)
     with pytest.raises(ValueError):
         oracle.lnq_codebook(W, Q + 1, H, m)
+
+
+# ---------------------------------------------------------------- damped Cholesky, sequential rounding (GPTQ / LDLQ)
+def _spd(r, G, d, cond=50.0):
+    out = []
+    for _ in range(G):
+        B = r.normal(size=(3 * d, d)) * np.linspace(1.0, np.sqrt(cond), d)[None, :]
+        out.append(B.T @ B / (3 * d))
+    return np.stack(out)
+
+
+def test_sequential_rounding_worked_example():
+    ex = _golden("sequential_rounding_worked_example.json")
+    np.testing.assert_allclose(oracle.damped_cholesky(np.array(ex["chol_A"]), 0.0, 0.0), ex["chol_L"], rtol=0, atol=1e-13)
+    A, W, C = np.array(ex["A"]), np.array(ex["W"]), np.array(ex["codebook"])
+    Q, What = oracle.gptq_assign(W, C, A, damp_rel=0.0)
+    assert Q.tolist() == ex["Q"] and What.tolist() == ex["What"]
+    Q2, What2, Tgt = oracle.ldlq_assign(W, C, oracle.damped_cholesky(A, 0.0, 0.0, reverse=True))
+    assert Q2.tolist() == ex["Q"] and What2.tolist() == ex["What"]
+    np.testing.assert_allclose(Tgt, ex["targets"], rtol=0, atol=1e-14)
+
+
+def test_damped_cholesky_is_the_unique_triangular_factor_of_the_damped_matrix():
+    # a positive definite matrix has exactly one lower (upper) triangular factor with positive diagonal:
+    # shape, sign and the product pin the result without reference to how it was computed
+    r = _rng(60)
+    H = _spd(r, 3, 9)
+    for rel, ab in ((0.0, 0.0), (0.01, 0.0), (0.05, 0.3)):
+        L = oracle.damped_cholesky(H, rel, ab)
+        R = oracle.damped_cholesky(H, rel, ab, reverse=True)
+        for k in range(3):
+            eps = ab + rel * np.trace(H[k]) / 9
+            A = H[k] + eps * np.eye(9)
+            assert np.all(np.triu(L[k], 1) == 0) and np.all(np.diag(L[k]) > 0)
+            assert np.all(np.tril(R[k], -1) == 0) and np.all(np.diag(R[k]) > 0)
+            np.testing.assert_allclose(L[k] @ L[k].T, A, rtol=1e-13, atol=1e-13)
+            np.testing.assert_allclose(R[k] @ R[k].T, A, rtol=1e-13, atol=1e-13)
+    # the two factors differ (they are not transposes of each other) unless the matrix is diagonal
+    assert np.abs(oracle.damped_cholesky(H[0], 0, 0, reverse=True) - oracle.damped_cholesky(H[0], 0, 0).T).max() > 1e-3
+    D = np.diag([4.0, 9.0, 16.0])
+    np.testing.assert_allclose(oracle.damped_cholesky(D, 0.0, 0.0, reverse=True), np.diag([2.0, 3.0, 4.0]), atol=1e-15)
+    with pytest.raises(np.linalg.LinAlgError):
+        oracle.damped_cholesky(np.array([[1.0, 2.0], [2.0, 1.0]]), 0.0, 0.0)       # indefinite without damping
+
+
+def test_each_rounding_target_is_the_conditional_minimiser_given_the_coordinates_already_rounded():
+    # the defining property (optimal-brain-surgeon update, textbook constrained least squares): before
+    # coordinate i is rounded, the free coordinates i.. sit at the minimiser of (w' - w)^T A (w' - w)
+    # subject to the coordinates < i being fixed at their rounded values:
+    #   w'_R = w_R - A_RR^-1 A_RF (what_F - w_F),   R = {i, ..., d-1}, F = {0, ..., i-1}
+    r = _rng(61)
+    d_out, d_in, G, m = 4, 7, 2, 4
+    H = _spd(r, G, d_in)
+    W = r.normal(size=(d_out, d_in))
+    C = np.sort(r.normal(size=(d_out, m)), axis=1)
+    rel = 0.02
+    Q, What = oracle.gptq_assign(W, C, H, G, damp_rel=rel)
+    Rf = oracle.damped_cholesky(H, rel, 0.0, reverse=True)
+    Q2, What2, Tgt = oracle.ldlq_assign(W, C, Rf, G)
+    np.testing.assert_array_equal(Q, Q2)                                   # inverse-factor form == factor form
+    np.testing.assert_array_equal(What, What2)
+    for j in range(d_out):
+        k = j // (d_out // G)
+        A = H[k] + rel * np.trace(H[k]) / d_in * np.eye(d_in)
+        for i in range(d_in):
+            Rset, F = np.arange(i, d_in), np.arange(0, i)
+            free = W[j, Rset] - np.linalg.solve(A[np.ix_(Rset, Rset)], A[np.ix_(Rset, F)] @ (What[j, F] - W[j, F]))
+            assert abs(free[0] - Tgt[j, i]) < 1e-11
+            assert Q[j, i] == int(np.argmin(np.abs(C[j] - free[0])))
+            assert What[j, i] == C[j, Q[j, i]]
+        # and the error decomposes over the coordinates: (what - w)^T A (what - w) = sum_i R[i,i]^2 (what_i - t_i)^2
+        e = What[j] - W[j]
+        assert abs(e @ A @ e - np.sum(np.diag(Rf[k]) ** 2 * (What[j] - Tgt[j]) ** 2)) < 1e-10
+
+
+def test_sequential_rounding_special_cases():
+    r = _rng(62)
+    d_out, d_in, m = 6, 11, 8
+    W = r.normal(size=(d_out, d_in))
+    C = r.normal(size=(d_out, m))                                          # grids in any order
+    Hd = np.stack([np.diag(r.uniform(0.5, 2.0, d_in)) for _ in range(2)])
+    rtn = np.argmin(np.abs(C[:, None, :] - W[:, :, None]), axis=2)
+    Q, What = oracle.gptq_assign(W, C, Hd, 2)                              # diagonal matrix: no feedback, plain rounding
+    np.testing.assert_array_equal(Q, rtn)
+    np.testing.assert_array_equal(What, np.take_along_axis(C, rtn, axis=1))
+    # a weight already on its grid everywhere is left alone, whatever the matrix
+    H = _spd(r, 2, d_in)
+    Won = np.take_along_axis(C, r.integers(0, m, size=(d_out, d_in)), axis=1)
+    _, What = oracle.gptq_assign(Won, C, H, 2)
+    np.testing.assert_array_equal(What, Won)
+    # ties go to the lower index: w exactly between two grid points
+    Qt, _ = oracle.gptq_assign(np.array([[0.5]]), np.array([[1.0, 0.0]]), np.array([[[1.0]]]), 1, damp_rel=0.0)
+    assert Qt[0, 0] == 0
+    # every group uses its own matrix: swapping the matrices changes the result of a coupled problem
+    Wb = r.normal(size=(4, d_in))
+    Cb = np.tile(np.array([[-1.0, 0.0, 1.0]]), (4, 1))
+    Qa, _ = oracle.gptq_assign(Wb, Cb, H, 2)
+    Qb, _ = oracle.gptq_assign(Wb, Cb, H[::-1], 2)
+    assert np.any(Qa != Qb)
+    # feedback does better than plain rounding on the objective it is built for, on average
+    obj_seq = oracle.objective(Wb, oracle.gptq_assign(Wb, Cb, H, 2, damp_rel=0.0)[1], H, 2)[0].sum()
+    obj_rtn = oracle.objective(Wb, np.take_along_axis(Cb, np.argmin(np.abs(Cb[:, None, :] - Wb[:, :, None]), axis=2), axis=1), H, 2)[0].sum()
+    assert obj_seq < obj_rtn

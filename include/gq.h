@@ -11,6 +11,7 @@
  *   gq_fisher_mirror  H[k][b,a] = H[k][a,b]  for a < b                    (storage of the full square)
  *   gq_objective      obj[k]  = sum_{j in J_k} (w_j-what_j)^T H[k] (w_j-what_j)   (Eq. "ours2", Section 3.2)
  *   gq_cd_assign      cyclic coordinate descent on the assignments against H[k]   (Section 4.2, Eq. "cd_closed")
+ *   gq_ldlq_assign    sequential rounding with error feedback (GPTQ / LDLQ) from a factor of H[k]
  *   gq_lnq_codebook   closed-form grids for fixed assignments against H[k]        (Section 4.2, Eq. "conti-sol")
  *
  * Conventions shared by every call
@@ -203,6 +204,35 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
                  int64_t d_out, int64_t d_in, int64_t ld_w, const float* H, int32_t G,
                  int32_t n_cycles, uint8_t* Q,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Sequential rounding with error feedback against the group Hessians: the GPTQ / LDLQ
+ * quantizers the paper feeds its Hessians to (Appendix "Implementation Details for
+ * Different Quantization Types"; the alternative assignment step of the LNQ ablation),
+ * with a grid per output channel (a uniform grid is a special case).  From the UPPER
+ * triangular factor R[k] of the damped matrix, H[k] + eps I = R[k] R[k]^T, for
+ * i = 0..d_in-1 in this order every output channel j (group k = j / (d_out/G)) sets
+ *
+ *   What[j,i] = the grid point nearest to
+ *               W[j,i] - sum_{i' < i} (What[j,i'] - W[j,i']) * R[k][i',i] / R[k][i,i].
+ *
+ * Ties go to the lowest grid index; the sums are evaluated in fp32-grade arithmetic as
+ * in gq_cd_assign (same kernels, blocks of 128 coordinates), with the same caveat about
+ * targets at a midpoint.
+ *
+ *   W         [d_out, d_in]     device fp32, row pitch ld_w elements
+ *   What      [d_out, d_in]     device fp32, same pitch, written; must not overlap W
+ *   codebook  [d_out, n_levels] device fp32, dense, 1 <= n_levels <= 16, any order
+ *   R         [G, d_in, d_in]   device fp32, dense; only the upper triangle (incl. the
+ *                               positive diagonal) is read
+ *   Q         [d_out, d_in]     device bytes, dense, or NULL: the grid indices chosen
+ *   workspace  at least gq_cd_workspace_bytes(d_out, d_in, G) bytes, 256-byte aligned
+ *
+ * Errors: as gq_cd_assign (no n_cycles); GQ_ERR_SHAPE also if What == W.
+ */
+int gq_ldlq_assign(const float* W, float* What, const float* codebook, int32_t n_levels,
+                   int64_t d_out, int64_t d_in, int64_t ld_w, const float* R, int32_t G,
+                   uint8_t* Q, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of device workspace gq_lnq_codebook needs (0 for invalid sizes). */
 size_t gq_lnq_codebook_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G, int32_t n_levels);

@@ -62,6 +62,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                  c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_cd_workspace_bytes.restype = c.c_size_t
     lib.gq_cd_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
+    lib.gq_ldlq_assign.restype = c.c_int
+    lib.gq_ldlq_assign.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int64, c.c_int64,
+                                   c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_lnq_codebook_workspace_bytes.restype = c.c_size_t
     lib.gq_lnq_codebook_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32, c.c_int32]
     lib.gq_lnq_codebook.restype = c.c_int
@@ -256,3 +259,29 @@ def gq_lnq_codebook(W: torch.Tensor, Q: torch.Tensor, H: torch.Tensor, n_levels:
                              ws_ptr, ws_bytes, _stream())
     _check(st, "gq_lnq_codebook")
     return codebook
+
+
+def gq_ldlq_assign(W: torch.Tensor, codebook: torch.Tensor, R: torch.Tensor, What: Optional[torch.Tensor] = None,
+                   want_codes: bool = True, workspace: Optional[torch.Tensor] = None):
+    """Sequential rounding with error feedback (GPTQ / LDLQ) from the upper triangular factor `R`
+    [G, d_in, d_in] of the damped group Hessians, H + eps I = R R^T.  Returns (What, Q)."""
+    _require_gpu(W, codebook, R, What, workspace)
+    d_out, d_in = W.shape
+    G = int(R.shape[0])
+    assert W.dtype == torch.float32 and R.dtype == torch.float32 and R.is_contiguous()
+    assert codebook.dtype == torch.float32 and codebook.is_contiguous() and codebook.shape[0] == d_out
+    if What is None:
+        What = torch.empty_strided(W.shape, W.stride(), dtype=W.dtype, device=W.device)
+    assert What.dtype == torch.float32 and What.shape == W.shape and _rows(W) == _rows(What)
+    lib = load_library()
+    need = int(lib.gq_cd_workspace_bytes(d_out, d_in, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(max(need, 1), W.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    Q = torch.empty((d_out, d_in), dtype=torch.uint8, device=W.device) if want_codes else None
+    st = lib.gq_ldlq_assign(W.data_ptr(), What.data_ptr(), codebook.data_ptr(), int(codebook.shape[1]), d_out, d_in,
+                            _rows(W), R.data_ptr(), G, Q.data_ptr() if want_codes else None, ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_ldlq_assign")
+    return What, Q

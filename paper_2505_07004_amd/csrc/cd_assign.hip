@@ -79,6 +79,59 @@ __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ 
   }
 }
 
+// The same two outputs for sequential rounding with error feedback (GPTQ / LDLQ) from the upper
+// triangular factor R of the damped matrix, A = R R^T: the feedback a coordinate i receives from an
+// EARLIER coordinate i' is R[i'][i] / R[i][i] per unit of error, later coordinates give none:
+//   Ht[i][i'] = R[i'][i] / R[i][i]  for i' < i,  0 otherwise.
+__global__ __launch_bounds__(256) void ldlq_prep_kernel(const float* __restrict__ R, int64_t d, int64_t ldp,
+                                                        unsigned short* __restrict__ Hth,
+                                                        unsigned short* __restrict__ Htl, float* __restrict__ Cd) {
+  __shared__ float tile[64][65];
+  __shared__ float diag[64];
+  const int k = blockIdx.z;
+  const int ti = blockIdx.y, tj = blockIdx.x;              // tile of rows i, of columns i'
+  const float* Rk = R + (int64_t)k * d * d;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  for (int r = ty; r < 64; r += 4) {                       // R[i'][i]: rows from the tile of i', columns from the tile of i
+    const int64_t a = (int64_t)tj * 64 + r, b = (int64_t)ti * 64 + tx;
+    tile[r][tx] = (tj <= ti && a < d && b < d) ? Rk[a * d + b] : 0.f;
+  }
+  if (threadIdx.x < 64) {
+    const int64_t i = (int64_t)ti * 64 + threadIdx.x;
+    diag[threadIdx.x] = i < d ? Rk[i * d + i] : 1.f;
+  }
+  __syncthreads();
+  const int64_t n_blk = ldp / kBlk;
+  for (int r = ty; r < 64; r += 4) {
+    const int li = r, lj = tx;                             // local row i, local column i'
+    const int64_t i = (int64_t)ti * 64 + li, ip = (int64_t)tj * 64 + lj;
+    const float v = (i < d && ip < i) ? tile[lj][li] / diag[li] : 0.f;
+    unsigned short hi, lo;
+    split_bf16(v, hi, lo);
+    const int64_t off = (int64_t)k * ldp * ldp + i * ldp + ip;
+    Hth[off] = hi;
+    Htl[off] = lo;
+    if (i / kBlk == ip / kBlk) {
+      const int64_t blk = i / kBlk;
+      const int64_t base = ((int64_t)k * n_blk + blk) * kBlk * kBlk;
+      Cd[base + (ip % kBlk) * kBlk + (i % kBlk)] = v;
+    }
+  }
+}
+
+// Sequential rounding starts from the weights themselves: What = W, no error yet.
+__global__ __launch_bounds__(256) void ldlq_init_kernel(const float* __restrict__ W, float* __restrict__ What,
+                                                        int64_t d, int64_t ld, int64_t ldp,
+                                                        unsigned short* __restrict__ Dh,
+                                                        unsigned short* __restrict__ Dl) {
+  const int64_t j = blockIdx.y;
+  for (int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x; a < ldp; a += (int64_t)gridDim.x * 256) {
+    if (a < d) What[j * ld + a] = W[j * ld + a];
+    Dh[j * ldp + a] = 0;
+    Dl[j * ldp + a] = 0;
+  }
+}
+
 // Dh/Dl[j][a] = hi/lo of What[j][a] - W[j][a], row pitch ldp, zero padded.
 __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__ W, const float* __restrict__ What,
                                                        int64_t d, int64_t ld, int64_t ldp,
@@ -448,9 +501,13 @@ size_t cd_workspace(int64_t d_out, int64_t d_in, int G) {
   return 2 * L.ht_bytes + L.cdt_bytes + 2 * L.delta_bytes + L.c_bytes;
 }
 
-hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
-                            int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q,
-                            void* ws, hipStream_t st) {
+namespace {
+// The block loop shared by the two entry points.  ldlq = false: cyclic coordinate descent against H
+// (What in: the current feasible weights).  ldlq = true: one pass of sequential rounding with the
+// feedback coefficients of the factor R passed as H (What out only).
+hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
+                      int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q, void* ws,
+                      hipStream_t st) {
   const Layout L = make_layout(d_out, d_in, G);
   char* p = (char*)ws;
   unsigned short* Hth = (unsigned short*)p;
@@ -467,12 +524,18 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
 
   hipError_t e;
   const unsigned t64 = (unsigned)(L.ldp / 64);
-  cd_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
+  if (ldlq)
+    ldlq_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
+  else
+    cd_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
     int64_t bx = (L.ldp + 255) / 256;
     if (bx > 64) bx = 64;
-    cd_delta_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(W, What, d_in, ld, L.ldp, Dh, Dl);
+    if (ldlq)
+      ldlq_init_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(W, What, d_in, ld, L.ldp, Dh, Dl);
+    else
+      cd_delta_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(W, What, d_in, ld, L.ldp, Dh, Dl);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   const unsigned n_tiles = (unsigned)(L.n_rt * G);
@@ -495,6 +558,19 @@ hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, 
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
   return hipSuccess;
+}
+}  // namespace
+
+hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
+                            int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q,
+                            void* ws, hipStream_t st) {
+  return run_assign(false, W, What, codebook, n_levels, d_out, d_in, ld, H, G, n_cycles, Q, ws, st);
+}
+
+hipError_t launch_ldlq_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
+                              int64_t d_in, int64_t ld, const float* R, int G, unsigned char* Q, void* ws,
+                              hipStream_t st) {
+  return run_assign(true, W, What, codebook, n_levels, d_out, d_in, ld, R, G, 1, Q, ws, st);
 }
 
 }  // namespace gq

@@ -126,6 +126,20 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
                                        (hipStream_t)hip_stream));
 }
 
+int gq_ldlq_assign(const float* W, float* What, const float* codebook, int32_t n_levels, int64_t d_out, int64_t d_in,
+                   int64_t ld_w, const float* R, int32_t G, uint8_t* Q, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+  if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_levels <= 0) return GQ_ERR_SHAPE;
+  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (!W || !What || !codebook || !R) return GQ_ERR_NULLPTR;
+  if (W == What) return GQ_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(What) || !aligned16(R) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;
+  const size_t need = gq_cd_workspace_bytes(d_out, d_in, G);
+  if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
+  return from_hip(gq::launch_ldlq_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, R, G, Q, workspace,
+                                         (hipStream_t)hip_stream));
+}
+
 size_t gq_lnq_codebook_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G, int32_t n_levels) {
   if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || n_levels <= 0 || n_levels > 16) return 0;
   return gq::lnq_codebook_workspace(d_out, d_in, G, n_levels);

@@ -121,3 +121,26 @@ def sampled_objective_check(oracle, X, s, W, What, obj, obj_row, G, tol, rows_pe
     say(f"{what}: objective on {len(rows)} sampled channels rel-Frobenius {e_rows:.2e}; obj vs sum of rows {e_sum:.2e} (tol {tol:g})")
     assert e_rows <= tol and e_sum <= 1e-6
     return e_rows
+
+
+# ------------------------------------------------------------------ sequential rounding decisions
+def check_rounding_decisions(T, S, Cn, Qg, new, what):
+    """The GPU rounded, for every (channel, coordinate), a target to a grid point.  T holds the exact
+    (fp64) targets for the state the GPU was in, S the sum of the absolute values of the terms of each
+    target's sum.  The GPU forms every product of the sum from two-term bf16 splits of both factors and
+    drops the lo*lo product, a relative error below 2^-15 per term in the worst case, and adds the terms
+    in fp32; so its target is within 2^-14 * S + 2^-20 * |t| of the exact one, and the grid point it picks
+    can be farther from the exact target than the nearest one by at most twice that."""
+    dist = np.abs(Cn[:, None, :] - T[:, :, None])                     # [d_out, d_in, m]
+    chosen = np.take_along_axis(dist, Qg[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    best = dist.min(axis=2)
+    slack = 2.0 ** -14 * S + 2.0 ** -20 * np.abs(T)
+    excess = chosen - best
+    bad = excess > 2 * slack
+    spacing = np.median(np.diff(np.sort(Cn, axis=1), axis=1))
+    say(f"{what}: decisions off the nearest grid point by more than the slack: {int(bad.sum())} of {bad.size}; "
+        f"max excess {float(excess.max()):.2e}, largest slack {float(2 * slack.max()):.2e}, median grid spacing {spacing:.2e}")
+    assert not bad.any()
+    assert 2 * slack.max() <= 0.1 * spacing                            # the bound is small against the grid itself,
+    assert np.mean(excess > 0) <= 2e-3                                 # and almost every decision IS the exact nearest point
+    assert np.array_equal(new, np.take_along_axis(Cn, Qg.astype(np.int64), axis=1))   # What is the grid value of its code, exactly

@@ -17,7 +17,7 @@ import torch
 import oracle
 from paper_2505_07004_amd import binding as gq
 from paper_2505_07004_amd import workloads as wl
-from parity_utils import say, to_np64
+from parity_utils import check_rounding_decisions, say, to_np64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -61,19 +61,7 @@ def _check_cycle(Wn, old, new, Qg, Cn, Hn, G, what):
     adds the terms in fp32; so its target is within 2^-14 * S + 2^-20 * |t| of the exact one, and the
     grid point it picks can be farther from the exact target than the nearest one by at most twice that."""
     T, S = _targets_along(Wn, old, new, Hn, G)
-    dist = np.abs(Cn[:, None, :] - T[:, :, None])                     # [d_out, d_in, m]
-    chosen = np.take_along_axis(dist, Qg[:, :, None].astype(np.int64), axis=2)[:, :, 0]
-    best = dist.min(axis=2)
-    slack = 2.0 ** -14 * S + 2.0 ** -20 * np.abs(T)
-    excess = chosen - best
-    bad = excess > 2 * slack
-    spacing = np.median(np.diff(np.sort(Cn, axis=1), axis=1))
-    say(f"{what}: decisions off the nearest grid point by more than the slack: {int(bad.sum())} of {bad.size}; "
-        f"max excess {float(excess.max()):.2e}, largest slack {float(2 * slack.max()):.2e}, median grid spacing {spacing:.2e}")
-    assert not bad.any()
-    assert 2 * slack.max() <= 0.1 * spacing                            # the bound is small against the grid itself,
-    assert np.mean(excess > 0) <= 2e-3                                 # and almost every decision IS the exact nearest point
-    assert np.array_equal(new, np.take_along_axis(Cn, Qg.astype(np.int64), axis=1))   # What is the grid value of its code, exactly
+    check_rounding_decisions(T, S, Cn, Qg, new, what)
 
 
 @pytest.mark.parametrize("n,d_in,d_out,G,bits,ld", [

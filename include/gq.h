@@ -11,6 +11,7 @@
  *   gq_fisher_mirror  H[k][b,a] = H[k][a,b]  for a < b                    (storage of the full square)
  *   gq_objective      obj[k]  = sum_{j in J_k} (w_j-what_j)^T H[k] (w_j-what_j)   (Eq. "ours2", Section 3.2)
  *   gq_cd_assign      cyclic coordinate descent on the assignments against H[k]   (Section 4.2, Eq. "cd_closed")
+ *   gq_damped_cholesky  H[k] + eps I = L L^T (or R R^T, R upper)                     (Algorithm 2, line 1)
  *   gq_ldlq_assign    sequential rounding with error feedback (GPTQ / LDLQ) from a factor of H[k]
  *   gq_lnq_codebook   closed-form grids for fixed assignments against H[k]        (Section 4.2, Eq. "conti-sol")
  *
@@ -204,6 +205,42 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
                  int64_t d_out, int64_t d_in, int64_t ld_w, const float* H, int32_t G,
                  int32_t n_cycles, uint8_t* Q,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* flags of gq_damped_cholesky */
+enum {
+  GQ_CHOL_REVERSE = 1u << 0 /* the upper triangular factor R, A = R R^T, instead of the lower L, A = L L^T */
+};
+
+/* Bytes of device workspace gq_damped_cholesky needs (0 for invalid sizes). */
+size_t gq_cholesky_workspace_bytes(int64_t d_in, int32_t G);
+
+/*
+ * Cholesky factorization of the damped group Hessians (Algorithm 2, line 1; Section 4.2:
+ * a small constant on the diagonal makes the matrix positive definite), in fp32:
+ *
+ *   A_k = H[k] + eps_k I,   eps_k = damp_abs + damp_rel * mean_i H[k][i,i]
+ *   flags == 0:               A_k = L L^T,  F[k] = L lower triangular, zeros above the diagonal
+ *   flags == GQ_CHOL_REVERSE: A_k = R R^T,  F[k] = R UPPER triangular, zeros below the diagonal
+ *                             (the factorization taken from the last coordinate backwards; its
+ *                             columns are the feedback coefficients gq_ldlq_assign needs)
+ *
+ *   H     [G, d_in, d_in]  device fp32, dense; only the upper triangle (incl. diagonal) is read
+ *   F     [G, d_in, d_in]  device fp32, dense, every entry written; must not overlap H
+ *   info  [G]              device int32 or NULL: 0, or 1 + the coordinate (in the order of
+ *                          elimination: from the end for GQ_CHOL_REVERSE) of the first pivot
+ *                          that was not positive; such a pivot is replaced by 1, so F stays
+ *                          finite but is not a factor of A_k
+ *   workspace  at least gq_cholesky_workspace_bytes() bytes, 256-byte aligned
+ *
+ * The paper leaves the constant open; the relative form is the convention of the GPTQ line
+ * of work it cites (1 % of the mean diagonal).
+ * Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_in <= 0, G <= 0, a damping constant negative or
+ * NaN, F == H), GQ_ERR_UNSUPPORTED (unknown flag), GQ_ERR_ALIGN (H or F not 16-byte aligned),
+ * GQ_ERR_WORKSPACE, GQ_ERR_HIP.
+ */
+int gq_damped_cholesky(const float* H, int64_t d_in, int32_t G, double damp_rel, double damp_abs,
+                       uint32_t flags, float* F, int32_t* info,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Sequential rounding with error feedback against the group Hessians: the GPTQ / LDLQ

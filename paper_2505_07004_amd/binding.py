@@ -62,6 +62,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                  c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_cd_workspace_bytes.restype = c.c_size_t
     lib.gq_cd_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
+    lib.gq_cholesky_workspace_bytes.restype = c.c_size_t
+    lib.gq_cholesky_workspace_bytes.argtypes = [c.c_int64, c.c_int32]
+    lib.gq_damped_cholesky.restype = c.c_int
+    lib.gq_damped_cholesky.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_double, c.c_double, c.c_uint32, c.c_void_p,
+                                       c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_ldlq_assign.restype = c.c_int
     lib.gq_ldlq_assign.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int64, c.c_int64,
                                    c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -285,3 +290,28 @@ def gq_ldlq_assign(W: torch.Tensor, codebook: torch.Tensor, R: torch.Tensor, Wha
                             _rows(W), R.data_ptr(), G, Q.data_ptr() if want_codes else None, ws_ptr, ws_bytes, _stream())
     _check(st, "gq_ldlq_assign")
     return What, Q
+
+
+GQ_CHOL_REVERSE = 1
+
+
+def gq_damped_cholesky(H: torch.Tensor, damp_rel: float = 0.01, damp_abs: float = 0.0, reverse: bool = False,
+                       workspace: Optional[torch.Tensor] = None):
+    """H[k] + eps_k I = L L^T (L lower) or, with reverse=True, = R R^T (R upper), eps_k = damp_abs +
+    damp_rel * mean diag H[k] (Algorithm 2, line 1).  Returns (F [G, d, d] fp32, info [G] int32)."""
+    _require_gpu(H, workspace)
+    assert H.dtype == torch.float32 and H.is_contiguous() and H.dim() == 3 and H.shape[1] == H.shape[2]
+    G, d = int(H.shape[0]), int(H.shape[1])
+    lib = load_library()
+    need = int(lib.gq_cholesky_workspace_bytes(d, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(max(need, 1), H.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    F = torch.empty_like(H)
+    info = torch.empty(G, dtype=torch.int32, device=H.device)
+    st = lib.gq_damped_cholesky(H.data_ptr(), d, G, float(damp_rel), float(damp_abs), GQ_CHOL_REVERSE if reverse else 0,
+                                F.data_ptr(), info.data_ptr(), ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_damped_cholesky")
+    return F, info

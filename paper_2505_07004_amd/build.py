@@ -22,7 +22,7 @@ SOURCES = [
     "fisher_gram_bf16.hip",
     "mirror.hip",
     "objective.hip",
-    "cd_assign.hip", "lnq_codebook.hip",
+    "cd_assign.hip", "lnq_codebook.hip", "cholesky.hip",
 ]
 
 HIPCC_FLAGS = [

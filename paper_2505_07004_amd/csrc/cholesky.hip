@@ -1,0 +1,321 @@
+// Damped Cholesky factorization of the group Hessians (Algorithm 2, line 1; Section 4.2: a small
+// constant on the diagonal makes the matrix positive definite):
+//     A_k = H[k] + eps_k I,   eps_k = damp_abs + damp_rel * mean_i H[k][i][i],
+//     A_k = L L^T  (L lower triangular)    or    A_k = R R^T  (R UPPER triangular: the factorization
+//     taken from the last coordinate backwards, whose columns are the feedback coefficients of
+//     sequential rounding in the order 0, 1, ..., d_in-1).
+//
+// Both are one algorithm on a working matrix A' = U^T U, U upper triangular, processed by block rows
+// of 128 in fp32:  A' = A gives L = U^T;  A'[a][b] = A[d-1-a][d-1-b] gives R[i][j] = U[d-1-j][d-1-i].
+// Per block row:  (1) the 128 x 128 diagonal block is factored in LDS by one workgroup per group;
+// (2) the panel to its right is solved against it, U12 = U11^-T A12, one thread per column;
+// (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32), rows of U12 staged through LDS as they lie in memory.
+// Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its
+// coordinate + 1, the first one) and replaced by 1 so that everything stays finite.
+#include "gq_internal.hpp"
+
+namespace gq {
+namespace {
+
+constexpr int kNb = 128;             // block size
+constexpr int kPitch = kNb + 1;      // LDS row pitch in floats: rows start on consecutive banks
+
+// eps[k] and info[k] = 0.  One workgroup per group; fixed-order fp64 sum of the diagonal.
+__global__ __launch_bounds__(256) void chol_eps_kernel(const float* __restrict__ H, int64_t d, double damp_rel,
+                                                       double damp_abs, double* __restrict__ eps,
+                                                       int* __restrict__ info) {
+  __shared__ double part[256];
+  const int k = blockIdx.x;
+  const float* Hk = H + (int64_t)k * d * d;
+  double acc = 0.0;
+  for (int64_t i = threadIdx.x; i < d; i += 256) acc += (double)Hk[i * d + i];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    eps[k] = damp_abs + damp_rel * (part[0] / (double)d);
+    if (info) info[k] = 0;
+  }
+}
+
+// Working matrix, upper triangle: Uw[r][c] = A'[r][c] for r <= c.  One workgroup per 64 x 64 tile.
+__global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict__ H, int64_t d, int reverse,
+                                                        const double* __restrict__ eps, float* __restrict__ Uw) {
+  __shared__ float tile[64][65];
+  const int k = blockIdx.z;
+  const int by = blockIdx.y, bx = blockIdx.x;              // tile of rows r, of columns c
+  if (by > bx) return;
+  const float* Hk = H + (int64_t)k * d * d;
+  float* Uk = Uw + (int64_t)k * d * d;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  const int64_t r0 = (int64_t)by * 64, c0 = (int64_t)bx * 64;
+  const double e = eps[k];
+  if (!reverse) {
+    for (int lr = ty; lr < 64; lr += 4) {
+      const int64_t r = r0 + lr, c = c0 + tx;
+      if (r < d && c < d && r <= c) {
+        const float h = Hk[r * d + c];
+        Uk[r * d + c] = r == c ? (float)((double)h + e) : h;
+      }
+    }
+    return;
+  }
+  // A'[r][c] = A[d-1-r][d-1-c] = (upper triangle of H)[d-1-c][d-1-r]
+  for (int lc = ty; lc < 64; lc += 4) {
+    const int64_t sr = d - 1 - (c0 + lc), sc = d - 1 - (r0 + tx);
+    tile[lc][tx] = (sr >= 0 && sc >= 0 && sr <= sc) ? Hk[sr * d + sc] : 0.f;
+  }
+  __syncthreads();
+  for (int lr = ty; lr < 64; lr += 4) {
+    const int64_t r = r0 + lr, c = c0 + tx;
+    if (r < d && c < d && r <= c) {
+      const float h = tile[tx][lr];
+      Uk[r * d + c] = r == c ? (float)((double)h + e) : h;
+    }
+  }
+}
+
+// (1) The diagonal block at (r0, r0): A11 = U11^T U11 in LDS, row by row.  Step j reads row j of the
+// upper triangle (final since step j-1), writes the scaled row into the unused LOWER triangle (so no
+// one's input changes under them), and updates the rows below it; one barrier per step.  Wave w
+// takes the rows j+1+w, j+5+w, ..., a lane the columns from the row's diagonal on: consecutive banks.
+// Rows and columns past the end of the matrix are those of the identity.
+__global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, int64_t d, int64_t r0,
+                                                        int* __restrict__ info) {
+  __shared__ float a[kNb][kPitch];
+  __shared__ float dg[kNb];
+  __shared__ int bad;
+  const int k = blockIdx.x;
+  float* Uk = Uw + (int64_t)k * d * d;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  if (tid == 0) bad = -1;
+  for (int idx = tid; idx < kNb * kNb; idx += 256) {
+    const int r = idx / kNb, c = idx % kNb;
+    const int64_t gr = r0 + r, gc = r0 + c;
+    float v = r == c ? 1.f : 0.f;
+    if (gr < d && gc < d && r <= c) v = Uk[gr * d + gc];
+    a[r][c] = v;
+  }
+  __syncthreads();
+  for (int j = 0; j < kNb; ++j) {
+    float p = a[j][j];
+    const bool ok = p > 0.f;                                // false for NaN as well
+    if (!ok && tid == 0 && bad < 0) bad = j;
+    p = ok ? p : 1.f;
+    const float sp = sqrtf(p), ip = 1.f / p;
+    for (int r = j + 1 + wave; r < kNb; r += 4) {
+      const float f = a[j][r] * ip;
+      for (int c = r + lane; c < kNb; c += kWave) a[r][c] -= f * a[j][c];
+    }
+    if (tid == 0) dg[j] = sp;
+    if (tid > 0 && j + tid < kNb) a[j + tid][j] = a[j][j + tid] / sp;
+    __syncthreads();
+  }
+  for (int idx = tid; idx < kNb * kNb; idx += 256) {
+    const int r = idx / kNb, c = idx % kNb;
+    const int64_t gr = r0 + r, gc = r0 + c;
+    if (gr < d && gc < d && r <= c) Uk[gr * d + gc] = r == c ? dg[r] : a[c][r];
+  }
+  if (tid == 0 && bad >= 0 && info && info[k] == 0) info[k] = (int)(r0 + bad) + 1;
+}
+
+// (2) The panel right of the diagonal block: U11^T X = A12, 128 columns per workgroup, one thread per
+// column, forward substitution in LDS (column sweep: once x[k] is known, the rows below lose
+// U11[k][i] * x[k]).  A thread touches its own column only; the reads of U11 are broadcasts.
+__global__ __launch_bounds__(128) void chol_panel_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
+  __shared__ float u[kNb][kPitch];
+  __shared__ float x[kNb][kPitch];
+  const int k = blockIdx.y;
+  float* Uk = Uw + (int64_t)k * d * d;
+  const int tid = threadIdx.x;
+  const int64_t c0 = r0 + kNb + (int64_t)blockIdx.x * kNb;
+  for (int idx = tid; idx < kNb * kNb; idx += 128) {
+    const int r = idx / kNb, c = idx % kNb;
+    u[r][c] = r <= c ? Uk[(r0 + r) * d + r0 + c] : 0.f;     // the block row is complete: r0 + 127 < d
+    x[r][c] = c0 + c < d ? Uk[(r0 + r) * d + c0 + c] : 0.f;
+  }
+  __syncthreads();
+  const int c = tid;
+  for (int kk = 0; kk < kNb; ++kk) {
+    const float xk = x[kk][c] / u[kk][kk];
+    x[kk][c] = xk;
+#pragma unroll 8
+    for (int i = kk + 1; i < kNb; ++i) x[i][c] -= u[kk][i] * xk;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kNb * kNb; idx += 128) {
+    const int r = idx / kNb, cc = idx % kNb;
+    if (c0 + cc < d) Uk[(r0 + r) * d + c0 + cc] = x[r][cc];
+  }
+}
+
+// (3) Trailing update: for the 128 x 128 tiles (ti <= tj) of the upper triangle right of and below
+// the block row,  A22[a][b] -= sum_{k < 128} U12[k][a] * U12[k][b].  4 waves of 64 x 64; the rows of
+// U12 are staged through LDS as they lie in memory, 16 at a time; the operand layout of the fp32
+// MFMA (lane -> column l%32, row l/32) reads that tile row-wise.
+constexpr int kStep = 16;
+constexpr int kSPitch = kNb + 32;    // floats; keeps the two rows of one MFMA read on disjoint banks
+
+__device__ inline f32x4 load4(const float* __restrict__ p, int64_t c, int64_t d, bool vec) {
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (vec && c + 4 <= d) {
+    v = *reinterpret_cast<const f32x4*>(p);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (c + e < d) v[e] = p[e];
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
+  __shared__ __attribute__((aligned(16))) float As[2][kStep][kSPitch];
+  __shared__ __attribute__((aligned(16))) float Bs[2][kStep][kSPitch];
+  const int k = blockIdx.y;
+  float* Uk = Uw + (int64_t)k * d * d;
+  int ti, tj;
+  tri_decode(blockIdx.x, ti, tj);                            // ti <= tj
+  const int64_t t0 = r0 + kNb;                               // first trailing row / column
+  const int64_t a0 = t0 + (int64_t)ti * kNb, b0 = t0 + (int64_t)tj * kNb;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int wm = wave / 2, wn = wave % 2;
+  const int lrow = tid / 32, lcol = (tid % 32) * 4;          // staging: 16 rows x 32 float4 per operand, two per thread
+  const bool vec = d % 4 == 0;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+  f32x4 ra[2], rb[2];
+  auto fetch = [&](int step) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const float* row = Uk + (r0 + step * kStep + lrow + 8 * h) * d;
+      ra[h] = load4(row + a0 + lcol, a0 + lcol, d, vec);
+      rb[h] = load4(row + b0 + lcol, b0 + lcol, d, vec);
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      *reinterpret_cast<f32x4*>(&As[buf][lrow + 8 * h][lcol]) = ra[h];
+      *reinterpret_cast<f32x4*>(&Bs[buf][lrow + 8 * h][lcol]) = rb[h];
+    }
+  };
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  constexpr int kSteps = kNb / kStep;
+  for (int step = 0; step < kSteps; ++step) {
+    const int buf = step & 1;
+    if (step + 1 < kSteps) fetch(step + 1);
+#pragma unroll
+    for (int kk = 0; kk < kStep; kk += 2) {
+      float av[2], bv[2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) av[x] = As[buf][kk + lane / 32][wm * 64 + x * 32 + lane % 32];
+#pragma unroll
+      for (int y = 0; y < 2; ++y) bv[y] = Bs[buf][kk + lane / 32][wn * 64 + y * 32 + lane % 32];
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
+    }
+    if (step + 1 < kSteps) stash(buf ^ 1);
+    __syncthreads();
+  }
+  // accumulator register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y) {
+      const int64_t col = b0 + wn * 64 + y * 32 + lane % 32;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = a0 + wm * 64 + x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        if (row < d && col < d && row <= col) {
+          float* p = Uk + row * d + col;
+          const float val = acc[x][y][r];
+          *p -= val;
+        }
+      }
+    }
+}
+
+// The factor in the requested form, every entry of F written: L[i][j] = U[j][i] (i >= j), zeros above
+// the diagonal; or R[i][j] = U[d-1-j][d-1-i] (i <= j), zeros below.  One workgroup per 64 x 64 tile of F.
+__global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict__ Uw, int64_t d, int reverse,
+                                                        float* __restrict__ F) {
+  __shared__ float tile[64][65];
+  const int k = blockIdx.z;
+  const float* Uk = Uw + (int64_t)k * d * d;
+  float* Fk = F + (int64_t)k * d * d;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  const int64_t i0 = (int64_t)blockIdx.y * 64, j0 = (int64_t)blockIdx.x * 64;   // tile of F: rows i, columns j
+  // source entry of F[i0+li][j0+lj]:  U[sr][sc], sr = j (or d-1-j), sc = i (or d-1-i); tile[lj][li]
+  for (int lj = ty; lj < 64; lj += 4) {
+    const int64_t j = j0 + lj, i = i0 + tx;
+    const int64_t sr = reverse ? d - 1 - j : j, sc = reverse ? d - 1 - i : i;
+    tile[lj][tx] = (i < d && j < d && sr >= 0 && sc >= 0 && sr <= sc) ? Uk[sr * d + sc] : 0.f;
+  }
+  __syncthreads();
+  for (int li = ty; li < 64; li += 4) {
+    const int64_t i = i0 + li, j = j0 + tx;
+    if (i < d && j < d) Fk[i * d + j] = tile[tx][li];
+  }
+}
+
+struct Layout {
+  size_t u_bytes, eps_bytes;
+};
+Layout make_layout(int64_t d, int G) {
+  auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+  Layout L;
+  L.u_bytes = up((size_t)G * d * d * sizeof(float));
+  L.eps_bytes = up((size_t)G * sizeof(double));
+  return L;
+}
+
+}  // namespace
+
+size_t cholesky_workspace(int64_t d, int G) {
+  const Layout L = make_layout(d, G);
+  return L.u_bytes + L.eps_bytes;
+}
+
+hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_rel, double damp_abs, bool reverse,
+                                  float* F, int* info, void* ws, hipStream_t st) {
+  const Layout L = make_layout(d, G);
+  float* Uw = (float*)ws;
+  double* eps = (double*)((char*)ws + L.u_bytes);
+  hipError_t e;
+  chol_eps_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(H, d, damp_rel, damp_abs, eps, info);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const unsigned t64 = (unsigned)((d + 63) / 64);
+  chol_load_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d, reverse ? 1 : 0, eps, Uw);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  for (int64_t r0 = 0; r0 < d; r0 += kNb) {
+    chol_diag_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, info);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int64_t trail = d - (r0 + kNb);
+    if (trail <= 0) break;
+    const int64_t tt = (trail + kNb - 1) / kNb;
+    chol_panel_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(128), 0, st>>>(Uw, d, r0);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    chol_syrk_kernel<<<dim3((unsigned)tri_count(tt), (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, d, reverse ? 1 : 0, F);
+  return hipGetLastError();
+}
+
+}  // namespace gq

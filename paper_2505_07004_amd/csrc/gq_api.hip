@@ -126,6 +126,24 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
                                        (hipStream_t)hip_stream));
 }
 
+size_t gq_cholesky_workspace_bytes(int64_t d_in, int32_t G) {
+  if (d_in <= 0 || G <= 0) return 0;
+  return gq::cholesky_workspace(d_in, G);
+}
+
+int gq_damped_cholesky(const float* H, int64_t d_in, int32_t G, double damp_rel, double damp_abs, uint32_t flags,
+                       float* F, int32_t* info, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (d_in <= 0 || G <= 0 || !(damp_rel >= 0.0) || !(damp_abs >= 0.0)) return GQ_ERR_SHAPE;
+  if (flags & ~(uint32_t)GQ_CHOL_REVERSE) return GQ_ERR_UNSUPPORTED;
+  if (!H || !F) return GQ_ERR_NULLPTR;
+  if (H == F) return GQ_ERR_SHAPE;
+  if (!aligned16(H) || !aligned16(F)) return GQ_ERR_ALIGN;
+  const size_t need = gq_cholesky_workspace_bytes(d_in, G);
+  if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
+  return from_hip(gq::launch_damped_cholesky(H, d_in, G, damp_rel, damp_abs, (flags & GQ_CHOL_REVERSE) != 0, F, info,
+                                             workspace, (hipStream_t)hip_stream));
+}
+
 int gq_ldlq_assign(const float* W, float* What, const float* codebook, int32_t n_levels, int64_t d_out, int64_t d_in,
                    int64_t ld_w, const float* R, int32_t G, uint8_t* Q, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {

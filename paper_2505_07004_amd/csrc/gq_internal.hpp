@@ -118,6 +118,10 @@ hipError_t launch_ldlq_assign(const float* W, float* What, const float* codebook
                               int64_t d_in, int64_t ld, const float* R, int G, unsigned char* Q, void* ws,
                               hipStream_t st);
 
+hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_rel, double damp_abs, bool reverse,
+                                  float* F, int* info, void* ws, hipStream_t st);
+size_t cholesky_workspace(int64_t d, int G);
+
 hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld, const unsigned char* Q,
                                const float* H, int G, int n_levels, double lam, float* codebook, float* What,
                                void* ws, hipStream_t st);

@@ -23,7 +23,10 @@ DEV = "cuda"
 def _hessian(n, d_in, d_out, G, seed):
     X = wl.make_x_outlier(n, d_in, max(1, d_in // 64), 20.0, seed, DEV, torch.float32)
     dZ = wl.make_dz(n, d_out, 1.0, 1.5, seed + 1, DEV)
-    return gq.gq_fisher_gram(X, gq.gq_group_weights(dZ, G), mirror=True)
+    s = gq.gq_group_weights(dZ, G)
+    if d_in % 4:                        # rows of X not 16-byte aligned: an input for the factorization all the same
+        return torch.einsum("ia,ik,ib->kab", X, s, X).contiguous()
+    return gq.gq_fisher_gram(X, s, mirror=True)
 
 
 def _targets_from_factor(Wn, new, Rn, G):
@@ -87,3 +90,109 @@ def test_sequential_rounding_with_a_diagonal_factor_is_plain_rounding():
     rtn = torch.argmin((C[:, None, :] - W[:, :, None]).abs(), dim=2)
     assert torch.equal(Q.long(), rtn)
     assert torch.equal(What, torch.gather(C, 1, rtn))
+
+
+# ------------------------------------------------------------------ damped Cholesky
+def _check_factor(Hn, Fg, rel, ab, reverse, what):
+    """A positive definite matrix has ONE triangular factor with positive diagonal, so shape, sign and
+    the product pin the result.  Backward: ||F F^T - A||_F / ||A||_F (fp32 arithmetic, blocks of 128:
+    a few 2^-24 times a slowly growing function of d; bar 1e-5, the fp32 bar of this build).  Forward:
+    against the oracle's fp64 factor, relative to the condition number of A."""
+    G, d, _ = Hn.shape
+    Fo = oracle.damped_cholesky(Hn, rel, ab, reverse=reverse)
+    worst_b = worst_f = 0.0
+    for k in range(G):
+        A = Hn[k] + (ab + rel * np.trace(Hn[k]) / d) * np.eye(d)
+        F = Fg[k]
+        if reverse:
+            assert np.all(np.tril(F, -1) == 0.0)
+        else:
+            assert np.all(np.triu(F, 1) == 0.0)
+        assert np.all(np.diag(F) > 0)
+        back = np.linalg.norm(F @ F.T - A) / np.linalg.norm(A)
+        fwd = np.linalg.norm(F - Fo[k]) / np.linalg.norm(Fo[k])
+        cond = np.linalg.cond(A)
+        worst_b, worst_f = max(worst_b, back), max(worst_f, fwd / cond)
+        say(f"  {what} group {k}: backward {back:.2e}, forward {fwd:.2e} at condition number {cond:.1e}")
+    assert worst_b <= 1e-5
+    assert worst_f <= 1e-6
+
+
+@pytest.mark.parametrize("n,d_in,G,reverse", [
+    (512, 256, 2, False),       # two blocks
+    (512, 256, 2, True),
+    (400, 200, 3, True),        # ragged last block of 72
+    (300, 132, 1, False),       # last block of 4
+    (300, 100, 2, True),        # a single, ragged block
+    (700, 450, 1, True),        # four blocks, d % 4 != 0: the scalar loads of the trailing update
+])
+def test_damped_cholesky_is_the_factor_of_the_damped_matrix(n, d_in, G, reverse):
+    say(f"cholesky n={n} d_in={d_in} G={G} reverse={reverse}")
+    H = _hessian(n, d_in, 4 * G, G, 51 + d_in)
+    F, info = gq.gq_damped_cholesky(H, 0.01, 0.0, reverse=reverse)
+    torch.cuda.synchronize()
+    assert info.tolist() == [0] * G
+    _check_factor(to_np64(H), to_np64(F), 0.01, 0.0, reverse, "damp 1 %")
+    F2, info2 = gq.gq_damped_cholesky(H, 0.0, 0.37, reverse=reverse)      # an absolute constant instead
+    torch.cuda.synchronize()
+    assert info2.tolist() == [0] * G
+    _check_factor(to_np64(H), to_np64(F2), 0.0, 0.37, reverse, "damp 0.37 abs")
+    F3, _ = gq.gq_damped_cholesky(H, 0.01, 0.0, reverse=reverse)
+    assert torch.equal(F, F3)                                              # deterministic
+
+
+def test_damped_cholesky_reports_the_first_non_positive_pivot():
+    d = 200
+    g = torch.Generator().manual_seed(3)
+    B = torch.randn(d, d, generator=g, dtype=torch.float64)
+    A = (B @ B.T / d + torch.eye(d, dtype=torch.float64))
+    bad = A.clone()
+    bad[150, 150] = -1.0                                                   # the leading 150 x 150 block stays positive definite
+    H = torch.stack([A, bad]).to(torch.float32).to(DEV).contiguous()
+    F, info = gq.gq_damped_cholesky(H, 0.0, 0.0)
+    torch.cuda.synchronize()
+    assert info.tolist() == [0, 151]
+    assert torch.isfinite(F).all()
+    _check_factor(to_np64(H[:1]), to_np64(F[:1]), 0.0, 0.0, False, "the good group")
+    F, info = gq.gq_damped_cholesky(H, 0.0, 0.0, reverse=True)             # from the end: coordinate 150 is the 50th eliminated
+    torch.cuda.synchronize()
+    assert info.tolist() == [0, 50]
+
+
+def test_cholesky_then_sequential_rounding_at_the_llama2_7b_shape():
+    """Config 2 shape (d_in = d_out = 4096, G = 4): factor on the GPU, check it against the damped matrix
+    in fp64, round with it, replay the decisions of sampled channels from the GPU's own factor, and compare
+    the objective with the oracle's GPTQ pass (from the inverse, in fp64) on a few channels."""
+    spec = wl.CONFIGS["llama2_7b_attn"]
+    X = wl.make_x(spec, DEV)
+    s = gq.gq_group_weights(wl.make_dz_for(spec, DEV), spec.G)
+    H = gq.gq_fisher_gram(X, s, mirror=True)
+    del X, s
+    R, info = gq.gq_damped_cholesky(H, 0.01, 0.0, reverse=True)
+    torch.cuda.synchronize()
+    assert info.tolist() == [0] * spec.G
+    Hn = to_np64(H[:1])
+    _check_factor(Hn, to_np64(R[:1]), 0.01, 0.0, True, "config 2 shape")
+    W = wl.make_w(spec.d_out, spec.d_in, 7, DEV)
+    _, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)
+    C = C.contiguous()
+    What, Q = gq.gq_ldlq_assign(W, C, R)
+    rtn = torch.gather(C, 1, torch.argmin((C[:, None, :] - W[:, :, None]).abs(), dim=2))
+    Hd = H + 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, spec.d_in))
+    o_seq, o_rtn = gq.gq_objective(W, What, Hd), gq.gq_objective(W, rtn, Hd)
+    torch.cuda.synchronize()
+    say(f"  objective: plain rounding {o_rtn.tolist()}, sequential rounding {o_seq.tolist()}")
+    assert torch.all(o_seq < 0.8 * o_rtn)
+    assert torch.equal(What, torch.gather(C, 1, Q.long()))
+    rows = torch.arange(0, 48, device=DEV) * 7                             # 48 channels of group 0
+    R64 = to_np64(R[:1])
+    Wn, new = to_np64(W[rows]), to_np64(What[rows])
+    T, S = _targets_from_factor(Wn, new, R64, 1)
+    check_rounding_decisions(T, S, to_np64(C[rows]), Q[rows].cpu().numpy(), new, "config 2 shape, 48 sampled channels")
+    r4 = rows[:4]
+    _, ref = oracle.gptq_assign(to_np64(W[r4]), to_np64(C[r4]), Hn, 1, damp_rel=0.01)
+    A = to_np64(Hd[:1])
+    o_g = oracle.objective(to_np64(W[r4]), to_np64(What[r4]), A, 1)[1]
+    o_o = oracle.objective(to_np64(W[r4]), ref, A, 1)[1]
+    say(f"  4 channels: objective gpu {o_g.sum():.5f}, oracle GPTQ {o_o.sum():.5f}")
+    assert abs(o_g.sum() - o_o.sum()) <= 1e-2 * o_o.sum()

@@ -8,7 +8,8 @@
 // Both are one algorithm on a working matrix A' = U^T U, U upper triangular, processed by block rows
 // of 128 in fp32:  A' = A gives L = U^T;  A'[a][b] = A[d-1-a][d-1-b] gives R[i][j] = U[d-1-j][d-1-i].
 // Per block row:  (1) the 128 x 128 diagonal block is factored in LDS by one workgroup per group;
-// (2) the panel to its right is solved against it, U12 = U11^-T A12, one thread per column;
+// (2) the panel to its right is solved against it, U12 = U11^-T A12 (both with the block in registers,
+// 8 x 8 per thread, one barrier per row);
 // (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the fp32 matrix cores
 // (v_mfma_f32_32x32x2_f32), rows of U12 staged through LDS as they lie in memory.
 // Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its
@@ -19,7 +20,6 @@ namespace gq {
 namespace {
 
 constexpr int kNb = 128;             // block size
-constexpr int kPitch = kNb + 1;      // LDS row pitch in floats: rows start on consecutive banks
 
 // eps[k] and info[k] = 0.  One workgroup per group; fixed-order fp64 sum of the diagonal.
 __global__ __launch_bounds__(256) void chol_eps_kernel(const float* __restrict__ H, int64_t d, double damp_rel,
@@ -79,78 +79,139 @@ __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict_
   }
 }
 
-// (1) The diagonal block at (r0, r0): A11 = U11^T U11 in LDS, row by row.  Step j reads row j of the
-// upper triangle (final since step j-1), writes the scaled row into the unused LOWER triangle (so no
-// one's input changes under them), and updates the rows below it; one barrier per step.  Wave w
-// takes the rows j+1+w, j+5+w, ..., a lane the columns from the row's diagonal on: consecutive banks.
+// (1) The diagonal block at (r0, r0): A11 = U11^T U11, row by row, the block held in registers:
+// thread (tr, tc) of 16 x 16 owns the 8 x 8 tile at rows 8 tr, columns 8 tc.  At step j the owners
+// of row j publish it (unscaled) in LDS; after ONE barrier (two row buffers alternate) everyone
+// reads the pivot, its 8 row entries and 8 column entries and updates its tile,
+//   a[r][c] -= (a[j][r] / a[j][j]) * a[j][c]   for r > j,
+// while the owners turn their copy of row j into U[j][:] = a[j][:] / sqrt(a[j][j]).
 // Rows and columns past the end of the matrix are those of the identity.
 __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, int64_t d, int64_t r0,
                                                         int* __restrict__ info) {
-  __shared__ float a[kNb][kPitch];
-  __shared__ float dg[kNb];
+  __shared__ __attribute__((aligned(16))) float rowbuf[2][kNb];
   __shared__ int bad;
   const int k = blockIdx.x;
   float* Uk = Uw + (int64_t)k * d * d;
-  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int tid = threadIdx.x, tr = tid / 16, tc = tid % 16;
   if (tid == 0) bad = -1;
-  for (int idx = tid; idx < kNb * kNb; idx += 256) {
-    const int r = idx / kNb, c = idx % kNb;
-    const int64_t gr = r0 + r, gc = r0 + c;
-    float v = r == c ? 1.f : 0.f;
-    if (gr < d && gc < d && r <= c) v = Uk[gr * d + gc];
-    a[r][c] = v;
-  }
-  __syncthreads();
-  for (int j = 0; j < kNb; ++j) {
-    float p = a[j][j];
-    const bool ok = p > 0.f;                                // false for NaN as well
-    if (!ok && tid == 0 && bad < 0) bad = j;
-    p = ok ? p : 1.f;
-    const float sp = sqrtf(p), ip = 1.f / p;
-    for (int r = j + 1 + wave; r < kNb; r += 4) {
-      const float f = a[j][r] * ip;
-      for (int c = r + lane; c < kNb; c += kWave) a[r][c] -= f * a[j][c];
+  float a[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+      const int r = 8 * tr + i, c = 8 * tc + l;
+      const int64_t gr = r0 + r, gc = r0 + c;
+      const bool in = gr < d && gc < d && r <= c;
+      const float v = Uk[in ? gr * d + gc : 0];
+      a[i][l] = in ? v : (r == c ? 1.f : 0.f);
     }
-    if (tid == 0) dg[j] = sp;
-    if (tid > 0 && j + tid < kNb) a[j + tid][j] = a[j][j + tid] / sp;
-    __syncthreads();
+  for (int jb = 0; jb < 16; ++jb) {
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      const int j = 8 * jb + jj, buf = j & 1;
+      if (tr == jb) {
+#pragma unroll
+        for (int l = 0; l < 8; ++l) rowbuf[buf][8 * tc + l] = a[jj][l];
+      }
+      __syncthreads();
+      float p = rowbuf[buf][j];
+      const bool ok = p > 0.f;                              // false for NaN as well
+      if (!ok && tr == jb && tc == jb && bad < 0) bad = j;
+      p = ok ? p : 1.f;
+      if (tr >= jb && tc >= tr) {
+        const float ip = __builtin_amdgcn_rcpf(p);             // 1 ulp; the step's critical path
+        float f[8], cl[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (8 * tr + i > j) ? rowbuf[buf][8 * tr + i] * ip : 0.f;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) cl[l] = rowbuf[buf][8 * tc + l];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int l = 0; l < 8; ++l) a[i][l] -= f[i] * cl[l];
+        if (tr == jb) {                                     // f[jj] was 0: row j is untouched; make it the row of U
+          const float sp = __builtin_amdgcn_sqrtf(p), isp = __builtin_amdgcn_rcpf(sp);
+#pragma unroll
+          for (int l = 0; l < 8; ++l) a[jj][l] = (8 * tc + l == j) ? sp : cl[l] * isp;
+        }
+      }
+    }
   }
-  for (int idx = tid; idx < kNb * kNb; idx += 256) {
-    const int r = idx / kNb, c = idx % kNb;
-    const int64_t gr = r0 + r, gc = r0 + c;
-    if (gr < d && gc < d && r <= c) Uk[gr * d + gc] = r == c ? dg[r] : a[c][r];
-  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+      const int r = 8 * tr + i, c = 8 * tc + l;
+      const int64_t gr = r0 + r, gc = r0 + c;
+      if (gr < d && gc < d && r <= c) Uk[gr * d + gc] = a[i][l];
+    }
+  __syncthreads();
   if (tid == 0 && bad >= 0 && info && info[k] == 0) info[k] = (int)(r0 + bad) + 1;
 }
 
-// (2) The panel right of the diagonal block: U11^T X = A12, 128 columns per workgroup, one thread per
-// column, forward substitution in LDS (column sweep: once x[k] is known, the rows below lose
-// U11[k][i] * x[k]).  A thread touches its own column only; the reads of U11 are broadcasts.
-__global__ __launch_bounds__(128) void chol_panel_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
-  __shared__ float u[kNb][kPitch];
-  __shared__ float x[kNb][kPitch];
+// (2) The panel right of the diagonal block: U11^T X = A12, 128 columns per workgroup, forward
+// substitution with the 128 x 128 tile of A12 in registers (thread (tk, tc) owns rows 8 tk, columns
+// 8 tc) and U11 in LDS.  At step k the owners of row k divide it by U11[k][k] and publish it; after one
+// barrier every row i > k loses U11[k][i] * x[k][:].
+constexpr int kUPitch = kNb + 4;     // floats: rows 16-byte aligned for the four-float reads
+
+__global__ __launch_bounds__(256) void chol_panel_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
+  __shared__ __attribute__((aligned(16))) float u[kNb][kUPitch];
+  __shared__ __attribute__((aligned(16))) float rowbuf[2][kNb];
+  __shared__ float rdiag[kNb];
   const int k = blockIdx.y;
   float* Uk = Uw + (int64_t)k * d * d;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, tk = tid / 16, tc = tid % 16;
+  if (tid < kNb) rdiag[tid] = 1.f / Uk[(r0 + tid) * d + r0 + tid];
   const int64_t c0 = r0 + kNb + (int64_t)blockIdx.x * kNb;
-  for (int idx = tid; idx < kNb * kNb; idx += 128) {
+  for (int idx = tid; idx < kNb * kNb; idx += 256) {
     const int r = idx / kNb, c = idx % kNb;
-    u[r][c] = r <= c ? Uk[(r0 + r) * d + r0 + c] : 0.f;     // the block row is complete: r0 + 127 < d
-    x[r][c] = c0 + c < d ? Uk[(r0 + r) * d + c0 + c] : 0.f;
+    const float v = Uk[(r0 + r) * d + r0 + (r <= c ? c : r)];  // the block row is complete: r0 + 127 < d
+    u[r][c] = r <= c ? v : 0.f;
   }
+  float x[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+      const int64_t gc = c0 + 8 * tc + l;
+      const float v = Uk[(r0 + 8 * tk + i) * d + (gc < d ? gc : d - 1)];
+      x[i][l] = gc < d ? v : 0.f;
+    }
   __syncthreads();
-  const int c = tid;
-  for (int kk = 0; kk < kNb; ++kk) {
-    const float xk = x[kk][c] / u[kk][kk];
-    x[kk][c] = xk;
-#pragma unroll 8
-    for (int i = kk + 1; i < kNb; ++i) x[i][c] -= u[kk][i] * xk;
+  for (int kb = 0; kb < 16; ++kb) {
+#pragma unroll
+    for (int kj = 0; kj < 8; ++kj) {
+      const int kk = 8 * kb + kj, buf = kk & 1;
+      if (tk == kb) {
+        const float rp = rdiag[kk];
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+          x[kj][l] = x[kj][l] * rp;
+          rowbuf[buf][8 * tc + l] = x[kj][l];
+        }
+      }
+      __syncthreads();
+      if (tk >= kb) {
+        float f[8], xr[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (8 * tk + i > kk) ? u[kk][8 * tk + i] : 0.f;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) xr[l] = rowbuf[buf][8 * tc + l];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int l = 0; l < 8; ++l) x[i][l] -= f[i] * xr[l];
+      }
+    }
   }
-  __syncthreads();
-  for (int idx = tid; idx < kNb * kNb; idx += 128) {
-    const int r = idx / kNb, cc = idx % kNb;
-    if (c0 + cc < d) Uk[(r0 + r) * d + c0 + cc] = x[r][cc];
-  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+      const int64_t gc = c0 + 8 * tc + l;
+      if (gc < d) Uk[(r0 + 8 * tk + i) * d + gc] = x[i][l];
+    }
 }
 
 // (3) Trailing update: for the 128 x 128 tiles (ti <= tj) of the upper triangle right of and below
@@ -309,7 +370,7 @@ hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_
     const int64_t trail = d - (r0 + kNb);
     if (trail <= 0) break;
     const int64_t tt = (trail + kNb - 1) / kNb;
-    chol_panel_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(128), 0, st>>>(Uw, d, r0);
+    chol_panel_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     chol_syrk_kernel<<<dim3((unsigned)tri_count(tt), (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0);
     if ((e = hipGetLastError()) != hipSuccess) return e;

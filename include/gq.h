@@ -122,7 +122,10 @@ size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in,
  *   x_dtype selects the arithmetic: GQ_F32 -> fp32 matrix-core path (fp32 products,
  *          fp32 accumulation); GQ_BF16 -> bf16 matrix-core path: one operand is
  *          bf16_rne(s[i,k]*X[i,a]) (fp32 multiply, round to nearest even), the
- *          other the raw X[i,b]; fp32 accumulation.
+ *          other the raw X[i,b]; fp32 accumulation.  The result is symmetric once
+ *          mirrored, but positive semidefinite only up to that rounding (about
+ *          5e-4 of its largest eigenvalue): damp accordingly before factoring it,
+ *          or use GQ_F32.
  *   workspace  device buffer of at least gq_fisher_gram_workspace_bytes() bytes,
  *          256-byte aligned (may be NULL when that size is 0); contents are
  *          scratch.

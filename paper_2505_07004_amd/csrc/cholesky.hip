@@ -7,9 +7,9 @@
 //
 // Both are one algorithm on a working matrix A' = U^T U, U upper triangular, processed by block rows
 // of 128 in fp32:  A' = A gives L = U^T;  A'[a][b] = A[d-1-a][d-1-b] gives R[i][j] = U[d-1-j][d-1-i].
-// Per block row:  (1) the 128 x 128 diagonal block is factored in LDS by one workgroup per group;
+// Per block row:  (1) the 128 x 128 diagonal block is factored by one workgroup per group;
 // (2) the panel to its right is solved against it, U12 = U11^-T A12 (both with the block in registers,
-// 8 x 8 per thread, one barrier per row);
+// 8 x 8 per thread, rows published through LDS, one barrier per row);
 // (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the fp32 matrix cores
 // (v_mfma_f32_32x32x2_f32), rows of U12 staged through LDS as they lie in memory.
 // Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its

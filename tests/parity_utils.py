@@ -144,3 +144,67 @@ def check_rounding_decisions(T, S, Cn, Qg, new, what):
     assert 2 * slack.max() <= 0.1 * spacing                            # the bound is small against the grid itself,
     assert np.mean(excess > 0) <= 2e-3                                 # and almost every decision IS the exact nearest point
     assert np.array_equal(new, np.take_along_axis(Cn, Qg.astype(np.int64), axis=1))   # What is the grid value of its code, exactly
+
+
+def cd_targets_along(Wn, old, new, Hn, G):
+    """t[j, i] of Eq. (cd_closed) for the state in which coordinate i was updated during one cycle
+    that turned `old` into `new` (coordinates < i new, coordinates > i old), and the sum of the
+    absolute values of the terms of its sum, S[j, i] = sum_i' |Ht[i, i']| |delta[j, i']|."""
+    d_out, d_in = Wn.shape
+    m = d_out // G
+    T, S = np.empty_like(Wn), np.empty_like(Wn)
+    for k in range(G):
+        r = slice(k * m, (k + 1) * m)
+        Ht = Hn[k] / np.diag(Hn[k])[:, None]
+        lower, upper = np.tril(Ht, -1), np.triu(Ht, 1)
+        dn, do = new[r] - Wn[r], old[r] - Wn[r]
+        T[r] = Wn[r] - dn @ lower.T - do @ upper.T
+        S[r] = np.abs(dn) @ np.abs(lower).T + np.abs(do) @ np.abs(upper).T
+    return T, S
+
+
+def ldlq_targets(Wn, new, Rn, G):
+    """t[j, i] = w[j, i] - sum_{i' < i} (new[j, i'] - w[j, i']) R[i', i] / R[i, i] and the sum of the
+    absolute values of the terms, for the rounded weights `new` the GPU produced."""
+    d_out, d_in = Wn.shape
+    m = d_out // G
+    T, S = np.empty_like(Wn), np.empty_like(Wn)
+    for k in range(G):
+        r = slice(k * m, (k + 1) * m)
+        U = np.triu(Rn[k], 1) / np.diag(Rn[k])[None, :]                # U[i', i] = R[i', i] / R[i, i], i' < i
+        dn = new[r] - Wn[r]
+        T[r] = Wn[r] - dn @ U
+        S[r] = np.abs(dn) @ np.abs(U)
+    return T, S
+
+
+# ------------------------------------------------------------------ codebook step
+def check_codebook_channels(oracle, Wn, Qn, Hk, Cg, m, lam, what):
+    """Wn, Qn, Cg: the rows of some channels of ONE group; Hk that group's Hessian (fp64)."""
+    d_in = Wn.shape[1]
+    Habs = np.abs(Hk)
+    worst_back, worst_obj, worst_fwd = 0.0, 0.0, 0.0
+    Co, _ = oracle.lnq_codebook(Wn, Qn, Hk[None], m, 1, lam)
+    for j in range(Wn.shape[0]):
+        P = np.zeros((d_in, m))
+        P[np.arange(d_in), Qn[j]] = 1.0
+        A = P.T @ Hk @ P + lam * np.eye(m)
+        b = P.T @ (Hk @ Wn[j])
+        c = Cg[j]
+        scale = (P.T @ Habs @ P) @ np.abs(c) + P.T @ (Habs @ np.abs(Wn[j]))
+        used = P.sum(axis=0) > 0
+        resid = np.abs(A @ c - b)
+        back = float(np.max(resid[used] / scale[used]))
+        worst_back = max(worst_back, back)
+        assert np.all(c[~used] == 0.0), f"{what}: channel {j}: an unused grid point is not 0"
+        e_g, e_o = Wn[j] - P @ c, Wn[j] - P @ Co[j]
+        o_g, o_o = e_g @ Hk @ e_g, e_o @ Hk @ e_o
+        worst_obj = max(worst_obj, float((o_g - o_o) / o_o))
+        cond = np.linalg.cond(A[np.ix_(used, used)])
+        fwd = float(np.max(np.abs(c - Co[j])) / np.max(np.abs(Co[j])))
+        worst_fwd = max(worst_fwd, fwd / cond)
+    say(f"{what}: backward error {worst_back:.2e} (bound 9.5e-07), objective above the minimum by {worst_obj:.2e} (rel), "
+        f"grid error / condition number {worst_fwd:.2e}")
+    assert worst_back <= 2.0 ** -20
+    assert worst_obj <= 1e-6
+    assert worst_fwd <= 1e-5

@@ -17,7 +17,7 @@ import torch
 import oracle
 from paper_2505_07004_amd import binding as gq
 from paper_2505_07004_amd import workloads as wl
-from parity_utils import check_rounding_decisions, say, to_np64
+from parity_utils import cd_targets_along, check_rounding_decisions, say, to_np64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -38,29 +38,12 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
     return W, What, C.contiguous(), H
 
 
-def _targets_along(Wn, old, new, Hn, G):
-    """t[j, i] of Eq. (cd_closed) for the state in which coordinate i was updated during one cycle
-    that turned `old` into `new` (coordinates < i new, coordinates > i old), and the sum of the
-    absolute values of the terms of its sum, S[j, i] = sum_i' |Ht[i, i']| |delta[j, i']|."""
-    d_out, d_in = Wn.shape
-    m = d_out // G
-    T, S = np.empty_like(Wn), np.empty_like(Wn)
-    for k in range(G):
-        r = slice(k * m, (k + 1) * m)
-        Ht = Hn[k] / np.diag(Hn[k])[:, None]
-        lower, upper = np.tril(Ht, -1), np.triu(Ht, 1)
-        dn, do = new[r] - Wn[r], old[r] - Wn[r]
-        T[r] = Wn[r] - dn @ lower.T - do @ upper.T
-        S[r] = np.abs(dn) @ np.abs(lower).T + np.abs(do) @ np.abs(upper).T
-    return T, S
-
-
 def _check_cycle(Wn, old, new, Qg, Cn, Hn, G, what):
     """Slack of a decision: the GPU forms every product of the sum from two-term bf16 splits of both
     factors and drops the lo*lo product, a relative error below 2^-15 per term in the worst case, and
     adds the terms in fp32; so its target is within 2^-14 * S + 2^-20 * |t| of the exact one, and the
     grid point it picks can be farther from the exact target than the nearest one by at most twice that."""
-    T, S = _targets_along(Wn, old, new, Hn, G)
+    T, S = cd_targets_along(Wn, old, new, Hn, G)
     check_rounding_decisions(T, S, Cn, Qg, new, what)
 
 

@@ -14,7 +14,7 @@ import torch
 import oracle
 from paper_2505_07004_amd import binding as gq
 from paper_2505_07004_amd import workloads as wl
-from parity_utils import check_rounding_decisions, say, to_np64
+from parity_utils import check_rounding_decisions, ldlq_targets, say, to_np64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -27,21 +27,6 @@ def _hessian(n, d_in, d_out, G, seed):
     if d_in % 4:                        # rows of X not 16-byte aligned: an input for the factorization all the same
         return torch.einsum("ia,ik,ib->kab", X, s, X).contiguous()
     return gq.gq_fisher_gram(X, s, mirror=True)
-
-
-def _targets_from_factor(Wn, new, Rn, G):
-    """t[j, i] = w[j, i] - sum_{i' < i} (new[j, i'] - w[j, i']) R[i', i] / R[i, i] and the sum of the
-    absolute values of the terms, for the rounded weights `new` the GPU produced."""
-    d_out, d_in = Wn.shape
-    m = d_out // G
-    T, S = np.empty_like(Wn), np.empty_like(Wn)
-    for k in range(G):
-        r = slice(k * m, (k + 1) * m)
-        U = np.triu(Rn[k], 1) / np.diag(Rn[k])[None, :]                # U[i', i] = R[i', i] / R[i, i], i' < i
-        dn = new[r] - Wn[r]
-        T[r] = Wn[r] - dn @ U
-        S[r] = np.abs(dn) @ np.abs(U)
-    return T, S
 
 
 @pytest.mark.parametrize("n,d_in,d_out,G,bits,ld", [
@@ -66,7 +51,7 @@ def test_sequential_rounding_decisions_are_valid_and_match_the_oracle(n, d_in, d
     torch.cuda.synchronize()
     Wn, Cn, new, Qg = to_np64(W), to_np64(C), to_np64(What), Q.cpu().numpy()
     R64 = Rn.astype(np.float64)
-    T, S = _targets_from_factor(Wn, new, R64, G)
+    T, S = ldlq_targets(Wn, new, R64, G)
     check_rounding_decisions(T, S, Cn, Qg, new, "sequential rounding")
     Qo, ref, _ = oracle.ldlq_assign(Wn, Cn, R64, G)
     differ = float(np.mean(Qo != Qg))
@@ -187,7 +172,7 @@ def test_cholesky_then_sequential_rounding_at_the_llama2_7b_shape():
     rows = torch.arange(0, 48, device=DEV) * 7                             # 48 channels of group 0
     R64 = to_np64(R[:1])
     Wn, new = to_np64(W[rows]), to_np64(What[rows])
-    T, S = _targets_from_factor(Wn, new, R64, 1)
+    T, S = ldlq_targets(Wn, new, R64, 1)
     check_rounding_decisions(T, S, to_np64(C[rows]), Q[rows].cpu().numpy(), new, "config 2 shape, 48 sampled channels")
     r4 = rows[:4]
     _, ref = oracle.gptq_assign(to_np64(W[r4]), to_np64(C[r4]), Hn, 1, damp_rel=0.01)

@@ -16,7 +16,7 @@ import torch
 import oracle
 from paper_2505_07004_amd import binding as gq
 from paper_2505_07004_amd import workloads as wl
-from parity_utils import say, to_np64
+from parity_utils import check_codebook_channels, say, to_np64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -39,37 +39,6 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
     return W, Q, H
 
 
-def _check_channels(Wn, Qn, Hk, Cg, m, lam, what):
-    """Wn, Qn, Cg: the rows of some channels of ONE group; Hk that group's Hessian (fp64)."""
-    d_in = Wn.shape[1]
-    Habs = np.abs(Hk)
-    worst_back, worst_obj, worst_fwd = 0.0, 0.0, 0.0
-    Co, _ = oracle.lnq_codebook(Wn, Qn, Hk[None], m, 1, lam)
-    for j in range(Wn.shape[0]):
-        P = np.zeros((d_in, m))
-        P[np.arange(d_in), Qn[j]] = 1.0
-        A = P.T @ Hk @ P + lam * np.eye(m)
-        b = P.T @ (Hk @ Wn[j])
-        c = Cg[j]
-        scale = (P.T @ Habs @ P) @ np.abs(c) + P.T @ (Habs @ np.abs(Wn[j]))
-        used = P.sum(axis=0) > 0
-        resid = np.abs(A @ c - b)
-        back = float(np.max(resid[used] / scale[used]))
-        worst_back = max(worst_back, back)
-        assert np.all(c[~used] == 0.0), f"{what}: channel {j}: an unused grid point is not 0"
-        e_g, e_o = Wn[j] - P @ c, Wn[j] - P @ Co[j]
-        o_g, o_o = e_g @ Hk @ e_g, e_o @ Hk @ e_o
-        worst_obj = max(worst_obj, float((o_g - o_o) / o_o))
-        cond = np.linalg.cond(A[np.ix_(used, used)])
-        fwd = float(np.max(np.abs(c - Co[j])) / np.max(np.abs(Co[j])))
-        worst_fwd = max(worst_fwd, fwd / cond)
-    say(f"{what}: backward error {worst_back:.2e} (bound 9.5e-07), objective above the minimum by {worst_obj:.2e} (rel), "
-        f"grid error / condition number {worst_fwd:.2e}")
-    assert worst_back <= 2.0 ** -20
-    assert worst_obj <= 1e-6
-    assert worst_fwd <= 1e-5
-
-
 @pytest.mark.parametrize("n,d_in,d_out,G,bits,ld", [
     (512, 256, 128, 2, 3, None),        # two column tiles, 64 channels x 8 grid points = 4 row tiles per group
     (400, 200, 96, 4, 2, 208),          # ragged contraction and columns, 24 x 4 = 96 rows per group (ragged row tile), padded pitch
@@ -88,7 +57,7 @@ def test_codebook_step_solves_the_oracles_system(n, d_in, d_out, G, bits, ld):
     per = d_out // G
     for k in range(G):
         r = slice(k * per, (k + 1) * per)
-        _check_channels(Wn[r], Qn[r], Hn[k], Cg[r], m, LAM, f"group {k}")
+        check_codebook_channels(oracle, Wn[r], Qn[r], Hn[k], Cg[r], m, LAM, f"group {k}")
     # and without the optional output
     C2 = gq.gq_lnq_codebook(W, Q, H, m, LAM)
     torch.cuda.synchronize()
@@ -159,6 +128,6 @@ def test_codebook_step_at_the_llama2_7b_shape_on_sampled_channels():
         assert torch.equal(What, torch.gather(C, 1, Q.long()))
         for k in range(spec.G):
             rows = (k * per + torch.randperm(per, generator=g)[:12]).to(DEV)
-            _check_channels(to_np64(W[rows]), Q[rows].cpu().numpy().astype(np.int64), to_np64(H[k]), to_np64(C[rows]),
+            check_codebook_channels(oracle, to_np64(W[rows]), Q[rows].cpu().numpy().astype(np.int64), to_np64(H[k]), to_np64(C[rows]),
                             m, LAM, f"  group {k}, 12 sampled channels")
         del What, C, What0, C0, Q

@@ -148,7 +148,9 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
 }
 
 // Partial sums of B0 for block `blk`:  C[part][i][j] = sum over this part's contraction range
-// of delta[j][i'] * Ht[blk*128 + i][i'],  i < 128, j a channel (j contiguous, pitch d_out).
+// of delta[j][i'] * Ht[blk*128 + i][i'],  i < 128, j a channel (j contiguous, pitch d_out),
+// WITHOUT the 128 contraction elements of block `excl`: those belong to the block that is being
+// walked while this runs, and the walk of `blk` adds their share itself once they are final.
 // A workgroup owns 128 channels of one group and all 128 coordinates of the block; its 4
 // waves compute 64 x 64 each.  Both operands are contraction-major in memory; a stage is 64
 // contraction elements = one whole 128-byte line of each of the 4 x 128 operand rows
@@ -156,29 +158,29 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
 // wave w copies operand w) into a ring of two stages, one barrier per stage.  A row of a staged
 // tile holds eight 16-byte chunks; chunk c of row r sits at position c ^ ((r >> 1) & 7), which
 // makes the 16-byte fragment reads of 16 consecutive rows conflict-free (the loading lane
-// applies the same XOR when it picks its global chunk).  The parts (gridDim.y) split the
-// contraction; the sequential kernel adds them in a fixed order.
+// applies the same XOR when it picks its global chunk).  The parts split the contraction; the
+// walk adds them in a fixed order.
 constexpr int kGemmRows = 128;                       // channels per workgroup
 constexpr int kGemmK = 64;                           // contraction elements per stage
 constexpr int kGemmTile = 128 * kGemmK * 2;          // bytes of one staged operand tile (16 KiB)
 constexpr int kGemmStage = 4 * kGemmTile;            // 64 KiB
-__global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short* __restrict__ Dh,
-                                                            const unsigned short* __restrict__ Dl,
-                                                            const unsigned short* __restrict__ Hth,
-                                                            const unsigned short* __restrict__ Htl, int64_t d_out,
-                                                            int64_t ldp, int G, int n_gt, int blk,
-                                                            float* __restrict__ C) {
-  __shared__ __attribute__((aligned(1024))) char smem[2 * kGemmStage];
-  const int k = blockIdx.x / n_gt, gt = blockIdx.x % n_gt;
+__device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, int n_parts,
+                                              const unsigned short* __restrict__ Dh,
+                                              const unsigned short* __restrict__ Dl,
+                                              const unsigned short* __restrict__ Hth,
+                                              const unsigned short* __restrict__ Htl, int64_t d_out, int64_t ldp,
+                                              int G, int n_gt, int blk, int excl, float* __restrict__ C) {
+  const int k = gidx / n_gt, gt = gidx % n_gt;
   const int64_t m = d_out / G;
   const int64_t j0 = (int64_t)k * m + (int64_t)gt * kGemmRows, j_last = (int64_t)(k + 1) * m - 1;
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int wm = wave / 2, wn = wave % 2;
 
-  // contraction range of this part, in stages of 64
-  const int64_t n_stages = ldp / kGemmK;
-  const int64_t s0 = (int64_t)blockIdx.y * n_stages / gridDim.y, s1 = ((int64_t)blockIdx.y + 1) * n_stages / gridDim.y;
+  // contraction range of this part, in stages of 64; the excluded block's two stages are stepped over
+  const int64_t n_stages = ldp / kGemmK - 2;
+  const int64_t s0 = (int64_t)part * n_stages / n_parts, s1 = ((int64_t)part + 1) * n_stages / n_parts;
+  const int64_t skip_from = 2 * (int64_t)excl;
 
   // ---- staging: wave w copies operand w (0: delta hi, 1: delta lo, 2: Ht hi, 3: Ht lo); load
   // number i moves rows 8 i .. 8 i + 7, lane -> (row 8 i + lane / 8, position lane % 8)
@@ -192,7 +194,8 @@ __global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short
       const int c = (lane % 8) ^ ((r >> 1) & 7);
       int64_t row = row_first + r;
       row = row < row_last ? row : row_last;             // rows past the group: repeat its last row (never stored)
-      dma16(src + row * ldp + stage * kGemmK + 8 * c, smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
+      dma16(src + row * ldp + (stage < skip_from ? stage : stage + 2) * kGemmK + 8 * c,
+            smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
     }
   };
 
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(256) void cd_block_gemm_kernel(const unsigned short
       for (int r = 0; r < 16; ++r)
         out[wn * 64 + 32 * y + lane % 32][wm * 64 + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] = acc[x][y][r];
   __syncthreads();
-  float* Cp = C + (int64_t)blockIdx.y * kBlk * d_out;
+  float* Cp = C + (int64_t)part * kBlk * d_out;
   for (int idx = tid; idx < kBlk * kGemmRows; idx += 256) {
     const int i = idx / kGemmRows, r = idx % kGemmRows;
     const int64_t j = j0 + r;
@@ -283,20 +286,26 @@ template <int CTRL>
 __device__ inline int quad_dpp(int v) {
   return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
 }
+constexpr int kWalkTw = 0;                                              // byte offsets of the walk's LDS arrays
+constexpr int kWalkCur = kWalkTw + kBlk * (kRows + 1) * 4;
+constexpr int kWalkCoef = kWalkCur + kBlk * (kRows + 1) * 4;
+constexpr int kWalkCode = kWalkCoef + kBlk * kBlk * 4;
+constexpr int kWalkBytes = kWalkCode + kBlk * (kRows + 4);
+static_assert(kWalkCoef % 16 == 0, "the coefficient rows are read 16 bytes at a time");
 template <int LV>
-__global__ __launch_bounds__(256) void cd_block_seq_kernel(const float* __restrict__ C, int n_parts,
-                                                           const float* __restrict__ W, float* __restrict__ What,
-                                                           const float* __restrict__ codebook, int n_levels,
-                                                           const float* __restrict__ Cd, int64_t d_out, int64_t d,
-                                                           int64_t ld, int64_t ldp, int G, int n_rt, int blk,
-                                                           unsigned char* __restrict__ Q,
-                                                           unsigned short* __restrict__ Dh,
-                                                           unsigned short* __restrict__ Dl) {
-  __shared__ float tw[kBlk][kRows + 1];                    // the block of W; then the targets; then W again
-  __shared__ float cur[kBlk][kRows + 1];                   // the block of What, old values then new ones
-  __shared__ __attribute__((aligned(16))) float coef[kBlk][kBlk];   // coef[a][b] = Ht[i0 + b][i0 + a]
-  __shared__ unsigned char code[kBlk][kRows + 4];
-  const int k = blockIdx.x / n_rt, rt = blockIdx.x % n_rt;
+__device__ __forceinline__ void walk_body(char* smem, int tile, const float* __restrict__ C, int n_parts,
+                                          const float* __restrict__ W, float* __restrict__ What,
+                                          const float* __restrict__ codebook, int n_levels,
+                                          const float* __restrict__ Cd, const unsigned short* __restrict__ Hth,
+                                          const unsigned short* __restrict__ Htl, int64_t d_out, int64_t d,
+                                          int64_t ld, int64_t ldp, int G, int n_rt, int blk, int prev,
+                                          unsigned char* __restrict__ Q, unsigned short* __restrict__ Dh,
+                                          unsigned short* __restrict__ Dl) {
+  float (*tw)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkTw);      // the block of W; then the targets; then W again
+  float (*cur)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkCur);    // the block of What, old values then new ones
+  float (*coef)[kBlk] = reinterpret_cast<float (*)[kBlk]>(smem + kWalkCoef);            // coef[a][b] = Ht[i0 + b][i0 + a]
+  unsigned char (*code)[kRows + 4] = reinterpret_cast<unsigned char (*)[kRows + 4]>(smem + kWalkCode);
+  const int k = tile / n_rt, rt = tile % n_rt;
   const int64_t m = d_out / G;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int64_t j0 = (int64_t)k * m + (int64_t)rt * kRows, j_last = (int64_t)(k + 1) * m - 1;
@@ -304,6 +313,49 @@ __global__ __launch_bounds__(256) void cd_block_seq_kernel(const float* __restri
   const int64_t i0 = (int64_t)blk * kBlk;
   const int n_valid = (int)((d - i0) < kBlk ? (d - i0) : kBlk);   // coordinates of this block inside the matrix
 
+  // The share of block `prev` (final since the previous launch; the GEMM stepped over it):
+  //   near[j][i] = sum_{i' in prev} delta[j][i'] * Ht[i0 + i][i'],   64 channels x 128 coordinates x 128,
+  // on the matrix cores, wave w the coordinates 32 w .. 32 w + 31; fragments straight from global memory.
+  f32x16 near[2];
+  {
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) near[x][r] = 0.f;
+    const int64_t kcol = (int64_t)prev * kBlk + 8 * (lane / 32);
+    int64_t arow[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int r = 32 * x + lane % 32;
+      arow[x] = (r < n_rows ? j0 + r : j_last) * ldp + kcol;
+    }
+    const int64_t brow = (int64_t)k * ldp * ldp + (i0 + 32 * wave + lane % 32) * ldp + kcol;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {                  // 4 of the 8 contraction steps at a time: 24 loads in flight
+      u32x4 fa[4][2][2], fb[4][2];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int off = 16 * (4 * half + t);
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          fa[t][x][0] = *reinterpret_cast<const u32x4*>(Dh + arow[x] + off);
+          fa[t][x][1] = *reinterpret_cast<const u32x4*>(Dl + arow[x] + off);
+        }
+        fb[t][0] = *reinterpret_cast<const u32x4*>(Hth + brow + off);
+        fb[t][1] = *reinterpret_cast<const u32x4*>(Htl + brow + off);
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const bf16x8 ah = __builtin_bit_cast(bf16x8, fa[t][x][0]), al = __builtin_bit_cast(bf16x8, fa[t][x][1]);
+          const bf16x8 bh = __builtin_bit_cast(bf16x8, fb[t][0]), bl = __builtin_bit_cast(bf16x8, fb[t][1]);
+          near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, near[x], 0, 0, 0);
+          near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, near[x], 0, 0, 0);
+          near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, near[x], 0, 0, 0);
+        }
+    }
+  }
   {
     const f32x4* src = reinterpret_cast<const f32x4*>(Cd + (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk);
     f32x4* dst = reinterpret_cast<f32x4*>(&coef[0][0]);
@@ -354,6 +406,15 @@ __global__ __launch_bounds__(256) void cd_block_seq_kernel(const float* __restri
       for (int u = 0; u < 16; ++u) tw[ib + u][r] -= b[u];
     }
   }
+  __syncthreads();
+  // register r of lane l holds channel 8*(r/4)+4*(l/32)+(r%4) of a block of 32, coordinate l%32 of the wave's 32
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float v = near[x][r];
+      tw[32 * wave + lane % 32][32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] -= v;
+    }
   __syncthreads();
 
   // ---- the walk: channel ch of the tile, lane q of its quad ----------------------------------
@@ -467,6 +528,32 @@ __global__ __launch_bounds__(256) void cd_block_seq_kernel(const float* __restri
   }
 }
 
+// One launch per block: the first n_walk workgroups walk block `blk` (reading the partial sums in
+// Cin), the others compute the partial sums of block `next_blk` into Cout, stepping over the
+// contraction elements of `blk`, which change meanwhile.  The two halves share nothing but read-only
+// data, so the GEMM for the next block hides behind the latency-bound walk of this one.
+constexpr int kSmemBytes = (kWalkBytes > 2 * kGemmStage ? kWalkBytes : 2 * kGemmStage);
+template <int LV>
+__global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* __restrict__ Cin, int n_parts,
+                                                       const float* __restrict__ W, float* __restrict__ What,
+                                                       const float* __restrict__ codebook, int n_levels,
+                                                       const float* __restrict__ Cd,
+                                                       const unsigned short* __restrict__ Hth,
+                                                       const unsigned short* __restrict__ Htl, int64_t d_out,
+                                                       int64_t d, int64_t ld, int64_t ldp, int G, int n_rt, int n_gt,
+                                                       int blk, int prev, int next_blk, unsigned char* __restrict__ Q,
+                                                       unsigned short* __restrict__ Dh,
+                                                       unsigned short* __restrict__ Dl, float* __restrict__ Cout) {
+  __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
+  if ((int)blockIdx.x < n_walk) {
+    walk_body<LV>(smem, (int)blockIdx.x, Cin, n_parts, W, What, codebook, n_levels, Cd, Hth, Htl, d_out, d, ld, ldp, G,
+                  n_rt, blk, prev, Q, Dh, Dl);
+  } else {
+    const int g = (int)blockIdx.x - n_walk, n_tiles = n_gt * G;
+    gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, next_blk, blk, Cout);
+  }
+}
+
 struct Layout {
   int64_t ldp, n_blk;
   int n_rt, n_gt, n_parts;
@@ -479,9 +566,10 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   const int64_t m = d_out / G;
   L.n_rt = (int)((m + kRows - 1) / kRows);
   L.n_gt = (int)((m + kGemmRows - 1) / kGemmRows);
-  // enough GEMM workgroups to fill the chip, at least two 64-deep stages each
-  int parts = (int)(256 / ((int64_t)L.n_gt * G));
-  const int max_parts = (int)(L.ldp / kGemmK / 2);
+  // enough GEMM workgroups to fill the compute units the walk leaves free, at least two 64-deep stages each
+  const int64_t n_walk = (int64_t)L.n_rt * G;
+  int parts = (int)((n_walk < 192 ? 256 - n_walk : 64) / ((int64_t)L.n_gt * G));
+  const int max_parts = (int)((L.ldp / kGemmK - 2) / 2);
   if (parts > max_parts) parts = max_parts;
   if (parts > 16) parts = 16;
   if (parts < 1) parts = 1;
@@ -490,7 +578,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   L.ht_bytes = up((size_t)G * L.ldp * L.ldp * 2);
   L.cdt_bytes = up((size_t)G * L.n_blk * kBlk * kBlk * sizeof(float));
   L.delta_bytes = up((size_t)d_out * L.ldp * 2);
-  L.c_bytes = up((size_t)L.n_parts * kBlk * d_out * sizeof(float));
+  L.c_bytes = up((size_t)L.n_parts * kBlk * d_out * sizeof(float));   // one of the two buffers that alternate
   return L;
 }
 
@@ -498,7 +586,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
 
 size_t cd_workspace(int64_t d_out, int64_t d_in, int G) {
   const Layout L = make_layout(d_out, d_in, G);
-  return 2 * L.ht_bytes + L.cdt_bytes + 2 * L.delta_bytes + L.c_bytes;
+  return 2 * L.ht_bytes + L.cdt_bytes + 2 * L.delta_bytes + 2 * L.c_bytes;
 }
 
 namespace {
@@ -538,25 +626,31 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
       cd_delta_kernel<<<dim3((unsigned)bx, (unsigned)d_out), dim3(256), 0, st>>>(W, What, d_in, ld, L.ldp, Dh, Dl);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  const unsigned n_tiles = (unsigned)(L.n_rt * G);
-  for (int cycle = 0; cycle < n_cycles; ++cycle)
-    for (int blk = 0; blk < (int)L.n_blk; ++blk) {
-      cd_block_gemm_kernel<<<dim3((unsigned)(L.n_gt * G), (unsigned)L.n_parts), dim3(256), 0, st>>>(Dh, Dl, Hth, Htl, d_out, L.ldp, G, L.n_gt,
-                                                                                    blk, C);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-#define GQ_LAUNCH_SEQ(LV)                                                                                              \
-  cd_block_seq_kernel<LV><<<dim3(n_tiles), dim3(256), 0, st>>>(C, L.n_parts, W, What, codebook, n_levels, Cd, d_out,      \
-                                                                 d_in, ld, L.ldp, G, L.n_rt, blk, Q, Dh, Dl)
-      if (n_levels <= 4) {
-        GQ_LAUNCH_SEQ(4);
-      } else if (n_levels <= 8) {
-        GQ_LAUNCH_SEQ(8);
-      } else {
-        GQ_LAUNCH_SEQ(kMaxLevels);
-      }
-#undef GQ_LAUNCH_SEQ
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
+  float* Cbuf[2] = {C, (float*)((char*)C + L.c_bytes)};
+  const int n_walk = L.n_rt * G, n_gemm = L.n_gt * G * L.n_parts, n_blk = (int)L.n_blk;
+  const int64_t total = (int64_t)n_cycles * n_blk;
+#define GQ_LAUNCH_BLOCK(LV, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT)                                                    \
+  cd_block_kernel<LV><<<dim3((unsigned)(GRID)), dim3(256), 0, st>>>(NWALK, CIN, L.n_parts, W, What, codebook, n_levels,  \
+                                                                   Cd, Hth, Htl, d_out, d_in, ld, L.ldp, G, L.n_rt,     \
+                                                                   L.n_gt, BLK, PREV, NEXT, Q, Dh, Dl, COUT)
+#define GQ_LAUNCH_ANY(GRID, NWALK, CIN, BLK, PREV, NEXT, COUT)                                                          \
+  do {                                                                                                                  \
+    if (n_levels <= 4) GQ_LAUNCH_BLOCK(4, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT);                                     \
+    else if (n_levels <= 8) GQ_LAUNCH_BLOCK(8, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT);                                \
+    else GQ_LAUNCH_BLOCK(kMaxLevels, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT);                                          \
+  } while (0)
+  // the partial sums of block 0 first (its predecessor in the cycle, the last block, stepped over) ...
+  GQ_LAUNCH_ANY(n_gemm, 0, Cbuf[1], n_blk - 1, 0, 0, Cbuf[0]);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // ... then one launch per block: its walk, and beside it the partial sums of the next block
+  for (int64_t t = 0; t < total; ++t) {
+    const int blk = (int)(t % n_blk), prev = (blk + n_blk - 1) % n_blk, next = (blk + 1) % n_blk;
+    const bool more = t + 1 < total;
+    GQ_LAUNCH_ANY(n_walk + (more ? n_gemm : 0), n_walk, Cbuf[t & 1], blk, prev, next, Cbuf[(t + 1) & 1]);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+#undef GQ_LAUNCH_ANY
+#undef GQ_LAUNCH_BLOCK
   return hipSuccess;
 }
 }  // namespace

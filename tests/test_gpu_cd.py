@@ -52,6 +52,7 @@ def _check_cycle(Wn, old, new, Qg, Cn, Hn, G, what):
     (400, 200, 96, 4, 2, 208),          # ragged last block, 24 channels per group, padded pitch
     (600, 384, 192, 1, 4, None),        # 16 grid points, three row tiles
     (300, 132, 40, 2, 3, 136),          # last block of 4 coordinates
+    (256, 96, 64, 2, 3, None),          # a single, ragged block: its predecessor in the cycle is itself
 ])
 def test_cd_one_cycle_decisions_are_valid_and_match_the_oracle(n, d_in, d_out, G, bits, ld):
     say(f"cd n={n} d_in={d_in} d_out={d_out} G={G} bits={bits} ld={ld}")
@@ -71,8 +72,9 @@ def test_cd_one_cycle_decisions_are_valid_and_match_the_oracle(n, d_in, d_out, G
     assert np.all(og <= o0 * (1 + 1e-9)) and np.all(np.abs(og - oo) <= 1e-3 * oo)
 
 
-def test_cd_cycles_in_one_call_equal_chained_calls_and_descend_to_the_oracle_level():
-    W, What, C, H = _case(512, 256, 128, 2, 3, 77)
+@pytest.mark.parametrize("d_in", [256, 96])
+def test_cd_cycles_in_one_call_equal_chained_calls_and_descend_to_the_oracle_level(d_in):
+    W, What, C, H = _case(512, d_in, 128, 2, 3, 77)
     Wn, Cn, Hn = to_np64(W), to_np64(C), to_np64(H)
     chained = What.clone()
     prev = oracle.objective(Wn, to_np64(chained), Hn, 2)[0]

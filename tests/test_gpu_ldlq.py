@@ -34,6 +34,7 @@ def _hessian(n, d_in, d_out, G, seed):
     (400, 200, 96, 4, 2, 208),          # ragged last block, padded pitch
     (600, 384, 192, 1, 4, None),        # 16 grid points, three blocks
     (300, 132, 40, 2, 3, 136),          # last block of 4 coordinates
+    (256, 96, 64, 2, 3, None),          # a single, ragged block
 ])
 def test_sequential_rounding_decisions_are_valid_and_match_the_oracle(n, d_in, d_out, G, bits, ld):
     say(f"ldlq n={n} d_in={d_in} d_out={d_out} G={G} bits={bits} ld={ld}")

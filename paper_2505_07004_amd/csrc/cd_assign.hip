@@ -10,10 +10,12 @@
 // The coordinates are processed in blocks of 128.  For a block, one GEMM gives
 //     B0[j][i] = sum_{i'} delta[j][i'] * Ht[i][i']            (all i', current delta)
 // for its 128 coordinates at once (bf16 matrix cores at fp32-grade accuracy: both operands
-// split into hi + lo bf16 terms, three products), and a second kernel walks the block
+// split into hi + lo bf16 terms, three products), and a walk goes through the block
 // sequentially, four lanes per channel: after coordinate i changes by eps, the targets of the
 // later coordinates i'' of the block move by -eps * Ht[i''][i].  The block's new delta is
-// written back (split) for the next block's GEMM.
+// written back (split) for the later GEMMs.  The GEMM of block b + 1 runs in the same launch as
+// the walk of block b (other workgroups) and leaves out block b's 128 contraction elements; the
+// walk of b + 1 adds their share itself.
 // Compared with Algorithm 4 the bookkeeping differs (the part of the sum that lies outside
 // the block is recomputed per block from the current weights instead of being carried along
 // and corrected after each block; the flop count is the same), the update rule does not.

@@ -214,17 +214,24 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(float* __restrict__ Uw,
     }
 }
 
-// (3) Trailing update: for the 128 x 128 tiles (ti <= tj) of the upper triangle right of and below
-// the block row,  A22[a][b] -= sum_{k < 128} U12[k][a] * U12[k][b].  4 waves of 64 x 64; the rows of
-// U12 are staged through LDS as they lie in memory, 16 at a time; the operand layout of the fp32
-// MFMA (lane -> column l%32, row l/32) reads that tile row-wise.
+// (3) Trailing update: for 128 x 128 tiles (ti <= tj) of the upper triangle with origin t0,
+//   A[a][b] -= sum_{k < 16 n_steps} U[r0 + k][a] * U[r0 + k][b].
+// Block rows are processed in pairs: after the first of a pair only the strip of the second one is
+// updated (strip = 1: the tiles of the first tile row, 128 rows of U), after the second everything
+// behind the pair with the 256 rows of both at once, which halves the read-modify-write traffic of the
+// trailing matrix.  4 waves of 64 x 64; the rows of U are staged through LDS as they lie in memory,
+// 16 at a time; the operand layout of the fp32 MFMA (lane -> column l%32, row l/32) reads that tile
+// row-wise.
 constexpr int kStep = 16;
+constexpr int kBufferWord3 = 0x00020000;       // raw buffer, 32-bit elements
+constexpr unsigned kBufferOutside = 0x7ffffff0u;
 constexpr int kSPitch = kNb + 32;    // floats; keeps the two rows of one MFMA read on disjoint banks
 
 __device__ inline f32x4 load4(const float* __restrict__ p, int64_t c, int64_t d, bool vec) {
   f32x4 v = {0.f, 0.f, 0.f, 0.f};
-  if (vec && c + 4 <= d) {
-    v = *reinterpret_cast<const f32x4*>(p);
+  if (vec) {                                                // d % 4 == 0: a group of four is inside or outside as a whole
+    const f32x4 w = *reinterpret_cast<const f32x4*>(c < d ? p : p - c);   // outside: the row's first four, not used
+    if (c < d) v = w;
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
@@ -233,14 +240,14 @@ __device__ inline f32x4 load4(const float* __restrict__ p, int64_t c, int64_t d,
   return v;
 }
 
-__global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
+__global__ __launch_bounds__(256, 3) void chol_syrk_kernel(float* __restrict__ Uw, int64_t d, int64_t r0, int n_steps,
+                                                        int64_t t0, int strip) {
   __shared__ __attribute__((aligned(16))) float As[2][kStep][kSPitch];
   __shared__ __attribute__((aligned(16))) float Bs[2][kStep][kSPitch];
   const int k = blockIdx.y;
   float* Uk = Uw + (int64_t)k * d * d;
-  int ti, tj;
-  tri_decode(blockIdx.x, ti, tj);                            // ti <= tj
-  const int64_t t0 = r0 + kNb;                               // first trailing row / column
+  int ti = 0, tj = (int)blockIdx.x;                          // strip: the first tile row only
+  if (!strip) tri_decode(blockIdx.x, ti, tj);                // ti <= tj
   const int64_t a0 = t0 + (int64_t)ti * kNb, b0 = t0 + (int64_t)tj * kNb;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int wm = wave / 2, wn = wave % 2;
@@ -255,29 +262,29 @@ __global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  f32x4 ra[2], rb[2];
-  auto fetch = [&](int step) {
+  // Two register sets: the rows of step s are fetched during step s - 2 and stashed at the end of step
+  // s - 1, so a load has a whole step of MFMAs (and the barrier) to arrive.  n_steps is even.
+  struct Regs {
+    f32x4 a[2], b[2];
+  } set0, set1;
+  auto fetch = [&](int step, Regs& rg) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const float* row = Uk + (r0 + step * kStep + lrow + 8 * h) * d;
-      ra[h] = load4(row + a0 + lcol, a0 + lcol, d, vec);
-      rb[h] = load4(row + b0 + lcol, b0 + lcol, d, vec);
+      rg.a[h] = load4(row + a0 + lcol, a0 + lcol, d, vec);
+      rg.b[h] = load4(row + b0 + lcol, b0 + lcol, d, vec);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](int buf, const Regs& rg) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      *reinterpret_cast<f32x4*>(&As[buf][lrow + 8 * h][lcol]) = ra[h];
-      *reinterpret_cast<f32x4*>(&Bs[buf][lrow + 8 * h][lcol]) = rb[h];
+      *reinterpret_cast<f32x4*>(&As[buf][lrow + 8 * h][lcol]) = rg.a[h];
+      *reinterpret_cast<f32x4*>(&Bs[buf][lrow + 8 * h][lcol]) = rg.b[h];
     }
   };
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  constexpr int kSteps = kNb / kStep;
-  for (int step = 0; step < kSteps; ++step) {
+  auto one_step = [&](int step, Regs& mine, const Regs& next) {   // mine: held step `step`, free again; next: step + 1
     const int buf = step & 1;
-    if (step + 1 < kSteps) fetch(step + 1);
+    if (step + 2 < n_steps) fetch(step + 2, mine);
 #pragma unroll
     for (int kk = 0; kk < kStep; kk += 2) {
       float av[2], bv[2];
@@ -291,25 +298,51 @@ __global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, 
         for (int y = 0; y < 2; ++y)
           acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
     }
-    if (step + 1 < kSteps) stash(buf ^ 1);
+    if (step + 1 < n_steps) stash(buf ^ 1, next);
     __syncthreads();
+  };
+  fetch(0, set0);
+  fetch(1, set1);
+  stash(0, set0);
+  __syncthreads();
+  for (int step = 0; step < n_steps; step += 2) {
+    one_step(step, set0, set1);
+    one_step(step + 1, set1, set0);
   }
-  // accumulator register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32
+  // accumulator register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32.
+  // Straight-line code with every lane active: the trailing matrix is addressed through a buffer
+  // resource that spans the valid rows of this wave's 64-row block; an entry below the diagonal or
+  // right of column d gets an offset outside it (such a load returns 0, such a store is dropped).
+  // 32 loads are in flight together, then updated and stored.
+  const int64_t row_w = a0 + wm * 64;
+  const int64_t rows_valid = (d - row_w) < 64 ? (d - row_w) : 64;
+  const int records = rows_valid > 0 ? (int)(rows_valid * d * (int64_t)sizeof(float)) : 0;
+  const __amdgpu_buffer_rsrc_t res =
+      __builtin_amdgcn_make_buffer_rsrc(Uk + (rows_valid > 0 ? row_w : 0) * d, 0, records, kBufferWord3);
+  const unsigned dbytes = (unsigned)(d * (int64_t)sizeof(float));
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < 2; ++x) {
+    float old[2][16];
+    unsigned off[2][16];
 #pragma unroll
     for (int y = 0; y < 2; ++y) {
       const int64_t col = b0 + wn * 64 + y * 32 + lane % 32;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t row = a0 + wm * 64 + x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-        if (row < d && col < d && row <= col) {
-          float* p = Uk + row * d + col;
-          const float val = acc[x][y][r];
-          *p -= val;
-        }
+        const int lr = x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        const bool keep = (row_w + lr < d) & (col < d) & (row_w + lr <= col);
+        off[y][r] = keep ? (unsigned)lr * dbytes + (unsigned)(col * (int64_t)sizeof(float)) : kBufferOutside;
+        old[y][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(res, off[y][r], 0, 0));
       }
     }
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float val = acc[x][y][r];
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, old[y][r] - val), res, off[y][r], 0, 0);
+      }
+  }
 }
 
 // The factor in the requested form, every entry of F written: L[i][j] = U[j][i] (i >= j), zeros above
@@ -364,15 +397,24 @@ hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_
   const unsigned t64 = (unsigned)((d + 63) / 64);
   chol_load_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d, reverse ? 1 : 0, eps, Uw);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  for (int64_t r0 = 0; r0 < d; r0 += kNb) {
+  for (int64_t r0 = 0; r0 < d; r0 += 2 * kNb) {              // a pair of block rows per turn
     chol_diag_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, info);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const int64_t trail = d - (r0 + kNb);
+    const int64_t t0 = r0 + kNb, trail = d - t0;
     if (trail <= 0) break;
     const int64_t tt = (trail + kNb - 1) / kNb;
     chol_panel_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    chol_syrk_kernel<<<dim3((unsigned)tri_count(tt), (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0);
+    chol_syrk_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, kNb / kStep, t0, 1);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    chol_diag_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(Uw, d, t0, info);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int64_t t1 = t0 + kNb, trail1 = d - t1;
+    if (trail1 <= 0) break;
+    const int64_t tt1 = (trail1 + kNb - 1) / kNb;
+    chol_panel_kernel<<<dim3((unsigned)tt1, (unsigned)G), dim3(256), 0, st>>>(Uw, d, t0);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, 2 * kNb / kStep, t1, 0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, d, reverse ? 1 : 0, F);

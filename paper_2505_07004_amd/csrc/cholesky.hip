@@ -9,7 +9,7 @@
 // of 128 in fp32:  A' = A gives L = U^T;  A'[a][b] = A[d-1-a][d-1-b] gives R[i][j] = U[d-1-j][d-1-i].
 // Per block row:  (1) the 128 x 128 diagonal block is factored by one workgroup per group;
 // (2) the panel to its right is solved against it, U12 = U11^-T A12 (both with the block in registers,
-// 8 x 8 per thread, rows published through LDS, one barrier per row);
+// 8 x 8 per thread, eight rows at a time published through LDS);
 // (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the fp32 matrix cores
 // (v_mfma_f32_32x32x2_f32), rows of U12 staged through LDS as they lie in memory.
 // Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its
@@ -79,16 +79,20 @@ __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict_
   }
 }
 
-// (1) The diagonal block at (r0, r0): A11 = U11^T U11, row by row, the block held in registers:
-// thread (tr, tc) of 16 x 16 owns the 8 x 8 tile at rows 8 tr, columns 8 tc.  At step j the owners
-// of row j publish it (unscaled) in LDS; after ONE barrier (two row buffers alternate) everyone
-// reads the pivot, its 8 row entries and 8 column entries and updates its tile,
-//   a[r][c] -= (a[j][r] / a[j][j]) * a[j][c]   for r > j,
-// while the owners turn their copy of row j into U[j][:] = a[j][:] / sqrt(a[j][j]).
+// (1) The diagonal block at (r0, r0): A11 = U11^T U11 with the block in registers: thread (tr, tc) of
+// 16 x 16 owns the 8 x 8 tile at rows 8 tr, columns 8 tc.  Eight rows at a time:
+//   a. the thread of the diagonal tile factors its tile on its own (eight pivots, no barrier) and
+//      publishes the 8 x 8 factor;
+//   b. the other owners of these eight rows solve their tiles against it (forward substitution, eight
+//      steps, no barrier) and publish the finished rows of U;
+//   c. every tile further down subtracts the product of its eight row entries and eight column entries
+//      (a rank-8 update).
+// Two barriers per eight rows (the published data alternate between two buffers).
 // Rows and columns past the end of the matrix are those of the identity.
 __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, int64_t d, int64_t r0,
                                                         int* __restrict__ info) {
-  __shared__ __attribute__((aligned(16))) float rowbuf[2][kNb];
+  __shared__ __attribute__((aligned(16))) float dtile[2][8][8];
+  __shared__ __attribute__((aligned(16))) float rows[2][8][kNb];
   __shared__ int bad;
   const int k = blockIdx.x;
   float* Uk = Uw + (int64_t)k * d * d;
@@ -105,35 +109,65 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, 
       const float v = Uk[in ? gr * d + gc : 0];
       a[i][l] = in ? v : (r == c ? 1.f : 0.f);
     }
+  __syncthreads();
   for (int jb = 0; jb < 16; ++jb) {
+    const int buf = jb & 1;
+    if (tr == jb && tc == jb) {                               // a. the diagonal tile
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int j = 8 * jb + jj, buf = j & 1;
-      if (tr == jb) {
+      for (int jj = 0; jj < 8; ++jj) {
+        float p = a[jj][jj];
+        const bool ok = p > 0.f;                              // false for NaN as well
+        if (!ok && bad < 0) bad = 8 * jb + jj;
+        p = ok ? p : 1.f;
+        const float sp = __builtin_amdgcn_sqrtf(p), isp = __builtin_amdgcn_rcpf(sp);
+        a[jj][jj] = sp;
 #pragma unroll
-        for (int l = 0; l < 8; ++l) rowbuf[buf][8 * tc + l] = a[jj][l];
+        for (int l = jj + 1; l < 8; ++l) a[jj][l] *= isp;
+#pragma unroll
+        for (int i = jj + 1; i < 8; ++i)
+#pragma unroll
+          for (int l = i; l < 8; ++l) a[i][l] -= a[jj][i] * a[jj][l];
       }
-      __syncthreads();
-      float p = rowbuf[buf][j];
-      const bool ok = p > 0.f;                              // false for NaN as well
-      if (!ok && tr == jb && tc == jb && bad < 0) bad = j;
-      p = ok ? p : 1.f;
-      if (tr >= jb && tc >= tr) {
-        const float ip = __builtin_amdgcn_rcpf(p);             // 1 ulp; the step's critical path
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+          const float v = l >= i ? a[i][l] : 0.f;
+          dtile[buf][i][l] = v;
+          rows[buf][i][8 * tc + l] = v;
+        }
+    }
+    __syncthreads();
+    if (tr == jb && tc > jb) {                                // b. the rest of the eight rows: U_dd^T X = A
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+        const float rp = __builtin_amdgcn_rcpf(dtile[buf][jj][jj]);
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+          float v = a[jj][l];
+#pragma unroll
+          for (int i = 0; i < jj; ++i) v -= dtile[buf][i][jj] * a[i][l];
+          a[jj][l] = v * rp;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int l = 0; l < 8; ++l) rows[buf][i][8 * tc + l] = a[i][l];
+    }
+    __syncthreads();
+    if (tr > jb && tc >= tr) {                                // c. rank-8 update of everything further down
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
         float f[8], cl[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = (8 * tr + i > j) ? rowbuf[buf][8 * tr + i] * ip : 0.f;
+        for (int i = 0; i < 8; ++i) f[i] = rows[buf][jj][8 * tr + i];
 #pragma unroll
-        for (int l = 0; l < 8; ++l) cl[l] = rowbuf[buf][8 * tc + l];
+        for (int l = 0; l < 8; ++l) cl[l] = rows[buf][jj][8 * tc + l];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
           for (int l = 0; l < 8; ++l) a[i][l] -= f[i] * cl[l];
-        if (tr == jb) {                                     // f[jj] was 0: row j is untouched; make it the row of U
-          const float sp = __builtin_amdgcn_sqrtf(p), isp = __builtin_amdgcn_rcpf(sp);
-#pragma unroll
-          for (int l = 0; l < 8; ++l) a[jj][l] = (8 * tc + l == j) ? sp : cl[l] * isp;
-        }
       }
     }
   }
@@ -151,13 +185,14 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, 
 
 // (2) The panel right of the diagonal block: U11^T X = A12, 128 columns per workgroup, forward
 // substitution with the 128 x 128 tile of A12 in registers (thread (tk, tc) owns rows 8 tk, columns
-// 8 tc) and U11 in LDS.  At step k the owners of row k divide it by U11[k][k] and publish it; after one
-// barrier every row i > k loses U11[k][i] * x[k][:].
+// 8 tc) and U11 in LDS.  Eight rows at a time: their owners solve against the 8 x 8 diagonal tile of
+// U11 on their own and publish the finished rows; after one barrier every tile further down loses the
+// product of the matching 8 x 8 tile of U11 and those rows.
 constexpr int kUPitch = kNb + 4;     // floats: rows 16-byte aligned for the four-float reads
 
 __global__ __launch_bounds__(256) void chol_panel_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
   __shared__ __attribute__((aligned(16))) float u[kNb][kUPitch];
-  __shared__ __attribute__((aligned(16))) float rowbuf[2][kNb];
+  __shared__ __attribute__((aligned(16))) float rows[2][8][kNb];
   __shared__ float rdiag[kNb];
   const int k = blockIdx.y;
   float* Uk = Uw + (int64_t)k * d * d;
@@ -180,24 +215,33 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(float* __restrict__ Uw,
     }
   __syncthreads();
   for (int kb = 0; kb < 16; ++kb) {
+    const int buf = kb & 1;
+    if (tk == kb) {
 #pragma unroll
-    for (int kj = 0; kj < 8; ++kj) {
-      const int kk = 8 * kb + kj, buf = kk & 1;
-      if (tk == kb) {
-        const float rp = rdiag[kk];
+      for (int jj = 0; jj < 8; ++jj) {
+        const float rp = rdiag[8 * kb + jj];
 #pragma unroll
         for (int l = 0; l < 8; ++l) {
-          x[kj][l] = x[kj][l] * rp;
-          rowbuf[buf][8 * tc + l] = x[kj][l];
+          float v = x[jj][l];
+#pragma unroll
+          for (int i = 0; i < jj; ++i) v -= u[8 * kb + i][8 * kb + jj] * x[i][l];
+          x[jj][l] = v * rp;
         }
       }
-      __syncthreads();
-      if (tk >= kb) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int l = 0; l < 8; ++l) rows[buf][i][8 * tc + l] = x[i][l];
+    }
+    __syncthreads();
+    if (tk > kb) {
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
         float f[8], xr[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = (8 * tk + i > kk) ? u[kk][8 * tk + i] : 0.f;
+        for (int i = 0; i < 8; ++i) f[i] = u[8 * kb + jj][8 * tk + i];
 #pragma unroll
-        for (int l = 0; l < 8; ++l) xr[l] = rowbuf[buf][8 * tc + l];
+        for (int l = 0; l < 8; ++l) xr[l] = rows[buf][jj][8 * tc + l];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll

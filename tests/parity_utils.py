@@ -201,7 +201,7 @@ def check_codebook_channels(oracle, Wn, Qn, Hk, Cg, m, lam, what):
         o_g, o_o = e_g @ Hk @ e_g, e_o @ Hk @ e_o
         worst_obj = max(worst_obj, float((o_g - o_o) / o_o))
         cond = np.linalg.cond(A[np.ix_(used, used)])
-        fwd = float(np.max(np.abs(c - Co[j])) / np.max(np.abs(Co[j])))
+        fwd = float(np.max(np.abs(c - Co[j])) / max(np.max(np.abs(Co[j])), np.max(np.abs(Wn[j]))))   # on the scale of the weights
         worst_fwd = max(worst_fwd, fwd / cond)
     say(f"{what}: backward error {worst_back:.2e} (bound 9.5e-07), objective above the minimum by {worst_obj:.2e} (rel), "
         f"grid error / condition number {worst_fwd:.2e}")

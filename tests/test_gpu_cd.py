@@ -153,3 +153,28 @@ def test_cd_at_the_llama2_7b_shape_on_sampled_channels():
         say(f"  group {k}: 4 channels, codes that differ from the oracle's {100 * differ:.2f} %; "
             f"objective start {o_start.sum():.5f}, gpu {o_gpu.sum():.5f}, oracle {o_ref.sum():.5f}")
         assert np.all(o_gpu < o_start) and abs(o_gpu.sum() - o_ref.sum()) <= 1e-2 * o_ref.sum()
+
+
+@pytest.mark.parametrize("m", [1, 3, 5, 11])
+def test_cd_with_a_number_of_grid_points_that_is_not_a_power_of_two(m):
+    d_out, d_in, G = 80, 200, 2
+    X = wl.make_x_outlier(400, d_in, 3, 20.0, 19, DEV, torch.float32)
+    H = gq.gq_fisher_gram(X, gq.gq_group_weights(wl.make_dz(400, d_out, 1.0, 1.5, 20, DEV), G), mirror=True)
+    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+    W = wl.make_w(d_out, d_in, 21, DEV)
+    g = torch.Generator(device="cpu").manual_seed(22 + m)
+    C = (0.05 * torch.randn(d_out, m, generator=g)).to(DEV).contiguous()      # grids in no particular order
+    What = torch.gather(C, 1, torch.randint(0, m, (d_out, d_in), generator=g).to(DEV))
+    Wn, old, Cn, Hn = to_np64(W), to_np64(What), to_np64(C), to_np64(H)
+    Qg = gq.gq_cd_assign(W, What, C, H, n_cycles=1)
+    torch.cuda.synchronize()
+    new, Qg = to_np64(What), Qg.cpu().numpy()
+    assert Qg.max() < m
+    T, S = cd_targets_along(Wn, old, new, Hn, G)
+    dist = np.abs(Cn[:, None, :] - T[:, :, None])
+    chosen = np.take_along_axis(dist, Qg[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    slack = 2.0 ** -14 * S + 2.0 ** -20 * np.abs(T)
+    assert np.all(chosen - dist.min(axis=2) <= 2 * slack)                     # the nearest point up to the arithmetic's slack
+    assert np.array_equal(new, np.take_along_axis(Cn, Qg.astype(np.int64), axis=1))
+    o0, o1 = oracle.objective(Wn, old, Hn, G)[0], oracle.objective(Wn, new, Hn, G)[0]
+    assert np.all(o1 <= o0 * (1 + 1e-9))

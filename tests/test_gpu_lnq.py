@@ -131,3 +131,24 @@ def test_codebook_step_at_the_llama2_7b_shape_on_sampled_channels():
             check_codebook_channels(oracle, to_np64(W[rows]), Q[rows].cpu().numpy().astype(np.int64), to_np64(H[k]), to_np64(C[rows]),
                             m, LAM, f"  group {k}, 12 sampled channels")
         del What, C, What0, C0, Q
+
+
+@pytest.mark.parametrize("m", [1, 3, 5, 11])
+def test_codebook_step_with_a_number_of_grid_points_that_is_not_a_power_of_two(m):
+    """Whole channels per workgroup tile: 256 // m of them (at most 64), so tiles end inside a row block."""
+    d_out, d_in, G = 140, 200, 2                                         # 70 channels per group: two tiles for m = 5, 11
+    X = wl.make_x_outlier(400, d_in, 3, 20.0, 9, DEV, torch.float32)
+    H = gq.gq_fisher_gram(X, gq.gq_group_weights(wl.make_dz(400, d_out, 1.0, 1.5, 10, DEV), G), mirror=True)
+    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+    W = wl.make_w(d_out, d_in, 11, DEV)
+    g = torch.Generator(device="cpu").manual_seed(12 + m)
+    Q = torch.randint(0, m, (d_out, d_in), generator=g, dtype=torch.uint8).to(DEV)
+    What = torch.empty_like(W)
+    C = gq.gq_lnq_codebook(W, Q, H, m, LAM, What=What)
+    torch.cuda.synchronize()
+    assert C.shape == (d_out, m) and torch.equal(What, torch.gather(C, 1, Q.long()))
+    Wn, Qn, Hn, Cg = to_np64(W), Q.cpu().numpy().astype(np.int64), to_np64(H), to_np64(C)
+    per = d_out // G
+    for k in range(G):
+        r = slice(k * per, (k + 1) * per)
+        check_codebook_channels(oracle, Wn[r], Qn[r], Hn[k], Cg[r], m, LAM, f"{m} grid points, group {k}")

@@ -432,60 +432,68 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   }
 
   for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
-    float own[8], eps[kRun];
+    // Coordinates past the end of the matrix (last block only) are walked like the others: their
+    // coefficients are zero, so nothing they do reaches a real coordinate, and they are not stored.
+    float own[8], eps[kRun], was[kRun];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) own[kk] = tw[c0 + 8 * q + kk][ch];
 #pragma unroll
+    for (int ii = 0; ii < kRun; ++ii) was[ii] = cur[c0 + ii][ch];   // the old values, off the chain of decisions
+    // the coefficients of a coordinate are read one coordinate ahead, before this one's LDS stores
+    const f32x4* row0 = reinterpret_cast<const f32x4*>(&coef[c0][c0 + 8 * q]);   // Ht[c0 + 8q + kk][c0 + ii] over kk
+    f32x4 n_lo = row0[0], n_hi = row0[1];
+#pragma unroll
     for (int ii = 0; ii < kRun; ++ii) {
-      eps[ii] = 0.f;
-      if (c0 + ii < n_valid) {                              // uniform
-        constexpr int kBroadcast[4] = {0x00, 0x55, 0xAA, 0xFF};
-        float ti;                                           // target of coordinate c0 + ii: lane ii / 8 of the quad owns it
-        switch (ii / 8) {
-          case 0: ti = quad_dpp<kBroadcast[0]>(own[ii % 8]); break;
-          case 1: ti = quad_dpp<kBroadcast[1]>(own[ii % 8]); break;
-          case 2: ti = quad_dpp<kBroadcast[2]>(own[ii % 8]); break;
-          default: ti = quad_dpp<kBroadcast[3]>(own[ii % 8]); break;
-        }
-        // this lane's quarter of the grid (levels q, q + 4, ...: increasing, so '<' keeps the lower index)
-        float best = usable[0] ? fabsf(grid[0] - ti) : __builtin_inff(), val = grid[0];
-        int bq = q;
+      const f32x4 c_lo = n_lo, c_hi = n_hi;
+      if (ii + 1 < kRun) {
+        const f32x4* row = reinterpret_cast<const f32x4*>(&coef[c0 + ii + 1][c0 + 8 * q]);
+        n_lo = row[0];
+        n_hi = row[1];
+      }
+      constexpr int kBroadcast[4] = {0x00, 0x55, 0xAA, 0xFF};
+      float ti;                                             // target of coordinate c0 + ii: lane ii / 8 of the quad owns it
+      switch (ii / 8) {
+        case 0: ti = quad_dpp<kBroadcast[0]>(own[ii % 8]); break;
+        case 1: ti = quad_dpp<kBroadcast[1]>(own[ii % 8]); break;
+        case 2: ti = quad_dpp<kBroadcast[2]>(own[ii % 8]); break;
+        default: ti = quad_dpp<kBroadcast[3]>(own[ii % 8]); break;
+      }
+      // this lane's quarter of the grid (levels q, q + 4, ...: increasing, so '<' keeps the lower index)
+      float best = usable[0] ? fabsf(grid[0] - ti) : __builtin_inff(), val = grid[0];
+      int bq = q;
 #pragma unroll
-        for (int u = 1; u < LV / 4; ++u) {
-          const float dist = fabsf(grid[u] - ti);
-          const bool better = usable[u] && (dist < best);
-          best = better ? dist : best;
-          val = better ? grid[u] : val;
-          bq = better ? q + 4 * u : bq;
-        }
-        // settle it inside the quad: nearest point, lowest index among equally near ones
-        {
-          const float ob = quad_dpp<kQuadSwap1>(best), ov = quad_dpp<kQuadSwap1>(val);
-          const int oq = quad_dpp<kQuadSwap1>(bq);
-          const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
-          best = take ? ob : best;
-          val = take ? ov : val;
-          bq = take ? oq : bq;
-        }
-        {
-          const float ob = quad_dpp<kQuadSwap2>(best), ov = quad_dpp<kQuadSwap2>(val);
-          const int oq = quad_dpp<kQuadSwap2>(bq);
-          const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
-          best = take ? ob : best;
-          val = take ? ov : val;
-          bq = take ? oq : bq;
-        }
-        const float e = val - cur[c0 + ii][ch];
-        cur[c0 + ii][ch] = val;                             // all four lanes of the quad store the same value
-        code[c0 + ii][ch] = (unsigned char)bq;
-        eps[ii] = e;
-        const f32x4* row = reinterpret_cast<const f32x4*>(&coef[c0 + ii][c0 + 8 * q]);   // Ht[c0 + 8q + kk][c0 + ii] over kk
-        const f32x4 c_lo = row[0], c_hi = row[1];
+      for (int u = 1; u < LV / 4; ++u) {
+        const float dist = fabsf(grid[u] - ti);
+        const bool better = usable[u] && (dist < best);
+        best = better ? dist : best;
+        val = better ? grid[u] : val;
+        bq = better ? q + 4 * u : bq;
+      }
+      // settle it inside the quad: nearest point, lowest index among equally near ones
+      {
+        const float ob = quad_dpp<kQuadSwap1>(best), ov = quad_dpp<kQuadSwap1>(val);
+        const int oq = quad_dpp<kQuadSwap1>(bq);
+        const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
+        best = take ? ob : best;
+        val = take ? ov : val;
+        bq = take ? oq : bq;
+      }
+      {
+        const float ob = quad_dpp<kQuadSwap2>(best), ov = quad_dpp<kQuadSwap2>(val);
+        const int oq = quad_dpp<kQuadSwap2>(bq);
+        const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
+        best = take ? ob : best;
+        val = take ? ov : val;
+        bq = take ? oq : bq;
+      }
+      const float e = val - was[ii];
+      cur[c0 + ii][ch] = val;                               // all four lanes of the quad store the same value
+      code[c0 + ii][ch] = (unsigned char)bq;
+      eps[ii] = e;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          own[kk] -= e * c_lo[kk];                          // (targets already used are corrected too: harmless)
-          own[4 + kk] -= e * c_hi[kk];
-        }
+      for (int kk = 0; kk < 4; ++kk) {
+        own[kk] -= e * c_lo[kk];                            // (targets already used are corrected too: harmless)
+        own[4 + kk] -= e * c_hi[kk];
       }
     }
     for (int c1 = c0 + kRun; c1 < n_valid; c1 += kRun) {    // the targets after the run, a run at a time

@@ -276,7 +276,10 @@ def main():
         result["sequential_rounding"] = {
             "cholesky_ms": chol_ms, "ldlq_assign_ms": seq_ms, "levels": 8, "info": [int(v) for v in info.tolist()],
             "objective_plain_rounding": [float(v) for v in o_before.tolist()],
-            "objective_after": [float(v) for v in o_seq.tolist()],
+            "objective_after": [float(v) for v in o_seq.tolist()] if not any(info.tolist()) else None,
+            "note": None if not any(info.tolist()) else
+                    "the bf16-path H is not positive definite at 1 % damping for this shape (one operand of every product "
+                    "is rounded): the factor is invalid, only the times are meaningful; use the fp32 Gram path or more damping",
             "roofline": {"bound": "mfma", "kernel": "cholesky (fp32)", "achieved": chol_fl / (chol_ms * 1e-3) / 1e12,
                          "peak": 157.3, "unit": "TFLOP/s", "frac": chol_fl / (chol_ms * 1e-3) / 1e12 / 157.3, "traffic": None,
                          "note": "fp32 matrix-core peak; the 128 sequential pivots of every diagonal block and panel "

@@ -60,7 +60,8 @@ typedef enum {
 /* flags of gq_fisher_gram */
 enum {
   GQ_ACCUMULATE = 1u << 0, /* H += ... ; without it the upper triangle of H is overwritten */
-  GQ_MIRROR = 1u << 1      /* after the update also fill the strictly lower triangle       */
+  GQ_MIRROR = 1u << 1,     /* after the update also fill the strictly lower triangle       */
+  GQ_TWO_TERMS = 1u << 2   /* GQ_BF16 only: carry the scaled operand as two bf16 terms     */
 };
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -125,7 +126,12 @@ size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in,
  *          other the raw X[i,b]; fp32 accumulation.  The result is symmetric once
  *          mirrored, but positive semidefinite only up to that rounding (about
  *          5e-4 of its largest eigenvalue): damp accordingly before factoring it,
- *          or use GQ_F32.
+ *          or use GQ_TWO_TERMS or GQ_F32.
+ *          GQ_TWO_TERMS (with GQ_BF16; ignored with GQ_F32): the scaled operand is
+ *          carried as hi + lo, hi = bf16_rne(s*x), lo = bf16_rne(s*x - hi), two
+ *          matrix-core products per pair: twice the work of the one-term path, every
+ *          product exact to 2^-17, the result within about 1e-5 of the fp32 path and
+ *          positive semidefinite to that level.
  *   workspace  device buffer of at least gq_fisher_gram_workspace_bytes() bytes,
  *          256-byte aligned (may be NULL when that size is 0); contents are
  *          scratch.

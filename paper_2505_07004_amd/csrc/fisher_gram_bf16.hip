@@ -74,6 +74,7 @@ __device__ inline bf16x8 scale_frag(u32x2 lo, u32x2 hi, f32x4 s0, f32x4 s1) {
 // eight raw 32-column fragments as read.
 struct Operands {
   bf16x8 a[kMA];
+  bf16x8 a2[kMA];        // second bf16 term of the scaled operand (two-term mode only)
   u32x2 b[kNB][2];
 };
 struct RawA {
@@ -146,7 +147,10 @@ constexpr int kTileFloats = 4 * kMA * kNB * 16 * 64;   // accumulators of one wo
 // an item goes straight into H; a partial run is parked in the workspace and a second small
 // kernel adds the parts of every split item in a fixed order.  No workgroup ever waits for
 // another one.
-template <int GPC>
+// SPLIT: the scaled operand s * x is carried as TWO bf16 terms (hi + lo, 16 mantissa bits) and every
+// fragment pair takes two MFMAs: twice the matrix-core work for products that are exact to 2^-17, so
+// that the result is positive semidefinite up to ~1e-5 of its largest eigenvalue instead of ~5e-4.
+template <int GPC, bool SPLIT>
 __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __restrict__ X, int64_t n, int64_t d,
                                                                int64_t ld, const float* __restrict__ sp,
                                                                int64_t n_pad, float* __restrict__ H, int accumulate,
@@ -304,10 +308,38 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
       v[1] = __builtin_bit_cast(float, w & 0xffff0000u) * sv[2 * (q % 2) + 1];
       return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));
     };
-    auto mfma1 = [&](const Operands& o, int i) {   // MFMA number i of a sub-step: fragment pair (x, y) = (i%2, i/2)
-      const int x = i % 2, y = i / 2;
+    // The two terms of one dword of a scaled fragment: hi = bf16(s * x), lo = bf16(s * x - hi).
+    auto scale2 = [&](const RawA& f, int x, int q) -> u32x2 {
+      const unsigned int w = f.a[x][q / 2][q % 2];
+      const f32x4 sv = f.s[q / 2];
+      f32x2 v, r;
+      v[0] = __builtin_bit_cast(float, w << 16) * sv[2 * (q % 2)];
+      v[1] = __builtin_bit_cast(float, w & 0xffff0000u) * sv[2 * (q % 2) + 1];
+      const unsigned int hi = __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));
+      r[0] = v[0] - __builtin_bit_cast(float, hi << 16);
+      r[1] = v[1] - __builtin_bit_cast(float, hi & 0xffff0000u);
+      const unsigned int lo = __builtin_bit_cast(unsigned int, __builtin_convertvector(r, bf16x2));
+      return u32x2{hi, lo};
+    };
+    // Slot i of a sub-step.  One term: MFMA number i, fragment pair (x, y) = (i%2, i/2).  Two terms: slot
+    // i works on y = i/2 for both x, first with the hi term (i even), then with the lo term (i odd), so
+    // that the two MFMAs into one accumulator are two MFMAs apart.
+    auto mfma1 = [&](const Operands& o, int i) {
+      const int y = i / 2;
       u32x4 bw = {o.b[y][0][0], o.b[y][0][1], o.b[y][1][0], o.b[y][1][1]};
-      acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[x], __builtin_bit_cast(bf16x8, bw), acc[x][y], 0, 0, 0);
+      const bf16x8 b8 = __builtin_bit_cast(bf16x8, bw);
+      if constexpr (SPLIT) {
+        if (i % 2 == 0) {
+          acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[0], b8, acc[0][y], 0, 0, 0);
+          acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[1], b8, acc[1][y], 0, 0, 0);
+        } else {
+          acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a2[0], b8, acc[0][y], 0, 0, 0);
+          acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a2[1], b8, acc[1][y], 0, 0, 0);
+        }
+      } else {
+        const int x = i % 2;
+        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[x], b8, acc[x][y], 0, 0, 0);
+      }
     };
     // One 16-token sub-step in its exact issue order (scheduling fences keep the compiler from
     // regrouping it): the 16 MFMAs on the current operands, each occupying the matrix core for
@@ -318,7 +350,7 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     // every third MFMA): issued back to back they would queue up in the memory pipeline.
     auto sub_step = [&](const Operands& cur, Operands& nxt, RawA& raw, const char* stage, int ks, int dma_first,
                         int dma_count, int slot) {
-      u32x4 an[kMA];
+      u32x4 an[kMA], an2[kMA];
       mfma1(cur, 0);
       read_raw_a(raw, stage, ks);
       __builtin_amdgcn_sched_barrier(0);
@@ -327,7 +359,14 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
         mfma1(cur, i);
         read_b1(nxt, stage, ks, i - 1);
         if (i == 8) {
-          an[0][0] = scale1(raw, 0, 0);
+          if constexpr (SPLIT) {
+            const u32x2 hl = scale2(raw, 0, 0);
+            an[0][0] = hl[0];
+            an2[0][0] = hl[1];
+            asm volatile("" : "+v"(an2[0][0]));
+          } else {
+            an[0][0] = scale1(raw, 0, 0);
+          }
           asm volatile("" : "+v"(an[0][0]));           // keeps the scaling where it is written (see below)
         }
         if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
@@ -337,7 +376,14 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
       for (int i = 9; i <= 15; ++i) {
         mfma1(cur, i);
         const int piece = i - 8;                       // 1..7
-        an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
+        if constexpr (SPLIT) {
+          const u32x2 hl = scale2(raw, piece / 4, piece % 4);
+          an[piece / 4][piece % 4] = hl[0];
+          an2[piece / 4][piece % 4] = hl[1];
+          asm volatile("" : "+v"(an2[piece / 4][piece % 4]));
+        } else {
+          an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
+        }
         // an empty asm that "uses" the value: without it the optimiser sinks all the scaling
         // below the last MFMA of the sub-step, where nothing hides it
         asm volatile("" : "+v"(an[piece / 4][piece % 4]));
@@ -345,7 +391,10 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int x = 0; x < kMA; ++x) nxt.a[x] = __builtin_bit_cast(bf16x8, an[x]);
+      for (int x = 0; x < kMA; ++x) {
+        nxt.a[x] = __builtin_bit_cast(bf16x8, an[x]);
+        if constexpr (SPLIT) nxt.a2[x] = __builtin_bit_cast(bf16x8, an2[x]);
+      }
     };
 
     // Token step k0 + t of the run lives in ring slot t % NS.  Loads of the first NS-1 stages are
@@ -364,7 +413,21 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
 #pragma unroll
     for (int y = 0; y < kNB; ++y) read_b1(o0, smem, 0, y);
 #pragma unroll
-    for (int x = 0; x < kMA; ++x) o0.a[x] = scale_frag(raw.a[x][0], raw.a[x][1], raw.s[0], raw.s[1]);
+    for (int x = 0; x < kMA; ++x) {
+      if constexpr (SPLIT) {
+        u32x4 h4, l4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const u32x2 hl = scale2(raw, x, q);
+          h4[q] = hl[0];
+          l4[q] = hl[1];
+        }
+        o0.a[x] = __builtin_bit_cast(bf16x8, h4);
+        o0.a2[x] = __builtin_bit_cast(bf16x8, l4);
+      } else {
+        o0.a[x] = scale_frag(raw.a[x][0], raw.a[x][1], raw.s[0], raw.s[1]);
+      }
+    }
     for (int64_t step = k0; step < k1; ++step) {
       wait_vmcnt<(NS - 3) * C::kLoads>();
       __builtin_amdgcn_s_barrier();
@@ -535,7 +598,7 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
 }
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                   float* H, bool accumulate, void* ws, size_t, hipStream_t st) {
+                                   float* H, bool accumulate, bool two_terms, void* ws, size_t, hipStream_t st) {
   const Plan pl = make_plan(n, d_in, G);
   float* sp = (float*)ws;
   float* partial = (float*)((char*)ws + pl.sp_bytes);
@@ -547,8 +610,12 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
   const __bf16* Xb = (const __bf16*)X;
   const int acc = accumulate ? 1 : 0;
 #define GQ_LAUNCH_GRAM(GPC)                                                                                     \
-  fisher_gram_bf16_kernel<GPC><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc, pl.n_gsets,  \
-                                                           pl.n_items, partial);                                 \
+  if (two_terms)                                                                                                \
+    fisher_gram_bf16_kernel<GPC, true><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc,        \
+                                                                   pl.n_gsets, pl.n_items, partial);             \
+  else                                                                                                          \
+    fisher_gram_bf16_kernel<GPC, false><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc,       \
+                                                                    pl.n_gsets, pl.n_items, partial);            \
   e = hipGetLastError();                                                                                        \
   if (e == hipSuccess && left_over > 0) {                                                                            \
     fisher_gram_fixup_kernel<GPC><<<fix, dim3(256), 0, st>>>(n, d_in, H, acc, pl.n_gsets, pl.n_items, pl.P,      \

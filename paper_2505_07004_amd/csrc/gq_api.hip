@@ -60,7 +60,7 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
                    float* H, uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!valid_dtype((int)x_dtype)) return GQ_ERR_DTYPE;
   if (n < 0 || d_in <= 0 || G <= 0 || ld_x < d_in) return GQ_ERR_SHAPE;
-  if (flags & ~(uint32_t)(GQ_ACCUMULATE | GQ_MIRROR)) return GQ_ERR_UNSUPPORTED;
+  if (flags & ~(uint32_t)(GQ_ACCUMULATE | GQ_MIRROR | GQ_TWO_TERMS)) return GQ_ERR_UNSUPPORTED;
   if (!H) return GQ_ERR_NULLPTR;
   if (n > 0 && (!X || !s)) return GQ_ERR_NULLPTR;
   if (!aligned16(H)) return GQ_ERR_ALIGN;
@@ -76,7 +76,8 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
   } else if (x_dtype == GQ_F32) {
     e = gq::launch_fisher_gram_f32((const float*)X, n, d_in, ld_x, s, G, H, accumulate, st);
   } else {
-    e = gq::launch_fisher_gram_bf16(X, n, d_in, ld_x, s, G, H, accumulate, workspace, workspace_bytes, st);
+    e = gq::launch_fisher_gram_bf16(X, n, d_in, ld_x, s, G, H, accumulate, (flags & GQ_TWO_TERMS) != 0, workspace,
+                                    workspace_bytes, st);
   }
   if (e != hipSuccess) return GQ_ERR_HIP;
   if (flags & GQ_MIRROR) e = gq::launch_mirror(H, d_in, G, st);

@@ -98,7 +98,7 @@ hipError_t launch_fisher_gram_f32(const float* X, int64_t n, int64_t d_in, int64
                                   int G, float* H, bool accumulate, hipStream_t st);
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
-                                   int G, float* H, bool accumulate, void* ws, size_t ws_bytes,
+                                   int G, float* H, bool accumulate, bool two_terms, void* ws, size_t ws_bytes,
                                    hipStream_t st);
 size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
 

@@ -59,6 +59,7 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_fisher_gram(odd, 1, 4, 8, 8, a16, 2, a16, 0, None, 0, None) == -4
     assert lib.gq_fisher_gram(a16, 1, 4, 12, 12, a16, 2, a16, 0, None, 0, None) == -4  # bf16 pitch 24 B
     assert lib.gq_fisher_gram(a16, 1, 4, 8, 8, a16, 2, a16, 64, None, 0, None) == -7   # unknown flag
+    assert lib.gq_fisher_gram(a16, 1, 4, 8, 8, a16, 2, a16, 4, None, 0, None) == -5    # two terms: a known flag (no workspace given)
     assert lib.gq_group_weights_strided(a16, 0, 4, 8, 8, 2, 1.0, a16, 1, None) == -2      # output pitch smaller than G
     assert lib.gq_group_weights_strided(a16, 0, 0, 8, 8, 2, 1.0, a16, 6, None) == 0       # no tokens: nothing to do
     # mirror

@@ -25,12 +25,13 @@ def test_hot_loop_of_the_gram_kernel_is_compact_and_spill_free():
                                       os.path.join(CSRC, "fisher_gram_bf16.hip"), "-o", "-"]
     asm = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, check=True).stdout
     kernels = re.findall(r"^(_ZN2gq\S*fisher_gram_bf16_kernel\S*):[^\n]*\n(.*?)s_endpgm", asm, flags=re.S | re.M)
-    assert len(kernels) == 3                      # one instantiation per groups-per-workgroup (4, 2, 1)
+    assert len(kernels) == 6                      # groups per workgroup (4, 2, 1) x one or two terms of the scaled operand
     for name, body in kernels:
         lines = body.splitlines()
         mfma = [i for i, l in enumerate(lines) if "v_mfma_f32_32x32x16_bf16" in l]
-        # 2 sub-steps x 16 MFMAs, exactly once: the loop was neither unrolled further nor peeled
-        assert len(mfma) == 32, (name, len(mfma))
+        # 2 sub-steps x 16 MFMAs (x 2 terms), exactly once: the loop was neither unrolled further nor peeled
+        two_terms = "Lb1E" in name
+        assert len(mfma) == (64 if two_terms else 32), (name, len(mfma))
         loop = lines[mfma[0]:mfma[-1] + 1]
         assert not [l for l in loop if "scratch_" in l], f"{name}: register spill inside the hot loop"
         # the direct loads of one stage and the single barrier per stage are in there too

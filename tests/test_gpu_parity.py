@@ -177,6 +177,44 @@ def test_gram_bf16_matches_its_documented_rounding():
         assert err <= 2e-6
 
 
+TOL_TWO_TERMS = 2e-5     # two bf16 terms carry s*x to 2^-17 (random sign: ~3e-6 on the sum); fp32 accumulation adds ~1e-5 at most
+
+
+@pytest.mark.parametrize("n,d_in,G,ld,kind", [
+    (4096, 512, 4, None, "outlier"),
+    (4096, 512, 1, None, "outlier"),
+    (2048, 768, 2, None, "silu"),
+    (1500, 520, 8, None, "outlier"),
+    (1000, 328, 3, None, "silu"),
+    (700, 300, 4, 304, "outlier"),
+    (5, 16, 4, None, "outlier"),
+])
+def test_gram_bf16_two_terms_shapes(n, d_in, G, ld, kind):
+    say(f"gram bf16, two terms n={n} d_in={d_in} G={G} ld={ld} {kind}")
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 300 + n, ld, kind)
+    H = gq.gq_fisher_gram(X, s, two_terms=True)
+    _check_gram(H, X, s, TOL_TWO_TERMS, f"bf16 two terms n={n} d_in={d_in} G={G}")
+
+
+def test_gram_bf16_two_terms_accumulates_over_chunks_and_is_positive_semidefinite_where_one_term_is_not():
+    X, s = _gram_case(3000, 264, 4, torch.bfloat16, 21)
+    H = None
+    for c0 in range(0, 3000, 1000):
+        H = gq.gq_fisher_gram(X[c0:c0 + 1000], s[c0:c0 + 1000], H=H, accumulate=c0 > 0, two_terms=True)
+    gq.gq_fisher_mirror(H)
+    _check_gram(H, X, s, TOL_TWO_TERMS, "3 chunks, two terms")
+    # rank-deficient on purpose (fewer tokens than columns): the exact matrix has 64 zero eigenvalues, and the
+    # rounding of the one-term path pushes some of them well below zero
+    Xs, ss = X[:200], s[:200]
+    H1 = to_np64(gq.gq_fisher_gram(Xs, ss, mirror=True))
+    H2 = to_np64(gq.gq_fisher_gram(Xs, ss, mirror=True, two_terms=True))
+    for k in range(4):
+        e1, e2 = np.linalg.eigvalsh(H1[k]), np.linalg.eigvalsh(H2[k])
+        say(f"group {k}: smallest eigenvalue / largest: one term {e1[0] / e1[-1]:.2e}, two terms {e2[0] / e2[-1]:.2e}")
+        assert e2[0] >= -2e-6 * e2[-1]
+        assert e1[0] < 10 * e2[0] or e1[0] >= -2e-6 * e1[-1]
+
+
 def test_gram_is_deterministic():
     X, s = _gram_case(2048, 512, 4, torch.bfloat16, 77)
     a = gq.gq_fisher_gram(X, s, mirror=True).clone()

@@ -256,7 +256,25 @@ def main():
                                  "the whole call: split of H, contraction, binning and the fp64 solves"},
         }
         log(f"lnq_codebook: {lnq_ms:.2f} ms; objective -> {result['lnq_codebook']['objective_after']}")
-        del Wq, ws_l, Wl, Qc
+        # ... and the whole alternation of Algorithm 2 with the paper's T and K (T = 1 for the 70B shapes), from plain rounding.
+        T_lnq = 1 if "70b" in spec.name else 2
+        Q0 = torch.argmin((C[:, None, :] - What[:, :, None]).abs(), dim=2).to(torch.uint8).contiguous() if d_out * d_in * m <= (1 << 31) \
+            else torch.cat([torch.argmin((C[r:r + 1024, None, :] - What[r:r + 1024, :, None]).abs(), dim=2).to(torch.uint8)
+                            for r in range(0, d_out, 1024)]).contiguous()
+        ws_a = torch.empty(int(lib.gq_lnq_workspace_bytes(d_out, d_in, G, m)), dtype=torch.uint8, device=dev)
+        Qa = Q0.clone()
+        gq.gq_lnq(W, Qa, Hd, m, n_iters=T_lnq, n_cycles=4, What=Wl, workspace=ws_a)     # warm-up
+        Qa = Q0.clone()
+        e0.record()
+        gq.gq_lnq(W, Qa, Hd, m, n_iters=T_lnq, n_cycles=4, What=Wl, workspace=ws_a)
+        e1.record()
+        o_lnq = gq.gq_objective(W, Wl, Hd, workspace=ws_o)
+        torch.cuda.synchronize()
+        result["lnq"] = {"ms": e0.elapsed_time(e1), "T": T_lnq, "K": 4, "levels": m,
+                         "objective_plain_rounding": [float(v) for v in o_before.tolist()],
+                         "objective_after": [float(v) for v in o_lnq.tolist()]}
+        log(f"lnq (T={T_lnq}, K=4): {result['lnq']['ms']:.2f} ms; objective -> {result['lnq']['objective_after']}")
+        del Wq, ws_l, ws_a, Wl, Qc, Qa, Q0
         # ... and the sequential-rounding alternative (GPTQ / LDLQ): factor the damped H, round with feedback.
         # A factorization needs a positive definite H: the Gram with the scaled operand in two bf16 terms
         # (timed here as well; the one-term H of the step above is indefinite at 1 % damping for most shapes).

@@ -14,6 +14,7 @@
  *   gq_damped_cholesky  H[k] + eps I = L L^T (or R R^T, R upper)                     (Algorithm 2, line 1)
  *   gq_ldlq_assign    sequential rounding with error feedback (GPTQ / LDLQ) from a factor of H[k]
  *   gq_lnq_codebook   closed-form grids for fixed assignments against H[k]        (Section 4.2, Eq. "conti-sol")
+ *   gq_lnq            grids and coordinate descent in alternation                 (Algorithm 2)
  *
  * Conventions shared by every call
  *   - Every data pointer is DEVICE memory on the current HIP device, allocated
@@ -313,6 +314,35 @@ int gq_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld_w, c
                     const float* H, int32_t G, int32_t n_levels, double lam,
                     float* codebook, float* What,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace gq_lnq needs (0 for invalid sizes). */
+size_t gq_lnq_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G, int32_t n_levels);
+
+/*
+ * Layer-wise non-uniform quantization against the group Hessians, the whole alternation of
+ * Algorithm 2 (Section 4.2) in one call: starting from the assignments Q,
+ *
+ *   repeat n_iters times (T):  grids <- gq_lnq_codebook(Q);  What <- grids[Q];
+ *                              Q, What <- n_cycles cycles (K) of gq_cd_assign
+ *   finally:                   grids <- gq_lnq_codebook(Q);  What <- grids[Q]
+ *
+ * exactly as those two calls would do it (same kernels, same order).  The paper uses T = 2, K = 4
+ * (T = 1 for the 70B models), lam = 1e-7.  By Prop. 4.1 no step increases the layer objective.
+ *
+ *   W         [d_out, d_in]     device fp32, row pitch ld_w elements
+ *   What      [d_out, d_in]     device fp32, same pitch, written; must not overlap W
+ *   Q         [d_out, d_in]     device bytes, dense; in: the initial assignments (every entry
+ *                               < n_levels), out: the final ones
+ *   codebook  [d_out, n_levels] device fp32, dense, written: the final grids
+ *   H         [G, d_in, d_in]   device fp32 with positive diagonals; only the upper triangle is read
+ *   workspace  at least gq_lnq_workspace_bytes() bytes, 256-byte aligned
+ *
+ * Errors: as gq_lnq_codebook and gq_cd_assign; GQ_ERR_SHAPE also if n_iters < 0 or What == W.
+ */
+int gq_lnq(const float* W, float* What, uint8_t* Q, float* codebook, int32_t n_levels,
+           int64_t d_out, int64_t d_in, int64_t ld_w, const float* H, int32_t G,
+           int32_t n_iters, int32_t n_cycles, double lam,
+           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -16,6 +16,7 @@ from .gq_oracle import (  # noqa: F401
     cd_coordinate_target,
     cd_assign,
     lnq_codebook,
+    lnq,
     damped_cholesky,
     gptq_assign,
     ldlq_assign,

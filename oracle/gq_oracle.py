@@ -281,6 +281,30 @@ def lnq_codebook(W, Q, H, n_levels: int, G: int | None = None, lam: float = 1e-7
     return C, What
 
 
+def lnq(W, Q, H, n_levels: int, G: int | None = None, n_iters: int = 2, n_cycles: int = 4, lam: float = 1e-7):
+    """Algorithm 2 (LNQ) against the group Hessians: starting from the assignments Q, n_iters (T) times
+    {closed-form grids for the current assignments (line 4), What = P c (line 5), n_cycles (K) cycles of
+    coordinate descent on the assignments (lines 6-12)}, then the grids once more (line 14).
+    Returns (Q, What, codebook, trace) with trace the layer objective summed over the groups after every
+    codebook step and every batch of CD cycles, in order."""
+    W = np.asarray(W, dtype=_F64)
+    H = np.asarray(H, dtype=_F64)
+    if H.ndim == 2:
+        H = H[None]
+    G = H.shape[0] if G is None else G
+    Q = np.array(Q, dtype=np.int64, copy=True)
+    trace = []
+    for _ in range(n_iters):
+        C, What = lnq_codebook(W, Q, H, n_levels, G, lam)
+        trace.append(float(objective(W, What, H, G)[0].sum()))
+        if n_cycles > 0:
+            Q, What = cd_assign(W, What, C, H, G, n_cycles)
+            trace.append(float(objective(W, What, H, G)[0].sum()))
+    C, What = lnq_codebook(W, Q, H, n_levels, G, lam)
+    trace.append(float(objective(W, What, H, G)[0].sum()))
+    return Q, What, C, trace
+
+
 def damped_cholesky(H, damp_rel: float = 0.01, damp_abs: float = 0.0, reverse: bool = False) -> np.ndarray:
     """The triangular factor of the damped group Hessians (Algorithm 2, line 1; Section 4.2:
     a small constant is added to the diagonal so that the matrix is positive definite).

@@ -67,6 +67,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_damped_cholesky.restype = c.c_int
     lib.gq_damped_cholesky.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_double, c.c_double, c.c_uint32, c.c_void_p,
                                        c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.gq_lnq_workspace_bytes.restype = c.c_size_t
+    lib.gq_lnq_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32, c.c_int32]
+    lib.gq_lnq.restype = c.c_int
+    lib.gq_lnq.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int64, c.c_int64,
+                           c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_double, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_ldlq_assign.restype = c.c_int
     lib.gq_ldlq_assign.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int64, c.c_int64,
                                    c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -316,3 +321,30 @@ def gq_damped_cholesky(H: torch.Tensor, damp_rel: float = 0.01, damp_abs: float 
                                 F.data_ptr(), info.data_ptr(), ws_ptr, ws_bytes, _stream())
     _check(st, "gq_damped_cholesky")
     return F, info
+
+
+def gq_lnq(W: torch.Tensor, Q: torch.Tensor, H: torch.Tensor, n_levels: int, n_iters: int = 2, n_cycles: int = 4,
+           lam: float = 1e-7, What: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Algorithm 2 (LNQ) against H[k]: n_iters x (closed-form grids, n_cycles CD cycles), then the grids once
+    more.  `Q` [d_out, d_in] uint8 holds the initial assignments and is updated IN PLACE.
+    Returns (What, codebook [d_out, n_levels])."""
+    _require_gpu(W, Q, H, What, workspace)
+    d_out, d_in = W.shape
+    G = int(H.shape[0])
+    assert W.dtype == torch.float32 and H.dtype == torch.float32 and H.is_contiguous()
+    assert Q.dtype == torch.uint8 and Q.is_contiguous() and tuple(Q.shape) == (d_out, d_in)
+    if What is None:
+        What = torch.empty_strided(W.shape, W.stride(), dtype=W.dtype, device=W.device)
+    assert What.dtype == torch.float32 and What.shape == W.shape and _rows(W) == _rows(What)
+    lib = load_library()
+    need = int(lib.gq_lnq_workspace_bytes(d_out, d_in, G, int(n_levels)))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(max(need, 1), W.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    codebook = torch.empty((d_out, int(n_levels)), dtype=torch.float32, device=W.device)
+    st = lib.gq_lnq(W.data_ptr(), What.data_ptr(), Q.data_ptr(), codebook.data_ptr(), int(n_levels), d_out, d_in, _rows(W),
+                    H.data_ptr(), G, int(n_iters), int(n_cycles), float(lam), ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_lnq")
+    return What, codebook

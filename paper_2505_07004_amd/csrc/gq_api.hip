@@ -179,4 +179,34 @@ int gq_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld_w, c
                                           (hipStream_t)hip_stream));
 }
 
+size_t gq_lnq_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G, int32_t n_levels) {
+  const size_t a = gq_cd_workspace_bytes(d_out, d_in, G), b = gq_lnq_codebook_workspace_bytes(d_out, d_in, G, n_levels);
+  if (a == 0 || b == 0) return 0;
+  return a > b ? a : b;
+}
+
+int gq_lnq(const float* W, float* What, uint8_t* Q, float* codebook, int32_t n_levels, int64_t d_out, int64_t d_in,
+           int64_t ld_w, const float* H, int32_t G, int32_t n_iters, int32_t n_cycles, double lam, void* workspace,
+           size_t workspace_bytes, void* hip_stream) {
+  if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_levels <= 0 || n_iters < 0 ||
+      n_cycles < 0 || !(lam >= 0.0))
+    return GQ_ERR_SHAPE;
+  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (!W || !What || !Q || !codebook || !H) return GQ_ERR_NULLPTR;
+  if (W == What) return GQ_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(What) || !aligned16(H) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;
+  const size_t need = gq_lnq_workspace_bytes(d_out, d_in, G, n_levels);
+  if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = hipSuccess;
+  for (int t = 0; t < n_iters && e == hipSuccess; ++t) {
+    e = gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, workspace, st);
+    if (e == hipSuccess && n_cycles > 0)
+      e = gq::launch_cd_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, H, G, n_cycles, Q, workspace, st);
+  }
+  if (e == hipSuccess)
+    e = gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, workspace, st);
+  return from_hip(e);
+}
+
 }  // extern "C"

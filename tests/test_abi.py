@@ -22,7 +22,7 @@ def test_header_declares_the_expected_calls():
     for name in ("gq_group_weights", "gq_fisher_gram", "gq_objective", "gq_fisher_mirror",
                  "gq_fisher_gram_workspace_bytes", "gq_objective_workspace_bytes",
                  "gq_cd_assign", "gq_cd_workspace_bytes", "gq_group_weights_strided",
-                 "gq_lnq_codebook", "gq_lnq_codebook_workspace_bytes", "gq_ldlq_assign", "gq_damped_cholesky", "gq_cholesky_workspace_bytes", "gq_version", "gq_status_string"):
+                 "gq_lnq_codebook", "gq_lnq_codebook_workspace_bytes", "gq_ldlq_assign", "gq_lnq", "gq_lnq_workspace_bytes", "gq_damped_cholesky", "gq_cholesky_workspace_bytes", "gq_version", "gq_status_string"):
         assert name in syms
 
 
@@ -103,6 +103,14 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_ldlq_assign(a16, P(0x2000), a16, 8, 8, 8, 8, None, 4, None, P(0x1100), big, None) == -1   # no factor
     assert lib.gq_ldlq_assign(a16, P(0x2004), a16, 8, 8, 8, 8, a16, 4, None, P(0x1100), big, None) == -4
     assert lib.gq_ldlq_assign(a16, P(0x2000), a16, 8, 8, 8, 8, a16, 4, None, P(0x1100), 16, None) == -5
+    # the whole alternation
+    assert lib.gq_lnq(a16, P(0x2000), a16, a16, 8, 10, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), big, None) == -2         # G does not divide d_out
+    assert lib.gq_lnq(a16, P(0x2000), a16, a16, 8, 8, 8, 8, a16, 4, -1, 4, 1e-7, P(0x1100), big, None) == -2         # negative iteration count
+    assert lib.gq_lnq(a16, a16, a16, a16, 8, 8, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), big, None) == -2                # What == W
+    assert lib.gq_lnq(a16, P(0x2000), None, a16, 8, 8, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), big, None) == -1         # no assignments
+    assert lib.gq_lnq(a16, P(0x2000), a16, a16, 17, 8, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), big, None) == -7
+    assert lib.gq_lnq(a16, P(0x2000), a16, a16, 8, 8, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), 16, None) == -5
+    assert lib.gq_lnq_workspace_bytes(8, 8, 4, 8) >= lib.gq_cd_workspace_bytes(8, 8, 4)
     # codebook step
     lam = 1e-7
     assert lib.gq_lnq_codebook(a16, 10, 8, 8, a16, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -2   # G does not divide d_out

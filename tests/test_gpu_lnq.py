@@ -152,3 +152,40 @@ def test_codebook_step_with_a_number_of_grid_points_that_is_not_a_power_of_two(m
     for k in range(G):
         r = slice(k * per, (k + 1) * per)
         check_codebook_channels(oracle, Wn[r], Qn[r], Hn[k], Cg[r], m, LAM, f"{m} grid points, group {k}")
+
+
+def test_lnq_alternation_in_one_call_equals_its_parts_and_reaches_the_oracles_objective():
+    """Algorithm 2 with T = 2, K = 2: bit-identical to the same calls made one by one, every step a descent,
+    and the final objective within 1e-3 of the fp64 oracle's run from the same start (the two trajectories
+    part at rounding-level near-ties, so the assignments themselves are compared only in bulk)."""
+    W, Q0, H = _case(512, 256, 128, 2, 3, 555)
+    m = 8
+    Q = Q0.clone()
+    What, C = gq.gq_lnq(W, Q, H, m, n_iters=2, n_cycles=2, lam=LAM)
+    torch.cuda.synchronize()
+    assert torch.equal(What, torch.gather(C, 1, Q.long()))
+    # by hand
+    Qh, Wh = Q0.clone(), torch.empty_like(W)
+    objs = []
+    for _ in range(2):
+        Ch = gq.gq_lnq_codebook(W, Qh, H, m, LAM, What=Wh)
+        objs.append(gq.gq_objective(W, Wh, H).sum().item())
+        Qh = gq.gq_cd_assign(W, Wh, Ch, H, n_cycles=2)
+        objs.append(gq.gq_objective(W, Wh, H).sum().item())
+    Ch = gq.gq_lnq_codebook(W, Qh, H, m, LAM, What=Wh)
+    objs.append(gq.gq_objective(W, Wh, H).sum().item())
+    torch.cuda.synchronize()
+    assert torch.equal(Qh, Q) and torch.equal(Wh, What) and torch.equal(Ch, C)
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(objs[:-1], objs[1:]))
+    Qo, Wo, Co, trace = oracle.lnq(to_np64(W), Q0.cpu().numpy(), to_np64(H), m, 2, n_iters=2, n_cycles=2, lam=LAM)
+    say("objective gpu " + ", ".join(f"{o:.4f}" for o in objs) + " | oracle " + ", ".join(f"{o:.4f}" for o in trace))
+    assert abs(objs[0] - trace[0]) <= 5e-6 * trace[0]                    # the first codebook step: same assignments (gq_objective itself is good to ~2e-6)
+    assert abs(objs[-1] - trace[-1]) <= 1e-3 * trace[-1]
+    assert float(np.mean(Qo != Q.cpu().numpy())) <= 0.02
+    # no iterations: the codebook step alone
+    Qz = Q0.clone()
+    Wz, Cz = gq.gq_lnq(W, Qz, H, m, n_iters=0, lam=LAM)
+    Wc = torch.empty_like(W)
+    Cc = gq.gq_lnq_codebook(W, Q0, H, m, LAM, What=Wc)
+    torch.cuda.synchronize()
+    assert torch.equal(Qz, Q0) and torch.equal(Wz, Wc) and torch.equal(Cz, Cc)

@@ -368,6 +368,32 @@ def test_lnq_codebook_recovers_an_exactly_representable_weight_and_is_relabeling
         oracle.lnq_codebook(W, Q + 1, H, m)
 
 
+def test_lnq_alternation_descends_and_reduces_to_its_parts():
+    # Prop. 4.1: neither step can increase the objective; with no iterations the alternation is the codebook
+    # step alone; one iteration is codebook step -> CD cycles -> codebook step, composed by hand here
+    r = _rng(55)
+    d_out, d_in, G, m = 6, 24, 2, 4
+    X = r.normal(size=(80, d_in))
+    H = np.stack([X.T @ (r.uniform(0.5, 2.0, 80)[:, None] * X) for _ in range(G)]) + 0.01 * np.eye(d_in)
+    W = r.normal(size=(d_out, d_in))
+    Q0 = r.integers(0, m, size=(d_out, d_in))
+    Q, What, C, trace = oracle.lnq(W, Q0, H, m, G, n_iters=3, n_cycles=2)
+    assert len(trace) == 7 and all(b <= a * (1 + 1e-12) for a, b in zip(trace[:-1], trace[1:]))
+    assert trace[-1] < 0.7 * trace[0]
+    np.testing.assert_array_equal(What, np.take_along_axis(C, Q, axis=1))
+    Qz, Wz, Cz, tz = oracle.lnq(W, Q0, H, m, G, n_iters=0)
+    C0, W0 = oracle.lnq_codebook(W, Q0, H, m, G)
+    np.testing.assert_array_equal(Qz, Q0)
+    np.testing.assert_array_equal(Wz, W0)
+    np.testing.assert_array_equal(Cz, C0)
+    Q1, W1 = oracle.cd_assign(W, W0, C0, H, G, n_cycles=2)
+    C1, W1b = oracle.lnq_codebook(W, Q1, H, m, G)
+    Qo, Wo, Co, _ = oracle.lnq(W, Q0, H, m, G, n_iters=1, n_cycles=2)
+    np.testing.assert_array_equal(Qo, Q1)
+    np.testing.assert_array_equal(Wo, W1b)
+    np.testing.assert_array_equal(Co, C1)
+
+
 # ---------------------------------------------------------------- damped Cholesky, sequential rounding (GPTQ / LDLQ)
 def _spd(r, G, d, cond=50.0):
     out = []

@@ -152,6 +152,16 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
  */
 int gq_fisher_mirror(float* H, int64_t d_in, int32_t G, void* hip_stream);
 
+/*
+ * Damping of the group Hessians in place (Section 4.2: a small constant on the diagonal; the
+ * users of H it names all damp it):  H[k][i,i] += damp_abs + damp_rel * mean_i H[k][i,i].
+ * The same constant as gq_damped_cholesky applies internally; gq_cd_assign, gq_lnq_codebook
+ * and gq_lnq take H as it is, so a caller who wants them to see the damped matrix calls this
+ * first.  H [G, d_in, d_in] device fp32.  Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_in <= 0,
+ * G <= 0, a constant negative or NaN).
+ */
+int gq_damp_diagonal(float* H, int64_t d_in, int32_t G, double damp_rel, double damp_abs, void* hip_stream);
+
 /* Bytes of device workspace gq_objective needs (never 0 for valid sizes). */
 size_t gq_objective_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G);
 

@@ -67,6 +67,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_damped_cholesky.restype = c.c_int
     lib.gq_damped_cholesky.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_double, c.c_double, c.c_uint32, c.c_void_p,
                                        c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.gq_damp_diagonal.restype = c.c_int
+    lib.gq_damp_diagonal.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_double, c.c_double, c.c_void_p]
     lib.gq_lnq_workspace_bytes.restype = c.c_size_t
     lib.gq_lnq_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32, c.c_int32]
     lib.gq_lnq.restype = c.c_int
@@ -348,3 +350,13 @@ def gq_lnq(W: torch.Tensor, Q: torch.Tensor, H: torch.Tensor, n_levels: int, n_i
                     H.data_ptr(), G, int(n_iters), int(n_cycles), float(lam), ws_ptr, ws_bytes, _stream())
     _check(st, "gq_lnq")
     return What, codebook
+
+
+def gq_damp_diagonal(H: torch.Tensor, damp_rel: float = 0.01, damp_abs: float = 0.0) -> torch.Tensor:
+    """H[k][i,i] += damp_abs + damp_rel * mean diag H[k], in place."""
+    _require_gpu(H)
+    assert H.dtype == torch.float32 and H.is_contiguous() and H.dim() == 3 and H.shape[1] == H.shape[2]
+    st = load_library().gq_damp_diagonal(H.data_ptr(), int(H.shape[1]), int(H.shape[0]), float(damp_rel), float(damp_abs),
+                                         _stream())
+    _check(st, "gq_damp_diagonal")
+    return H

@@ -91,6 +91,12 @@ int gq_fisher_mirror(float* H, int64_t d_in, int32_t G, void* hip_stream) {
   return from_hip(gq::launch_mirror(H, d_in, G, (hipStream_t)hip_stream));
 }
 
+int gq_damp_diagonal(float* H, int64_t d_in, int32_t G, double damp_rel, double damp_abs, void* hip_stream) {
+  if (d_in <= 0 || G <= 0 || !(damp_rel >= 0.0) || !(damp_abs >= 0.0)) return GQ_ERR_SHAPE;
+  if (!H) return GQ_ERR_NULLPTR;
+  return from_hip(gq::launch_damp_diagonal(H, d_in, G, damp_rel, damp_abs, (hipStream_t)hip_stream));
+}
+
 size_t gq_objective_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G) {
   if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0) return 0;
   return gq::objective_workspace(d_out, d_in, G);

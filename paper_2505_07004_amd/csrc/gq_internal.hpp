@@ -104,6 +104,7 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
 
 hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st);
+hipError_t launch_damp_diagonal(float* H, int64_t d_in, int G, double damp_rel, double damp_abs, hipStream_t st);
 
 hipError_t launch_objective(const float* W, const float* What, int64_t d_out, int64_t d_in, int64_t ld,
                             const float* H, int G, double* obj, float* obj_row, void* ws,

@@ -47,7 +47,30 @@ __global__ __launch_bounds__(256) void zero_upper_kernel(float* __restrict__ H, 
   }
 }
 
+// H[k][i][i] += damp_abs + damp_rel * mean_i H[k][i][i].  One workgroup per group: the mean in fp64
+// in a fixed order, then the diagonal.
+__global__ __launch_bounds__(256) void damp_diagonal_kernel(float* __restrict__ H, int64_t d, double damp_rel,
+                                                            double damp_abs) {
+  __shared__ double part[256];
+  float* Hk = H + (int64_t)blockIdx.x * d * d;
+  double acc = 0.0;
+  for (int64_t i = threadIdx.x; i < d; i += 256) acc += (double)Hk[i * d + i];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+    __syncthreads();
+  }
+  const double eps = damp_abs + damp_rel * (part[0] / (double)d);
+  for (int64_t i = threadIdx.x; i < d; i += 256) Hk[i * d + i] = (float)((double)Hk[i * d + i] + eps);
+}
+
 }  // namespace
+
+hipError_t launch_damp_diagonal(float* H, int64_t d_in, int G, double damp_rel, double damp_abs, hipStream_t st) {
+  damp_diagonal_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(H, d_in, damp_rel, damp_abs);
+  return hipGetLastError();
+}
 
 hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st) {
   const int64_t T = (d_in + kT - 1) / kT;

@@ -22,7 +22,7 @@ def test_header_declares_the_expected_calls():
     for name in ("gq_group_weights", "gq_fisher_gram", "gq_objective", "gq_fisher_mirror",
                  "gq_fisher_gram_workspace_bytes", "gq_objective_workspace_bytes",
                  "gq_cd_assign", "gq_cd_workspace_bytes", "gq_group_weights_strided",
-                 "gq_lnq_codebook", "gq_lnq_codebook_workspace_bytes", "gq_ldlq_assign", "gq_lnq", "gq_lnq_workspace_bytes", "gq_damped_cholesky", "gq_cholesky_workspace_bytes", "gq_version", "gq_status_string"):
+                 "gq_lnq_codebook", "gq_lnq_codebook_workspace_bytes", "gq_ldlq_assign", "gq_damp_diagonal", "gq_lnq", "gq_lnq_workspace_bytes", "gq_damped_cholesky", "gq_cholesky_workspace_bytes", "gq_version", "gq_status_string"):
         assert name in syms
 
 
@@ -85,6 +85,10 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_cd_assign(a16, a16, a16, 8, 8, 8, 8, a16, 4, 0, None, P(0x1100), big, None) == 0       # zero cycles: nothing to do
     assert lib.gq_cd_workspace_bytes(8, 8, 4) > 0
     assert lib.gq_cd_workspace_bytes(10, 8, 4) == 0
+    # damping
+    assert lib.gq_damp_diagonal(None, 8, 2, 0.01, 0.0, None) == -1
+    assert lib.gq_damp_diagonal(a16, 0, 2, 0.01, 0.0, None) == -2
+    assert lib.gq_damp_diagonal(a16, 8, 2, -0.01, 0.0, None) == -2
     # damped Cholesky
     assert lib.gq_damped_cholesky(a16, 0, 4, 0.01, 0.0, 0, P(0x2000), None, P(0x1100), big, None) == -2       # no coordinates
     assert lib.gq_damped_cholesky(a16, 8, 4, -0.01, 0.0, 0, P(0x2000), None, P(0x1100), big, None) == -2      # negative damping

@@ -182,3 +182,16 @@ def test_cholesky_then_sequential_rounding_at_the_llama2_7b_shape():
     o_o = oracle.objective(to_np64(W[r4]), ref, A, 1)[1]
     say(f"  4 channels: objective gpu {o_g.sum():.5f}, oracle GPTQ {o_o.sum():.5f}")
     assert abs(o_g.sum() - o_o.sum()) <= 1e-2 * o_o.sum()
+
+
+def test_damp_diagonal_adds_the_same_constant_the_cholesky_uses():
+    H = _hessian(300, 200, 8, 2, 9)
+    Hn = to_np64(H)
+    F0, _ = gq.gq_damped_cholesky(H, 0.02, 0.1)
+    Hd = gq.gq_damp_diagonal(H.clone(), 0.02, 0.1)
+    F1, _ = gq.gq_damped_cholesky(Hd, 0.0, 0.0)
+    torch.cuda.synchronize()
+    for k in range(2):
+        want = Hn[k] + (0.1 + 0.02 * np.trace(Hn[k]) / 200) * np.eye(200)
+        np.testing.assert_allclose(to_np64(Hd[k]), want, rtol=2e-7, atol=0)
+    assert torch.equal(F0, F1)

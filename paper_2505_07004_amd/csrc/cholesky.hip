@@ -7,9 +7,9 @@
 //
 // Both are one algorithm on a working matrix A' = U^T U, U upper triangular, processed by block rows
 // of 128 in fp32:  A' = A gives L = U^T;  A'[a][b] = A[d-1-a][d-1-b] gives R[i][j] = U[d-1-j][d-1-i].
-// Per block row:  (1) the 128 x 128 diagonal block is factored by one workgroup per group;
-// (2) the panel to its right is solved against it, U12 = U11^-T A12 (both with the block in registers,
-// 8 x 8 per thread, eight rows at a time published through LDS);
+// Per block row:  (1) the 128 x 128 diagonal block is factored and (2) the panel to its right is solved
+// against it, U12 = U11^-T A12, in one launch (both with the block in registers, 8 x 8 per thread, eight
+// rows at a time published through LDS);
 // (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the fp32 matrix cores
 // (v_mfma_f32_32x32x2_f32), rows of U12 staged through LDS as they lie in memory.
 // Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its
@@ -79,24 +79,33 @@ __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict_
   }
 }
 
-// (1) The diagonal block at (r0, r0): A11 = U11^T U11 with the block in registers: thread (tr, tc) of
-// 16 x 16 owns the 8 x 8 tile at rows 8 tr, columns 8 tc.  Eight rows at a time:
-//   a. the thread of the diagonal tile factors its tile on its own (eight pivots, no barrier) and
+// (1) + (2) One block row: the diagonal block A11 = U11^T U11 at (r0, r0) and the panel to its right,
+// U12 = U11^-T A12, in one launch.  A workgroup owns 128 columns of the panel; its threads 256..511 hold
+// that 128 x 128 tile of A12 in registers (thread (tr, tc) of 16 x 16 the 8 x 8 tile at rows 8 tr, columns
+// 8 tc), its threads 0..255 hold the diagonal block the same way: every workgroup factors the diagonal
+// block again beside its panel (the two halves run on different waves, so this costs no time and saves
+// the launch and the round trip of U11 through memory that a separate kernel needs).  Eight rows at a time:
+//   a. the thread of the diagonal 8 x 8 tile factors it on its own (eight pivots, no barrier) and
 //      publishes the 8 x 8 factor;
-//   b. the other owners of these eight rows solve their tiles against it (forward substitution, eight
-//      steps, no barrier) and publish the finished rows of U;
-//   c. every tile further down subtracts the product of its eight row entries and eight column entries
-//      (a rank-8 update).
-// Two barriers per eight rows (the published data alternate between two buffers).
+//   b. the other owners of these eight rows, of the diagonal block and of the panel alike, solve their
+//      tiles against it (forward substitution, eight steps, no barrier) and publish the finished rows;
+//   c. every tile further down subtracts the product of its eight row entries (from the diagonal
+//      block's rows) and its eight column entries: a rank-8 update.
+// Two barriers per eight rows (the published data alternate between two buffers).  Launched with 256
+// threads there is no panel (the last block row).  Workgroup 0 stores U11 and reports bad pivots; U11
+// goes to a buffer of its own (Ud[k][block][128][128]), not over A11, which workgroups that start
+// later still have to read.
 // Rows and columns past the end of the matrix are those of the identity.
-__global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, int64_t d, int64_t r0,
-                                                        int* __restrict__ info) {
+__global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__ Uw, int64_t d, int64_t r0,
+                                                             float* __restrict__ Ud, int* __restrict__ info) {
   __shared__ __attribute__((aligned(16))) float dtile[2][8][8];
-  __shared__ __attribute__((aligned(16))) float rows[2][8][kNb];
+  __shared__ __attribute__((aligned(16))) float rows[2][8][2 * kNb];   // columns 0..127: diagonal block, 128..255: panel
   __shared__ int bad;
-  const int k = blockIdx.x;
+  const int k = blockIdx.y;
   float* Uk = Uw + (int64_t)k * d * d;
-  const int tid = threadIdx.x, tr = tid / 16, tc = tid % 16;
+  const int tid = threadIdx.x, role = tid / 256, tr = (tid % 256) / 16, tc = tid % 16;
+  const int cb = role * kNb + 8 * tc;                                    // this thread's columns in `rows`
+  const int64_t c0 = role == 0 ? r0 : r0 + kNb + (int64_t)blockIdx.x * kNb;   // first global column of this half's tile
   if (tid == 0) bad = -1;
   float a[8][8];
 #pragma unroll
@@ -104,15 +113,15 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, 
 #pragma unroll
     for (int l = 0; l < 8; ++l) {
       const int r = 8 * tr + i, c = 8 * tc + l;
-      const int64_t gr = r0 + r, gc = r0 + c;
-      const bool in = gr < d && gc < d && r <= c;
+      const int64_t gr = r0 + r, gc = c0 + c;
+      const bool in = gr < d && gc < d && (role == 1 || r <= c);
       const float v = Uk[in ? gr * d + gc : 0];
-      a[i][l] = in ? v : (r == c ? 1.f : 0.f);
+      a[i][l] = in ? v : ((role == 0 && r == c) ? 1.f : 0.f);
     }
   __syncthreads();
   for (int jb = 0; jb < 16; ++jb) {
     const int buf = jb & 1;
-    if (tr == jb && tc == jb) {                               // a. the diagonal tile
+    if (role == 0 && tr == jb && tc == jb) {                  // a. the diagonal tile
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
         float p = a[jj][jj];
@@ -134,11 +143,11 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, 
         for (int l = 0; l < 8; ++l) {
           const float v = l >= i ? a[i][l] : 0.f;
           dtile[buf][i][l] = v;
-          rows[buf][i][8 * tc + l] = v;
+          rows[buf][i][cb + l] = v;
         }
     }
     __syncthreads();
-    if (tr == jb && tc > jb) {                                // b. the rest of the eight rows: U_dd^T X = A
+    if (tr == jb && (role == 1 || tc > jb)) {                 // b. the rest of the eight rows: U_dd^T X = A
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
         const float rp = __builtin_amdgcn_rcpf(dtile[buf][jj][jj]);
@@ -153,17 +162,17 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, 
 #pragma unroll
       for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int l = 0; l < 8; ++l) rows[buf][i][8 * tc + l] = a[i][l];
+        for (int l = 0; l < 8; ++l) rows[buf][i][cb + l] = a[i][l];
     }
     __syncthreads();
-    if (tr > jb && tc >= tr) {                                // c. rank-8 update of everything further down
+    if (tr > jb && (role == 1 || tc >= tr)) {                 // c. rank-8 update of everything further down
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
         float f[8], cl[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) f[i] = rows[buf][jj][8 * tr + i];
 #pragma unroll
-        for (int l = 0; l < 8; ++l) cl[l] = rows[buf][jj][8 * tc + l];
+        for (int l = 0; l < 8; ++l) cl[l] = rows[buf][jj][cb + l];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -171,91 +180,23 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(float* __restrict__ Uw, 
       }
     }
   }
+  if (role == 1) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int l = 0; l < 8; ++l) {
-      const int r = 8 * tr + i, c = 8 * tc + l;
-      const int64_t gr = r0 + r, gc = r0 + c;
-      if (gr < d && gc < d && r <= c) Uk[gr * d + gc] = a[i][l];
-    }
-  __syncthreads();
-  if (tid == 0 && bad >= 0 && info && info[k] == 0) info[k] = (int)(r0 + bad) + 1;
-}
-
-// (2) The panel right of the diagonal block: U11^T X = A12, 128 columns per workgroup, forward
-// substitution with the 128 x 128 tile of A12 in registers (thread (tk, tc) owns rows 8 tk, columns
-// 8 tc) and U11 in LDS.  Eight rows at a time: their owners solve against the 8 x 8 diagonal tile of
-// U11 on their own and publish the finished rows; after one barrier every tile further down loses the
-// product of the matching 8 x 8 tile of U11 and those rows.
-constexpr int kUPitch = kNb + 4;     // floats: rows 16-byte aligned for the four-float reads
-
-__global__ __launch_bounds__(256) void chol_panel_kernel(float* __restrict__ Uw, int64_t d, int64_t r0) {
-  __shared__ __attribute__((aligned(16))) float u[kNb][kUPitch];
-  __shared__ __attribute__((aligned(16))) float rows[2][8][kNb];
-  __shared__ float rdiag[kNb];
-  const int k = blockIdx.y;
-  float* Uk = Uw + (int64_t)k * d * d;
-  const int tid = threadIdx.x, tk = tid / 16, tc = tid % 16;
-  if (tid < kNb) rdiag[tid] = 1.f / Uk[(r0 + tid) * d + r0 + tid];
-  const int64_t c0 = r0 + kNb + (int64_t)blockIdx.x * kNb;
-  for (int idx = tid; idx < kNb * kNb; idx += 256) {
-    const int r = idx / kNb, c = idx % kNb;
-    const float v = Uk[(r0 + r) * d + r0 + (r <= c ? c : r)];  // the block row is complete: r0 + 127 < d
-    u[r][c] = r <= c ? v : 0.f;
-  }
-  float x[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int l = 0; l < 8; ++l) {
-      const int64_t gc = c0 + 8 * tc + l;
-      const float v = Uk[(r0 + 8 * tk + i) * d + (gc < d ? gc : d - 1)];
-      x[i][l] = gc < d ? v : 0.f;
-    }
-  __syncthreads();
-  for (int kb = 0; kb < 16; ++kb) {
-    const int buf = kb & 1;
-    if (tk == kb) {
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        const float rp = rdiag[8 * kb + jj];
-#pragma unroll
-        for (int l = 0; l < 8; ++l) {
-          float v = x[jj][l];
-#pragma unroll
-          for (int i = 0; i < jj; ++i) v -= u[8 * kb + i][8 * kb + jj] * x[i][l];
-          x[jj][l] = v * rp;
-        }
+      for (int l = 0; l < 8; ++l) {
+        const int64_t gr = r0 + 8 * tr + i, gc = c0 + 8 * tc + l;
+        if (gr < d && gc < d) Uk[gr * d + gc] = a[i][l];
       }
+  } else if (blockIdx.x == 0) {
+    float* Ub = Ud + ((int64_t)k * ((d + kNb - 1) / kNb) + r0 / kNb) * (kNb * kNb);
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int l = 0; l < 8; ++l) rows[buf][i][8 * tc + l] = x[i][l];
-    }
-    __syncthreads();
-    if (tk > kb) {
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        float f[8], xr[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = u[8 * kb + jj][8 * tk + i];
-#pragma unroll
-        for (int l = 0; l < 8; ++l) xr[l] = rows[buf][jj][8 * tc + l];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int l = 0; l < 8; ++l) x[i][l] -= f[i] * xr[l];
-      }
-    }
+      for (int l = 0; l < 8; ++l) Ub[(8 * tr + i) * kNb + 8 * tc + l] = (8 * tr + i <= 8 * tc + l) ? a[i][l] : 0.f;
   }
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int l = 0; l < 8; ++l) {
-      const int64_t gc = c0 + 8 * tc + l;
-      if (gc < d) Uk[(r0 + 8 * tk + i) * d + gc] = x[i][l];
-    }
+  __syncthreads();
+  if (tid == 0 && blockIdx.x == 0 && bad >= 0 && info && info[k] == 0) info[k] = (int)(r0 + bad) + 1;
 }
 
 // (3) Trailing update: for 128 x 128 tiles (ti <= tj) of the upper triangle with origin t0,
@@ -391,8 +332,8 @@ __global__ __launch_bounds__(256, 3) void chol_syrk_kernel(float* __restrict__ U
 
 // The factor in the requested form, every entry of F written: L[i][j] = U[j][i] (i >= j), zeros above
 // the diagonal; or R[i][j] = U[d-1-j][d-1-i] (i <= j), zeros below.  One workgroup per 64 x 64 tile of F.
-__global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict__ Uw, int64_t d, int reverse,
-                                                        float* __restrict__ F) {
+__global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict__ Uw, const float* __restrict__ Ud,
+                                                        int64_t d, int reverse, float* __restrict__ F) {
   __shared__ float tile[64][65];
   const int k = blockIdx.z;
   const float* Uk = Uw + (int64_t)k * d * d;
@@ -403,7 +344,13 @@ __global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict_
   for (int lj = ty; lj < 64; lj += 4) {
     const int64_t j = j0 + lj, i = i0 + tx;
     const int64_t sr = reverse ? d - 1 - j : j, sc = reverse ? d - 1 - i : i;
-    tile[lj][tx] = (i < d && j < d && sr >= 0 && sc >= 0 && sr <= sc) ? Uk[sr * d + sc] : 0.f;
+    const bool in = i < d && j < d && sr >= 0 && sc >= 0 && sr <= sc;
+    const int64_t srr = in ? sr : 0, scc = in ? sc : 0;
+    const float* src = (srr / kNb == scc / kNb)                // entries of a diagonal block live in Ud
+                           ? Ud + (((int64_t)k * ((d + kNb - 1) / kNb) + srr / kNb) * kNb + srr % kNb) * kNb + scc % kNb
+                           : Uk + srr * d + scc;
+    const float v = *src;
+    tile[lj][tx] = in ? v : 0.f;
   }
   __syncthreads();
   for (int li = ty; li < 64; li += 4) {
@@ -413,12 +360,13 @@ __global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict_
 }
 
 struct Layout {
-  size_t u_bytes, eps_bytes;
+  size_t u_bytes, ud_bytes, eps_bytes;
 };
 Layout make_layout(int64_t d, int G) {
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
   Layout L;
   L.u_bytes = up((size_t)G * d * d * sizeof(float));
+  L.ud_bytes = up((size_t)G * ((d + kNb - 1) / kNb) * kNb * kNb * sizeof(float));
   L.eps_bytes = up((size_t)G * sizeof(double));
   return L;
 }
@@ -427,41 +375,44 @@ Layout make_layout(int64_t d, int G) {
 
 size_t cholesky_workspace(int64_t d, int G) {
   const Layout L = make_layout(d, G);
-  return L.u_bytes + L.eps_bytes;
+  return L.u_bytes + L.ud_bytes + L.eps_bytes;
 }
 
 hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_rel, double damp_abs, bool reverse,
                                   float* F, int* info, void* ws, hipStream_t st) {
   const Layout L = make_layout(d, G);
   float* Uw = (float*)ws;
-  double* eps = (double*)((char*)ws + L.u_bytes);
+  float* Ud = (float*)((char*)ws + L.u_bytes);
+  double* eps = (double*)((char*)ws + L.u_bytes + L.ud_bytes);
   hipError_t e;
   chol_eps_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(H, d, damp_rel, damp_abs, eps, info);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const unsigned t64 = (unsigned)((d + 63) / 64);
   chol_load_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d, reverse ? 1 : 0, eps, Uw);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  // one block row: its diagonal block and, if there is anything to its right, the panel
+  auto block_row = [&](int64_t r0) -> hipError_t {
+    const int64_t trail = d - (r0 + kNb);
+    const int64_t tt = trail > 0 ? (trail + kNb - 1) / kNb : 0;
+    chol_block_row_kernel<<<dim3((unsigned)(tt > 0 ? tt : 1), (unsigned)G), dim3(tt > 0 ? 512 : 256), 0, st>>>(Uw, d, r0,
+                                                                                                            Ud, info);
+    return hipGetLastError();
+  };
   for (int64_t r0 = 0; r0 < d; r0 += 2 * kNb) {              // a pair of block rows per turn
-    chol_diag_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, info);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = block_row(r0)) != hipSuccess) return e;
     const int64_t t0 = r0 + kNb, trail = d - t0;
     if (trail <= 0) break;
     const int64_t tt = (trail + kNb - 1) / kNb;
-    chol_panel_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
     chol_syrk_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, kNb / kStep, t0, 1);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    chol_diag_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(Uw, d, t0, info);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = block_row(t0)) != hipSuccess) return e;
     const int64_t t1 = t0 + kNb, trail1 = d - t1;
     if (trail1 <= 0) break;
     const int64_t tt1 = (trail1 + kNb - 1) / kNb;
-    chol_panel_kernel<<<dim3((unsigned)tt1, (unsigned)G), dim3(256), 0, st>>>(Uw, d, t0);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
     chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, 2 * kNb / kStep, t1, 0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, d, reverse ? 1 : 0, F);
+  chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, Ud, d, reverse ? 1 : 0, F);
   return hipGetLastError();
 }
 

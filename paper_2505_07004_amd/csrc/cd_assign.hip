@@ -28,13 +28,6 @@ constexpr int kBlk = 128;             // coordinates per block
 constexpr int kRows = 64;             // channels per workgroup row tile (GEMM) / per wave (sequential kernel)
 constexpr int kMaxLevels = 16;        // most grid points per channel (4 bits)
 
-__device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
-  const __bf16 h = (__bf16)x;
-  const __bf16 l = (__bf16)(x - (float)h);
-  hi = __builtin_bit_cast(unsigned short, h);
-  lo = __builtin_bit_cast(unsigned short, l);
-}
-
 // Ht (hi/lo bf16, [G][ldp][ldp], row i contiguous over i', zero diagonal and zero padding) and
 // the fp32 coefficients of every diagonal block,
 //   Cd[k][blk][a][b] = Ht[blk*128 + b][blk*128 + a]

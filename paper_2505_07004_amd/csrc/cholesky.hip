@@ -10,8 +10,8 @@
 // Per block row:  (1) the 128 x 128 diagonal block is factored and (2) the panel to its right is solved
 // against it, U12 = U11^-T A12, in one launch (both with the block in registers, 8 x 8 per thread, eight
 // rows at a time published through LDS);
-// (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the fp32 matrix cores
-// (v_mfma_f32_32x32x2_f32), rows of U12 staged through LDS as they lie in memory.
+// (3) the trailing upper triangle is updated, A22 -= U12^T U12, on the bf16 matrix cores at fp32
+// accuracy (U12 as three bf16 terms, six products).
 // Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its
 // coordinate + 1, the first one) and replaced by 1 so that everything stays finite.
 #include "gq_internal.hpp"
@@ -20,6 +20,7 @@ namespace gq {
 namespace {
 
 constexpr int kNb = 128;             // block size
+constexpr int kPair = 2 * kNb;       // rows of U that one trailing update applies (a pair of block rows)
 
 // eps[k] and info[k] = 0.  One workgroup per group; fixed-order fp64 sum of the diagonal.
 __global__ __launch_bounds__(256) void chol_eps_kernel(const float* __restrict__ H, int64_t d, double damp_rel,
@@ -97,7 +98,8 @@ __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict_
 // later still have to read.
 // Rows and columns past the end of the matrix are those of the identity.
 __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__ Uw, int64_t d, int64_t r0,
-                                                             float* __restrict__ Ud, int* __restrict__ info) {
+                                                             float* __restrict__ Ud, unsigned short* __restrict__ P3,
+                                                             int64_t ldc, int koff, int* __restrict__ info) {
   __shared__ __attribute__((aligned(16))) float dtile[2][8][8];
   __shared__ __attribute__((aligned(16))) float rows[2][8][2 * kNb];   // columns 0..127: diagonal block, 128..255: panel
   __shared__ int bad;
@@ -188,6 +190,23 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
         const int64_t gr = r0 + 8 * tr + i, gc = c0 + 8 * tc + l;
         if (gr < d && gc < d) Uk[gr * d + gc] = a[i][l];
       }
+    // ... and once more for the trailing update: three bf16 terms, column-major (the rows of U12, the
+    // contraction index of the update, contiguous): P3[k][term][column][koff + row]; a thread's eight
+    // rows of one column are 16 bytes per term
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+      unsigned short t[3][8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) split3_bf16(a[i][l], t[0][i], t[1][i], t[2][i]);
+      const int64_t gc = c0 + 8 * tc + l;                         // < ldc: the buffer covers whole panels
+#pragma unroll
+      for (int term = 0; term < 3; ++term) {
+        u32x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (unsigned)t[term][2 * e] | ((unsigned)t[term][2 * e + 1] << 16);
+        *reinterpret_cast<u32x4*>(P3 + ((((int64_t)k * 3 + term) * ldc + gc) * kPair + koff + 8 * tr)) = w;
+      }
+    }
   } else if (blockIdx.x == 0) {
     float* Ub = Ud + ((int64_t)k * ((d + kNb - 1) / kNb) + r0 / kNb) * (kNb * kNb);
 #pragma unroll
@@ -200,44 +219,61 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
 }
 
 // (3) Trailing update: for 128 x 128 tiles (ti <= tj) of the upper triangle with origin t0,
-//   A[a][b] -= sum_{k < 16 n_steps} U[r0 + k][a] * U[r0 + k][b].
+//   A[a][b] -= sum_{k < n_k} U[r0 + k][a] * U[r0 + k][b],     n_k = 128 or 256.
 // Block rows are processed in pairs: after the first of a pair only the strip of the second one is
 // updated (strip = 1: the tiles of the first tile row, 128 rows of U), after the second everything
 // behind the pair with the 256 rows of both at once, which halves the read-modify-write traffic of the
-// trailing matrix.  4 waves of 64 x 64; the rows of U are staged through LDS as they lie in memory,
-// 16 at a time; the operand layout of the fp32 MFMA (lane -> column l%32, row l/32) reads that tile
-// row-wise.
-constexpr int kStep = 16;
-constexpr int kBufferWord3 = 0x00020000;       // raw buffer, 32-bit elements
+// trailing matrix.  The rows of U arrive as three bf16 terms each, contraction-major (P3, written by
+// the block-row kernel), and the product runs on the bf16 matrix cores at fp32 accuracy: of the nine
+// term products the six that matter (hi*hi, hi*mid, mid*hi, hi*lo, lo*hi, mid*mid; the others are
+// below 2^-24 of the result) -- 2.7 times fewer matrix-core cycles than the fp32 instruction.
+// 4 waves of 64 x 64; a stage is 32 contraction elements of the 2 x 3 x 128 operand rows (48 KiB,
+// global_load_lds_dwordx4, chunk c of row r at position c ^ ((r >> 2) & 3)), ring of three stages.
+// The tile itself is read and written through a buffer resource, 32 loads in flight, no branch.
+constexpr int kSK = 32;                               // contraction elements per stage
+constexpr int kSTile = kNb * kSK * 2;                 // one staged term of one side (8 KiB)
+constexpr int kSStage = 6 * kSTile;                   // {row side, column side} x {hi, mid, lo}: 48 KiB
+constexpr int kSRing = 3;
+constexpr int kSLoads = 12;                           // 1 KiB loads per wave and stage
+constexpr int kBufferWord3 = 0x00020000;              // raw buffer, 32-bit elements
 constexpr unsigned kBufferOutside = 0x7ffffff0u;
-constexpr int kSPitch = kNb + 32;    // floats; keeps the two rows of one MFMA read on disjoint banks
 
-__device__ inline f32x4 load4(const float* __restrict__ p, int64_t c, int64_t d, bool vec) {
-  f32x4 v = {0.f, 0.f, 0.f, 0.f};
-  if (vec) {                                                // d % 4 == 0: a group of four is inside or outside as a whole
-    const f32x4 w = *reinterpret_cast<const f32x4*>(c < d ? p : p - c);   // outside: the row's first four, not used
-    if (c < d) v = w;
-  } else {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (c + e < d) v[e] = p[e];
-  }
-  return v;
-}
-
-__global__ __launch_bounds__(256, 3) void chol_syrk_kernel(float* __restrict__ Uw, int64_t d, int64_t r0, int n_steps,
-                                                        int64_t t0, int strip) {
-  __shared__ __attribute__((aligned(16))) float As[2][kStep][kSPitch];
-  __shared__ __attribute__((aligned(16))) float Bs[2][kStep][kSPitch];
+__global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, int64_t d, const unsigned short* __restrict__ P3,
+                                                        int64_t ldc, int n_k, int64_t t0, int strip) {
+  __shared__ __attribute__((aligned(1024))) char smem[kSRing * kSStage];
   const int k = blockIdx.y;
   float* Uk = Uw + (int64_t)k * d * d;
   int ti = 0, tj = (int)blockIdx.x;                          // strip: the first tile row only
   if (!strip) tri_decode(blockIdx.x, ti, tj);                // ti <= tj
   const int64_t a0 = t0 + (int64_t)ti * kNb, b0 = t0 + (int64_t)tj * kNb;
-  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int wm = wave / 2, wn = wave % 2;
-  const int lrow = tid / 32, lcol = (tid % 32) * 4;          // staging: 16 rows x 32 float4 per operand, two per thread
-  const bool vec = d % 4 == 0;
+  const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
+
+  // staging: load g = 12 wave + i of a stage moves rows 16 (g % 8) .. + 15 of tile g / 8
+  // (tiles 0..2: the three terms of the tile's rows a0.., 3..5: of its columns b0..)
+  const unsigned short* lsrc[kSLoads];
+  unsigned ldst[kSLoads];
+#pragma unroll
+  for (int i = 0; i < kSLoads; ++i) {
+    const int g = wave * kSLoads + i, tile = g / 8, i8 = g % 8;
+    const int r = 16 * i8 + lane / 4;
+    const int c = (lane % 4) ^ ((r >> 2) & 3);
+    const int64_t col = (tile < 3 ? a0 : b0) + r;               // < ldc
+    lsrc[i] = P3 + ((((int64_t)k * 3 + tile % 3) * ldc + col) * kPair + 8 * c);
+    ldst[i] = tile * kSTile + i8 * 1024;
+  }
+  auto issue = [&](int stage, int slot) {
+#pragma unroll
+    for (int i = 0; i < kSLoads; ++i) dma16(lsrc[i] + stage * kSK, smem_base + slot * kSStage + ldst[i]);
+  };
+  const int lrow = lane % 32;
+  auto frag = [&](int slot, int tile, int row0, int t) -> bf16x8 {
+    const int pos = (2 * t + lane / 32) ^ ((lrow >> 2) & 3);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kSStage + tile * kSTile + (row0 + lrow) * 64 + pos * 16]);
+    return __builtin_bit_cast(bf16x8, v);
+  };
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -247,58 +283,41 @@ __global__ __launch_bounds__(256, 3) void chol_syrk_kernel(float* __restrict__ U
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // Two register sets: the rows of step s are fetched during step s - 2 and stashed at the end of step
-  // s - 1, so a load has a whole step of MFMAs (and the barrier) to arrive.  n_steps is even.
-  struct Regs {
-    f32x4 a[2], b[2];
-  } set0, set1;
-  auto fetch = [&](int step, Regs& rg) {
+  const int n_stages = n_k / kSK;                               // 4 or 8
+  issue(0, 0);
+  issue(1, 1);
+  for (int s = 0; s < n_stages; ++s) {
+    const int slot = s % kSRing;
+    if (s + 1 < n_stages) wait_vmcnt<kSLoads>();                // the next stage may still be in flight
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();                               // everyone's part of stage s is there; stage s - 1 is done with
+    if (s + 2 < n_stages) issue(s + 2, (s + 2) % kSRing);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const float* row = Uk + (r0 + step * kStep + lrow + 8 * h) * d;
-      rg.a[h] = load4(row + a0 + lcol, a0 + lcol, d, vec);
-      rg.b[h] = load4(row + b0 + lcol, b0 + lcol, d, vec);
-    }
-  };
-  auto stash = [&](int buf, const Regs& rg) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      *reinterpret_cast<f32x4*>(&As[buf][lrow + 8 * h][lcol]) = rg.a[h];
-      *reinterpret_cast<f32x4*>(&Bs[buf][lrow + 8 * h][lcol]) = rg.b[h];
-    }
-  };
-  auto one_step = [&](int step, Regs& mine, const Regs& next) {   // mine: held step `step`, free again; next: step + 1
-    const int buf = step & 1;
-    if (step + 2 < n_steps) fetch(step + 2, mine);
-#pragma unroll
-    for (int kk = 0; kk < kStep; kk += 2) {
-      float av[2], bv[2];
-#pragma unroll
-      for (int x = 0; x < 2; ++x) av[x] = As[buf][kk + lane / 32][wm * 64 + x * 32 + lane % 32];
-#pragma unroll
-      for (int y = 0; y < 2; ++y) bv[y] = Bs[buf][kk + lane / 32][wn * 64 + y * 32 + lane % 32];
+    for (int t = 0; t < kSK / 16; ++t) {
+      bf16x8 a[2][3], b[2][3];
 #pragma unroll
       for (int x = 0; x < 2; ++x)
 #pragma unroll
+        for (int term = 0; term < 3; ++term) {
+          a[x][term] = frag(slot, term, wm * 64 + x * 32, t);
+          b[x][term] = frag(slot, 3 + term, wn * 64 + x * 32, t);
+        }
+      // smallest products first; (row term, column term): (0,2) (2,0) (1,1) (0,1) (1,0) (0,0)
+      constexpr int kTa[6] = {0, 2, 1, 0, 1, 0}, kTb[6] = {2, 0, 1, 1, 0, 0};
+#pragma unroll
+      for (int pr = 0; pr < 6; ++pr)
+#pragma unroll
         for (int y = 0; y < 2; ++y)
-          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
+#pragma unroll
+          for (int x = 0; x < 2; ++x)
+            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x][kTa[pr]], b[y][kTb[pr]], acc[x][y], 0, 0, 0);
     }
-    if (step + 1 < n_steps) stash(buf ^ 1, next);
-    __syncthreads();
-  };
-  fetch(0, set0);
-  fetch(1, set1);
-  stash(0, set0);
-  __syncthreads();
-  for (int step = 0; step < n_steps; step += 2) {
-    one_step(step, set0, set1);
-    one_step(step + 1, set1, set0);
   }
+
   // accumulator register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32.
   // Straight-line code with every lane active: the trailing matrix is addressed through a buffer
   // resource that spans the valid rows of this wave's 64-row block; an entry below the diagonal or
   // right of column d gets an offset outside it (such a load returns 0, such a store is dropped).
-  // 32 loads are in flight together, then updated and stored.
   const int64_t row_w = a0 + wm * 64;
   const int64_t rows_valid = (d - row_w) < 64 ? (d - row_w) : 64;
   const int records = rows_valid > 0 ? (int)(rows_valid * d * (int64_t)sizeof(float)) : 0;
@@ -360,13 +379,16 @@ __global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict_
 }
 
 struct Layout {
-  size_t u_bytes, ud_bytes, eps_bytes;
+  int64_t ldc;
+  size_t u_bytes, ud_bytes, p3_bytes, eps_bytes;
 };
 Layout make_layout(int64_t d, int G) {
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
   Layout L;
   L.u_bytes = up((size_t)G * d * d * sizeof(float));
   L.ud_bytes = up((size_t)G * ((d + kNb - 1) / kNb) * kNb * kNb * sizeof(float));
+  L.ldc = (d + kNb - 1) / kNb * kNb;
+  L.p3_bytes = up((size_t)G * 3 * L.ldc * kPair * sizeof(unsigned short));
   L.eps_bytes = up((size_t)G * sizeof(double));
   return L;
 }
@@ -375,7 +397,7 @@ Layout make_layout(int64_t d, int G) {
 
 size_t cholesky_workspace(int64_t d, int G) {
   const Layout L = make_layout(d, G);
-  return L.u_bytes + L.ud_bytes + L.eps_bytes;
+  return L.u_bytes + L.ud_bytes + L.p3_bytes + L.eps_bytes;
 }
 
 hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_rel, double damp_abs, bool reverse,
@@ -383,7 +405,8 @@ hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_
   const Layout L = make_layout(d, G);
   float* Uw = (float*)ws;
   float* Ud = (float*)((char*)ws + L.u_bytes);
-  double* eps = (double*)((char*)ws + L.u_bytes + L.ud_bytes);
+  unsigned short* P3 = (unsigned short*)((char*)ws + L.u_bytes + L.ud_bytes);
+  double* eps = (double*)((char*)ws + L.u_bytes + L.ud_bytes + L.p3_bytes);
   hipError_t e;
   chol_eps_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(H, d, damp_rel, damp_abs, eps, info);
   if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -391,25 +414,25 @@ hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_
   chol_load_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d, reverse ? 1 : 0, eps, Uw);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // one block row: its diagonal block and, if there is anything to its right, the panel
-  auto block_row = [&](int64_t r0) -> hipError_t {
+  auto block_row = [&](int64_t r0, int koff) -> hipError_t {
     const int64_t trail = d - (r0 + kNb);
     const int64_t tt = trail > 0 ? (trail + kNb - 1) / kNb : 0;
-    chol_block_row_kernel<<<dim3((unsigned)(tt > 0 ? tt : 1), (unsigned)G), dim3(tt > 0 ? 512 : 256), 0, st>>>(Uw, d, r0,
-                                                                                                            Ud, info);
+    chol_block_row_kernel<<<dim3((unsigned)(tt > 0 ? tt : 1), (unsigned)G), dim3(tt > 0 ? 512 : 256), 0, st>>>(
+        Uw, d, r0, Ud, P3, L.ldc, koff, info);
     return hipGetLastError();
   };
   for (int64_t r0 = 0; r0 < d; r0 += 2 * kNb) {              // a pair of block rows per turn
-    if ((e = block_row(r0)) != hipSuccess) return e;
+    if ((e = block_row(r0, 0)) != hipSuccess) return e;
     const int64_t t0 = r0 + kNb, trail = d - t0;
     if (trail <= 0) break;
     const int64_t tt = (trail + kNb - 1) / kNb;
-    chol_syrk_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, kNb / kStep, t0, 1);
+    chol_syrk_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kNb, t0, 1);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = block_row(t0)) != hipSuccess) return e;
+    if ((e = block_row(t0, kNb)) != hipSuccess) return e;
     const int64_t t1 = t0 + kNb, trail1 = d - t1;
     if (trail1 <= 0) break;
     const int64_t tt1 = (trail1 + kNb - 1) / kNb;
-    chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, r0, 2 * kNb / kStep, t1, 0);
+    chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, 0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, Ud, d, reverse ? 1 : 0, F);

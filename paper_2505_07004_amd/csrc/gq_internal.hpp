@@ -34,6 +34,24 @@ __device__ inline void dma16(const void* gptr, unsigned lds_base) {
 __device__ inline void dma4(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
+// fp32 as a sum of bf16 terms (round to nearest even each): two terms carry 16 mantissa bits, three
+// carry all 24 (exact for every x whose exponent leaves room for the last term).
+__device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
+  const __bf16 h = (__bf16)x;
+  const __bf16 l = (__bf16)(x - (float)h);
+  hi = __builtin_bit_cast(unsigned short, h);
+  lo = __builtin_bit_cast(unsigned short, l);
+}
+__device__ inline void split3_bf16(float x, unsigned short& hi, unsigned short& mid, unsigned short& lo) {
+  const __bf16 h = (__bf16)x;
+  const float r1 = x - (float)h;
+  const __bf16 m = (__bf16)r1;
+  const __bf16 l = (__bf16)(r1 - (float)m);
+  hi = __builtin_bit_cast(unsigned short, h);
+  mid = __builtin_bit_cast(unsigned short, m);
+  lo = __builtin_bit_cast(unsigned short, l);
+}
+
 template <int N>
 __device__ inline void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");

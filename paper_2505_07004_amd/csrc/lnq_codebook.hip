@@ -29,17 +29,6 @@ constexpr int kLoadsPerStage = 7;                    // per wave: 6 pieces of H,
 constexpr unsigned kPadCode = 0x7F;                  // a code no grid point has
 constexpr unsigned kNoLevel = 0x7E7E7E7Eu;           // a grid point no code has (rows past the tile's channels)
 
-// x = hi + mid + lo, three bf16 terms (exact for every fp32 x whose exponent leaves room).
-__device__ inline void split3_bf16(float x, unsigned short& hi, unsigned short& mid, unsigned short& lo) {
-  const __bf16 h = (__bf16)x;
-  const float r1 = x - (float)h;
-  const __bf16 m = (__bf16)r1;
-  const __bf16 l = (__bf16)(r1 - (float)m);
-  hi = __builtin_bit_cast(unsigned short, h);
-  mid = __builtin_bit_cast(unsigned short, m);
-  lo = __builtin_bit_cast(unsigned short, l);
-}
-
 // The full symmetric H[k] from its upper triangle, split into three bf16 terms,
 // [G][ldp][ldp] each, zero padded.  One workgroup per 64 x 64 tile.
 __global__ __launch_bounds__(256) void lnq_split_h_kernel(const float* __restrict__ H, int64_t d, int64_t ldp,

@@ -42,13 +42,6 @@ constexpr int kTileElems = kTile * kKS;             // bf16 elements of one stag
 // fragment reads of 16 consecutive rows fall into 16 different bank groups.
 __host__ __device__ inline int tile_pos(int r, int e) { return r * kKS + ((((e >> 3) ^ (r >> 3)) & 1) << 3) + (e & 7); }
 
-__device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {
-  const __bf16 h = (__bf16)x;
-  const __bf16 l = (__bf16)(x - (float)h);
-  hi = __builtin_bit_cast(unsigned short, h);
-  lo = __builtin_bit_cast(unsigned short, l);
-}
-
 // Staged tiles of delta: block (k, rb) holds channels k*m + rb*128 + r, r < 128 (zero past the
 // end of the group), stage st the contraction elements 16 st .. 16 st + 15 (zero past d):
 //   Dh/Dl[((k*n_rb + rb) * n_st + st) * kTileElems + tile_pos(r, e)].

@@ -573,10 +573,12 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   const int64_t n_walk = (int64_t)L.n_rt * G, tiles = (int64_t)L.n_gt * G;
   const int64_t free_cus = n_walk < 192 ? 256 - n_walk : 64;
   int parts = (int)(free_cus / tiles);
+  if (parts < 1) parts = 1;
   // Where the GEMM outlasts the walk by far (about 2 us per 64-deep stage and workgroup against some
-  // 50 us of walk), it is cut finer than the compute units free at the start: the units the walk
-  // releases then pick up the rest.
-  if (tiles * (L.ldp / kGemmK) * 2 / free_cus > 80 && parts * tiles < 512) parts = (int)((512 + tiles - 1) / tiles);
+  // 50 us of walk) and would occupy well under the whole chip, it is cut finer than the compute units
+  // free at the start: the units the walk releases then pick up the rest.  (More parts also mean more
+  // partial sums for the walk to add, so shapes that fill the chip anyway are left alone.)
+  if (tiles * (L.ldp / kGemmK) * 2 / free_cus > 80 && parts * tiles < 160) parts = (int)((512 + tiles - 1) / tiles);
   const int max_parts = (int)((L.ldp / kGemmK - 2) / 2);
   if (parts > max_parts) parts = max_parts;
   if (parts > 16) parts = 16;

@@ -164,7 +164,8 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
                                               const unsigned short* __restrict__ Dl,
                                               const unsigned short* __restrict__ Hth,
                                               const unsigned short* __restrict__ Htl, int64_t d_out, int64_t ldp,
-                                              int G, int n_gt, int blk, int excl, float* __restrict__ C) {
+                                              int G, int n_gt, int n_rt, int blk, int excl,
+                                              float* __restrict__ C) {
   const int k = gidx / n_gt, gt = gidx % n_gt;
   const int64_t m = d_out / G;
   const int64_t j0 = (int64_t)k * m + (int64_t)gt * kGemmRows, j_last = (int64_t)(k + 1) * m - 1;
@@ -242,21 +243,32 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
   }
   __syncthreads();                                        // the ring is idle: the output tile may reuse it
 
-  // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4) (channel), column l%32 (coordinate)
-  float (*out)[kGemmRows + 1] = reinterpret_cast<float (*)[kGemmRows + 1]>(&smem[0]);   // [coordinate][channel]
+  // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4) (channel), column l%32 (coordinate): four
+  // consecutive channels per 16-byte LDS store.  The tile leaves as C[part][walk tile][coordinate][64
+  // channel slots] (the walk's tiles are 64 channels, so this tile covers two of them); rows past the
+  // end of the group repeat its last channel, which fills the slots the walk reads for lanes it never stores.
+  constexpr int kOutPitch = kGemmRows + 4;
+  float (*out)[kOutPitch] = reinterpret_cast<float (*)[kOutPitch]>(&smem[0]);   // [coordinate][channel]
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
     for (int y = 0; y < 2; ++y)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        out[wn * 64 + 32 * y + lane % 32][wm * 64 + 32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] = acc[x][y][r];
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[x][y][4 * r4 + e];
+        *reinterpret_cast<f32x4*>(&out[wn * 64 + 32 * y + lane % 32][wm * 64 + 32 * x + 8 * r4 + 4 * (lane / 32)]) = v;
+      }
   __syncthreads();
-  float* Cp = C + (int64_t)part * kBlk * d_out;
-  for (int idx = tid; idx < kBlk * kGemmRows; idx += 256) {
-    const int i = idx / kGemmRows, r = idx % kGemmRows;
-    const int64_t j = j0 + r;
-    if (j <= j_last) Cp[(int64_t)i * d_out + j] = out[i][r];
+  const int n_walk = n_rt * G;
+  for (int idx = tid; idx < kBlk * kGemmRows / 4; idx += 256) {
+    const int i = idx / (kGemmRows / 4), r = 4 * (idx % (kGemmRows / 4));
+    const int rt = 2 * gt + r / kRows;
+    if (rt < n_rt) {
+      float* dst = C + ((((int64_t)part * n_walk + k * n_rt + rt) * kBlk + i) * kRows + r % kRows);
+      *reinterpret_cast<f32x4*>(dst) = *reinterpret_cast<const f32x4*>(&out[i][r]);
+    }
   }
 }
 
@@ -273,13 +285,31 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
 // LV = 4, 8 or 16 bounds the number of grid points (the search is unrolled over it).
 constexpr int kRun = 32;
 constexpr int kQuadSwap1 = 0xB1, kQuadSwap2 = 0x4E;        // DPP quad_perm [1,0,3,2] and [2,3,0,1]
+// (every lane of a quad permutation has a source lane, so bound_ctrl only spares the fill of the old value)
 template <int CTRL>
 __device__ inline float quad_dpp(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ inline unsigned long long quad_key(float dist, int index) {
+  return ((unsigned long long)__builtin_bit_cast(unsigned, dist) << 32) | (unsigned)index;
 }
 template <int CTRL>
 __device__ inline int quad_dpp(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+// b[u] += the N parts p .. p + N - 1 of the partial sums, 4 channels of 8 coordinates (src points at the
+// thread's first one in part 0; a part is `part_stride` floats long): 8 N 16-byte loads in flight
+template <int N>
+__device__ __forceinline__ void add_parts(f32x4 (&b)[8], const float* __restrict__ src, int p, int64_t part_stride) {
+  f32x4 t[N][8];
+#pragma unroll
+  for (int v = 0; v < N; ++v)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[v][u] = *reinterpret_cast<const f32x4*>(src + (p + v) * part_stride + u * kRows);
+#pragma unroll
+  for (int v = 0; v < N; ++v)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) b[u] += t[v][u];
 }
 constexpr int kWalkTw = 0;                                              // byte offsets of the walk's LDS arrays
 constexpr int kWalkCur = kWalkTw + kBlk * (kRows + 1) * 4;
@@ -296,7 +326,7 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
                                           int64_t ld, int64_t ldp, int G, int n_rt, int blk, int prev,
                                           unsigned char* __restrict__ Q, unsigned short* __restrict__ Dh,
                                           unsigned short* __restrict__ Dl) {
-  float (*tw)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkTw);      // the block of W; then the targets; then W again
+  float (*tw)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkTw);      // the block of W; then the targets
   float (*cur)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkCur);    // the block of What, old values then new ones
   float (*coef)[kBlk] = reinterpret_cast<float (*)[kBlk]>(smem + kWalkCoef);            // coef[a][b] = Ht[i0 + b][i0 + a]
   unsigned char (*code)[kRows + 4] = reinterpret_cast<unsigned char (*)[kRows + 4]>(smem + kWalkCode);
@@ -307,6 +337,54 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   const int n_rows = (int)((j_last - j0 + 1) < kRows ? (j_last - j0 + 1) : kRows);
   const int64_t i0 = (int64_t)blk * kBlk;
   const int n_valid = (int)((d - i0) < kBlk ? (d - i0) : kBlk);   // coordinates of this block inside the matrix
+
+  // The block's 128 x 128 coefficients go straight into LDS (64 KiB, 16 direct loads per wave), and the
+  // rows of W and What into registers: wave w moves rows 16 w .. 16 w + 15, lane l the coordinates l and
+  // l + 64; everything is in flight while the matrix cores work on the predecessor's share below.
+  {
+    const float* src = Cd + (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk;
+    const unsigned dst = (unsigned)(uintptr_t)(lds_char_ptr)(smem + kWalkCoef);
+    const int w_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dma16(src + (w_u * 16 + i) * 256 + lane * 4, dst + (w_u * 16 + i) * 1024);
+  }
+  // 16 bytes per lane: wave w moves rows 16 w .. 16 w + 15, two at a time, lane l the coordinates
+  // 4 (l % 32) .. + 3 of row l / 32 of the pair.  Rows are 16-byte aligned and ld is a multiple of 4, so a
+  // vector that starts inside the matrix ends inside the row; coordinates past the end count as zero.
+  const int vc = 4 * (lane % 32);                           // first coordinate of this lane's vectors
+  const bool vec_in = i0 + vc < d;
+  f32x4 wreg[8], creg[8];                                   // W stays in registers for the write-back
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int r = 16 * wave + 2 * u + lane / 32;
+    const int64_t jr = r < n_rows ? j0 + r : j_last;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    wreg[u] = vec_in ? *reinterpret_cast<const f32x4*>(W + jr * ld + i0 + vc) : zero;
+    creg[u] = vec_in ? *reinterpret_cast<const f32x4*>(What + jr * ld + i0 + vc) : zero;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (i0 + vc + e >= d) {
+        wreg[u][e] = 0.f;
+        creg[u][e] = 0.f;
+      }
+  }
+
+  // B0 = the sum of the parts in order (final since the previous launch).  Thread: channels 4 (tid % 16)
+  // .. + 3, coordinates 8 (tid / 16) .. + 7; up to 32 16-byte loads in flight behind the ones above.
+  f32x4 b0[8];
+  {
+    const int64_t part_stride = (int64_t)n_rt * G * kBlk * kRows;
+    const float* src = C + ((int64_t)tile * kBlk + 8 * (tid / 16)) * kRows + 4 * (tid % 16);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) b0[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int p = 0;
+    for (; p + 4 <= n_parts; p += 4) add_parts<4>(b0, src, p, part_stride);
+    if (p + 2 <= n_parts) {
+      add_parts<2>(b0, src, p, part_stride);
+      p += 2;
+    }
+    if (p < n_parts) add_parts<1>(b0, src, p, part_stride);
+  }
 
   // The share of block `prev` (final since the previous launch; the GEMM stepped over it):
   //   near[j][i] = sum_{i' in prev} delta[j][i'] * Ht[i0 + i][i'],   64 channels x 128 coordinates x 128,
@@ -351,56 +429,21 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
         }
     }
   }
-  {
-    const f32x4* src = reinterpret_cast<const f32x4*>(Cd + (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk);
-    f32x4* dst = reinterpret_cast<f32x4*>(&coef[0][0]);
-#pragma unroll 8
-    for (int q4 = tid; q4 < kBlk * kBlk / 4; q4 += 256) dst[q4] = src[q4];
-  }
-  // rows of W (and What): wave w moves rows 16 w .. 16 w + 15, 8 at a time with all loads in flight together
-  auto load_rows = [&](bool with_what) {
-    for (int r0 = 16 * wave; r0 < 16 * wave + 16; r0 += 8) {
-      float wv[8][2], cv[8][2];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int64_t jr = (r0 + u) < n_rows ? j0 + r0 + u : j_last;
+  for (int u = 0; u < 8; ++u)
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const int i = lane + 64 * half;
-          const int64_t a = (i0 + i) < d ? (i0 + i) : d - 1;
-          wv[u][half] = W[jr * ld + a];
-          if (with_what) cv[u][half] = What[jr * ld + a];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          tw[lane + 64 * half][r0 + u] = wv[u][half];
-          if (with_what) cur[lane + 64 * half][r0 + u] = cv[u][half];
-        }
+    for (int e = 0; e < 4; ++e) {
+      tw[vc + e][16 * wave + 2 * u + lane / 32] = wreg[u][e];
+      cur[vc + e][16 * wave + 2 * u + lane / 32] = creg[u][e];
     }
-  };
-  load_rows(true);
+  wait_vmcnt<0>();                                          // this wave's part of the coefficients has landed
   __syncthreads();
 
-  // targets t[i] = w[i] - B0[i], in place; B0 = sum of the parts in order.  Thread: channel tid % 64,
-  // coordinates 32 (tid / 64) .. + 31, 16 in flight.
-  {
-    const int r = tid % kRows;
-    const int64_t jr = r < n_rows ? j0 + r : j_last;
-    for (int ib = 32 * (tid / kRows); ib < 32 * (tid / kRows) + 32; ib += 16) {
-      float b[16];
+  // targets t[i] = w[i] - B0[i], in place
 #pragma unroll
-      for (int u = 0; u < 16; ++u) b[u] = 0.f;
-      for (int p = 0; p < n_parts; ++p) {
+  for (int u = 0; u < 8; ++u)
 #pragma unroll
-        for (int u = 0; u < 16; ++u) b[u] += C[((int64_t)p * kBlk + ib + u) * d_out + jr];
-      }
-#pragma unroll
-      for (int u = 0; u < 16; ++u) tw[ib + u][r] -= b[u];
-    }
-  }
+    for (int e = 0; e < 4; ++e) tw[8 * (tid / 16) + u][4 * (tid % 16) + e] -= b0[u][e];
   __syncthreads();
   // register r of lane l holds channel 8*(r/4)+4*(l/32)+(r%4) of a block of 32, coordinate l%32 of the wave's 32
 #pragma unroll
@@ -416,12 +459,10 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   const int ch = 16 * wave + lane / 4, q = lane % 4;
   const int64_t j = ch < n_rows ? j0 + ch : j_last;
   float grid[LV / 4];
-  bool usable[LV / 4];
 #pragma unroll
   for (int u = 0; u < LV / 4; ++u) {
     const int lvl = q + 4 * u;
-    usable[u] = lvl < n_levels;
-    grid[u] = codebook[j * n_levels + (usable[u] ? lvl : n_levels - 1)];
+    grid[u] = lvl < n_levels ? codebook[j * n_levels + lvl] : __builtin_inff();
   }
 
   for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
@@ -451,22 +492,25 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
         case 2: ti = quad_dpp<kBroadcast[2]>(own[ii % 8]); break;
         default: ti = quad_dpp<kBroadcast[3]>(own[ii % 8]); break;
       }
-      // this lane's quarter of the grid (levels q, q + 4, ...: increasing, so '<' keeps the lower index)
-      float best = usable[0] ? fabsf(grid[0] - ti) : __builtin_inff(), val = grid[0];
+      // this lane's quarter of the grid (levels q, q + 4, ...: increasing, so '<' keeps the lower index;
+      // a level past the end of the grid holds +inf and is never nearer)
+      float best = fabsf(grid[0] - ti), val = grid[0];
       int bq = q;
 #pragma unroll
       for (int u = 1; u < LV / 4; ++u) {
         const float dist = fabsf(grid[u] - ti);
-        const bool better = usable[u] && (dist < best);
+        const bool better = dist < best;
         best = better ? dist : best;
         val = better ? grid[u] : val;
         bq = better ? q + 4 * u : bq;
       }
-      // settle it inside the quad: nearest point, lowest index among equally near ones
+      // settle it inside the quad: nearest point, lowest index among equally near ones.  Distances are
+      // not negative, so their bit patterns order like the numbers, and (distance, index) compares as
+      // one 64-bit key.
       {
         const float ob = quad_dpp<kQuadSwap1>(best), ov = quad_dpp<kQuadSwap1>(val);
         const int oq = quad_dpp<kQuadSwap1>(bq);
-        const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
+        const bool take = quad_key(ob, oq) < quad_key(best, bq);
         best = take ? ob : best;
         val = take ? ov : val;
         bq = take ? oq : bq;
@@ -474,8 +518,7 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
       {
         const float ob = quad_dpp<kQuadSwap2>(best), ov = quad_dpp<kQuadSwap2>(val);
         const int oq = quad_dpp<kQuadSwap2>(bq);
-        const bool take = (ob < best) | ((ob == best) & (oq < bq));   // no short circuit: no branch
-        best = take ? ob : best;
+        const bool take = quad_key(ob, oq) < quad_key(best, bq);
         val = take ? ov : val;
         bq = take ? oq : bq;
       }
@@ -508,25 +551,41 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
     }
   }
   __syncthreads();
-  load_rows(false);                                         // W again, for the new delta
-  __syncthreads();
 
-  // write the block back row by row: What, the codes, and the split delta for the next block's GEMM
-  for (int r = 16 * wave; r < 16 * wave + 16 && r < n_rows; ++r) {
-    const int64_t jr = j0 + r;
+  // write the block back: What, the codes, and the split delta for the next block's GEMM; the lanes keep
+  // the rows and coordinates they loaded (W is still in their registers)
+  const bool q_packed = Q && d % 4 == 0 && (reinterpret_cast<uintptr_t>(Q) & 3) == 0;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int i = lane + 64 * half;
-      if (i < n_valid) {
-        const int64_t a = i0 + i;
-        const float v = cur[i][r];
-        What[jr * ld + a] = v;
-        if (Q) Q[jr * d + a] = code[i][r];
-        unsigned short h, l;
-        split_bf16(v - tw[i][r], h, l);
-        Dh[jr * ldp + a] = h;
-        Dl[jr * ldp + a] = l;
+  for (int u = 0; u < 8; ++u) {
+    const int r = 16 * wave + 2 * u + lane / 32;
+    const int64_t jr = j0 + r;
+    if ((r < n_rows) & vec_in) {
+      const int64_t a = i0 + vc;
+      f32x4 v;
+      unsigned codes = 0;
+      unsigned short h[4], l[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[e] = cur[vc + e][r];
+        codes |= (unsigned)code[vc + e][r] << (8 * e);
+        split_bf16(a + e < d ? v[e] - wreg[u][e] : 0.f, h[e], l[e]);
       }
+      if (a + 3 < d) {
+        *reinterpret_cast<f32x4*>(What + jr * ld + a) = v;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 3; ++e)
+          if (a + e < d) What[jr * ld + a + e] = v[e];
+      }
+      if (q_packed) {
+        *reinterpret_cast<unsigned*>(Q + jr * d + a) = codes;
+      } else if (Q) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (a + e < d) Q[jr * d + a + e] = (unsigned char)(codes >> (8 * e));
+      }
+      *reinterpret_cast<u32x2*>(Dh + jr * ldp + a) = u32x2{h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16)};
+      *reinterpret_cast<u32x2*>(Dl + jr * ldp + a) = u32x2{l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16)};
     }
   }
 }
@@ -553,7 +612,8 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
                   n_rt, blk, prev, Q, Dh, Dl);
   } else {
     const int g = (int)blockIdx.x - n_walk, n_tiles = n_gt * G;
-    gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, next_blk, blk, Cout);
+    gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, n_rt, next_blk, blk,
+                  Cout);
   }
 }
 
@@ -588,7 +648,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   L.ht_bytes = up((size_t)G * L.ldp * L.ldp * 2);
   L.cdt_bytes = up((size_t)G * L.n_blk * kBlk * kBlk * sizeof(float));
   L.delta_bytes = up((size_t)d_out * L.ldp * 2);
-  L.c_bytes = up((size_t)L.n_parts * kBlk * d_out * sizeof(float));   // one of the two buffers that alternate
+  L.c_bytes = up((size_t)L.n_parts * n_walk * kBlk * kRows * sizeof(float));   // one of the two buffers that alternate
   return L;
 }
 

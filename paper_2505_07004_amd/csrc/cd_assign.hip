@@ -315,7 +315,9 @@ constexpr int kWalkTw = 0;                                              // byte 
 constexpr int kWalkCur = kWalkTw + kBlk * (kRows + 1) * 4;
 constexpr int kWalkCoef = kWalkCur + kBlk * (kRows + 1) * 4;
 constexpr int kWalkCode = kWalkCoef + kBlk * kBlk * 4;
-constexpr int kWalkBytes = kWalkCode + kBlk * (kRows + 4);
+constexpr int kWalkEps = kWalkCode + kBlk * (kRows + 4);                // the changes made in the current run
+constexpr int kWalkBytes = kWalkEps + kRun * (kRows + 1) * 4;
+static_assert(kWalkEps % 4 == 0, "floats");
 static_assert(kWalkCoef % 16 == 0, "the coefficient rows are read 16 bytes at a time");
 template <int LV>
 __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __restrict__ C, int n_parts,
@@ -330,6 +332,7 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   float (*cur)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkCur);    // the block of What, old values then new ones
   float (*coef)[kBlk] = reinterpret_cast<float (*)[kBlk]>(smem + kWalkCoef);            // coef[a][b] = Ht[i0 + b][i0 + a]
   unsigned char (*code)[kRows + 4] = reinterpret_cast<unsigned char (*)[kRows + 4]>(smem + kWalkCode);
+  float (*eps)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkEps);
   const int k = tile / n_rt, rt = tile % n_rt;
   const int64_t m = d_out / G;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -468,7 +471,7 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
     // Coordinates past the end of the matrix (last block only) are walked like the others: their
     // coefficients are zero, so nothing they do reaches a real coordinate, and they are not stored.
-    float own[8], eps[kRun], was[kRun];
+    float own[8], was[kRun];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) own[kk] = tw[c0 + 8 * q + kk][ch];
 #pragma unroll
@@ -525,32 +528,33 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
       const float e = val - was[ii];
       cur[c0 + ii][ch] = val;                               // all four lanes of the quad store the same value
       code[c0 + ii][ch] = (unsigned char)bq;
-      eps[ii] = e;
+      eps[ii][ch] = e;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         own[kk] -= e * c_lo[kk];                            // (targets already used are corrected too: harmless)
         own[4 + kk] -= e * c_hi[kk];
       }
     }
-    for (int c1 = c0 + kRun; c1 < n_valid; c1 += kRun) {    // the targets after the run, a run at a time
-      float a[8];
+    // The targets after the run, on the matrix cores (fp32 operands): for the wave's 16 channels
+    //   t[ch][x] -= sum_ii eps[ch][ii] * coef[c0 + ii][x],   x = c0 + 32 .. , 16 coordinates at a time.
+    // 16x16x4: lane l gives A[channel l % 16][ii = 4 s + l / 16] and B[ii = 4 s + l / 16][x = l % 16], and
+    // holds the sums of channels 4 (l / 16) .. + 3 for coordinate l % 16.
+    __syncthreads();                                        // the changes of the run are in LDS
+    if (c0 + kRun < n_valid) {                              // uniform
+      float a_frag[kRun / 4];
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) a[kk] = 0.f;
+      for (int s = 0; s < kRun / 4; ++s) a_frag[s] = eps[4 * s + lane / 16][16 * wave + lane % 16];
+      for (int c1 = c0 + kRun; c1 < n_valid; c1 += 16) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ii = 0; ii < kRun; ++ii) {
-        const f32x4* row = reinterpret_cast<const f32x4*>(&coef[c0 + ii][c1 + 8 * q]);
-        const f32x4 c_lo = row[0], c_hi = row[1];
+        for (int s = 0; s < kRun / 4; ++s)
+          acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s], coef[c0 + 4 * s + lane / 16][c1 + lane % 16], acc, 0, 0, 0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          a[kk] += eps[ii] * c_lo[kk];
-          a[4 + kk] += eps[ii] * c_hi[kk];
-        }
+        for (int r = 0; r < 4; ++r) tw[c1 + lane % 16][16 * wave + 4 * (lane / 16) + r] -= acc[r];
       }
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) tw[c1 + 8 * q + kk][ch] -= a[kk];
     }
+    __syncthreads();                                        // the corrected targets, before the next run reads them
   }
-  __syncthreads();
 
   // write the block back: What, the codes, and the split delta for the next block's GEMM; the lanes keep
   // the rows and coordinates they loaded (W is still in their registers)

@@ -174,9 +174,9 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
   const int wm = wave / 2, wn = wave % 2;
 
   // contraction range of this part, in stages of 64; the excluded block's two stages are stepped over
-  const int64_t n_stages = ldp / kGemmK - 2;
+  const int64_t n_stages = ldp / kGemmK - (excl >= 0 ? 2 : 0);
   const int64_t s0 = (int64_t)part * n_stages / n_parts, s1 = ((int64_t)part + 1) * n_stages / n_parts;
-  const int64_t skip_from = 2 * (int64_t)excl;
+  const int64_t skip_from = excl >= 0 ? 2 * (int64_t)excl : n_stages;   // excl < 0: nothing is stepped over
 
   // ---- staging: wave w copies operand w (0: delta hi, 1: delta lo, 2: Ht hi, 3: Ht lo); load
   // number i moves rows 8 i .. 8 i + 7, lane -> (row 8 i + lane / 8, position lane % 8)
@@ -232,23 +232,25 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
       }
 #pragma unroll
       for (int y = 0; y < 2; ++y) {
-        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[0], bh[y], acc[0][y], 0, 0, 0);
-        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[1], bh[y], acc[1][y], 0, 0, 0);
-        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[0], bl[y], acc[0][y], 0, 0, 0);
-        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[1], bl[y], acc[1][y], 0, 0, 0);
-        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[0], bh[y], acc[0][y], 0, 0, 0);
-        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[1], bh[y], acc[1][y], 0, 0, 0);
+        // (Ht first: the result's rows, which a lane holds four at a time, are then coordinates)
+        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[y], al[0], acc[0][y], 0, 0, 0);
+        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[y], al[1], acc[1][y], 0, 0, 0);
+        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl[y], ah[0], acc[0][y], 0, 0, 0);
+        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl[y], ah[1], acc[1][y], 0, 0, 0);
+        acc[0][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[y], ah[0], acc[0][y], 0, 0, 0);
+        acc[1][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[y], ah[1], acc[1][y], 0, 0, 0);
       }
     }
   }
   __syncthreads();                                        // the ring is idle: the output tile may reuse it
 
-  // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4) (channel), column l%32 (coordinate): four
-  // consecutive channels per 16-byte LDS store.  The tile leaves as C[part][walk tile][coordinate][64
-  // channel slots] (the walk's tiles are 64 channels, so this tile covers two of them); rows past the
-  // end of the group repeat its last channel, which fills the slots the walk reads for lanes it never stores.
-  constexpr int kOutPitch = kGemmRows + 4;
-  float (*out)[kOutPitch] = reinterpret_cast<float (*)[kOutPitch]>(&smem[0]);   // [coordinate][channel]
+  // register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4) (coordinate), column l%32 (channel): four
+  // consecutive coordinates per 16-byte LDS store.  The tile leaves as C[part][walk tile][64 channel
+  // slots][coordinate] (the walk's tiles are 64 channels, so this tile covers two of them), the layout
+  // of W itself; rows past the end of the group repeat its last channel, which fills the slots the walk
+  // reads for lanes it never stores.
+  constexpr int kOutPitch = kBlk + 4;
+  float (*out)[kOutPitch] = reinterpret_cast<float (*)[kOutPitch]>(&smem[0]);   // [channel][coordinate]
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
@@ -258,16 +260,16 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[x][y][4 * r4 + e];
-        *reinterpret_cast<f32x4*>(&out[wn * 64 + 32 * y + lane % 32][wm * 64 + 32 * x + 8 * r4 + 4 * (lane / 32)]) = v;
+        *reinterpret_cast<f32x4*>(&out[wm * 64 + 32 * x + lane % 32][wn * 64 + 32 * y + 8 * r4 + 4 * (lane / 32)]) = v;
       }
   __syncthreads();
   const int n_walk = n_rt * G;
-  for (int idx = tid; idx < kBlk * kGemmRows / 4; idx += 256) {
-    const int i = idx / (kGemmRows / 4), r = 4 * (idx % (kGemmRows / 4));
+  for (int idx = tid; idx < kGemmRows * kBlk / 4; idx += 256) {
+    const int r = idx / (kBlk / 4), i = 4 * (idx % (kBlk / 4));
     const int rt = 2 * gt + r / kRows;
     if (rt < n_rt) {
-      float* dst = C + ((((int64_t)part * n_walk + k * n_rt + rt) * kBlk + i) * kRows + r % kRows);
-      *reinterpret_cast<f32x4*>(dst) = *reinterpret_cast<const f32x4*>(&out[i][r]);
+      float* dst = C + ((((int64_t)part * n_walk + k * n_rt + rt) * kRows + r % kRows) * kBlk + i);
+      *reinterpret_cast<f32x4*>(dst) = *reinterpret_cast<const f32x4*>(&out[r][i]);
     }
   }
 }
@@ -297,20 +299,21 @@ template <int CTRL>
 __device__ inline int quad_dpp(int v) {
   return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
 }
-// b[u] += the N parts p .. p + N - 1 of the partial sums, 4 channels of 8 coordinates (src points at the
-// thread's first one in part 0; a part is `part_stride` floats long): 8 N 16-byte loads in flight
+// b[u] += the N parts p .. p + N - 1 of the partial sums, 4 coordinates of 8 channels two rows apart (src
+// points at the thread's first one in part 0; a part is `part_stride` floats long): 8 N 16-byte loads in flight
 template <int N>
 __device__ __forceinline__ void add_parts(f32x4 (&b)[8], const float* __restrict__ src, int p, int64_t part_stride) {
   f32x4 t[N][8];
 #pragma unroll
   for (int v = 0; v < N; ++v)
 #pragma unroll
-    for (int u = 0; u < 8; ++u) t[v][u] = *reinterpret_cast<const f32x4*>(src + (p + v) * part_stride + u * kRows);
+    for (int u = 0; u < 8; ++u) t[v][u] = *reinterpret_cast<const f32x4*>(src + (p + v) * part_stride + u * 2 * kBlk);
 #pragma unroll
   for (int v = 0; v < N; ++v)
 #pragma unroll
     for (int u = 0; u < 8; ++u) b[u] += t[v][u];
 }
+constexpr int kDeltaPitch = kBlk * 2 + 16;                              // bytes per channel of a delta half staged in LDS
 constexpr int kWalkTw = 0;                                              // byte offsets of the walk's LDS arrays
 constexpr int kWalkCur = kWalkTw + kBlk * (kRows + 1) * 4;
 constexpr int kWalkCoef = kWalkCur + kBlk * (kRows + 1) * 4;
@@ -318,6 +321,7 @@ constexpr int kWalkCode = kWalkCoef + kBlk * kBlk * 4;
 constexpr int kWalkEps = kWalkCode + kBlk * (kRows + 4);                // the changes made in the current run
 constexpr int kWalkBytes = kWalkEps + kRun * (kRows + 1) * 4;
 static_assert(kWalkEps % 4 == 0, "floats");
+static_assert(2 * kRows * kDeltaPitch <= kWalkCode - kWalkCoef, "the staged delta halves fit where the coefficients were");
 static_assert(kWalkCoef % 16 == 0, "the coefficient rows are read 16 bytes at a time");
 template <int LV>
 __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __restrict__ C, int n_parts,
@@ -325,10 +329,10 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
                                           const float* __restrict__ codebook, int n_levels,
                                           const float* __restrict__ Cd, const unsigned short* __restrict__ Hth,
                                           const unsigned short* __restrict__ Htl, int64_t d_out, int64_t d,
-                                          int64_t ld, int64_t ldp, int G, int n_rt, int blk, int prev,
+                                          int64_t ld, int64_t ldp, int G, int n_rt, int blk, int next_blk,
                                           unsigned char* __restrict__ Q, unsigned short* __restrict__ Dh,
-                                          unsigned short* __restrict__ Dl) {
-  float (*tw)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkTw);      // the block of W; then the targets
+                                          unsigned short* __restrict__ Dl, float* __restrict__ E) {
+  float (*tw)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkTw);      // the targets
   float (*cur)[kRows + 1] = reinterpret_cast<float (*)[kRows + 1]>(smem + kWalkCur);    // the block of What, old values then new ones
   float (*coef)[kBlk] = reinterpret_cast<float (*)[kBlk]>(smem + kWalkCoef);            // coef[a][b] = Ht[i0 + b][i0 + a]
   unsigned char (*code)[kRows + 4] = reinterpret_cast<unsigned char (*)[kRows + 4]>(smem + kWalkCode);
@@ -342,8 +346,7 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   const int n_valid = (int)((d - i0) < kBlk ? (d - i0) : kBlk);   // coordinates of this block inside the matrix
 
   // The block's 128 x 128 coefficients go straight into LDS (64 KiB, 16 direct loads per wave), and the
-  // rows of W and What into registers: wave w moves rows 16 w .. 16 w + 15, lane l the coordinates l and
-  // l + 64; everything is in flight while the matrix cores work on the predecessor's share below.
+  // rows of W and What into registers.
   {
     const float* src = Cd + (((int64_t)k * (ldp / kBlk) + blk) * kBlk) * kBlk;
     const unsigned dst = (unsigned)(uintptr_t)(lds_char_ptr)(smem + kWalkCoef);
@@ -351,6 +354,16 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
 #pragma unroll
     for (int i = 0; i < 16; ++i) dma16(src + (w_u * 16 + i) * 256 + lane * 4, dst + (w_u * 16 + i) * 1024);
   }
+  // the walk proper: channel ch of the tile, lane q of its quad, which tries levels q, q + 4, ...
+  const int ch = 16 * wave + lane / 4, q = lane % 4;
+  const int64_t j = ch < n_rows ? j0 + ch : j_last;
+  float grid[LV / 4];
+#pragma unroll
+  for (int u = 0; u < LV / 4; ++u) {
+    const int lvl = q + 4 * u;
+    grid[u] = lvl < n_levels ? codebook[j * n_levels + lvl] : __builtin_inff();
+  }
+
   // 16 bytes per lane: wave w moves rows 16 w .. 16 w + 15, two at a time, lane l the coordinates
   // 4 (l % 32) .. + 3 of row l / 32 of the pair.  Rows are 16-byte aligned and ld is a multiple of 4, so a
   // vector that starts inside the matrix ends inside the row; coordinates past the end count as zero.
@@ -372,12 +385,12 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
       }
   }
 
-  // B0 = the sum of the parts in order (final since the previous launch).  Thread: channels 4 (tid % 16)
-  // .. + 3, coordinates 8 (tid / 16) .. + 7; up to 32 16-byte loads in flight behind the ones above.
+  // B0 = the sum of the parts in order (final since the previous launch), laid out like W and moved by
+  // the same lanes; up to 32 16-byte loads in flight behind the ones above.
   f32x4 b0[8];
   {
     const int64_t part_stride = (int64_t)n_rt * G * kBlk * kRows;
-    const float* src = C + ((int64_t)tile * kBlk + 8 * (tid / 16)) * kRows + 4 * (tid % 16);
+    const float* src = C + ((int64_t)tile * kRows + 16 * wave + lane / 32) * kBlk + vc;
 #pragma unroll
     for (int u = 0; u < 8; ++u) b0[u] = f32x4{0.f, 0.f, 0.f, 0.f};
     int p = 0;
@@ -389,83 +402,26 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
     if (p < n_parts) add_parts<1>(b0, src, p, part_stride);
   }
 
-  // The share of block `prev` (final since the previous launch; the GEMM stepped over it):
-  //   near[j][i] = sum_{i' in prev} delta[j][i'] * Ht[i0 + i][i'],   64 channels x 128 coordinates x 128,
-  // on the matrix cores, wave w the coordinates 32 w .. 32 w + 31; fragments straight from global memory.
-  f32x16 near[2];
-  {
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) near[x][r] = 0.f;
-    const int64_t kcol = (int64_t)prev * kBlk + 8 * (lane / 32);
-    int64_t arow[2];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const int r = 32 * x + lane % 32;
-      arow[x] = (r < n_rows ? j0 + r : j_last) * ldp + kcol;
-    }
-    const int64_t brow = (int64_t)k * ldp * ldp + (i0 + 32 * wave + lane % 32) * ldp + kcol;
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {                  // 4 of the 8 contraction steps at a time: 24 loads in flight
-      u32x4 fa[4][2][2], fb[4][2];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int off = 16 * (4 * half + t);
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          fa[t][x][0] = *reinterpret_cast<const u32x4*>(Dh + arow[x] + off);
-          fa[t][x][1] = *reinterpret_cast<const u32x4*>(Dl + arow[x] + off);
-        }
-        fb[t][0] = *reinterpret_cast<const u32x4*>(Hth + brow + off);
-        fb[t][1] = *reinterpret_cast<const u32x4*>(Htl + brow + off);
-      }
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          const bf16x8 ah = __builtin_bit_cast(bf16x8, fa[t][x][0]), al = __builtin_bit_cast(bf16x8, fa[t][x][1]);
-          const bf16x8 bh = __builtin_bit_cast(bf16x8, fb[t][0]), bl = __builtin_bit_cast(bf16x8, fb[t][1]);
-          near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, near[x], 0, 0, 0);
-          near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, near[x], 0, 0, 0);
-          near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, near[x], 0, 0, 0);
-        }
-    }
-  }
 #pragma unroll
   for (int u = 0; u < 8; ++u)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      tw[vc + e][16 * wave + 2 * u + lane / 32] = wreg[u][e];
+      tw[vc + e][16 * wave + 2 * u + lane / 32] = wreg[u][e] - b0[u][e];     // the targets t[i] = w[i] - B0[i]
       cur[vc + e][16 * wave + 2 * u + lane / 32] = creg[u][e];
     }
   wait_vmcnt<0>();                                          // this wave's part of the coefficients has landed
   __syncthreads();
-
-  // targets t[i] = w[i] - B0[i], in place
+  // This block's share in the NEXT block's targets is computed at the end, from the new values still in
+  // LDS; its other operand, rows 32 w .. 32 w + 31 of the next block of Ht restricted to this block's
+  // columns (hi and lo), is fetched now and arrives during the walk.
+  u32x4 fb[8][2];
+  if (next_blk >= 0) {                                      // uniform
+    const int64_t brow = (int64_t)k * ldp * ldp + ((int64_t)next_blk * kBlk + 32 * wave + lane % 32) * ldp + i0 + 8 * (lane / 32);
 #pragma unroll
-  for (int u = 0; u < 8; ++u)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) tw[8 * (tid / 16) + u][4 * (tid % 16) + e] -= b0[u][e];
-  __syncthreads();
-  // register r of lane l holds channel 8*(r/4)+4*(l/32)+(r%4) of a block of 32, coordinate l%32 of the wave's 32
-#pragma unroll
-  for (int x = 0; x < 2; ++x)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float v = near[x][r];
-      tw[32 * wave + lane % 32][32 * x + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)] -= v;
+    for (int t = 0; t < 8; ++t) {
+      fb[t][0] = *reinterpret_cast<const u32x4*>(Hth + brow + 16 * t);
+      fb[t][1] = *reinterpret_cast<const u32x4*>(Htl + brow + 16 * t);
     }
-  __syncthreads();
-
-  // ---- the walk: channel ch of the tile, lane q of its quad ----------------------------------
-  const int ch = 16 * wave + lane / 4, q = lane % 4;
-  const int64_t j = ch < n_rows ? j0 + ch : j_last;
-  float grid[LV / 4];
-#pragma unroll
-  for (int u = 0; u < LV / 4; ++u) {
-    const int lvl = q + 4 * u;
-    grid[u] = lvl < n_levels ? codebook[j * n_levels + lvl] : __builtin_inff();
   }
 
   for (int c0 = 0; c0 < n_valid; c0 += kRun) {             // uniform
@@ -556,24 +512,30 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
     __syncthreads();                                        // the corrected targets, before the next run reads them
   }
 
-  // write the block back: What, the codes, and the split delta for the next block's GEMM; the lanes keep
-  // the rows and coordinates they loaded (W is still in their registers)
+  // Write the block back: What, the codes, and the split delta for the next blocks' GEMMs; the lanes keep
+  // the rows and coordinates they loaded (W is still in their registers).  The delta halves of all 64
+  // channel slots (slots past the end of the group repeat its last channel, as in the walk) are also left
+  // in LDS, where the coefficients were: [channel][coordinate], rows of 272 bytes, hi then lo.
+  unsigned char* dlt = reinterpret_cast<unsigned char*>(smem + kWalkCoef);
   const bool q_packed = Q && d % 4 == 0 && (reinterpret_cast<uintptr_t>(Q) & 3) == 0;
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
     const int r = 16 * wave + 2 * u + lane / 32;
-    const int64_t jr = j0 + r;
-    if ((r < n_rows) & vec_in) {
-      const int64_t a = i0 + vc;
-      f32x4 v;
-      unsigned codes = 0;
-      unsigned short h[4], l[4];
+    const int64_t jr = j0 + r, a = i0 + vc;
+    f32x4 v;
+    unsigned codes = 0;
+    unsigned short h[4], l[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        v[e] = cur[vc + e][r];
-        codes |= (unsigned)code[vc + e][r] << (8 * e);
-        split_bf16(a + e < d ? v[e] - wreg[u][e] : 0.f, h[e], l[e]);
-      }
+    for (int e = 0; e < 4; ++e) {
+      v[e] = cur[vc + e][r];
+      codes |= (unsigned)code[vc + e][r] << (8 * e);
+      split_bf16(a + e < d ? v[e] - wreg[u][e] : 0.f, h[e], l[e]);
+    }
+    const u32x2 hv = {h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16)};
+    const u32x2 lv = {l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16)};
+    *reinterpret_cast<u32x2*>(dlt + r * kDeltaPitch + 2 * vc) = hv;
+    *reinterpret_cast<u32x2*>(dlt + (kRows + r) * kDeltaPitch + 2 * vc) = lv;
+    if ((r < n_rows) & vec_in) {
       if (a + 3 < d) {
         *reinterpret_cast<f32x4*>(What + jr * ld + a) = v;
       } else {
@@ -588,35 +550,73 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
         for (int e = 0; e < 4; ++e)
           if (a + e < d) Q[jr * d + a + e] = (unsigned char)(codes >> (8 * e));
       }
-      *reinterpret_cast<u32x2*>(Dh + jr * ldp + a) = u32x2{h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16)};
-      *reinterpret_cast<u32x2*>(Dl + jr * ldp + a) = u32x2{l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16)};
+      *reinterpret_cast<u32x2*>(Dh + jr * ldp + a) = hv;
+      *reinterpret_cast<u32x2*>(Dl + jr * ldp + a) = lv;
     }
   }
+  if (next_blk < 0) return;                                 // uniform: nothing follows this block
+
+  // The share of this block in the targets of the next one (the GEMM beside this walk steps over this
+  // block, whose values change meanwhile):
+  //   E[j][i] = sum_{i' in blk} delta[j][i'] * Ht[next i0 + i][i'],   64 channels x 128 coordinates x 128,
+  // from the same hi / lo halves that went to global memory, as one more part of the next block's sums.
+  __syncthreads();
+  f32x16 near[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) near[x][r] = 0.f;
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const unsigned char* arow = dlt + (32 * x + lane % 32) * kDeltaPitch + 2 * (16 * t + 8 * (lane / 32));
+      const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(arow));
+      const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(arow + kRows * kDeltaPitch));
+      const bf16x8 bh = __builtin_bit_cast(bf16x8, fb[t][0]), bl = __builtin_bit_cast(bf16x8, fb[t][1]);
+      near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh, al, near[x], 0, 0, 0);
+      near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl, ah, near[x], 0, 0, 0);
+      near[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh, ah, near[x], 0, 0, 0);
+    }
+  // register r of lane l holds coordinate 8*(r/4)+4*(l/32)+(r%4) of the wave's 32, channel l%32 of a block of 32
+  float* dst = E + ((int64_t)tile * kRows + lane % 32) * kBlk + 32 * wave + 4 * (lane / 32);
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = near[x][4 * r4 + e];
+      *reinterpret_cast<f32x4*>(dst + 32 * x * kBlk + 8 * r4) = v;
+    }
 }
 
-// One launch per block: the first n_walk workgroups walk block `blk` (reading the partial sums in
-// Cin), the others compute the partial sums of block `next_blk` into Cout, stepping over the
-// contraction elements of `blk`, which change meanwhile.  The two halves share nothing but read-only
-// data, so the GEMM for the next block hides behind the latency-bound walk of this one.
+// One launch per block: the first n_walk workgroups walk block `blk` (adding the n_in partial sums in
+// Cin), the others compute the partial sums of block `next_blk` into parts 0 .. n_parts - 1 of Cout,
+// stepping over the contraction elements of block `excl` (= blk, whose values change meanwhile; none
+// if negative).  The walk supplies that block's share itself, as part n_parts of Cout (walk_next: the
+// block it is for, negative if none follows).  The two halves share nothing but read-only data, so
+// the GEMM for the next block hides behind the latency-bound walk of this one.
 constexpr int kSmemBytes = (kWalkBytes > 2 * kGemmStage ? kWalkBytes : 2 * kGemmStage);
 template <int LV>
-__global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* __restrict__ Cin, int n_parts,
+__global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* __restrict__ Cin, int n_in, int n_parts,
                                                        const float* __restrict__ W, float* __restrict__ What,
                                                        const float* __restrict__ codebook, int n_levels,
                                                        const float* __restrict__ Cd,
                                                        const unsigned short* __restrict__ Hth,
                                                        const unsigned short* __restrict__ Htl, int64_t d_out,
                                                        int64_t d, int64_t ld, int64_t ldp, int G, int n_rt, int n_gt,
-                                                       int blk, int prev, int next_blk, unsigned char* __restrict__ Q,
+                                                       int blk, int walk_next, int next_blk, int excl,
+                                                       unsigned char* __restrict__ Q,
                                                        unsigned short* __restrict__ Dh,
                                                        unsigned short* __restrict__ Dl, float* __restrict__ Cout) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
   if ((int)blockIdx.x < n_walk) {
-    walk_body<LV>(smem, (int)blockIdx.x, Cin, n_parts, W, What, codebook, n_levels, Cd, Hth, Htl, d_out, d, ld, ldp, G,
-                  n_rt, blk, prev, Q, Dh, Dl);
+    walk_body<LV>(smem, (int)blockIdx.x, Cin, n_in, W, What, codebook, n_levels, Cd, Hth, Htl, d_out, d, ld, ldp, G,
+                  n_rt, blk, walk_next, Q, Dh, Dl, Cout + (int64_t)n_parts * n_walk * kBlk * kRows);
   } else {
     const int g = (int)blockIdx.x - n_walk, n_tiles = n_gt * G;
-    gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, n_rt, next_blk, blk,
+    gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, n_rt, next_blk, excl,
                   Cout);
   }
 }
@@ -652,7 +652,8 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   L.ht_bytes = up((size_t)G * L.ldp * L.ldp * 2);
   L.cdt_bytes = up((size_t)G * L.n_blk * kBlk * kBlk * sizeof(float));
   L.delta_bytes = up((size_t)d_out * L.ldp * 2);
-  L.c_bytes = up((size_t)L.n_parts * n_walk * kBlk * kRows * sizeof(float));   // one of the two buffers that alternate
+  // one of the two buffers that alternate: the GEMM's parts, and one more from the walk of the block before
+  L.c_bytes = up((size_t)(L.n_parts + 1) * n_walk * kBlk * kRows * sizeof(float));
   return L;
 }
 
@@ -703,24 +704,27 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
   float* Cbuf[2] = {C, (float*)((char*)C + L.c_bytes)};
   const int n_walk = L.n_rt * G, n_gemm = L.n_gt * G * L.n_parts, n_blk = (int)L.n_blk;
   const int64_t total = (int64_t)n_cycles * n_blk;
-#define GQ_LAUNCH_BLOCK(LV, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT)                                                    \
-  cd_block_kernel<LV><<<dim3((unsigned)(GRID)), dim3(256), 0, st>>>(NWALK, CIN, L.n_parts, W, What, codebook, n_levels,  \
-                                                                   Cd, Hth, Htl, d_out, d_in, ld, L.ldp, G, L.n_rt,     \
-                                                                   L.n_gt, BLK, PREV, NEXT, Q, Dh, Dl, COUT)
-#define GQ_LAUNCH_ANY(GRID, NWALK, CIN, BLK, PREV, NEXT, COUT)                                                          \
+#define GQ_LAUNCH_BLOCK(LV, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT)                                         \
+  cd_block_kernel<LV><<<dim3((unsigned)(GRID)), dim3(256), 0, st>>>(NWALK, CIN, NIN, L.n_parts, W, What, codebook,       \
+                                                                   n_levels, Cd, Hth, Htl, d_out, d_in, ld, L.ldp, G,   \
+                                                                   L.n_rt, L.n_gt, BLK, WNEXT, NEXT, EXCL, Q, Dh, Dl,   \
+                                                                   COUT)
+#define GQ_LAUNCH_ANY(GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT)                                              \
   do {                                                                                                                  \
-    if (n_levels <= 4) GQ_LAUNCH_BLOCK(4, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT);                                     \
-    else if (n_levels <= 8) GQ_LAUNCH_BLOCK(8, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT);                                \
-    else GQ_LAUNCH_BLOCK(kMaxLevels, GRID, NWALK, CIN, BLK, PREV, NEXT, COUT);                                          \
+    if (n_levels <= 4) GQ_LAUNCH_BLOCK(4, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT);                         \
+    else if (n_levels <= 8) GQ_LAUNCH_BLOCK(8, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT);                    \
+    else GQ_LAUNCH_BLOCK(kMaxLevels, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT);                              \
   } while (0)
-  // the partial sums of block 0 first (its predecessor in the cycle, the last block, stepped over) ...
-  GQ_LAUNCH_ANY(n_gemm, 0, Cbuf[1], n_blk - 1, 0, 0, Cbuf[0]);
+  // the partial sums of block 0 first, over the whole contraction (nothing changes meanwhile) ...
+  GQ_LAUNCH_ANY(n_gemm, 0, Cbuf[1], 0, 0, -1, 0, -1, Cbuf[0]);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  // ... then one launch per block: its walk, and beside it the partial sums of the next block
+  // ... then one launch per block: its walk, which ends with its own share in the next block's sums
+  // (one more part), and beside it the other blocks' share in them
   for (int64_t t = 0; t < total; ++t) {
-    const int blk = (int)(t % n_blk), prev = (blk + n_blk - 1) % n_blk, next = (blk + 1) % n_blk;
+    const int blk = (int)(t % n_blk), next = (blk + 1) % n_blk;
     const bool more = t + 1 < total;
-    GQ_LAUNCH_ANY(n_walk + (more ? n_gemm : 0), n_walk, Cbuf[t & 1], blk, prev, next, Cbuf[(t + 1) & 1]);
+    GQ_LAUNCH_ANY(n_walk + (more ? n_gemm : 0), n_walk, Cbuf[t & 1], L.n_parts + (t > 0 ? 1 : 0), blk, more ? next : -1,
+                  next, blk, Cbuf[(t + 1) & 1]);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
 #undef GQ_LAUNCH_ANY

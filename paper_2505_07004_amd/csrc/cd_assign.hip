@@ -114,6 +114,14 @@ __global__ __launch_bounds__(256) void ldlq_prep_kernel(const float* __restrict_
   }
 }
 
+// The split delta is stored in the order the GEMM consumes it: for every stage of 64 contraction
+// elements, all channels one after the other, each with its 64 hi halves followed by its 64 lo
+// halves (256 bytes).  A workgroup's operand tile for a stage (128 channels) is then one contiguous
+// 32 KiB run of memory instead of 256 pieces of 128 bytes a whole matrix row apart.  Dl = Dh + 64.
+__device__ __forceinline__ int64_t delta_index(int64_t j, int64_t a, int64_t d_out) {
+  return ((a >> 6) * d_out + j) * 128 + (a & 63);
+}
+
 // Sequential rounding starts from the weights themselves: What = W, no error yet.
 __global__ __launch_bounds__(256) void ldlq_init_kernel(const float* __restrict__ W, float* __restrict__ What,
                                                         int64_t d, int64_t ld, int64_t ldp,
@@ -122,12 +130,12 @@ __global__ __launch_bounds__(256) void ldlq_init_kernel(const float* __restrict_
   const int64_t j = blockIdx.y;
   for (int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x; a < ldp; a += (int64_t)gridDim.x * 256) {
     if (a < d) What[j * ld + a] = W[j * ld + a];
-    Dh[j * ldp + a] = 0;
-    Dl[j * ldp + a] = 0;
+    Dh[delta_index(j, a, gridDim.y)] = 0;
+    Dl[delta_index(j, a, gridDim.y)] = 0;
   }
 }
 
-// Dh/Dl[j][a] = hi/lo of What[j][a] - W[j][a], row pitch ldp, zero padded.
+// Dh/Dl = hi/lo of What[j][a] - W[j][a], a < ldp, zero padded, in the staged order of delta_index.
 __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__ W, const float* __restrict__ What,
                                                        int64_t d, int64_t ld, int64_t ldp,
                                                        unsigned short* __restrict__ Dh,
@@ -137,8 +145,8 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
     const float v = a < d ? What[j * ld + a] - W[j * ld + a] : 0.f;
     unsigned short h, l;
     split_bf16(v, h, l);
-    Dh[j * ldp + a] = h;
-    Dl[j * ldp + a] = l;
+    Dh[delta_index(j, a, gridDim.y)] = h;
+    Dl[delta_index(j, a, gridDim.y)] = l;
   }
 }
 
@@ -182,6 +190,8 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
   // number i moves rows 8 i .. 8 i + 7, lane -> (row 8 i + lane / 8, position lane % 8)
   const unsigned short* src = wave == 0 ? Dh : wave == 1 ? Dl : (wave == 2 ? Hth : Htl) + (int64_t)k * ldp * ldp;
   const int64_t row_first = wave < 2 ? j0 : (int64_t)blk * kBlk, row_last = wave < 2 ? j_last : ldp - 1;
+  // delta: stage-major, 128 halves per channel and stage; Ht: row-major with pitch ldp
+  const int64_t row_pitch = wave < 2 ? 128 : ldp, stage_pitch = wave < 2 ? d_out * 128 : kGemmK;
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
   auto issue = [&](int64_t stage, int slot) {
 #pragma unroll
@@ -190,7 +200,7 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
       const int c = (lane % 8) ^ ((r >> 1) & 7);
       int64_t row = row_first + r;
       row = row < row_last ? row : row_last;             // rows past the group: repeat its last row (never stored)
-      dma16(src + row * ldp + (stage < skip_from ? stage : stage + 2) * kGemmK + 8 * c,
+      dma16(src + row * row_pitch + (stage < skip_from ? stage : stage + 2) * stage_pitch + 8 * c,
             smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
     }
   };
@@ -550,8 +560,8 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
         for (int e = 0; e < 4; ++e)
           if (a + e < d) Q[jr * d + a + e] = (unsigned char)(codes >> (8 * e));
       }
-      *reinterpret_cast<u32x2*>(Dh + jr * ldp + a) = hv;
-      *reinterpret_cast<u32x2*>(Dl + jr * ldp + a) = lv;
+      *reinterpret_cast<u32x2*>(Dh + delta_index(jr, a, d_out)) = hv;
+      *reinterpret_cast<u32x2*>(Dl + delta_index(jr, a, d_out)) = lv;
     }
   }
   if (next_blk < 0) return;                                 // uniform: nothing follows this block
@@ -679,10 +689,9 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
   p += L.ht_bytes;
   float* Cd = (float*)p;
   p += L.cdt_bytes;
-  unsigned short* Dh = (unsigned short*)p;
-  p += L.delta_bytes;
-  unsigned short* Dl = (unsigned short*)p;
-  p += L.delta_bytes;
+  unsigned short* Dh = (unsigned short*)p;                  // hi and lo halves interleaved per channel and stage
+  unsigned short* Dl = Dh + 64;
+  p += 2 * L.delta_bytes;
   float* C = (float*)p;
 
   hipError_t e;

@@ -28,7 +28,39 @@ constexpr int kBlk = 128;             // coordinates per block
 constexpr int kRows = 64;             // channels per workgroup row tile (GEMM) / per wave (sequential kernel)
 constexpr int kMaxLevels = 16;        // most grid points per channel (4 bits)
 
-// Ht (hi/lo bf16, [G][ldp][ldp], row i contiguous over i', zero diagonal and zero padding) and
+// Ht is stored in the order the GEMM consumes it: per group and block of 128 rows i, for every stage
+// of 32 contraction elements i', the 128 rows one after the other, each with its 32 hi halves followed
+// by its 32 lo halves (128 bytes): a workgroup's operand tile for a stage is one contiguous 16 KiB run.
+// Htl = Hth + 32.
+__device__ __forceinline__ int64_t ht_index(int64_t k, int64_t i, int64_t ip, int64_t ldp) {
+  return (((k * (ldp / 128) + i / 128) * (ldp / 32) + ip / 32) * 128 + i % 128) * 64 + ip % 32;
+}
+
+// Eight consecutive elements i' = ip .. ip + 7 (ip a multiple of 8) of row i: two 16-byte stores, and the
+// fp32 copy for the diagonal block's coefficient tile.
+__device__ __forceinline__ void store_ht8(int64_t k, int64_t i, int64_t ip, int64_t ldp, const float (&v)[8],
+                                          unsigned short* __restrict__ Hth, unsigned short* __restrict__ Htl,
+                                          float* __restrict__ Cd) {
+  unsigned short hi[8], lo[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) split_bf16(v[e], hi[e], lo[e]);
+  u32x4 h, l;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    h[e] = hi[2 * e] | ((unsigned)hi[2 * e + 1] << 16);
+    l[e] = lo[2 * e] | ((unsigned)lo[2 * e + 1] << 16);
+  }
+  const int64_t off = ht_index(k, i, ip, ldp);
+  *reinterpret_cast<u32x4*>(Hth + off) = h;
+  *reinterpret_cast<u32x4*>(Htl + off) = l;
+  if (i / kBlk == ip / kBlk) {
+    const int64_t base = (k * (ldp / kBlk) + i / kBlk) * kBlk * kBlk;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) Cd[base + ((ip + e) % kBlk) * kBlk + (i % kBlk)] = v[e];
+  }
+}
+
+// Ht (hi/lo bf16, zero diagonal and zero padding, in the order of ht_index) and
 // the fp32 coefficients of every diagonal block,
 //   Cd[k][blk][a][b] = Ht[blk*128 + b][blk*128 + a]
 // (what the target of coordinate b moves by, per unit change of coordinate a; row a contiguous over b).
@@ -52,25 +84,21 @@ __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ 
     diag[threadIdx.x] = i < d ? Hk[i * d + i] : 1.f;
   }
   __syncthreads();
-  const int64_t n_blk = ldp / kBlk;
-  for (int r = ty; r < 64; r += 4) {
-    const int li = r, lj = tx;                             // local row i, local column i'
-    const int64_t i = (int64_t)ti * 64 + li, ip = (int64_t)tj * 64 + lj;
-    float h;
-    if (ti < tj) h = tile[li][lj];
-    else if (ti > tj) h = tile[lj][li];
-    else h = li <= lj ? tile[li][lj] : tile[lj][li];
-    const float v = (i < d && ip < d && i != ip) ? h / diag[li] : 0.f;
-    unsigned short hi, lo;
-    split_bf16(v, hi, lo);
-    const int64_t off = (int64_t)k * ldp * ldp + i * ldp + ip;
-    Hth[off] = hi;
-    Htl[off] = lo;
-    if (i / kBlk == ip / kBlk) {
-      const int64_t blk = i / kBlk;
-      const int64_t base = ((int64_t)k * n_blk + blk) * kBlk * kBlk;
-      Cd[base + (ip % kBlk) * kBlk + (i % kBlk)] = v;
+  for (int idx = threadIdx.x; idx < 64 * 8; idx += 256) {   // local row i, eight local columns i'
+    const int li = idx / 8, lj0 = 8 * (idx % 8);
+    const int64_t i = (int64_t)ti * 64 + li;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int lj = lj0 + e;
+      const int64_t ip = (int64_t)tj * 64 + lj;
+      float h;
+      if (ti < tj) h = tile[li][lj];
+      else if (ti > tj) h = tile[lj][li];
+      else h = li <= lj ? tile[li][lj] : tile[lj][li];
+      v[e] = (i < d && ip < d && i != ip) ? h / diag[li] : 0.f;
     }
+    store_ht8(k, i, (int64_t)tj * 64 + lj0, ldp, v, Hth, Htl, Cd);
   }
 }
 
@@ -96,30 +124,25 @@ __global__ __launch_bounds__(256) void ldlq_prep_kernel(const float* __restrict_
     diag[threadIdx.x] = i < d ? Rk[i * d + i] : 1.f;
   }
   __syncthreads();
-  const int64_t n_blk = ldp / kBlk;
-  for (int r = ty; r < 64; r += 4) {
-    const int li = r, lj = tx;                             // local row i, local column i'
-    const int64_t i = (int64_t)ti * 64 + li, ip = (int64_t)tj * 64 + lj;
-    const float v = (i < d && ip < i) ? tile[lj][li] / diag[li] : 0.f;
-    unsigned short hi, lo;
-    split_bf16(v, hi, lo);
-    const int64_t off = (int64_t)k * ldp * ldp + i * ldp + ip;
-    Hth[off] = hi;
-    Htl[off] = lo;
-    if (i / kBlk == ip / kBlk) {
-      const int64_t blk = i / kBlk;
-      const int64_t base = ((int64_t)k * n_blk + blk) * kBlk * kBlk;
-      Cd[base + (ip % kBlk) * kBlk + (i % kBlk)] = v;
+  for (int idx = threadIdx.x; idx < 64 * 8; idx += 256) {   // local row i, eight local columns i'
+    const int li = idx / 8, lj0 = 8 * (idx % 8);
+    const int64_t i = (int64_t)ti * 64 + li;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int64_t ip = (int64_t)tj * 64 + lj0 + e;
+      v[e] = (i < d && ip < i) ? tile[lj0 + e][li] / diag[li] : 0.f;
     }
+    store_ht8(k, i, (int64_t)tj * 64 + lj0, ldp, v, Hth, Htl, Cd);
   }
 }
 
-// The split delta is stored in the order the GEMM consumes it: for every stage of 64 contraction
-// elements, all channels one after the other, each with its 64 hi halves followed by its 64 lo
-// halves (256 bytes).  A workgroup's operand tile for a stage (128 channels) is then one contiguous
-// 32 KiB run of memory instead of 256 pieces of 128 bytes a whole matrix row apart.  Dl = Dh + 64.
+// The split delta is stored in the order the GEMM consumes it: for every stage of 32 contraction
+// elements, all channels one after the other, each with its 32 hi halves followed by its 32 lo
+// halves (128 bytes).  A workgroup's operand tile for a stage (128 channels) is then one contiguous
+// 16 KiB run of memory instead of 256 pieces of 64 bytes a whole matrix row apart.  Dl = Dh + 32.
 __device__ __forceinline__ int64_t delta_index(int64_t j, int64_t a, int64_t d_out) {
-  return ((a >> 6) * d_out + j) * 128 + (a & 63);
+  return ((a >> 5) * d_out + j) * 64 + (a & 31);
 }
 
 // Sequential rounding starts from the weights themselves: What = W, no error yet.
@@ -155,18 +178,22 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
 // WITHOUT the 128 contraction elements of block `excl`: those belong to the block that is being
 // walked while this runs, and the walk of `blk` adds their share itself once they are final.
 // A workgroup owns 128 channels of one group and all 128 coordinates of the block; its 4
-// waves compute 64 x 64 each.  Both operands are contraction-major in memory; a stage is 64
-// contraction elements = one whole 128-byte line of each of the 4 x 128 operand rows
-// ({delta, Ht} x {hi, lo}), copied straight into LDS (global_load_lds_dwordx4: 8 lanes per row,
-// wave w copies operand w) into a ring of two stages, one barrier per stage.  A row of a staged
-// tile holds eight 16-byte chunks; chunk c of row r sits at position c ^ ((r >> 1) & 7), which
-// makes the 16-byte fragment reads of 16 consecutive rows conflict-free (the loading lane
-// applies the same XOR when it picks its global chunk).  The parts split the contraction; the
-// walk adds them in a fixed order.
+// waves compute 64 x 64 each.  Both operands are contraction-major in memory; a stage is 32
+// contraction elements = 64 bytes of each of the 4 x 128 operand rows ({delta, Ht} x {hi, lo}),
+// copied straight into LDS (global_load_lds_dwordx4: 4 lanes per row, wave w copies operand w)
+// into a ring of four stages.  The loads of a stage are issued two stages ahead, BEFORE the wait
+// for the current one, so the memory pipe never runs dry, and a slot is not written again before
+// the barrier after its last reader: one barrier per stage.  A row of a staged tile holds four
+// 16-byte chunks; chunk c of row r sits at position c ^ ((r >> 1) & 3), which makes the 16-byte
+// fragment reads of 8 consecutive rows conflict-free (the loading lane applies the same XOR when it
+// picks its global chunk).  The parts split the contraction; the walk adds them in a fixed order.
 constexpr int kGemmRows = 128;                       // channels per workgroup
-constexpr int kGemmK = 64;                           // contraction elements per stage
-constexpr int kGemmTile = 128 * kGemmK * 2;          // bytes of one staged operand tile (16 KiB)
-constexpr int kGemmStage = 4 * kGemmTile;            // 64 KiB
+constexpr int kGemmK = 32;                           // contraction elements per stage
+constexpr int kGemmTile = 128 * kGemmK * 2;          // bytes of one staged operand tile (8 KiB)
+constexpr int kGemmStage = 4 * kGemmTile;            // 32 KiB
+constexpr int kGemmRing = 4;
+constexpr int kGemmLoads = kGemmTile / 1024;         // direct loads per lane and stage
+constexpr int kBlkStages = kBlk / kGemmK;            // stages per block of coordinates
 __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, int n_parts,
                                               const unsigned short* __restrict__ Dh,
                                               const unsigned short* __restrict__ Dl,
@@ -181,35 +208,40 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int wm = wave / 2, wn = wave % 2;
 
-  // contraction range of this part, in stages of 64; the excluded block's two stages are stepped over
-  const int64_t n_stages = ldp / kGemmK - (excl >= 0 ? 2 : 0);
+  // contraction range of this part, in stages; the excluded block's stages are stepped over
+  const int64_t n_stages = ldp / kGemmK - (excl >= 0 ? kBlkStages : 0);
   const int64_t s0 = (int64_t)part * n_stages / n_parts, s1 = ((int64_t)part + 1) * n_stages / n_parts;
-  const int64_t skip_from = excl >= 0 ? 2 * (int64_t)excl : n_stages;   // excl < 0: nothing is stepped over
+  const int64_t skip_from = excl >= 0 ? kBlkStages * (int64_t)excl : n_stages;   // excl < 0: nothing is stepped over
 
   // ---- staging: wave w copies operand w (0: delta hi, 1: delta lo, 2: Ht hi, 3: Ht lo); load
-  // number i moves rows 8 i .. 8 i + 7, lane -> (row 8 i + lane / 8, position lane % 8)
-  const unsigned short* src = wave == 0 ? Dh : wave == 1 ? Dl : (wave == 2 ? Hth : Htl) + (int64_t)k * ldp * ldp;
-  const int64_t row_first = wave < 2 ? j0 : (int64_t)blk * kBlk, row_last = wave < 2 ? j_last : ldp - 1;
-  // delta: stage-major, 128 halves per channel and stage; Ht: row-major with pitch ldp
-  const int64_t row_pitch = wave < 2 ? 128 : ldp, stage_pitch = wave < 2 ? d_out * 128 : kGemmK;
+  // number i moves rows 16 i .. 16 i + 15, lane -> (row 16 i + lane / 4, position lane % 4)
+  // both are stage-major with 64 halves per row and stage: delta over all channels, Ht over the block's 128 rows
+  const unsigned short* src = wave == 0 ? Dh : wave == 1 ? Dl : (wave == 2 ? Hth : Htl) + ht_index(k, (int64_t)blk * kBlk, 0, ldp);
+  const int64_t row_first = wave < 2 ? j0 : 0, row_last = wave < 2 ? j_last : kBlk - 1;
+  const int64_t row_pitch = 2 * kGemmK, stage_pitch = (wave < 2 ? d_out : (int64_t)kBlk) * 2 * kGemmK;
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
-  auto issue = [&](int64_t stage, int slot) {
+  const unsigned short* lane_src[kGemmLoads];               // this lane's chunk in stage 0, per load
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = 8 * i + lane / 8;
-      const int c = (lane % 8) ^ ((r >> 1) & 7);
-      int64_t row = row_first + r;
-      row = row < row_last ? row : row_last;             // rows past the group: repeat its last row (never stored)
-      dma16(src + row * row_pitch + (stage < skip_from ? stage : stage + 2) * stage_pitch + 8 * c,
-            smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
-    }
+  for (int i = 0; i < kGemmLoads; ++i) {
+    const int r = 16 * i + lane / 4;
+    const int c = (lane % 4) ^ ((r >> 1) & 3);
+    int64_t row = row_first + r;
+    row = row < row_last ? row : row_last;                  // rows past the group: repeat its last row
+    lane_src[i] = src + row * row_pitch + 8 * c;
+  }
+  auto issue = [&](int64_t stage) {
+    const int slot = (int)((stage - s0) % kGemmRing);
+    const int64_t off = (stage < skip_from ? stage : stage + kBlkStages) * stage_pitch;
+#pragma unroll
+    for (int i = 0; i < kGemmLoads; ++i)
+      dma16(lane_src[i] + off, smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
   };
 
-  // ---- fragments: row l % 32 of a 32-row block, chunk 2 t + l / 32 of its 64 contraction elements
+  // ---- fragments: row l % 32 of a 32-row block, chunk 2 t + l / 32 of its 32 contraction elements
   const int lrow = lane % 32;
   auto frag = [&](int slot, int tile, int row0, int t) -> bf16x8 {
-    const int pos = (2 * t + lane / 32) ^ ((lrow >> 1) & 7);
-    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kGemmStage + tile * kGemmTile + (row0 + lrow) * 128 + pos * 16]);
+    const int pos = (2 * t + lane / 32) ^ ((lrow >> 1) & 3);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kGemmStage + tile * kGemmTile + (row0 + lrow) * 64 + pos * 16]);
     return __builtin_bit_cast(bf16x8, v);
   };
 
@@ -221,12 +253,19 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  if (s0 < s1) issue(s0, 0);
+  if (s0 < s1) issue(s0);
+  if (s0 + 1 < s1) issue(s0 + 1);
   for (int64_t s = s0; s < s1; ++s) {
-    const int slot = (int)((s - s0) & 1);
-    wait_vmcnt<0>();                                      // this wave's loads of stage s have landed
-    __builtin_amdgcn_s_barrier();                         // everyone's have; and everyone is done with the other slot
-    if (s + 1 < s1) issue(s + 1, slot ^ 1);
+    const int slot = (int)((s - s0) % kGemmRing);
+    if (s + 2 < s1) {                                     // uniform
+      issue(s + 2);                                       // its slot's last readers were two barriers ago
+      wait_vmcnt<2 * kGemmLoads>();                       // this wave's loads of stage s have landed
+    } else if (s + 1 < s1) {
+      wait_vmcnt<kGemmLoads>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();                         // everyone's have
 #pragma unroll
     for (int t = 0; t < kGemmK / 16; ++t) {
       bf16x8 ah[2], al[2], bh[2], bl[2];
@@ -426,11 +465,12 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
   // columns (hi and lo), is fetched now and arrives during the walk.
   u32x4 fb[8][2];
   if (next_blk >= 0) {                                      // uniform
-    const int64_t brow = (int64_t)k * ldp * ldp + ((int64_t)next_blk * kBlk + 32 * wave + lane % 32) * ldp + i0 + 8 * (lane / 32);
+    const int64_t irow = (int64_t)next_blk * kBlk + 32 * wave + lane % 32;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-      fb[t][0] = *reinterpret_cast<const u32x4*>(Hth + brow + 16 * t);
-      fb[t][1] = *reinterpret_cast<const u32x4*>(Htl + brow + 16 * t);
+      const int64_t off = ht_index(k, irow, i0 + 16 * t + 8 * (lane / 32), ldp);
+      fb[t][0] = *reinterpret_cast<const u32x4*>(Hth + off);
+      fb[t][1] = *reinterpret_cast<const u32x4*>(Htl + off);
     }
   }
 
@@ -607,7 +647,7 @@ __device__ __forceinline__ void walk_body(char* smem, int tile, const float* __r
 // if negative).  The walk supplies that block's share itself, as part n_parts of Cout (walk_next: the
 // block it is for, negative if none follows).  The two halves share nothing but read-only data, so
 // the GEMM for the next block hides behind the latency-bound walk of this one.
-constexpr int kSmemBytes = (kWalkBytes > 2 * kGemmStage ? kWalkBytes : 2 * kGemmStage);
+constexpr int kSmemBytes = (kWalkBytes > kGemmRing * kGemmStage ? kWalkBytes : kGemmRing * kGemmStage);
 template <int LV>
 __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* __restrict__ Cin, int n_in, int n_parts,
                                                        const float* __restrict__ W, float* __restrict__ What,
@@ -619,12 +659,20 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
                                                        int blk, int walk_next, int next_blk, int excl,
                                                        unsigned char* __restrict__ Q,
                                                        unsigned short* __restrict__ Dh,
-                                                       unsigned short* __restrict__ Dl, float* __restrict__ Cout) {
+                                                       unsigned short* __restrict__ Dl, float* __restrict__ Cout,
+                                                       int gemm_delay) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
   if ((int)blockIdx.x < n_walk) {
     walk_body<LV>(smem, (int)blockIdx.x, Cin, n_in, W, What, codebook, n_levels, Cd, Hth, Htl, d_out, d, ld, ldp, G,
                   n_rt, blk, walk_next, Q, Dh, Dl, Cout + (int64_t)n_parts * n_walk * kBlk * kRows);
   } else {
+    // The walk begins with a burst of loads (some 300 KiB per workgroup) and then hardly touches memory;
+    // where the GEMM is the shorter of the two, it starts `gemm_delay` ticks of the 100 MHz clock late and
+    // leaves the memory system to the walk for that burst.  (A bounded wait on a free-running clock.)
+    if (gemm_delay > 0) {
+      const uint64_t t0 = wall_clock64();
+      while (wall_clock64() - t0 < (uint64_t)gemm_delay) __builtin_amdgcn_s_sleep(16);
+    }
     const int g = (int)blockIdx.x - n_walk, n_tiles = n_gt * G;
     gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, n_rt, next_blk, excl,
                   Cout);
@@ -634,6 +682,7 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
 struct Layout {
   int64_t ldp, n_blk;
   int n_rt, n_gt, n_parts;
+  int gemm_delay;                                           // ticks of the 100 MHz clock the GEMM half starts late
   size_t ht_bytes, cdt_bytes, delta_bytes, c_bytes;
 };
 Layout make_layout(int64_t d_out, int64_t d_in, int G) {
@@ -643,7 +692,7 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   const int64_t m = d_out / G;
   L.n_rt = (int)((m + kRows - 1) / kRows);
   L.n_gt = (int)((m + kGemmRows - 1) / kGemmRows);
-  // enough GEMM workgroups to fill the compute units the walk leaves free, at least two 64-deep stages each
+  // enough GEMM workgroups to fill the compute units the walk leaves free, at least 128 contraction elements each
   const int64_t n_walk = (int64_t)L.n_rt * G, tiles = (int64_t)L.n_gt * G;
   const int64_t free_cus = n_walk < 192 ? 256 - n_walk : 64;
   int parts = (int)(free_cus / tiles);
@@ -652,12 +701,23 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   // 50 us of walk) and would occupy well under the whole chip, it is cut finer than the compute units
   // free at the start: the units the walk releases then pick up the rest.  (More parts also mean more
   // partial sums for the walk to add, so shapes that fill the chip anyway are left alone.)
-  if (tiles * (L.ldp / kGemmK) * 2 / free_cus > 80 && parts * tiles < 160) parts = (int)((512 + tiles - 1) / tiles);
-  const int max_parts = (int)((L.ldp / kGemmK - 2) / 2);
+  if (tiles * (L.ldp / 64) * 2 / free_cus > 80 && parts * tiles < 160) parts = (int)((512 + tiles - 1) / tiles);
+  const int max_parts = (int)((L.ldp / 64 - 2) / 2);
   if (parts > max_parts) parts = max_parts;
   if (parts > 16) parts = 16;
   if (parts < 1) parts = 1;
   L.n_parts = parts;
+  // Measured on MI355X: a walk takes about 31 us whatever the shape, 8 of them for its opening burst of
+  // loads when it has the memory system to itself and twice that beside a GEMM in full swing; a GEMM
+  // workgroup takes about 2.5 us plus 1 us per 32-deep stage.  A GEMM that would end well before the
+  // walk therefore starts late by the difference (at most 9 us), which costs nothing and shortens the
+  // walk; one that outlasts the walk starts at once.
+  {
+    const double stages = (double)(L.ldp / kGemmK - kBlkStages) / parts;
+    double late_us = 31.0 - (2.5 + stages);
+    late_us = late_us < 0.0 ? 0.0 : (late_us > 9.0 ? 9.0 : late_us);
+    L.gemm_delay = (int)(late_us * 100.0);
+  }
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
   L.ht_bytes = up((size_t)G * L.ldp * L.ldp * 2);
   L.cdt_bytes = up((size_t)G * L.n_blk * kBlk * kBlk * sizeof(float));
@@ -683,14 +743,13 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
                       hipStream_t st) {
   const Layout L = make_layout(d_out, d_in, G);
   char* p = (char*)ws;
-  unsigned short* Hth = (unsigned short*)p;
-  p += L.ht_bytes;
-  unsigned short* Htl = (unsigned short*)p;
-  p += L.ht_bytes;
+  unsigned short* Hth = (unsigned short*)p;                 // hi and lo halves interleaved per row and stage
+  unsigned short* Htl = Hth + 32;
+  p += 2 * L.ht_bytes;
   float* Cd = (float*)p;
   p += L.cdt_bytes;
   unsigned short* Dh = (unsigned short*)p;                  // hi and lo halves interleaved per channel and stage
-  unsigned short* Dl = Dh + 64;
+  unsigned short* Dl = Dh + 32;
   p += 2 * L.delta_bytes;
   float* C = (float*)p;
 
@@ -711,13 +770,14 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   float* Cbuf[2] = {C, (float*)((char*)C + L.c_bytes)};
+  const int gemm_delay = L.gemm_delay;
   const int n_walk = L.n_rt * G, n_gemm = L.n_gt * G * L.n_parts, n_blk = (int)L.n_blk;
   const int64_t total = (int64_t)n_cycles * n_blk;
 #define GQ_LAUNCH_BLOCK(LV, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT)                                         \
   cd_block_kernel<LV><<<dim3((unsigned)(GRID)), dim3(256), 0, st>>>(NWALK, CIN, NIN, L.n_parts, W, What, codebook,       \
                                                                    n_levels, Cd, Hth, Htl, d_out, d_in, ld, L.ldp, G,   \
                                                                    L.n_rt, L.n_gt, BLK, WNEXT, NEXT, EXCL, Q, Dh, Dl,   \
-                                                                   COUT)
+                                                                   COUT, (NWALK) > 0 ? gemm_delay : 0)
 #define GQ_LAUNCH_ANY(GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT)                                              \
   do {                                                                                                                  \
     if (n_levels <= 4) GQ_LAUNCH_BLOCK(4, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT);                         \

@@ -663,7 +663,9 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
                                                        int gemm_delay) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
   if ((int)blockIdx.x < n_walk) {
-    walk_body<LV>(smem, (int)blockIdx.x, Cin, n_in, W, What, codebook, n_levels, Cd, Hth, Htl, d_out, d, ld, ldp, G,
+    // (the same dealing for the walk: the tiles of a group, which share its coefficients, on as few XCDs as possible)
+    const int tile = n_walk % 8 == 0 ? ((int)blockIdx.x % 8) * (n_walk / 8) + (int)blockIdx.x / 8 : (int)blockIdx.x;
+    walk_body<LV>(smem, tile, Cin, n_in, W, What, codebook, n_levels, Cd, Hth, Htl, d_out, d, ld, ldp, G,
                   n_rt, blk, walk_next, Q, Dh, Dl, Cout + (int64_t)n_parts * n_walk * kBlk * kRows);
   } else {
     // The walk begins with a burst of loads (some 300 KiB per workgroup) and then hardly touches memory;
@@ -673,7 +675,12 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
       const uint64_t t0 = wall_clock64();
       while (wall_clock64() - t0 < (uint64_t)gemm_delay) __builtin_amdgcn_s_sleep(16);
     }
-    const int g = (int)blockIdx.x - n_walk, n_tiles = n_gt * G;
+    // Workgroups are dealt to the 8 XCDs in turn (each with its own L2).  All row tiles of a part read the
+    // same Ht tiles, so consecutive (part, tile) pairs are given to the same XCD: every XCD then fetches
+    // about an eighth of Ht instead of all of it.
+    int g = (int)blockIdx.x - n_walk;
+    const int n_tiles = n_gt * G, n_gemm = (int)gridDim.x - n_walk;
+    if (n_gemm % 8 == 0 && n_walk % 8 == 0) g = (g % 8) * (n_gemm / 8) + g / 8;
     gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, n_rt, next_blk, excl,
                   Cout);
   }

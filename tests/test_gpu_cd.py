@@ -27,12 +27,15 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
     X = wl.make_x_outlier(n, d_in, max(1, d_in // 64), 20.0, seed, DEV, torch.float32)
     dZ = wl.make_dz(n, d_out, 1.0, 1.5, seed + 1, DEV)
     s = gq.gq_group_weights(dZ, G)
-    H = gq.gq_fisher_gram(X, s, mirror=True)
+    if d_in % 4 == 0:
+        H = gq.gq_fisher_gram(X, s, mirror=True)
+    else:                                   # the fp32 Gram path wants 16-byte rows of X; H itself may have any size
+        H = torch.einsum("nk,na,nb->kab", s.double(), X.double(), X.double()).float().contiguous()
     H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))   # damping, as every user of H adds
     W = wl.make_w(d_out, d_in, seed + 2, DEV)
     What, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
     if ld:
-        buf = torch.zeros((2, d_out, ld), device=DEV)
+        buf = torch.full((2, d_out, ld), float("nan"), device=DEV)      # the padding of a row is not the library's to read or write
         buf[0, :, :d_in], buf[1, :, :d_in] = W, What
         W, What = buf[0, :, :d_in], buf[1, :, :d_in]
     return W, What, C.contiguous(), H
@@ -52,6 +55,7 @@ def _check_cycle(Wn, old, new, Qg, Cn, Hn, G, what):
     (400, 200, 96, 4, 2, 208),          # ragged last block, 24 channels per group, padded pitch
     (600, 384, 192, 1, 4, None),        # 16 grid points, three row tiles
     (300, 132, 40, 2, 3, 136),          # last block of 4 coordinates
+    (300, 130, 40, 2, 3, 132),          # d_in not a multiple of 4: a 16-byte vector straddles the end of a row
     (256, 96, 64, 2, 3, None),          # a single, ragged block: its predecessor in the cycle is itself
 ])
 def test_cd_one_cycle_decisions_are_valid_and_match_the_oracle(n, d_in, d_out, G, bits, ld):
@@ -62,6 +66,10 @@ def test_cd_one_cycle_decisions_are_valid_and_match_the_oracle(n, d_in, d_out, G
     torch.cuda.synchronize()
     new = to_np64(What)
     Qg = Qg.cpu().numpy()
+    if ld:
+        pad = torch.as_strided(What, (d_out, ld - d_in), (ld, 1), What.storage_offset() + d_in)
+        assert bool(torch.isnan(pad).all()), "the padding of What's rows was written"
+    assert np.all(np.isfinite(new))
     _check_cycle(Wn, old, new, Qg, Cn, Hn, G, "one cycle")
     Qo, ref = oracle.cd_assign(Wn, old, Cn, Hn, G, n_cycles=1)
     differ = float(np.mean(Qo != Qg))

@@ -45,7 +45,7 @@ def test_sequential_rounding_decisions_are_valid_and_match_the_oracle(n, d_in, d
     _, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
     C = C.contiguous()
     if ld:
-        buf = torch.zeros((d_out, ld), device=DEV)
+        buf = torch.full((d_out, ld), float("nan"), device=DEV)
         buf[:, :d_in] = W
         W = buf[:, :d_in]
     What, Q = gq.gq_ldlq_assign(W, C, R)

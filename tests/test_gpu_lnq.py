@@ -33,7 +33,7 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
     What, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
     Q = torch.argmin((C[:, None, :] - What[:, :, None]).abs(), dim=2).to(torch.uint8).contiguous()
     if ld:
-        buf = torch.zeros((d_out, ld), device=DEV)
+        buf = torch.full((d_out, ld), float("nan"), device=DEV)
         buf[:, :d_in] = W
         W = buf[:, :d_in]
     return W, Q, H
@@ -49,7 +49,7 @@ def test_codebook_step_solves_the_oracles_system(n, d_in, d_out, G, bits, ld):
     say(f"lnq codebook n={n} d_in={d_in} d_out={d_out} G={G} bits={bits} ld={ld}")
     W, Q, H = _case(n, d_in, d_out, G, bits, 131 + d_in, ld)
     m = 1 << bits
-    What = torch.zeros_like(W) if ld is None else torch.zeros((d_out, ld), device=DEV)[:, :d_in]
+    What = torch.zeros_like(W) if ld is None else torch.full((d_out, ld), float("nan"), device=DEV)[:, :d_in]
     C = gq.gq_lnq_codebook(W, Q, H, m, LAM, What=What)
     torch.cuda.synchronize()
     assert torch.equal(What, torch.gather(C, 1, Q.long()))              # What is the grid value of its code, exactly

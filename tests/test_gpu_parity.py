@@ -14,8 +14,9 @@ DEV = "cuda"
 
 
 def _pitched(t: torch.Tensor, ld: int) -> torch.Tensor:
-    """Same values in a buffer whose row pitch is ld elements."""
-    buf = torch.zeros((t.shape[0], ld), dtype=t.dtype, device=t.device)
+    """Same values in a buffer whose row pitch is ld elements; the padding holds NaN (it is not the library's
+    to read into a result, nor to write)."""
+    buf = torch.full((t.shape[0], ld), float("nan"), dtype=t.dtype, device=t.device)
     buf[:, : t.shape[1]] = t
     return buf[:, : t.shape[1]]
 

@@ -64,41 +64,54 @@ __device__ __forceinline__ void store_ht8(int64_t k, int64_t i, int64_t ip, int6
 // the fp32 coefficients of every diagonal block,
 //   Cd[k][blk][a][b] = Ht[blk*128 + b][blk*128 + a]
 // (what the target of coordinate b moves by, per unit change of coordinate a; row a contiguous over b).
-// Only the upper triangle of H is read.  One workgroup per 64 x 64 tile.
+// Only the upper triangle of H is read, every 64 x 64 tile of it once: its workgroup writes the two
+// tiles of Ht it determines.
 __global__ __launch_bounds__(256) void cd_prep_kernel(const float* __restrict__ H, int64_t d, int64_t ldp,
                                                       unsigned short* __restrict__ Hth,
                                                       unsigned short* __restrict__ Htl, float* __restrict__ Cd) {
   __shared__ float tile[64][65];
-  __shared__ float diag[64];
+  __shared__ float diag[2][64];
   const int k = blockIdx.z;
-  const int ti = blockIdx.y, tj = blockIdx.x;              // tile of rows i, of columns i'
+  // The tile (ta, tb) of H on or above the diagonal is read once and gives both Ht(ta, tb) and Ht(tb, ta).
+  // Consecutive workgroups take consecutive tiles of one tile row, so that together they stream whole rows of H.
+  const int n_t = (int)(ldp / 64);
+  int ta, tb;
+  tri_decode(blockIdx.x, tb, ta);
+  ta = n_t - 1 - ta;
+  tb = n_t - 1 - tb;
   const float* Hk = H + (int64_t)k * d * d;
-  const int tmin = ti < tj ? ti : tj, tmax = ti < tj ? tj : ti;
   const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
-  for (int r = ty; r < 64; r += 4) {                       // the tile on or above the diagonal
-    const int64_t a = (int64_t)tmin * 64 + r, b = (int64_t)tmax * 64 + tx;
-    tile[r][tx] = (a < d && b < d) ? Hk[a * d + b] : 0.f;
+  float in[16];                                            // all 16 loads of the thread in flight at once
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int64_t a = (int64_t)ta * 64 + ty + 4 * u, b = (int64_t)tb * 64 + tx;
+    in[u] = (a < d && b < d) ? Hk[a * d + b] : 0.f;
   }
-  if (threadIdx.x < 64) {
-    const int64_t i = (int64_t)ti * 64 + threadIdx.x;
-    diag[threadIdx.x] = i < d ? Hk[i * d + i] : 1.f;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) tile[ty + 4 * u][tx] = in[u];
+  if (threadIdx.x < 128) {
+    const int64_t i = (int64_t)(threadIdx.x < 64 ? ta : tb) * 64 + threadIdx.x % 64;
+    diag[threadIdx.x / 64][threadIdx.x % 64] = i < d ? Hk[i * d + i] : 1.f;
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < 64 * 8; idx += 256) {   // local row i, eight local columns i'
-    const int li = idx / 8, lj0 = 8 * (idx % 8);
-    const int64_t i = (int64_t)ti * 64 + li;
-    float v[8];
+  for (int side = 0; side < (ta == tb ? 1 : 2); ++side) {   // side 0: rows i in tile ta; side 1: rows i in tile tb (transposed)
+    const int ti = side == 0 ? ta : tb, tj = side == 0 ? tb : ta;
+    for (int idx = threadIdx.x; idx < 64 * 8; idx += 256) {   // local row i, eight local columns i'
+      const int li = idx / 8, lj0 = 8 * (idx % 8);
+      const int64_t i = (int64_t)ti * 64 + li;
+      const float rd = 1.f / diag[side][li];                // one division per row; the products differ from
+      float v[8];                                           // the quotients by at most one unit in the last place
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int lj = lj0 + e;
-      const int64_t ip = (int64_t)tj * 64 + lj;
-      float h;
-      if (ti < tj) h = tile[li][lj];
-      else if (ti > tj) h = tile[lj][li];
-      else h = li <= lj ? tile[li][lj] : tile[lj][li];
-      v[e] = (i < d && ip < d && i != ip) ? h / diag[li] : 0.f;
+      for (int e = 0; e < 8; ++e) {
+        const int lj = lj0 + e;
+        const int64_t ip = (int64_t)tj * 64 + lj;
+        float h;
+        if (ta == tb) h = li <= lj ? tile[li][lj] : tile[lj][li];
+        else h = side == 0 ? tile[li][lj] : tile[lj][li];
+        v[e] = (i < d && ip < d && i != ip) ? h * rd : 0.f;
+      }
+      store_ht8(k, i, (int64_t)tj * 64 + lj0, ldp, v, Hth, Htl, Cd);
     }
-    store_ht8(k, i, (int64_t)tj * 64 + lj0, ldp, v, Hth, Htl, Cd);
   }
 }
 
@@ -115,10 +128,14 @@ __global__ __launch_bounds__(256) void ldlq_prep_kernel(const float* __restrict_
   const int ti = blockIdx.y, tj = blockIdx.x;              // tile of rows i, of columns i'
   const float* Rk = R + (int64_t)k * d * d;
   const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
-  for (int r = ty; r < 64; r += 4) {                       // R[i'][i]: rows from the tile of i', columns from the tile of i
-    const int64_t a = (int64_t)tj * 64 + r, b = (int64_t)ti * 64 + tx;
-    tile[r][tx] = (tj <= ti && a < d && b < d) ? Rk[a * d + b] : 0.f;
+  float in[16];                                            // R[i'][i]: rows from the tile of i', columns from the tile of i;
+#pragma unroll                                             // all 16 loads of the thread in flight at once
+  for (int u = 0; u < 16; ++u) {
+    const int64_t a = (int64_t)tj * 64 + ty + 4 * u, b = (int64_t)ti * 64 + tx;
+    in[u] = (tj <= ti && a < d && b < d) ? Rk[a * d + b] : 0.f;
   }
+#pragma unroll
+  for (int u = 0; u < 16; ++u) tile[ty + 4 * u][tx] = in[u];
   if (threadIdx.x < 64) {
     const int64_t i = (int64_t)ti * 64 + threadIdx.x;
     diag[threadIdx.x] = i < d ? Rk[i * d + i] : 1.f;
@@ -127,11 +144,12 @@ __global__ __launch_bounds__(256) void ldlq_prep_kernel(const float* __restrict_
   for (int idx = threadIdx.x; idx < 64 * 8; idx += 256) {   // local row i, eight local columns i'
     const int li = idx / 8, lj0 = 8 * (idx % 8);
     const int64_t i = (int64_t)ti * 64 + li;
+    const float rd = 1.f / diag[li];
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int64_t ip = (int64_t)tj * 64 + lj0 + e;
-      v[e] = (i < d && ip < i) ? tile[lj0 + e][li] / diag[li] : 0.f;
+      v[e] = (i < d && ip < i) ? tile[lj0 + e][li] * rd : 0.f;
     }
     store_ht8(k, i, (int64_t)tj * 64 + lj0, ldp, v, Hth, Htl, Cd);
   }
@@ -765,7 +783,7 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
   if (ldlq)
     ldlq_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
   else
-    cd_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
+    cd_prep_kernel<<<dim3(t64 * (t64 + 1) / 2, 1, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
     int64_t bx = (L.ldp + 255) / 256;

@@ -217,7 +217,7 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
                                               const unsigned short* __restrict__ Dl,
                                               const unsigned short* __restrict__ Hth,
                                               const unsigned short* __restrict__ Htl, int64_t d_out, int64_t ldp,
-                                              int G, int n_gt, int n_rt, int blk, int excl,
+                                              int G, int n_gt, int n_rt, int blk, int excl, int k_stages,
                                               float* __restrict__ C) {
   const int k = gidx / n_gt, gt = gidx % n_gt;
   const int64_t m = d_out / G;
@@ -226,8 +226,10 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int wm = wave / 2, wn = wave % 2;
 
-  // contraction range of this part, in stages; the excluded block's stages are stepped over
-  const int64_t n_stages = ldp / kGemmK - (excl >= 0 ? kBlkStages : 0);
+  // contraction range of this part, in stages: the first k_stages of the matrix (all of it, or for the
+  // strictly lower triangular Ht of sequential rounding the part that is not zero); the excluded block's
+  // stages are stepped over
+  const int64_t n_stages = k_stages - (excl >= 0 ? kBlkStages : 0);
   const int64_t s0 = (int64_t)part * n_stages / n_parts, s1 = ((int64_t)part + 1) * n_stages / n_parts;
   const int64_t skip_from = excl >= 0 ? kBlkStages * (int64_t)excl : n_stages;   // excl < 0: nothing is stepped over
 
@@ -678,7 +680,7 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
                                                        unsigned char* __restrict__ Q,
                                                        unsigned short* __restrict__ Dh,
                                                        unsigned short* __restrict__ Dl, float* __restrict__ Cout,
-                                                       int gemm_delay) {
+                                                       int gemm_delay, int k_stages) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
   if ((int)blockIdx.x < n_walk) {
     // (the same dealing for the walk: the tiles of a group, which share its coefficients, on as few XCDs as possible)
@@ -700,7 +702,7 @@ __global__ __launch_bounds__(256) void cd_block_kernel(int n_walk, const float* 
     const int n_tiles = n_gt * G, n_gemm = (int)gridDim.x - n_walk;
     if (n_gemm % 8 == 0 && n_walk % 8 == 0) g = (g % 8) * (n_gemm / 8) + g / 8;
     gemm_far_body(smem, g % n_tiles, g / n_tiles, n_parts, Dh, Dl, Hth, Htl, d_out, ldp, G, n_gt, n_rt, next_blk, excl,
-                  Cout);
+                  k_stages, Cout);
   }
 }
 
@@ -802,7 +804,8 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
   cd_block_kernel<LV><<<dim3((unsigned)(GRID)), dim3(256), 0, st>>>(NWALK, CIN, NIN, L.n_parts, W, What, codebook,       \
                                                                    n_levels, Cd, Hth, Htl, d_out, d_in, ld, L.ldp, G,   \
                                                                    L.n_rt, L.n_gt, BLK, WNEXT, NEXT, EXCL, Q, Dh, Dl,   \
-                                                                   COUT, (NWALK) > 0 ? gemm_delay : 0)
+                                                                   COUT, (NWALK) > 0 ? gemm_delay : 0,                  \
+                                                                   ldlq ? kBlkStages * (NEXT) : (int)(L.ldp / kGemmK))
 #define GQ_LAUNCH_ANY(GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT)                                              \
   do {                                                                                                                  \
     if (n_levels <= 4) GQ_LAUNCH_BLOCK(4, GRID, NWALK, CIN, NIN, BLK, WNEXT, NEXT, EXCL, COUT);                         \

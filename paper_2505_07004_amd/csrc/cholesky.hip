@@ -109,17 +109,34 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
   const int cb = role * kNb + 8 * tc;                                    // this thread's columns in `rows`
   const int64_t c0 = role == 0 ? r0 : r0 + kNb + (int64_t)blockIdx.x * kNb;   // first global column of this half's tile
   if (tid == 0) bad = -1;
+  // The thread's 8 x 8 tile: 32 bytes per row, as two 16-byte loads where the rows are 16-byte aligned
+  // (d a multiple of 4) and the eight columns lie inside the matrix; all loads in flight at once.
+  const bool vec_rows = d % 4 == 0;                          // uniform
   float a[8][8];
+  {
+    const int64_t gc0 = c0 + 8 * tc;
+    const bool whole = vec_rows && gc0 + 7 < d;
+    f32x4 in4[8][2];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i) {
+      const int64_t gr = r0 + 8 * tr + i;
+      if (whole && gr < d) {
+        in4[i][0] = *reinterpret_cast<const f32x4*>(Uk + gr * d + gc0);
+        in4[i][1] = *reinterpret_cast<const f32x4*>(Uk + gr * d + gc0 + 4);
+      } else {
 #pragma unroll
-    for (int l = 0; l < 8; ++l) {
-      const int r = 8 * tr + i, c = 8 * tc + l;
-      const int64_t gr = r0 + r, gc = c0 + c;
-      const bool in = gr < d && gc < d && (role == 1 || r <= c);
-      const float v = Uk[in ? gr * d + gc : 0];
-      a[i][l] = in ? v : ((role == 0 && r == c) ? 1.f : 0.f);
+        for (int l = 0; l < 8; ++l) in4[i][l / 4][l % 4] = (gr < d && gc0 + l < d) ? Uk[gr * d + gc0 + l] : 0.f;
+      }
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int l = 0; l < 8; ++l) {
+        const int r = 8 * tr + i, c = 8 * tc + l;
+        const bool in = r0 + r < d && gc0 + l < d && (role == 1 || r <= c);
+        a[i][l] = in ? in4[i][l / 4][l % 4] : ((role == 0 && r == c) ? 1.f : 0.f);
+      }
+  }
   __syncthreads();
   for (int jb = 0; jb < 16; ++jb) {
     const int buf = jb & 1;
@@ -183,13 +200,20 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
     }
   }
   if (role == 1) {
+    const int64_t gc0 = c0 + 8 * tc;
+    const bool whole = vec_rows && gc0 + 7 < d;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i) {
+      const int64_t gr = r0 + 8 * tr + i;
+      if (whole && gr < d) {
+        *reinterpret_cast<f32x4*>(Uk + gr * d + gc0) = f32x4{a[i][0], a[i][1], a[i][2], a[i][3]};
+        *reinterpret_cast<f32x4*>(Uk + gr * d + gc0 + 4) = f32x4{a[i][4], a[i][5], a[i][6], a[i][7]};
+      } else {
 #pragma unroll
-      for (int l = 0; l < 8; ++l) {
-        const int64_t gr = r0 + 8 * tr + i, gc = c0 + 8 * tc + l;
-        if (gr < d && gc < d) Uk[gr * d + gc] = a[i][l];
+        for (int l = 0; l < 8; ++l)
+          if (gr < d && gc0 + l < d) Uk[gr * d + gc0 + l] = a[i][l];
       }
+    }
     // ... and once more for the trailing update: three bf16 terms, column-major (the rows of U12, the
     // contraction index of the update, contiguous): P3[k][term][column][koff + row]; a thread's eight
     // rows of one column are 16 bytes per term
@@ -210,9 +234,13 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
   } else if (blockIdx.x == 0) {
     float* Ub = Ud + ((int64_t)k * ((d + kNb - 1) / kNb) + r0 / kNb) * (kNb * kNb);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i) {
+      f32x4 o[2];
 #pragma unroll
-      for (int l = 0; l < 8; ++l) Ub[(8 * tr + i) * kNb + 8 * tc + l] = (8 * tr + i <= 8 * tc + l) ? a[i][l] : 0.f;
+      for (int l = 0; l < 8; ++l) o[l / 4][l % 4] = (8 * tr + i <= 8 * tc + l) ? a[i][l] : 0.f;
+      *reinterpret_cast<f32x4*>(Ub + (8 * tr + i) * kNb + 8 * tc) = o[0];
+      *reinterpret_cast<f32x4*>(Ub + (8 * tr + i) * kNb + 8 * tc + 4) = o[1];
+    }
   }
   __syncthreads();
   if (tid == 0 && blockIdx.x == 0 && bad >= 0 && info && info[k] == 0) info[k] = (int)(r0 + bad) + 1;

@@ -157,13 +157,16 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
           for (int l = i; l < 8; ++l) a[i][l] -= a[jj][i] * a[jj][l];
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int i = 0; i < 8; ++i) {
+        f32x4 o[2];
 #pragma unroll
-        for (int l = 0; l < 8; ++l) {
-          const float v = l >= i ? a[i][l] : 0.f;
-          dtile[buf][i][l] = v;
-          rows[buf][i][cb + l] = v;
+        for (int l = 0; l < 8; ++l) o[l / 4][l % 4] = l >= i ? a[i][l] : 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          *reinterpret_cast<f32x4*>(&dtile[buf][i][4 * h]) = o[h];
+          *reinterpret_cast<f32x4*>(&rows[buf][i][cb + 4 * h]) = o[h];
         }
+      }
     }
     __syncthreads();
     if (tr == jb && (role == 1 || tc > jb)) {                 // b. the rest of the eight rows: U_dd^T X = A
@@ -179,9 +182,10 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
         }
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int l = 0; l < 8; ++l) rows[buf][i][cb + l] = a[i][l];
+      for (int i = 0; i < 8; ++i) {
+        *reinterpret_cast<f32x4*>(&rows[buf][i][cb]) = f32x4{a[i][0], a[i][1], a[i][2], a[i][3]};
+        *reinterpret_cast<f32x4*>(&rows[buf][i][cb + 4]) = f32x4{a[i][4], a[i][5], a[i][6], a[i][7]};
+      }
     }
     __syncthreads();
     if (tr > jb && (role == 1 || tc >= tr)) {                 // c. rank-8 update of everything further down

@@ -80,6 +80,16 @@ __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict_
   }
 }
 
+// the value a register holds in lane `l` of the wave (l uniform)
+__device__ __forceinline__ float lane_value(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+// between an LDS write by one lane and the read of it by another lane of the same wave
+__device__ __forceinline__ void wave_lds_fence() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // (1) + (2) One block row: the diagonal block A11 = U11^T U11 at (r0, r0) and the panel to its right,
 // U12 = U11^-T A12, in one launch.  A workgroup owns 128 columns of the panel; its threads 256..511 hold
 // that 128 x 128 tile of A12 in registers (thread (tr, tc) of 16 x 16 the 8 x 8 tile at rows 8 tr, columns
@@ -101,6 +111,7 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
                                                              float* __restrict__ Ud, unsigned short* __restrict__ P3,
                                                              int64_t ldc, int koff, int* __restrict__ info) {
   __shared__ __attribute__((aligned(16))) float dtile[2][8][8];
+  __shared__ __attribute__((aligned(16))) float draw[8][8];            // the diagonal tile of a pass before it is factored
   __shared__ __attribute__((aligned(16))) float rows[2][8][2 * kNb];   // columns 0..127: diagonal block, 128..255: panel
   __shared__ int bad;
   const int k = blockIdx.y;
@@ -140,31 +151,55 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
   __syncthreads();
   for (int jb = 0; jb < 16; ++jb) {
     const int buf = jb & 1;
-    if (role == 0 && tr == jb && tc == jb) {                  // a. the diagonal tile
+    if (role == 0 && tr / 4 == jb / 4) {                      // a. the diagonal tile (uniform: the wave that holds it)
+      // Its owner hands the tile to eight lanes of its wave (those of tile row jb, columns 0..7 of it), one
+      // column each; the eight pivots then cost one cross-lane read each instead of a chain through all
+      // 36 elements in one lane.  Same operations on the same values as the factorization of an 8 x 8 tile
+      // by one thread.  LDS accesses of one wave execute in order; the fence only stops the compiler.
+      if (tr == jb && tc == jb) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          *reinterpret_cast<f32x4*>(&draw[i][0]) = f32x4{a[i][0], a[i][1], a[i][2], a[i][3]};
+          *reinterpret_cast<f32x4*>(&draw[i][4]) = f32x4{a[i][4], a[i][5], a[i][6], a[i][7]};
+        }
+      }
+      wave_lds_fence();
+      const int hl = tc & 7;
+      float col[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) col[i] = draw[i][hl];
+      const int lane_base = 16 * (jb % 4);                    // lane of (tile row jb, tile column 0) in this wave
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
-        float p = a[jj][jj];
-        const bool ok = p > 0.f;                              // false for NaN as well
-        if (!ok && bad < 0) bad = 8 * jb + jj;
+        float p = lane_value(col[jj], lane_base + jj);
+        const bool ok = p > 0.f;                              // false for NaN as well (uniform)
+        if (!ok && tr == jb && tc == 0 && bad < 0) bad = 8 * jb + jj;
         p = ok ? p : 1.f;
         const float sp = __builtin_amdgcn_sqrtf(p), isp = __builtin_amdgcn_rcpf(sp);
-        a[jj][jj] = sp;
+        const float u = hl == jj ? sp : col[jj] * isp;        // row jj of the factor, this lane's column
+        col[jj] = u;
 #pragma unroll
-        for (int l = jj + 1; l < 8; ++l) a[jj][l] *= isp;
-#pragma unroll
-        for (int i = jj + 1; i < 8; ++i)
-#pragma unroll
-          for (int l = i; l < 8; ++l) a[i][l] -= a[jj][i] * a[jj][l];
+        for (int i = jj + 1; i < 8; ++i) col[i] -= lane_value(u, lane_base + i) * u;
       }
+      if (tr == jb && tc < 8) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        f32x4 o[2];
+        for (int i = 0; i < 8; ++i) {
+          const float v = hl >= i ? col[i] : 0.f;
+          dtile[buf][i][hl] = v;
+          rows[buf][i][8 * jb + hl] = v;
+        }
+      }
+      wave_lds_fence();
+      if (tr == jb && tc == jb) {                             // the owner takes the factored tile back
 #pragma unroll
-        for (int l = 0; l < 8; ++l) o[l / 4][l % 4] = l >= i ? a[i][l] : 0.f;
+        for (int i = 0; i < 8; ++i) {
+          const f32x4 lo = *reinterpret_cast<const f32x4*>(&dtile[buf][i][0]);
+          const f32x4 hi = *reinterpret_cast<const f32x4*>(&dtile[buf][i][4]);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          *reinterpret_cast<f32x4*>(&dtile[buf][i][4 * h]) = o[h];
-          *reinterpret_cast<f32x4*>(&rows[buf][i][cb + 4 * h]) = o[h];
+          for (int l = 0; l < 4; ++l) {
+            a[i][l] = lo[l];
+            a[i][4 + l] = hi[l];
+          }
         }
       }
     }

@@ -15,7 +15,8 @@
 // later coordinates i'' of the block move by -eps * Ht[i''][i].  The block's new delta is
 // written back (split) for the later GEMMs.  The GEMM of block b + 1 runs in the same launch as
 // the walk of block b (other workgroups) and leaves out block b's 128 contraction elements; the
-// walk of b + 1 adds their share itself.
+// walk of b ends by computing their share from its own fresh values, as one more partial sum of
+// block b + 1.
 // Compared with Algorithm 4 the bookkeeping differs (the part of the sum that lies outside
 // the block is recomputed per block from the current weights instead of being carried along
 // and corrected after each block; the flop count is the same), the update rule does not.
@@ -25,7 +26,7 @@ namespace gq {
 namespace {
 
 constexpr int kBlk = 128;             // coordinates per block
-constexpr int kRows = 64;             // channels per workgroup row tile (GEMM) / per wave (sequential kernel)
+constexpr int kRows = 64;             // channels per workgroup of the walk
 constexpr int kMaxLevels = 16;        // most grid points per channel (4 bits)
 
 // Ht is stored in the order the GEMM consumes it: per group and block of 128 rows i, for every stage
@@ -191,10 +192,11 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
   }
 }
 
-// Partial sums of B0 for block `blk`:  C[part][i][j] = sum over this part's contraction range
-// of delta[j][i'] * Ht[blk*128 + i][i'],  i < 128, j a channel (j contiguous, pitch d_out),
-// WITHOUT the 128 contraction elements of block `excl`: those belong to the block that is being
-// walked while this runs, and the walk of `blk` adds their share itself once they are final.
+// Partial sums of B0 for block `blk`:  C[part][walk tile][j][i] = sum over this part's contraction
+// range of delta[j][i'] * Ht[blk*128 + i][i'],  i < 128, j a channel slot of a 64-channel walk tile
+// (the layout of W: coordinates contiguous), WITHOUT the 128 contraction elements of block `excl`:
+// those belong to the block that is being walked while this runs, and that walk supplies their
+// share itself, as one more part, once they are final.
 // A workgroup owns 128 channels of one group and all 128 coordinates of the block; its 4
 // waves compute 64 x 64 each.  Both operands are contraction-major in memory; a stage is 32
 // contraction elements = 64 bytes of each of the 4 x 128 operand rows ({delta, Ht} x {hi, lo}),
@@ -344,14 +346,14 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
 }
 
 // The sequential walk through block `blk`: a workgroup of 4 waves per 64 channels of a group,
-// FOUR LANES PER CHANNEL.  The block of W and What is moved between global memory and LDS row
-// by row (coalesced); the block's 128 x 128 coefficients sit in LDS too.  The 128 targets of a
+// FOUR LANES PER CHANNEL.  The block of W and What moves between global memory and LDS 16 bytes
+// per lane; the block's 128 x 128 coefficients sit in LDS too.  The 128 targets of a
 // channel live in LDS; the block is walked in four runs of 32 coordinates.  Inside a run every
 // lane of the quad keeps 8 of the 32 targets in registers: the owner broadcasts the target of
 // the current coordinate to its quad (DPP), every lane tries a quarter of the grid, two DPP
 // exchanges settle the nearest point (lowest index among equals), and every lane corrects its
 // own 8 targets.  The targets after the run are corrected when the run is over (32 changes at
-// a time, each lane again its own 8 per run).  Channels past the end of the group repeat its
+// a time, on the fp32 matrix cores).  Channels past the end of the group repeat its
 // last channel, and all four lanes of a quad store the same values, so no lane is ever masked.
 // LV = 4, 8 or 16 bounds the number of grid points (the search is unrolled over it).
 constexpr int kRun = 32;

@@ -416,6 +416,138 @@ __global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, 
   }
 }
 
+// The same update for tiles of 256 rows by 128 columns (used for the update with both block rows of a
+// pair, where it is nearly all of the work): a workgroup then pulls 3 x (256 + 128) operand rows for
+// twice the products, a quarter less per product, and the update is bound by exactly that traffic.
+// Tile row p covers the block rows 2p and 2p + 1 of the trailing matrix and the block columns tj >= 2p
+// (for tj = 2p the lower half lies below the diagonal and is masked like every entry there).
+// 4 waves of 128 x 64; a stage is 16 contraction elements (9 terms-of-128-rows of 4 KiB: 36 KiB), ring of
+// four, the loads of a stage issued two stages ahead and before the wait for the current one; chunk c
+// (of two) of row r sits at position c ^ ((r >> 2) & 1).
+constexpr int kS2K = 16;
+constexpr int kS2Tile = kNb * kS2K * 2;               // 4 KiB
+constexpr int kS2Stage = 9 * kS2Tile;                 // 36 KiB
+constexpr int kS2Ring = 4;
+constexpr int kS2Loads = 9;                           // 1 KiB loads per wave and stage
+__global__ __launch_bounds__(256) void chol_syrk2_kernel(float* __restrict__ Uw, int64_t d,
+                                                         const unsigned short* __restrict__ P3, int64_t ldc, int n_k,
+                                                         int64_t t0, int nb) {
+  __shared__ __attribute__((aligned(1024))) char smem[kS2Ring * kS2Stage];
+  const int k = blockIdx.y;
+  float* Uk = Uw + (int64_t)k * d * d;
+  int p = 0, tj = (int)blockIdx.x;                            // tile row p holds nb - 2p tiles (uniform loop)
+  while (2 * p < nb && tj >= nb - 2 * p) {
+    tj -= nb - 2 * p;
+    ++p;
+  }
+  if (2 * p >= nb) return;                                    // (the grid holds exactly the tiles there are)
+  tj += 2 * p;
+  const int64_t a0 = t0 + (int64_t)(2 * p) * kNb, b0 = t0 + (int64_t)tj * kNb;
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int wm = wave / 2, wn = wave % 2;
+  const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
+
+  // staging: load g = 9 wave + i of a stage moves rows 32 (g % 4) .. + 31 of staged tile g / 4
+  // (tiles 0..2: the three terms of rows a0 .. a0 + 127, 3..5: of rows a0 + 128 .., 6..8: of columns b0 ..)
+  const unsigned short* lsrc[kS2Loads];
+  unsigned ldst[kS2Loads];
+#pragma unroll
+  for (int i = 0; i < kS2Loads; ++i) {
+    const int g = wave * kS2Loads + i, tile = g / 4, i4 = g % 4;
+    const int r = 32 * i4 + lane / 2;
+    const int c = (lane % 2) ^ ((r >> 2) & 1);
+    int64_t col = (tile < 6 ? a0 + (int64_t)(tile / 3) * kNb : b0) + r;
+    col = col < ldc ? col : ldc - 1;                          // a second block row past the matrix: masked below
+    lsrc[i] = P3 + ((((int64_t)k * 3 + tile % 3) * ldc + col) * kPair + 8 * c);
+    ldst[i] = tile * kS2Tile + i4 * 1024;
+  }
+  auto issue = [&](int stage) {
+    const int slot = stage % kS2Ring;
+#pragma unroll
+    for (int i = 0; i < kS2Loads; ++i) dma16(lsrc[i] + stage * kS2K, smem_base + slot * kS2Stage + ldst[i]);
+  };
+  const int lrow = lane % 32;
+  auto frag = [&](int slot, int tile, int row0) -> bf16x8 {
+    const int pos = (lane / 32) ^ ((lrow >> 2) & 1);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kS2Stage + tile * kS2Tile + (row0 + lrow) * 32 + pos * 16]);
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int x = 0; x < 4; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+  const int n_stages = n_k / kS2K;
+  issue(0);
+  if (n_stages > 1) issue(1);
+  for (int s = 0; s < n_stages; ++s) {
+    const int slot = s % kS2Ring;
+    if (s + 2 < n_stages) {                                     // uniform
+      issue(s + 2);                                             // its slot's last readers were two barriers ago
+      wait_vmcnt<2 * kS2Loads>();
+    } else if (s + 1 < n_stages) {
+      wait_vmcnt<kS2Loads>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();                               // everyone's part of stage s is there
+    bf16x8 a[4][3], b[2][3];
+#pragma unroll
+    for (int term = 0; term < 3; ++term) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) a[x][term] = frag(slot, 3 * wm + term, 32 * x);
+#pragma unroll
+      for (int y = 0; y < 2; ++y) b[y][term] = frag(slot, 6 + term, wn * 64 + 32 * y);
+    }
+    // smallest products first; (row term, column term): (0,2) (2,0) (1,1) (0,1) (1,0) (0,0)
+    constexpr int kTa[6] = {0, 2, 1, 0, 1, 0}, kTb[6] = {2, 0, 1, 1, 0, 0};
+#pragma unroll
+    for (int pr = 0; pr < 6; ++pr)
+#pragma unroll
+      for (int y = 0; y < 2; ++y)
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x][kTa[pr]], b[y][kTb[pr]], acc[x][y], 0, 0, 0);
+  }
+
+  // accumulator register r of lane l holds row 8*(r/4)+4*(l/32)+(r%4), column l%32; the epilogue of the
+  // 128 x 128 kernel, over the wave's 128 rows
+  const int64_t row_w = a0 + wm * kNb;
+  const int64_t rows_valid = (d - row_w) < kNb ? (d - row_w) : kNb;
+  const int records = rows_valid > 0 ? (int)(rows_valid * d * (int64_t)sizeof(float)) : 0;
+  const __amdgpu_buffer_rsrc_t res =
+      __builtin_amdgcn_make_buffer_rsrc(Uk + (rows_valid > 0 ? row_w : 0) * d, 0, records, kBufferWord3);
+  const unsigned dbytes = (unsigned)(d * (int64_t)sizeof(float));
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    float old[2][16];
+    unsigned off[2][16];
+#pragma unroll
+    for (int y = 0; y < 2; ++y) {
+      const int64_t col = b0 + wn * 64 + y * 32 + lane % 32;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int lr = x * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        const bool keep = (row_w + lr < d) & (col < d) & (row_w + lr <= col);
+        off[y][r] = keep ? (unsigned)lr * dbytes + (unsigned)(col * (int64_t)sizeof(float)) : kBufferOutside;
+        old[y][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(res, off[y][r], 0, 0));
+      }
+    }
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float val = acc[x][y][r];
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, old[y][r] - val), res, off[y][r], 0, 0);
+      }
+  }
+}
+
 // The factor in the requested form, every entry of F written: L[i][j] = U[j][i] (i >= j), zeros above
 // the diagonal; or R[i][j] = U[d-1-j][d-1-i] (i <= j), zeros below.  One workgroup per 64 x 64 tile of F.
 __global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict__ Uw, const float* __restrict__ Ud,
@@ -499,7 +631,16 @@ hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_
     const int64_t t1 = t0 + kNb, trail1 = d - t1;
     if (trail1 <= 0) break;
     const int64_t tt1 = (trail1 + kNb - 1) / kNb;
-    chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, 0);
+    // Large trailing matrices take the 256 x 128 tiles (less operand traffic per product); small ones, where
+    // a launch is only a few rounds of workgroups, the 128 x 128 tiles (twice as many, shorter workgroups).
+    // Measured cross-over on MI355X: about 3000 workgroups of the smaller kind.
+    if (tri_count(tt1) * G >= 3000) {
+      int64_t n_tiles2 = 0;                                   // tile row p has tt1 - 2p tiles
+      for (int64_t p = 0; 2 * p < tt1; ++p) n_tiles2 += tt1 - 2 * p;
+      chol_syrk2_kernel<<<dim3((unsigned)n_tiles2, (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, (int)tt1);
+    } else {
+      chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, 0);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, Ud, d, reverse ? 1 : 0, F);

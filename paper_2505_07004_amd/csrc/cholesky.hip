@@ -80,6 +80,15 @@ __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict_
   }
 }
 
+// The rows of U12 as three bf16 terms, for the trailing update: per group and term, for every step of 16
+// contraction elements (rows of U12), all columns one after the other with their 16 elements (32 bytes).
+// A workgroup's operand tile for a step (128 columns) is one contiguous 4 KiB run, so every 1 KiB direct
+// load moves whole cache lines.
+constexpr int kP3Step = 16;
+__device__ __forceinline__ int64_t p3_index(int64_t k, int term, int64_t row, int64_t col, int64_t ldc) {
+  return ((((k * 3 + term) * (kPair / kP3Step) + row / kP3Step) * ldc + col) * kP3Step) + row % kP3Step;
+}
+
 // the value a register holds in lane `l` of the wave (l uniform)
 __device__ __forceinline__ float lane_value(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
@@ -253,9 +262,8 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
           if (gr < d && gc0 + l < d) Uk[gr * d + gc0 + l] = a[i][l];
       }
     }
-    // ... and once more for the trailing update: three bf16 terms, column-major (the rows of U12, the
-    // contraction index of the update, contiguous): P3[k][term][column][koff + row]; a thread's eight
-    // rows of one column are 16 bytes per term
+    // ... and once more for the trailing update: three bf16 terms in the order the update consumes them
+    // (p3_index): a thread's eight rows of one column are 16 bytes per term
 #pragma unroll
     for (int l = 0; l < 8; ++l) {
       unsigned short t[3][8];
@@ -267,7 +275,7 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
         u32x4 w;
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (unsigned)t[term][2 * e] | ((unsigned)t[term][2 * e + 1] << 16);
-        *reinterpret_cast<u32x4*>(P3 + ((((int64_t)k * 3 + term) * ldc + gc) * kPair + koff + 8 * tr)) = w;
+        *reinterpret_cast<u32x4*>(P3 + p3_index(k, term, koff + 8 * tr, gc, ldc)) = w;
       }
     }
   } else if (blockIdx.x == 0) {
@@ -295,7 +303,7 @@ __global__ __launch_bounds__(512) void chol_block_row_kernel(float* __restrict__
 // term products the six that matter (hi*hi, hi*mid, mid*hi, hi*lo, lo*hi, mid*mid; the others are
 // below 2^-24 of the result) -- 2.7 times fewer matrix-core cycles than the fp32 instruction.
 // 4 waves of 64 x 64; a stage is 32 contraction elements of the 2 x 3 x 128 operand rows (48 KiB,
-// global_load_lds_dwordx4, chunk c of row r at position c ^ ((r >> 2) & 3)), ring of three stages.
+// global_load_lds_dwordx4), ring of three stages.
 // The tile itself is read and written through a buffer resource, 32 loads in flight, no branch.
 constexpr int kSK = 32;                               // contraction elements per stage
 constexpr int kSTile = kNb * kSK * 2;                 // one staged term of one side (8 KiB)
@@ -318,27 +326,31 @@ __global__ __launch_bounds__(256) void chol_syrk_kernel(float* __restrict__ Uw, 
   const int wm = wave / 2, wn = wave % 2;
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
 
-  // staging: load g = 12 wave + i of a stage moves rows 16 (g % 8) .. + 15 of tile g / 8
-  // (tiles 0..2: the three terms of the tile's rows a0.., 3..5: of its columns b0..)
+  // staging: a staged tile (one term of one side, 8 KiB) is two halves of 16 contraction elements, each
+  // [128 rows][32 bytes] as it lies in P3; load g = 12 wave + i of a stage moves rows 32 (g % 4) .. + 31 of
+  // half (g / 4) % 2 of tile g / 8 (tiles 0..2: the three terms of the tile's rows a0.., 3..5: of its
+  // columns b0..); chunk c (of two) of row r sits at position c ^ ((r >> 2) & 1)
   const unsigned short* lsrc[kSLoads];
   unsigned ldst[kSLoads];
 #pragma unroll
   for (int i = 0; i < kSLoads; ++i) {
-    const int g = wave * kSLoads + i, tile = g / 8, i8 = g % 8;
-    const int r = 16 * i8 + lane / 4;
-    const int c = (lane % 4) ^ ((r >> 2) & 3);
+    const int g = wave * kSLoads + i, tile = g / 8, half = (g / 4) % 2, i4 = g % 4;
+    const int r = 32 * i4 + lane / 2;
+    const int c = (lane % 2) ^ ((r >> 2) & 1);
     const int64_t col = (tile < 3 ? a0 : b0) + r;               // < ldc
-    lsrc[i] = P3 + ((((int64_t)k * 3 + tile % 3) * ldc + col) * kPair + 8 * c);
-    ldst[i] = tile * kSTile + i8 * 1024;
+    lsrc[i] = P3 + p3_index(k, tile % 3, kP3Step * half + 8 * c, col, ldc);
+    ldst[i] = tile * kSTile + half * (kSTile / 2) + i4 * 1024;
   }
+  const int64_t stage_pitch = (kSK / kP3Step) * ldc * kP3Step;  // elements from one stage to the next
   auto issue = [&](int stage, int slot) {
 #pragma unroll
-    for (int i = 0; i < kSLoads; ++i) dma16(lsrc[i] + stage * kSK, smem_base + slot * kSStage + ldst[i]);
+    for (int i = 0; i < kSLoads; ++i) dma16(lsrc[i] + stage * stage_pitch, smem_base + slot * kSStage + ldst[i]);
   };
   const int lrow = lane % 32;
   auto frag = [&](int slot, int tile, int row0, int t) -> bf16x8 {
-    const int pos = (2 * t + lane / 32) ^ ((lrow >> 2) & 3);
-    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kSStage + tile * kSTile + (row0 + lrow) * 64 + pos * 16]);
+    const int pos = (lane / 32) ^ ((lrow >> 2) & 1);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(
+        &smem[slot * kSStage + tile * kSTile + t * (kSTile / 2) + (row0 + lrow) * 32 + pos * 16]);
     return __builtin_bit_cast(bf16x8, v);
   };
 
@@ -459,13 +471,15 @@ __global__ __launch_bounds__(256) void chol_syrk2_kernel(float* __restrict__ Uw,
     const int c = (lane % 2) ^ ((r >> 2) & 1);
     int64_t col = (tile < 6 ? a0 + (int64_t)(tile / 3) * kNb : b0) + r;
     col = col < ldc ? col : ldc - 1;                          // a second block row past the matrix: masked below
-    lsrc[i] = P3 + ((((int64_t)k * 3 + tile % 3) * ldc + col) * kPair + 8 * c);
+    lsrc[i] = P3 + p3_index(k, tile % 3, 8 * c, col, ldc);
     ldst[i] = tile * kS2Tile + i4 * 1024;
   }
+  static_assert(kS2K == kP3Step, "one step of P3 per stage");
+  const int64_t stage_pitch = ldc * kP3Step;                    // elements from one stage to the next
   auto issue = [&](int stage) {
     const int slot = stage % kS2Ring;
 #pragma unroll
-    for (int i = 0; i < kS2Loads; ++i) dma16(lsrc[i] + stage * kS2K, smem_base + slot * kS2Stage + ldst[i]);
+    for (int i = 0; i < kS2Loads; ++i) dma16(lsrc[i] + stage * stage_pitch, smem_base + slot * kS2Stage + ldst[i]);
   };
   const int lrow = lane % 32;
   auto frag = [&](int slot, int tile, int row0) -> bf16x8 {

@@ -199,14 +199,12 @@ __global__ __launch_bounds__(256) void cd_delta_kernel(const float* __restrict__
 // share itself, as one more part, once they are final.
 // A workgroup owns 128 channels of one group and all 128 coordinates of the block; its 4
 // waves compute 64 x 64 each.  Both operands are contraction-major in memory; a stage is 32
-// contraction elements = 64 bytes of each of the 4 x 128 operand rows ({delta, Ht} x {hi, lo}),
-// copied straight into LDS (global_load_lds_dwordx4: 4 lanes per row, wave w copies operand w)
+// contraction elements = one 128-byte line (hi halves, lo halves) of each of the 2 x 128 operand
+// rows (delta, Ht), copied straight into LDS (global_load_lds_dwordx4: 8 lanes per row)
 // into a ring of four stages.  The loads of a stage are issued two stages ahead, BEFORE the wait
 // for the current one, so the memory pipe never runs dry, and a slot is not written again before
-// the barrier after its last reader: one barrier per stage.  A row of a staged tile holds four
-// 16-byte chunks; chunk c of row r sits at position c ^ ((r >> 1) & 3), which makes the 16-byte
-// fragment reads of 8 consecutive rows conflict-free (the loading lane applies the same XOR when it
-// picks its global chunk).  The parts split the contraction; the walk adds them in a fixed order.
+// the barrier after its last reader: one barrier per stage.  The parts split the contraction; the
+// walk adds them in a fixed order.
 constexpr int kGemmRows = 128;                       // channels per workgroup
 constexpr int kGemmK = 32;                           // contraction elements per stage
 constexpr int kGemmTile = 128 * kGemmK * 2;          // bytes of one staged operand tile (8 KiB)
@@ -235,18 +233,22 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
   const int64_t s0 = (int64_t)part * n_stages / n_parts, s1 = ((int64_t)part + 1) * n_stages / n_parts;
   const int64_t skip_from = excl >= 0 ? kBlkStages * (int64_t)excl : n_stages;   // excl < 0: nothing is stepped over
 
-  // ---- staging: wave w copies operand w (0: delta hi, 1: delta lo, 2: Ht hi, 3: Ht lo); load
-  // number i moves rows 16 i .. 16 i + 15, lane -> (row 16 i + lane / 4, position lane % 4)
-  // both are stage-major with 64 halves per row and stage: delta over all channels, Ht over the block's 128 rows
-  const unsigned short* src = wave == 0 ? Dh : wave == 1 ? Dl : (wave == 2 ? Hth : Htl) + ht_index(k, (int64_t)blk * kBlk, 0, ldp);
-  const int64_t row_first = wave < 2 ? j0 : 0, row_last = wave < 2 ? j_last : kBlk - 1;
-  const int64_t row_pitch = 2 * kGemmK, stage_pitch = (wave < 2 ? d_out : (int64_t)kBlk) * 2 * kGemmK;
+  // ---- staging: a row of an operand in a stage is one 128-byte line (32 hi halves, then 32 lo halves) and
+  // is staged as it lies in memory, so every direct load moves 8 whole lines: waves 0 and 1 copy rows 0..63
+  // and 64..127 of delta, waves 2 and 3 of Ht; load number i moves rows 8 i .. 8 i + 7 of the wave's 64,
+  // lane -> (row 8 i + lane / 8, position lane % 8).  Logical 16-byte chunk c of row r sits at position
+  // c ^ (r & 7): the fragment reads of 8 consecutive rows are conflict-free (the loading lane applies the
+  // same XOR when it picks its global chunk; 8 i is a multiple of 8, so its chunk is the same for every load).
+  const int op = wave / 2;                                  // 0: delta (over all channels), 1: Ht (the block's 128 rows)
+  const unsigned short* src = op == 0 ? Dh : Hth + ht_index(k, (int64_t)blk * kBlk, 0, ldp);
+  const int64_t row_first = op == 0 ? j0 : 0, row_last = op == 0 ? j_last : kBlk - 1;
+  const int64_t row_pitch = 2 * kGemmK, stage_pitch = (op == 0 ? d_out : (int64_t)kBlk) * 2 * kGemmK;
   const unsigned smem_base = (unsigned)(uintptr_t)(lds_char_ptr)smem;
   const unsigned short* lane_src[kGemmLoads];               // this lane's chunk in stage 0, per load
 #pragma unroll
   for (int i = 0; i < kGemmLoads; ++i) {
-    const int r = 16 * i + lane / 4;
-    const int c = (lane % 4) ^ ((r >> 1) & 3);
+    const int r = 64 * (wave % 2) + 8 * i + lane / 8;
+    const int c = (lane % 8) ^ (r & 7);
     int64_t row = row_first + r;
     row = row < row_last ? row : row_last;                  // rows past the group: repeat its last row
     lane_src[i] = src + row * row_pitch + 8 * c;
@@ -256,14 +258,16 @@ __device__ __forceinline__ void gemm_far_body(char* smem, int gidx, int part, in
     const int64_t off = (stage < skip_from ? stage : stage + kBlkStages) * stage_pitch;
 #pragma unroll
     for (int i = 0; i < kGemmLoads; ++i)
-      dma16(lane_src[i] + off, smem_base + slot * kGemmStage + wave * kGemmTile + i * 1024);
+      dma16(lane_src[i] + off, smem_base + slot * kGemmStage + op * (2 * kGemmTile) + (64 * (wave % 2) + 8 * i) * 128);
   };
 
-  // ---- fragments: row l % 32 of a 32-row block, chunk 2 t + l / 32 of its 32 contraction elements
+  // ---- fragments: row l % 32 of a 32-row block, chunk 2 t + l / 32 of the 32 contraction elements of
+  // term `term` (0: hi, 1: lo) of operand `o`
   const int lrow = lane % 32;
   auto frag = [&](int slot, int tile, int row0, int t) -> bf16x8 {
-    const int pos = (2 * t + lane / 32) ^ ((lrow >> 1) & 3);
-    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kGemmStage + tile * kGemmTile + (row0 + lrow) * 64 + pos * 16]);
+    const int o = tile / 2, term = tile % 2;
+    const int pos = (4 * term + 2 * t + lane / 32) ^ (lrow & 7);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&smem[slot * kGemmStage + o * (2 * kGemmTile) + (row0 + lrow) * 128 + pos * 16]);
     return __builtin_bit_cast(bf16x8, v);
   };
 

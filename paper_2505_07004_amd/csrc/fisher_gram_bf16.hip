@@ -49,10 +49,19 @@ __device__ inline int lds_chunk_off(int r, int c) {
 }
 
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
-__device__ inline u32x2 lds_read_tr(const char* p) {
-  bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p);
+typedef const f32x4 __attribute__((address_space(3))) * lds_f32x4_ptr;
+// Transposing LDS read at a 32-bit LDS byte address.
+__device__ inline u32x2 lds_read_tr(unsigned addr) {
+  bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<lds_bf16x4_ptr>(addr));
   return __builtin_bit_cast(u32x2, v);
 }
+// Per-lane LDS byte addresses of one ring stage: the two scaled-operand fragments, the four
+// swizzle classes of the raw fragments, the wave's weights.
+struct LBase {
+  unsigned a[2];
+  unsigned b[4];
+  unsigned s;
+};
 
 // 8 bf16 (as 4 dwords) of tokens t..t+7 times their 8 fp32 weights, rounded to bf16 (RNE).
 __device__ inline bf16x8 scale_frag(u32x2 lo, u32x2 hi, f32x4 s0, f32x4 s1) {
@@ -236,19 +245,22 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     // 4-byte-per-lane load of its group's weights.  LDS slot q (16 B units) of a tile holds
     // token row q / CHUNKS and physical chunk q % CHUNKS; the lane fetches the logical chunk
     // that the swizzle stores there.
-    // Per load: the running global address (advancing one stage per issue) and the address of the
-    // same columns in the last token row.  Rows past the last token are read from that row
-    // instead (their weight is 0), which for a fixed column is simply min(running, last).
-    const char* prun[C::kLoads];
-    const char* plast[C::kLoads];
+    // Every load is "wave-uniform base + 32-bit byte offset of the lane": the base is the first
+    // token row of the stage and lives in scalar registers (advancing a stage is scalar
+    // arithmetic), the offset (token row inside the stage x pitch + column) is fixed for the
+    // whole item.  Stages past the last one re-read the last one (their data is never used);
+    // in the last stage, rows past the last token are read from that token's row instead (their
+    // weight is 0): a second set of offsets, swapped in once when the fill reaches that stage.
+    unsigned vo[C::kLoads - 1], vo_last[C::kLoads - 1];
+    const int r_last = (int)(last_row - (steps - 1) * kStep);      // last valid row of the last stage
 #pragma unroll
     for (int h = 0; h < C::kALoads; ++h) {
       const int q = (wave * C::kALoads + h) * 64 + lane;
       const int r = q / kAChunks;
       int64_t c = row_t + 8 * swizzle<kAChunks>(r, q % kAChunks);
       if (c + 8 > ld) c = ld - 8;                  // stays inside the row pitch; feeds only unstored outputs
-      prun[h] = reinterpret_cast<const char*>(X + (k0 * kStep + r) * ld + c);
-      plast[h] = reinterpret_cast<const char*>(X + last_row * ld + c);
+      vo[h] = (unsigned)((r * ld + c) * 2);
+      vo_last[h] = (unsigned)(((r < r_last ? r : r_last) * ld + c) * 2);
     }
 #pragma unroll
     for (int h = 0; h < C::kBLoads; ++h) {
@@ -256,46 +268,85 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
       const int r = q / kBChunks;
       int64_t c = col_t + 8 * swizzle<kBChunks>(r, q % kBChunks);
       if (c + 8 > ld) c = ld - 8;
-      prun[C::kALoads + h] = reinterpret_cast<const char*>(X + (k0 * kStep + r) * ld + c);
-      plast[C::kALoads + h] = reinterpret_cast<const char*>(X + last_row * ld + c);
+      vo[C::kALoads + h] = (unsigned)((r * ld + c) * 2);
+      vo_last[C::kALoads + h] = (unsigned)(((r < r_last ? r : r_last) * ld + c) * 2);
     }
-    // weights: lane l of every wave fetches float l of the wave's group from the current stage on
-    // (64 floats: the second half belongs to the next stage and is never read from this slot);
-    // the padding of the repacked weights makes every such read valid
-    prun[C::kLoads - 1] = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad + k0 * kStep + lane);
-    plast[C::kLoads - 1] = nullptr;
+    // weights: lane l of every wave fetches float l of the wave's group from the stage's first token
+    // on (64 floats: the second half belongs to the next stage and is never read from this slot);
+    // the padding of the repacked weights makes every such read valid, also past the last stage
+    const char* const spg = reinterpret_cast<const char*>(sp + (int64_t)(gbase + g_local) * n_pad);
+    unsigned vo_w = (unsigned)lane * 4u;
+    asm volatile("" : "+v"(vo_w));       // a fresh live range per item (see the LDS offsets below)
+    const char* fbase = nullptr;     // first token row of the stage being filled (scalar)
+    const char* wbase = nullptr;     // its weights
+    // Point the loads at stage `si` (wave-uniform).
+    const int steps32 = (int)steps, k0_32 = (int)k0, k1_32 = (int)k1;   // token steps fit 32 bits (checked on the host)
+    auto set_fill = [&](int si) {
+      const int se = si < steps32 - 1 ? si : steps32 - 1;
+      fbase = reinterpret_cast<const char*>(X) + (int64_t)se * step_bytes;
+      wbase = spg + (int64_t)si * (kStep * 4);
+      if (se == steps32 - 1) {
+#pragma unroll
+        for (int k = 0; k < C::kLoads - 1; ++k) vo[k] = vo_last[k];
+      }
+    };
 
-    // k-th load of the next stage to fetch, into ring slot `slot`; a handful of VALU operations
-    // and one memory instruction, small enough to sit between two MFMAs
+    // k-th load of the stage set_fill points at, into ring slot `slot`: one scalar move and one
+    // memory instruction, small enough to sit between two MFMAs
     auto issue_one = [&](int k, int slot) {
       const unsigned stage = smem_base + (unsigned)slot * kStageBytes;
       if (k < C::kLoads - 1) {
-        const char* ptr = prun[k] < plast[k] ? prun[k] : plast[k];
         if (k < C::kALoads)
-          dma16(ptr, stage + (wave * C::kALoads + k) * 1024);
+          dma16s(fbase, vo[k], stage + (wave * C::kALoads + k) * 1024);
         else
-          dma16(ptr, stage + kABytes + (wave * C::kBLoads + (k - C::kALoads)) * 1024);
-        prun[k] += step_bytes;
+          dma16s(fbase, vo[k], stage + kABytes + (wave * C::kBLoads + (k - C::kALoads)) * 1024);
       } else {
-        dma4(prun[k], stage + kABytes + kBBytes + wave * 256);
-        prun[k] += kStep * 4;
+        dma4s(wbase, vo_w, stage + kABytes + kBBytes + wave * 256);
       }
     };
     auto issue = [&](int slot) {
 #pragma unroll
       for (int k = 0; k < C::kLoads; ++k) issue_one(k, slot);
     };
-    auto read_raw_a = [&](RawA& f, const char* stage, int ks) {
-      f.s[0] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64);
-      f.s[1] = *reinterpret_cast<const f32x4*>(stage + offS + ks * 64 + 16);
+    // LDS reads of a stage go through per-lane byte addresses (`LBase`: the lane's invariant
+    // offsets plus the stage's position in the ring, formed once per stage); everything else is
+    // an immediate offset.
+    // The lane's invariant offsets, re-defined here for the allocator: their live ranges then start
+    // at the token loop that uses them, not at the top of the kernel (where they were being spilled
+    // and re-loaded inside the loop, and a scratch re-load waits for every direct load in flight).
+    unsigned la[kMA], lb[4], ls = (unsigned)offS;
+#pragma unroll
+    for (int x = 0; x < kMA; ++x) {
+      la[x] = (unsigned)offA[x];
+      asm volatile("" : "+v"(la[x]));
+    }
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+      lb[y] = (unsigned)offB[y];
+      asm volatile("" : "+v"(lb[y]));
+    }
+    asm volatile("" : "+v"(ls));
+    auto stage_base = [&](int slot) {
+      LBase b;
+      const unsigned st = smem_base + (unsigned)slot * kStageBytes;
+#pragma unroll
+      for (int x = 0; x < kMA; ++x) b.a[x] = st + la[x];
+#pragma unroll
+      for (int y = 0; y < 4; ++y) b.b[y] = st + lb[y];
+      b.s = st + ls;
+      return b;
+    };
+    auto read_raw_a = [&](RawA& f, const LBase& b, int ks) {
+      f.s[0] = *reinterpret_cast<lds_f32x4_ptr>(b.s + ks * 64);
+      f.s[1] = *reinterpret_cast<lds_f32x4_ptr>(b.s + ks * 64 + 16);
 #pragma unroll
       for (int x = 0; x < kMA; ++x) {
-        f.a[x][0] = lds_read_tr(stage + offA[x] + ks * 16 * (kAChunks * 16));
-        f.a[x][1] = lds_read_tr(stage + offA[x] + (ks * 16 + 4) * (kAChunks * 16));
+        f.a[x][0] = lds_read_tr(b.a[x] + ks * 16 * (kAChunks * 16));
+        f.a[x][1] = lds_read_tr(b.a[x] + (ks * 16 + 4) * (kAChunks * 16));
       }
     };
-    auto read_b1 = [&](Operands& o, const char* stage, int ks, int y) {
-      const char* pp = stage + offB[y % 4] + (y / 4) * 256;
+    auto read_b1 = [&](Operands& o, const LBase& b, int ks, int y) {
+      const unsigned pp = b.b[y % 4] + (y / 4) * 256;
       o.b[y][0] = lds_read_tr(pp + ks * 16 * (kBChunks * 16));
       o.b[y][1] = lds_read_tr(pp + (ks * 16 + 4) * (kBChunks * 16));
     };
@@ -344,56 +395,40 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     // One 16-token sub-step in its exact issue order (scheduling fences keep the compiler from
     // regrouping it): the 16 MFMAs on the current operands, each occupying the matrix core for
     // 32 cycles, with the next sub-step's work slotted in between them: after MFMA 0 the six LDS
-    // reads of the next scaled operand and its weights, after MFMAs 1..8 the reads of one raw
-    // fragment each, after MFMAs 8..15 one eighth of the scaling (5 VALU operations) each.
+    // reads of the next scaled operand and its weights; after every odd MFMA the reads of the
+    // raw fragment that MFMA was the last to use, for the next sub-step, INTO THE SAME registers
+    // (one set of raw fragments, refreshed in place: 32 registers less than two alternating sets);
+    // after MFMAs 8..15 one eighth of the scaling (5 VALU operations) each.
     // The direct loads of the stage NS-1 ahead are spread over the two sub-steps (one after
     // every third MFMA): issued back to back they would queue up in the memory pipeline.
-    auto sub_step = [&](const Operands& cur, Operands& nxt, RawA& raw, const char* stage, int ks, int dma_first,
-                        int dma_count, int slot) {
+    auto sub_step = [&](Operands& o, RawA& raw, const LBase& stage, int ks, int dma_first, int dma_count, int slot) {
       u32x4 an[kMA], an2[kMA];
-      mfma1(cur, 0);
-      read_raw_a(raw, stage, ks);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 1; i <= 8; ++i) {
-        mfma1(cur, i);
-        read_b1(nxt, stage, ks, i - 1);
-        if (i == 8) {
+      for (int i = 0; i < 16; ++i) {
+        mfma1(o, i);
+        if (i == 0) read_raw_a(raw, stage, ks);
+        if (i % 2 == 1) read_b1(o, stage, ks, i / 2);
+        if (i >= 8) {
+          const int piece = i - 8;                       // 0..7
           if constexpr (SPLIT) {
-            const u32x2 hl = scale2(raw, 0, 0);
-            an[0][0] = hl[0];
-            an2[0][0] = hl[1];
-            asm volatile("" : "+v"(an2[0][0]));
+            const u32x2 hl = scale2(raw, piece / 4, piece % 4);
+            an[piece / 4][piece % 4] = hl[0];
+            an2[piece / 4][piece % 4] = hl[1];
+            asm volatile("" : "+v"(an2[piece / 4][piece % 4]));
           } else {
-            an[0][0] = scale1(raw, 0, 0);
+            an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
           }
-          asm volatile("" : "+v"(an[0][0]));           // keeps the scaling where it is written (see below)
+          // an empty asm that "uses" the value: without it the optimiser sinks all the scaling
+          // below the last MFMA of the sub-step, where nothing hides it
+          asm volatile("" : "+v"(an[piece / 4][piece % 4]));
         }
-        if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-#pragma unroll
-      for (int i = 9; i <= 15; ++i) {
-        mfma1(cur, i);
-        const int piece = i - 8;                       // 1..7
-        if constexpr (SPLIT) {
-          const u32x2 hl = scale2(raw, piece / 4, piece % 4);
-          an[piece / 4][piece % 4] = hl[0];
-          an2[piece / 4][piece % 4] = hl[1];
-          asm volatile("" : "+v"(an2[piece / 4][piece % 4]));
-        } else {
-          an[piece / 4][piece % 4] = scale1(raw, piece / 4, piece % 4);
-        }
-        // an empty asm that "uses" the value: without it the optimiser sinks all the scaling
-        // below the last MFMA of the sub-step, where nothing hides it
-        asm volatile("" : "+v"(an[piece / 4][piece % 4]));
         if (i % 3 == 2 && i / 3 < dma_count) issue_one(dma_first + i / 3, slot);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int x = 0; x < kMA; ++x) {
-        nxt.a[x] = __builtin_bit_cast(bf16x8, an[x]);
-        if constexpr (SPLIT) nxt.a2[x] = __builtin_bit_cast(bf16x8, an2[x]);
+        o.a[x] = __builtin_bit_cast(bf16x8, an[x]);
+        if constexpr (SPLIT) o.a2[x] = __builtin_bit_cast(bf16x8, an2[x]);
       }
     };
 
@@ -403,15 +438,19 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     // every wave's part of stage t+1 visible and proves that stage t-1 is no longer being
     // read, so its slot is refilled with stage t+NS-1.
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t) issue(t);
+    for (int t = 0; t < NS - 1; ++t) {
+      set_fill(k0_32 + t);
+      issue(t);
+    }
     wait_vmcnt<(NS - 3) * C::kLoads>();
     __builtin_amdgcn_s_barrier();
     int slot_cur = 0, slot_nxt = 1, slot_fill = NS - 1;
-    Operands o0, o1;
+    Operands o0;
     RawA raw;
-    read_raw_a(raw, smem, 0);
+    const LBase lb0 = stage_base(0);
+    read_raw_a(raw, lb0, 0);
 #pragma unroll
-    for (int y = 0; y < kNB; ++y) read_b1(o0, smem, 0, y);
+    for (int y = 0; y < kNB; ++y) read_b1(o0, lb0, 0, y);
 #pragma unroll
     for (int x = 0; x < kMA; ++x) {
       if constexpr (SPLIT) {
@@ -428,17 +467,17 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
         o0.a[x] = scale_frag(raw.a[x][0], raw.a[x][1], raw.s[0], raw.s[1]);
       }
     }
-    for (int64_t step = k0; step < k1; ++step) {
+    for (int step = k0_32; step < k1_32; ++step) {
       wait_vmcnt<(NS - 3) * C::kLoads>();
       __builtin_amdgcn_s_barrier();
-      const char* st_cur = smem + slot_cur * kStageBytes;
-      const char* st_nxt = smem + slot_nxt * kStageBytes;
+      set_fill(step + (NS - 1));
+      const LBase cur = stage_base(slot_cur), nxt = stage_base(slot_nxt);
       constexpr int kFirstHalf = (C::kLoads + 1) / 2;
       __builtin_amdgcn_sched_barrier(0);
       // tokens 0..15 of the stage; fetches tokens 16..31
-      sub_step(o0, o1, raw, st_cur, 1, 0, kFirstHalf, slot_fill);
+      sub_step(o0, raw, cur, 1, 0, kFirstHalf, slot_fill);
       // tokens 16..31; fetches tokens 0..15 of the next stage (complete since the barrier)
-      sub_step(o1, o0, raw, st_nxt, 0, kFirstHalf, C::kLoads - kFirstHalf, slot_fill);
+      sub_step(o0, raw, nxt, 0, kFirstHalf, C::kLoads - kFirstHalf, slot_fill);
       slot_fill = slot_cur;
       slot_cur = slot_nxt;
       slot_nxt = (slot_nxt + 1 == NS) ? 0 : slot_nxt + 1;

@@ -34,6 +34,14 @@ __device__ inline void dma16(const void* gptr, unsigned lds_base) {
 __device__ inline void dma4(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
+// The same two loads with the address split into a wave-uniform 64-bit base (scalar registers) and
+// a 32-bit byte offset per lane: advancing the base costs scalar arithmetic only.
+__device__ inline void dma16s(const void* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ inline void dma4s(const void* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
 // fp32 as a sum of bf16 terms (round to nearest even each): two terms carry 16 mantissa bits, three
 // carry all 24 (exact for every x whose exponent leaves room for the last term).
 __device__ inline void split_bf16(float x, unsigned short& hi, unsigned short& lo) {

@@ -83,21 +83,48 @@ def test_config4_llama2_13b_attn_groups(G):
     sampled_objective_check(oracle, X, s, W, What, obj, rows, G, TOL_BF16, rows_per_group=16, seed=G, what=f"config 4 G={G}")
 
 
-def test_config4_llama2_13b_up_wide_gradients():
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_config4_llama2_13b_up_wide_gradients(G):
     # gate/up projections: the gradient matrix is 13824 wide, X is the shared attention-side input
-    spec, X, s = _layer("llama2_13b_up")
+    spec, X, s = _layer("llama2_13b_up", G)
     H = gq.gq_fisher_gram(X, s, mirror=True)
-    sampled_gram_check(oracle, X, s, H, TOL_BF16, n_random=8, seed=44, what="config 4 up_proj")
+    sampled_gram_check(oracle, X, s, H, TOL_BF16, n_random=8, seed=44 + G, what=f"config 4 up_proj G={G}")
     W, What = wl.make_weights(spec, DEV)
     obj, rows = gq.gq_objective(W, What, H, want_rows=True)
-    sampled_objective_check(oracle, X, s, W, What, obj, rows, spec.G, TOL_BF16, rows_per_group=16, seed=45, what="config 4 up_proj")
+    sampled_objective_check(oracle, X, s, W, What, obj, rows, G, TOL_BF16, rows_per_group=16 if G <= 4 else 8, seed=45 + G,
+                            what=f"config 4 up_proj G={G}")
 
 
-@pytest.mark.parametrize("G", [1, 8])
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
 def test_config4_llama2_13b_down(G):
     spec, X, s = _layer("llama2_13b_down", G)
     H = gq.gq_fisher_gram(X, s, mirror=True)
     sampled_gram_check(oracle, X, s, H, TOL_BF16, n_random=10, n_probe=2, seed=46 + G, what=f"config 4 down_proj G={G}")
+    W, What = wl.make_weights(spec, DEV)
+    obj, rows = gq.gq_objective(W, What, H, want_rows=True)
+    sampled_objective_check(oracle, X, s, W, What, obj, rows, G, TOL_BF16, rows_per_group=8 if G <= 4 else 4, seed=56 + G,
+                            what=f"config 4 down_proj G={G}")
+
+
+def test_config4_q_k_v_stacked_in_one_gram_call():
+    """The three attention projections of the 13B block read the same X: their group weights side by
+    side (3 x 4 columns) and ONE Gram call with 12 groups; every layer's four Hessians against the oracle."""
+    spec = wl.CONFIGS["llama2_13b_attn"]
+    G, layers = spec.G, 3
+    say(f"stacked q/k/v: X[{spec.n},{spec.d_in}], {layers} x dZ[{spec.n},{spec.d_out}], G={G} each")
+    X = wl.make_x(spec, DEV)
+    s_all = torch.empty((spec.n, layers * G), dtype=torch.float32, device=DEV)
+    for l in range(layers):
+        dZ = wl.make_dz(spec.n, spec.d_out, 1e-4, 1.5, 250507004 + 4000 + 17 * l, DEV)
+        gq.gq_group_weights(dZ, G, out=s_all, out_col=l * G)
+        one = gq.gq_group_weights(dZ, G)
+        assert torch.equal(one, s_all[:, l * G:(l + 1) * G])          # the strided call writes the same numbers
+        del dZ, one
+    H = gq.gq_fisher_gram(X, s_all, mirror=True)
+    assert H.shape == (layers * G, spec.d_in, spec.d_in)
+    for l in range(layers):
+        sampled_gram_check(oracle, X, s_all[:, l * G:(l + 1) * G].contiguous(), H[l * G:(l + 1) * G], TOL_BF16,
+                           n_random=8, n_probe=2, seed=70 + l, what=f"config 4 stacked q/k/v, layer {l}")
 
 
 @pytest.mark.parametrize("name", ["llama2_70b_attn", "llama2_70b_up"])

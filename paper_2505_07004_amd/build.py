@@ -20,6 +20,7 @@ SOURCES = [
     "group_weights.hip",
     "fisher_gram_f32.hip",
     "fisher_gram_bf16.hip",
+    "fisher_gram_bf16_wide.hip",
     "mirror.hip",
     "objective.hip",
     "cd_assign.hip", "lnq_codebook.hip", "cholesky.hip",
@@ -57,6 +58,8 @@ def build(verbose: bool = False, save_temps: bool = False) -> str:
     """Compile every HIP source and link libgq.so.  Always recompiles."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     hipcc = _hipcc()
+    # the token loop of the wide bf16 Gram kernel is generated assembly text (an include file)
+    _run([sys.executable, os.path.join(CSRC, "gen_gram_wide_loop.py")])
     objs = []
     cmds = []
     for src in SOURCES:

@@ -633,11 +633,18 @@ Plan make_plan(int64_t n, int64_t d_in, int G) {
 size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
   if (n <= 0) return 0;
   const Plan pl = make_plan(n, d_in, G);
-  return pl.sp_bytes + pl.partial_bytes;
+  size_t need = pl.sp_bytes + pl.partial_bytes;
+  if (fisher_gram_bf16_wide_applies(n, G, false)) {      // the flags are not known here: enough for either kernel
+    const size_t wide = fisher_gram_bf16_wide_workspace(n, d_in, G);
+    if (wide > need) need = wide;
+  }
+  return need;
 }
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                    float* H, bool accumulate, bool two_terms, void* ws, size_t, hipStream_t st) {
+  if (fisher_gram_bf16_wide_applies(n, G, two_terms))
+    return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, st);
   const Plan pl = make_plan(n, d_in, G);
   float* sp = (float*)ws;
   float* partial = (float*)((char*)ws + pl.sp_bytes);

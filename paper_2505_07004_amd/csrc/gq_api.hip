@@ -66,7 +66,7 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
   if (!aligned16(H)) return GQ_ERR_ALIGN;
   if (n > 0 && (!aligned16(X) || ((size_t)ld_x * elem_size(x_dtype)) % 16 != 0)) return GQ_ERR_ALIGN;
   // the bf16 kernel addresses a stage of 32 token rows with 32-bit byte offsets and counts stages in 32 bits
-  if (x_dtype == GQ_BF16 && (ld_x >= ((int64_t)1 << 26) || n >= ((int64_t)1 << 35))) return GQ_ERR_UNSUPPORTED;
+  if (x_dtype == GQ_BF16 && (ld_x >= ((int64_t)1 << 26) || n >= ((int64_t)1 << 28))) return GQ_ERR_UNSUPPORTED;
   const size_t need = gq_fisher_gram_workspace_bytes(x_dtype, n, d_in, G);
   if (need > 0 && (!workspace || workspace_bytes < need || !aligned256(workspace))) return GQ_ERR_WORKSPACE;
 

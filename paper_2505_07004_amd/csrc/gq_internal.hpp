@@ -116,6 +116,46 @@ __host__ __device__ inline void band_decode(int64_t t, int rpt, int64_t NT, int&
   J = (int)J0;
 }
 
+// Order of the wide bf16 Gram kernel's items (group counts divisible by 4): row blocks of 96 rows
+// against tile columns of 256 columns.  Row block I (rows 96 I ..) meets tile column J on or above the
+// diagonal iff 96 I < 256 (J + 1); rows_of_column counts those row blocks (NR = all row blocks of the
+// matrix).  Items are walked in bands of two tile columns, row block slow, so that consecutive items
+// (the workgroups resident on one XCD take such a run) share few row panels and few column panels.
+constexpr int kWideRows = 96, kWideCols = 256;
+__host__ __device__ inline int64_t wide_rows_of_column(int64_t J, int64_t NR) {
+  const int64_t c = (kWideCols * (J + 1) - 1) / kWideRows + 1;
+  return c < NR ? c : NR;
+}
+__host__ __device__ inline int64_t wide_tile_count(int64_t d) {
+  const int64_t NT = (d + kWideCols - 1) / kWideCols, NR = (d + kWideRows - 1) / kWideRows;
+  int64_t t = 0;
+  for (int64_t J = 0; J < NT; ++J) t += wide_rows_of_column(J, NR);
+  return t;
+}
+// Item t in [0, wide_tile_count(d)) -> row block I, tile column J.
+__host__ __device__ inline void wide_decode(int64_t t, int64_t d, int& I, int& J) {
+  const int64_t NT = (d + kWideCols - 1) / kWideCols, NR = (d + kWideRows - 1) / kWideRows;
+  for (int64_t J0 = 0; J0 < NT; J0 += 2) {
+    const int64_t c0 = wide_rows_of_column(J0, NR), c1 = (J0 + 1 < NT) ? wide_rows_of_column(J0 + 1, NR) : 0;
+    if (t < c0 + c1) {
+      if (c1 == 0) {
+        I = (int)t;
+        J = (int)J0;
+      } else if (t < 2 * c0) {             // both tile columns have this row block
+        I = (int)(t / 2);
+        J = (int)(J0 + t % 2);
+      } else {                             // the staircase: only the second tile column reaches down here
+        I = (int)(c0 + (t - 2 * c0));
+        J = (int)(J0 + 1);
+      }
+      return;
+    }
+    t -= c0 + c1;
+  }
+  I = 0;                                   // not reached for t in range
+  J = 0;
+}
+
 // ---- launchers (each validates nothing; the C ABI layer has done that) -----
 hipError_t launch_group_weights(const void* dZ, gq_dtype dt, int64_t n, int64_t d_out, int64_t ld,
                                 int G, float grad_scale, float* s, int64_t ld_s, hipStream_t st);
@@ -127,6 +167,11 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
                                    int G, float* H, bool accumulate, bool two_terms, void* ws, size_t ws_bytes,
                                    hipStream_t st);
 size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
+// the wide kernel (96 x 256 blocks per wave; group counts divisible by 4, one-term products, n >= 32)
+bool fisher_gram_bf16_wide_applies(int64_t n, int G, bool two_terms);
+size_t fisher_gram_bf16_wide_workspace(int64_t n, int64_t d_in, int G);
+hipError_t launch_fisher_gram_bf16_wide(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
+                                        float* H, bool accumulate, void* ws, hipStream_t st);
 
 hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st);

@@ -26,8 +26,10 @@
  *     Calls validate their arguments on the host, enqueue kernels on that stream
  *     and return without synchronising; outputs are valid once the stream has
  *     been synchronised.
- *   - Return value: GQ_OK (0) or a negative gq_status.  On any error nothing has
- *     been enqueued and no output has been touched.
+ *   - Return value: GQ_OK (0) or a negative gq_status.  On an argument error (every
+ *     status except GQ_ERR_HIP) nothing has been enqueued and no output has been
+ *     touched.  GQ_ERR_HIP reports a launch the runtime refused; kernels of the same
+ *     call that were enqueued before it may still run, so the outputs are undefined.
  *   - Results are deterministic: identical arguments give bit-identical outputs
  *     (no floating-point atomics whose order can vary).
  *   - NaN/Inf in the inputs propagate; nothing is checked.
@@ -148,7 +150,11 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
 
 /*
  * Fill the strictly lower triangle of every H[k] from its upper triangle, in
- * place (the paper's cached Hessians are full squares).  H [G, d_in, d_in] fp32.
+ * place: the paper caches its Hessians as full squares (the disk sizes of its
+ * Table "cost_hess" are those of g dense d_in x d_in matrices per layer), and
+ * the quantizers it feeds them to index them as such.  H [G, d_in, d_in] fp32;
+ * bit-exactly symmetric afterwards.  Errors: GQ_ERR_SHAPE, GQ_ERR_NULLPTR,
+ * GQ_ERR_ALIGN (H not 16-byte aligned).
  */
 int gq_fisher_mirror(float* H, int64_t d_in, int32_t G, void* hip_stream);
 
@@ -218,7 +224,9 @@ size_t gq_cd_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G);
  *
  * n_cycles == 0 is a valid no-op.  Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_out <= 0,
  * d_in <= 0, G <= 0, d_out % G != 0, ld_w < d_in, n_cycles < 0, n_levels <= 0),
- * GQ_ERR_UNSUPPORTED (n_levels > 16), GQ_ERR_ALIGN (W/What/H not 16-byte aligned or
+ * GQ_ERR_UNSUPPORTED (n_levels > 16, or d_out > 65535: the helper kernels put the channel
+ * in the second grid dimension; the same limit holds for gq_ldlq_assign, gq_lnq_codebook
+ * and gq_lnq), GQ_ERR_ALIGN (W/What/H not 16-byte aligned or
  * ld_w*4 not a multiple of 16), GQ_ERR_WORKSPACE, GQ_ERR_HIP.
  */
 int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_levels,

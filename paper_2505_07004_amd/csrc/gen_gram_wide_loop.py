@@ -45,6 +45,13 @@ S_XB, S_WB, S_B5 = 90, 92, 94       # 64-bit pairs
 S_FIRST, S_LAST = 84, 95
 
 
+# ---- the issue order inside a sub-step of 24 matrix instructions (slots 0..23) --------------------
+B_BATCH = int(os.environ.get("GQW_BBATCH", "1"))            # raw fragments re-read per batch (after the last use of the batch)
+A_SLOTS = [int(v) for v in os.environ.get("GQW_ASLOTS", "0,1").split(",")]          # weights + scaled-operand reads
+DMA_SLOTS = [int(v) for v in os.environ.get("GQW_DMASLOTS", "3,11,19").split(",")]  # M0 set here, the load one slot later
+SCALE_SLOTS = [int(v) for v in os.environ.get("GQW_SCALESLOTS", "9,10,11,12,13,14,15,16,17,18,19,20").split(",")]
+
+
 class Emitter:
     def __init__(self):
         self.lines = []
@@ -160,34 +167,37 @@ def sub_step(e, cur_set, nxt_set, fetch_ks, dma, slot_fill, first=False, fetch=T
     reads = fetch_reads(fetch_ks) if fetch else []
     pieces = [(x, q) for x in range(MA) for q in range(4)] if fetch else []
     dma = list(dma)
-    dma_at = {4: 0, 12: 1, 20: 2}
     for i in range(MA * NB):
         y, x = divmod(i, MA)
         e.need(list(range(BREG + 4 * y, BREG + 4 * y + 4)))
         c = "0" if first else acc(x, y)
         e.raw("v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (acc(x, y), frag(A_SET[cur_set], x), frag(BREG, y), c))
-        if fetch and i == 0:
+        if fetch and i == A_SLOTS[0]:
             for _, r in reads[:4]:
                 r(e)
-        if fetch and i == 1:
+        if fetch and i == A_SLOTS[1]:
             for _, r in reads[4:]:
                 r(e)
-        if fetch and x == MA - 1:
-            for r in b_reads(fetch_ks, y):
-                r(e)
-        if i in (3, 11, 19) and (i - 3) // 8 < len(dma):          # M0 one matrix instruction ahead of its load
-            dma_m0(e, dma[(i - 3) // 8], slot_fill)
-        if i in dma_at and dma_at[i] < len(dma):
-            dma_load(e, dma[dma_at[i]])
-        if fetch and 9 <= i <= 20:
-            px, pq = pieces[i - 9]
-            scale_piece(e, px, pq, nxt_set)
+        if fetch and x == MA - 1 and (y + 1) % B_BATCH == 0:       # the fragments whose last use has just been issued
+            for yy in range(y + 1 - B_BATCH, y + 1):
+                for r in b_reads(fetch_ks, yy):
+                    r(e)
+        if i in DMA_SLOTS and DMA_SLOTS.index(i) < len(dma):          # M0 one matrix instruction ahead of its load
+            dma_m0(e, dma[DMA_SLOTS.index(i)], slot_fill)
+        if i - 1 in DMA_SLOTS and DMA_SLOTS.index(i - 1) < len(dma):
+            dma_load(e, dma[DMA_SLOTS.index(i - 1)])
+        if fetch:
+            for px, pq in [p for s, p in zip(SCALE_SLOTS, pieces) if s == i]:
+                scale_piece(e, px, pq, nxt_set)
 
 
 def build():
     e = Emitter()
     # ---------------- prologue: fill the ring, fetch and scale the first sub-step --------------
-    e.raw("s_waitcnt vmcnt(0) lgkmcnt(0)")          # nothing of the surrounding code may still be counted
+    # Scalar loads of the surrounding code must not be counted against the LDS reads below.  Its vector
+    # memory operations (the stores of the previous item's results) may stay in flight: the counter retires
+    # in issue order, so every wait below also covers them.
+    e.raw("s_waitcnt lgkmcnt(0)")
     e.raw("s_mov_b32 s%d, %%[k0]" % S_SI)
     e.raw("s_mov_b32 s%d, %%[count]" % S_CNT)
     for t in range(NS - 1):

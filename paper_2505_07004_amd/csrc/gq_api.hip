@@ -125,7 +125,7 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
                  size_t workspace_bytes, void* hip_stream) {
   if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_cycles < 0 || n_levels <= 0)
     return GQ_ERR_SHAPE;
-  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (n_levels > 16 || d_out > 65535) return GQ_ERR_UNSUPPORTED;
   if (!W || !What || !codebook || !H) return GQ_ERR_NULLPTR;
   if (!aligned16(W) || !aligned16(What) || !aligned16(H) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;
   const size_t need = gq_cd_workspace_bytes(d_out, d_in, G);
@@ -157,7 +157,7 @@ int gq_ldlq_assign(const float* W, float* What, const float* codebook, int32_t n
                    int64_t ld_w, const float* R, int32_t G, uint8_t* Q, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
   if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_levels <= 0) return GQ_ERR_SHAPE;
-  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (n_levels > 16 || d_out > 65535) return GQ_ERR_UNSUPPORTED;
   if (!W || !What || !codebook || !R) return GQ_ERR_NULLPTR;
   if (W == What) return GQ_ERR_SHAPE;
   if (!aligned16(W) || !aligned16(What) || !aligned16(R) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;
@@ -177,7 +177,7 @@ int gq_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld_w, c
                     size_t workspace_bytes, void* hip_stream) {
   if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_levels <= 0 || !(lam >= 0.0))
     return GQ_ERR_SHAPE;
-  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (n_levels > 16 || d_out > 65535) return GQ_ERR_UNSUPPORTED;
   if (!W || !Q || !H || !codebook) return GQ_ERR_NULLPTR;
   if (!aligned16(W) || (What && !aligned16(What)) || !aligned16(H) || ((size_t)ld_w * 4) % 16 != 0)
     return GQ_ERR_ALIGN;
@@ -199,7 +199,7 @@ int gq_lnq(const float* W, float* What, uint8_t* Q, float* codebook, int32_t n_l
   if (d_out <= 0 || d_in <= 0 || G <= 0 || d_out % G != 0 || ld_w < d_in || n_levels <= 0 || n_iters < 0 ||
       n_cycles < 0 || !(lam >= 0.0))
     return GQ_ERR_SHAPE;
-  if (n_levels > 16) return GQ_ERR_UNSUPPORTED;
+  if (n_levels > 16 || d_out > 65535) return GQ_ERR_UNSUPPORTED;
   if (!W || !What || !Q || !codebook || !H) return GQ_ERR_NULLPTR;
   if (W == What) return GQ_ERR_SHAPE;
   if (!aligned16(W) || !aligned16(What) || !aligned16(H) || ((size_t)ld_w * 4) % 16 != 0) return GQ_ERR_ALIGN;

@@ -1,4 +1,4 @@
-"""Static checks on the generated gfx950 code of the bf16 Gram kernel (CPU only: hipcc
+"""Static checks on the generated gfx950 code of the bf16 Gram kernels (CPU only: hipcc
 cross-compiles).  The hot loop is written in an exact issue order around its 32 MFMAs per
 32-token stage; it must not have been duplicated or peeled by the compiler, and no register
 spill (scratch access) may sit inside it.  Outside the loop the kernel does spill, so it
@@ -10,6 +10,7 @@ import os
 import re
 import shutil
 import subprocess
+import sys
 
 import pytest
 
@@ -44,3 +45,42 @@ def test_hot_loop_of_the_gram_kernel_is_compact_and_spill_free():
     assert len(fixups) == 3
     for name, body in fixups:
         assert "scratch_" not in body, name
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="needs hipcc")
+def test_wide_gram_kernel_token_loop_is_the_generated_assembly_and_nothing_else():
+    """The wide kernel's token loop is one generated inline-assembly statement: 14 sub-steps of 24 matrix
+    instructions (one peeled, six unrolled ring stages of two, one tail), with its own register plan.  The
+    compiler must have placed the 24 accumulator tiles in both register files without touching the statement,
+    the code it generates around it must not write EXEC (spill code inside a lane-masked region saves only
+    the active lanes), and the committed include file must be what the generator produces."""
+    from paper_2505_07004_amd import build as b
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    inc = os.path.join(CSRC, "fisher_gram_bf16_wide_loop.inc")
+    before = open(inc).read()
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_gram_wide_loop.py")], check=True,
+                   stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL,
+                   env={k: v for k, v in os.environ.items() if not k.startswith("GQW_")})
+    assert open(inc).read() == before, "fisher_gram_bf16_wide_loop.inc is not the generator's output"
+    cmd = [hipcc] + b.HIPCC_FLAGS + ["-I", b.INCLUDE, "-I", CSRC, "-S", "--cuda-device-only",
+                                      os.path.join(CSRC, "fisher_gram_bf16_wide.hip"), "-o", "-"]
+    asm = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, check=True).stdout
+    (name, body), = re.findall(r"^(_ZN2gq\S*fisher_gram_bf16_wide_kernel\S*):[^\n]*\n(.*?)s_endpgm", asm, flags=re.S | re.M)
+    lines = body.splitlines()
+    start, end = [i for i, l in enumerate(lines) if "#ASMSTART" in l], [i for i, l in enumerate(lines) if "#ASMEND" in l]
+    loop = lines[start[0]:end[0] + 1]
+    mfma = [l for l in loop if "v_mfma_f32_32x32x16_bf16" in l]
+    assert len(mfma) == 14 * 24 and len([l for l in lines if "v_mfma" in l]) == len(mfma)
+    assert not [l for l in loop if "scratch_" in l]
+    dests = {l.split()[1].rstrip(",") for l in mfma}
+    assert len(dests) == 24                                              # 24 distinct accumulator tiles ...
+    assert sum(d.startswith("a[") for d in dests) == 16 and sum(d.startswith("v[") for d in dests) == 8   # ... in both files
+    for d in dests:                                                      # none of them inside the statement's own registers
+        lo = int(re.match(r"[av]\[(\d+):", d).group(1))
+        assert d.startswith("a[") or lo >= 84, d
+    assert sum("s_barrier" in l for l in loop) == 7 and sum("global_load_lds_dwordx4" in l for l in loop) == 5 * 6 + 6 * 6
+    outside = lines[:start[0]] + lines[end[0] + 1:]
+    writes_exec = [l for l in outside if re.search(r"saveexec|\bs_\w+\s+exec(_lo|_hi)?\s*,", l)]
+    assert not writes_exec, writes_exec[:3]
+    (fname, fbody), = re.findall(r"^(_ZN2gq\S*fisher_gram_wide_fixup_kernel\S*):[^\n]*\n(.*?)s_endpgm", asm, flags=re.S | re.M)
+    assert "scratch_" not in fbody

@@ -149,6 +149,26 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * gq_fisher_gram for callers that cannot allocate device memory and so cannot bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (minus the workspace), same arithmetic and same results up to the order of the fp32
+ * additions over tokens (every tile of H is accumulated by one workgroup over all tokens; the
+ * workspace version may split a tile's tokens between workgroups).  The scratch memory of the
+ * call (the token weights repacked for the kernels) is a fixed device array inside the library,
+ * gq_fisher_gram_noalloc_max_scratch_bytes() = 4 MiB per GPU, held until the process ends.
+ * Nothing is allocated or freed by the call.
+ *
+ * Limit: GQ_BF16 needs 4 * G * (32 * ceil(n / 32) + 256) bytes of it (n = 65536 tokens with
+ * G <= 15, for example); a larger call returns GQ_ERR_WORKSPACE and enqueues nothing.  GQ_F32 has
+ * no limit.  All calls on one GPU share that GPU's array: calls that may run concurrently on one
+ * GPU (different streams, different threads) race on it and must be serialised by the caller.
+ * Other errors as gq_fisher_gram.
+ */
+size_t gq_fisher_gram_noalloc_max_scratch_bytes(void);
+int gq_fisher_gram_noalloc(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int64_t ld_x,
+                           const float* s, int32_t G, float* H, uint32_t flags, void* hip_stream);
+
+/*
  * Fill the strictly lower triangle of every H[k] from its upper triangle, in
  * place: the paper caches its Hessians as full squares (the disk sizes of its
  * Table "cost_hess" are those of g dense d_in x d_in matrices per layer), and

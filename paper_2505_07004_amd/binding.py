@@ -53,6 +53,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_fisher_gram.restype = c.c_int
     lib.gq_fisher_gram.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
                                    c.c_int32, c.c_void_p, c.c_uint32, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.gq_fisher_gram_noalloc.restype = c.c_int
+    lib.gq_fisher_gram_noalloc.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
+                                           c.c_int32, c.c_void_p, c.c_uint32, c.c_void_p]
+    lib.gq_fisher_gram_noalloc_max_scratch_bytes.restype = c.c_size_t
+    lib.gq_fisher_gram_noalloc_max_scratch_bytes.argtypes = []
     lib.gq_fisher_mirror.restype = c.c_int
     lib.gq_fisher_mirror.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p]
     lib.gq_objective_workspace_bytes.restype = c.c_size_t
@@ -185,6 +190,22 @@ def gq_fisher_gram(X: torch.Tensor, s: torch.Tensor, H: Optional[torch.Tensor] =
     st = lib.gq_fisher_gram(X.data_ptr(), _dtype_code(X), n, d_in, _rows(X) if n > 0 else d_in,
                             s.data_ptr(), G, H.data_ptr(), flags, ws_ptr, ws_bytes, _stream())
     _check(st, "gq_fisher_gram")
+    return H
+
+
+def gq_fisher_gram_noalloc(X: torch.Tensor, s: torch.Tensor, H: torch.Tensor, accumulate: bool = False,
+                           mirror: bool = False, two_terms: bool = False) -> torch.Tensor:
+    """gq_fisher_gram without a workspace: the call allocates nothing (H must exist); raises GQError with
+    GQ_ERR_WORKSPACE when the repacked weights do not fit the library's fixed scratch array."""
+    _require_gpu(X, s, H)
+    n, d_in = X.shape
+    G = int(s.shape[1])
+    assert s.dtype == torch.float32 and s.is_contiguous() and s.shape[0] == n
+    assert H.dtype == torch.float32 and H.is_contiguous() and tuple(H.shape) == (G, d_in, d_in)
+    flags = (GQ_ACCUMULATE if accumulate else 0) | (GQ_MIRROR if mirror else 0) | (GQ_TWO_TERMS if two_terms else 0)
+    st = load_library().gq_fisher_gram_noalloc(X.data_ptr(), _dtype_code(X), n, d_in, _rows(X) if n > 0 else d_in,
+                                               s.data_ptr(), G, H.data_ptr(), flags, _stream())
+    _check(st, "gq_fisher_gram_noalloc")
     return H
 
 

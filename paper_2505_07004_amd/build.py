@@ -17,6 +17,7 @@ CEILING_PATH = os.path.join(PKG_DIR, "mfma_ceiling")
 
 SOURCES = [
     "gq_api.hip",
+    "gq_noalloc.hip",
     "group_weights.hip",
     "fisher_gram_f32.hip",
     "fisher_gram_bf16.hip",

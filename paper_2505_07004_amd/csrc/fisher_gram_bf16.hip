@@ -184,8 +184,10 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     p = x * q + (x < r ? x : r) + idx;
   }
   const int64_t steps = (n + kStep - 1) / kStep;
-  const int64_t rounds = n_items / P;                        // whole items per workgroup
-  const int64_t units = (n_items - rounds * P) * steps;      // left-over work, dealt out in runs
+  // Without a place to park partial tiles (partial == nullptr: the entry point that allocates nothing)
+  // every item is computed whole: ceil(n_items / P) rounds, the last one not full, no left-over runs.
+  const int64_t rounds = partial ? n_items / P : (n_items + P - 1) / P;     // whole items per workgroup
+  const int64_t units = partial ? (n_items - rounds * P) * steps : 0;       // left-over work, dealt out in runs
   const int64_t u_begin = first_unit(p, units, P), u_end = first_unit(p + 1, units, P);
 
   const int tid = threadIdx.x;
@@ -220,6 +222,7 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
     int64_t item, k0, k1;
     if (round < rounds) {            // a whole item, in step with every other workgroup
       item = round * P + p;
+      if (item >= n_items) break;    // the last round of the schedule without left-over runs
       k0 = 0;
       k1 = steps;
     } else {                         // (part of) a left-over item
@@ -630,6 +633,14 @@ Plan make_plan(int64_t n, int64_t d_in, int G) {
 
 }  // namespace
 
+// Bytes of the repacked weights alone (what a call without partial tiles needs), for either kernel.
+size_t fisher_gram_bf16_weights_bytes(int64_t n, int G) {
+  if (n <= 0) return 0;
+  const size_t narrow = make_plan(n, 8, G).sp_bytes;
+  const size_t wide = fisher_gram_bf16_wide_applies(n, G, false) ? fisher_gram_bf16_wide_weights_bytes(n, G) : 0;
+  return narrow > wide ? narrow : wide;
+}
+
 size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
   if (n <= 0) return 0;
   const Plan pl = make_plan(n, d_in, G);
@@ -642,16 +653,17 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
 }
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                   float* H, bool accumulate, bool two_terms, void* ws, size_t, hipStream_t st) {
+                                   float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st) {
   if (fisher_gram_bf16_wide_applies(n, G, two_terms))
-    return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, st);
-  const Plan pl = make_plan(n, d_in, G);
+    return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, no_partials, st);
+  Plan pl = make_plan(n, d_in, G);
   float* sp = (float*)ws;
-  float* partial = (float*)((char*)ws + pl.sp_bytes);
+  float* partial = no_partials ? nullptr : (float*)((char*)ws + pl.sp_bytes);
+  if (no_partials) pl.P = pl.n_items < kMaxWorkgroups ? pl.n_items : kMaxWorkgroups;   // whole items only
   pack_weights_kernel<<<dim3((unsigned)((pl.n_pad + 255) / 256)), dim3(256), 0, st>>>(s, n, G, pl.n_pad, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int64_t left_over = pl.n_items % pl.P;
+  const int64_t left_over = no_partials ? 0 : pl.n_items % pl.P;
   const dim3 grid((unsigned)pl.P), fix((unsigned)left_over, (unsigned)(kMA * kNB));
   const __bf16* Xb = (const __bf16*)X;
   const int acc = accumulate ? 1 : 0;

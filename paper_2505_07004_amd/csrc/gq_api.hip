@@ -79,7 +79,7 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
     e = gq::launch_fisher_gram_f32((const float*)X, n, d_in, ld_x, s, G, H, accumulate, st);
   } else {
     e = gq::launch_fisher_gram_bf16(X, n, d_in, ld_x, s, G, H, accumulate, (flags & GQ_TWO_TERMS) != 0, workspace,
-                                    workspace_bytes, st);
+                                    false, st);
   }
   if (e != hipSuccess) return GQ_ERR_HIP;
   if (flags & GQ_MIRROR) e = gq::launch_mirror(H, d_in, G, st);

@@ -164,14 +164,18 @@ hipError_t launch_fisher_gram_f32(const float* X, int64_t n, int64_t d_in, int64
                                   int G, float* H, bool accumulate, hipStream_t st);
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
-                                   int G, float* H, bool accumulate, bool two_terms, void* ws, size_t ws_bytes,
+                                   int G, float* H, bool accumulate, bool two_terms, void* ws, bool no_partials,
                                    hipStream_t st);
+// `no_partials`: ws holds only the repacked weights (fisher_gram_bf16_weights_bytes); every work item is then
+// computed whole by one workgroup (no left-over runs, no second pass)
+size_t fisher_gram_bf16_weights_bytes(int64_t n, int G);
+size_t fisher_gram_bf16_wide_weights_bytes(int64_t n, int G);
 size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
 // the wide kernel (96 x 256 blocks per wave; group counts divisible by 4, one-term products, n >= 32)
 bool fisher_gram_bf16_wide_applies(int64_t n, int G, bool two_terms);
 size_t fisher_gram_bf16_wide_workspace(int64_t n, int64_t d_in, int G);
 hipError_t launch_fisher_gram_bf16_wide(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                        float* H, bool accumulate, void* ws, hipStream_t st);
+                                        float* H, bool accumulate, void* ws, bool no_partials, hipStream_t st);
 
 hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st);

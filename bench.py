@@ -39,18 +39,19 @@ def gram_flops(G, n, d_in):
 def load_traffic(workload):
     """HBM bytes per Gram launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs of
     this script, scaled by a plain copy of known size); the committed summary under profiles/
-    holds the figures and the commands.  None when no measurement is on file."""
-    path = os.path.join(ROOT, "profiles", f"fisher_gram_bf16_{workload}.traffic.json")
+    holds the figures and the commands.  (None, None) when no measurement is on file."""
+    rel = os.path.join("profiles", f"fisher_gram_bf16_{workload}.traffic.json")
     try:
-        with open(path) as f:
-            return json.load(f)["hbm_bytes_per_launch"]
+        with open(os.path.join(ROOT, rel)) as f:
+            return json.load(f)["hbm_bytes_per_launch"], f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command; not measured in this run)"
     except Exception:
-        return None
+        return None, None
 
 
 def mfma_ceiling():
-    """What a loop of nothing but bf16 MFMAs sustains on this GPU (constant and random operands),
-    measured by the small stand-alone program built next to the library, as a child process."""
+    """What a loop of nothing but bf16 MFMAs sustains on this GPU (constant and random operands), the shader
+    clock it holds meanwhile, and what a plain read stream / copy of 1 GiB sustains, measured by the small
+    stand-alone program built next to the library, as a child process."""
     import subprocess
     exe = os.path.join(ROOT, "paper_2505_07004_amd", "mfma_ceiling")
     if not os.path.exists(exe):
@@ -181,14 +182,25 @@ def main():
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
     ms_per_step = total_s * 1e3 / args.steps
-    per_kernel = {nm: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, nm in enumerate(names)}
+    import statistics
+    samples = {nm: [e[i].elapsed_time(e[i + 1]) for e in evs] for i, nm in enumerate(names)}
+    samples["step"] = [e[0].elapsed_time(e[4]) for e in evs]
+    per_kernel = {nm: sum(v) / len(v) for nm, v in samples.items() if nm != "step"}
+    per_kernel_median = {nm: statistics.median(v) for nm, v in samples.items()}
+    per_kernel_min = {nm: min(v) for nm, v in samples.items()}
     log("per-call ms (HIP events, mean over timed steps):", json.dumps(per_kernel))
+    log("per-call ms (median):", json.dumps(per_kernel_median))
 
     fl = gram_flops(G, n, d_in)
     value = fl / (ms_per_step * 1e-3) / 1e12
     gram_ms = per_kernel["fisher_gram"]
     achieved = fl / (gram_ms * 1e-3) / 1e12
-    dz_gbs = (dZ.numel() * 4 + s.numel() * 4) / (per_kernel["group_weights"] * 1e-3) / 1e9
+    dz_bytes = dZ.numel() * 4 + s.numel() * 4                       # K1: dZ once, s written
+    mirror_bytes = 4.0 * G * d_in * (d_in - 1)                      # mirror: strict upper triangle read, strict lower written
+    dz_gbs = dz_bytes / (per_kernel["group_weights"] * 1e-3) / 1e9
+    mirror_gbs = mirror_bytes / (per_kernel["mirror"] * 1e-3) / 1e9
+    props = torch.cuda.get_device_properties(0)
+    traffic, traffic_source = load_traffic(spec.name)
 
     result = {
         "metric": "Fisher-Gram TFLOP/s (algorithmic, upper triangle) over one linear layer's whole GuidedQuant pass",
@@ -199,17 +211,27 @@ def main():
                                f"W[{d_out},{d_in}] f32 with 3-bit per-row codebook What",
                    "tokens": n, "d_in": d_in, "d_out": d_out, "G": G, "token_chunks": chunks},
         "pct_of_mfma_peak": 100.0 * achieved / PEAK_BF16_TFLOPS,
-        "ms_per_call": per_kernel,
+        "ms_per_call": per_kernel, "ms_per_call_median": per_kernel_median, "ms_per_call_min": per_kernel_min,
+        "ms_per_step_median": per_kernel_median["step"], "ms_per_step_min": per_kernel_min["step"],
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "hbm_GiB": round(props.total_memory / 2 ** 30, 1)},
         "group_weights_GBps": dz_gbs,
+        "hbm_kernels": {
+            "group_weights": {"bytes_per_launch": dz_bytes, "GBps": dz_gbs, "frac_of_8TBps": dz_gbs / 8000.0},
+            "mirror": {"bytes_per_launch": mirror_bytes, "GBps": mirror_gbs, "frac_of_8TBps": mirror_gbs / 8000.0}},
         "roofline": {"bound": "mfma", "kernel": "fisher_gram_bf16", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": load_traffic(spec.name),
-                     "flop_per_launch": fl, "ms_per_launch": gram_ms},
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_source": traffic_source,
+                     "flop_per_launch": fl, "ms_per_launch": gram_ms, "ms_per_launch_median": per_kernel_median["fisher_gram"],
+                     "ms_per_launch_min": per_kernel_min["fisher_gram"],
+                     "note": "one launch = one gq_fisher_gram call (weight repack + Gram kernel + second pass of the split tiles), "
+                             "HIP events on the launch stream around the call"},
     }
 
     if args.cd_cycles > 0:
         # The step that consumes H (Section 4.2): timed on its own, after the hot path, on the H just
         # built (diagonal damped by 1 % of its mean, as every user of H does) and the 3-bit grids.
-        Hd = H + 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+        Hd = gq.gq_damp_diagonal(H.clone(), 0.01, 0.0)
         _, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)
         ws_c = torch.empty(int(lib.gq_cd_workspace_bytes(d_out, d_in, G)), dtype=torch.uint8, device=dev)
         Wq = What.clone()
@@ -294,7 +316,10 @@ def main():
         torch.cuda.synchronize()
         gram2_ms = e0.elapsed_time(e1)
         result["fisher_gram_two_terms"] = {"ms": gram2_ms, "TFLOPs_algorithmic": fl / (gram2_ms * 1e-3) / 1e12,
-                                           "TFLOPs_executed_over_peak": 2 * fl / (gram2_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                                           "TFLOPs_executed_over_peak": 2 * fl / (gram2_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                           "note": "the H a factorization can consume at 1 % damping (positive semidefinite to "
+                                                   "~1e-5 of its largest eigenvalue); the one-term H of the timed step is within "
+                                                   "3e-3 but indefinite at that damping for most shapes"}
         ws_f = torch.empty(int(lib.gq_cholesky_workspace_bytes(d_in, G)), dtype=torch.uint8, device=dev)
         ws_c = torch.empty(int(lib.gq_cd_workspace_bytes(d_out, d_in, G)), dtype=torch.uint8, device=dev)
         gq.gq_damped_cholesky(H, 0.01, 0.0, reverse=True, workspace=ws_f)                 # warm-up
@@ -331,6 +356,15 @@ def main():
         if ceil:
             result["mfma_ceiling"] = ceil
             result["roofline"]["frac_of_measured_ceiling"] = achieved / ceil["random_operands_tflops"]
+            result["device"]["shader_clock_GHz_under_bf16_mfma_load"] = ceil.get("shader_clock_GHz_random_operands")
+            result["device"]["max_clock_MHz"] = ceil.get("max_clock_MHz")
+            rd, cp = ceil.get("hbm_read_stream_GBps"), ceil.get("hbm_copy_GBps")
+            if rd:
+                result["hbm_kernels"]["read_stream_ceiling_GBps"] = rd
+                result["hbm_kernels"]["group_weights"]["frac_of_read_stream_ceiling"] = dz_gbs / rd
+            if cp:
+                result["hbm_kernels"]["copy_ceiling_GBps"] = cp
+                result["hbm_kernels"]["mirror"]["frac_of_copy_ceiling"] = mirror_gbs / cp
 
     if not args.no_cpu_baseline:
         import numpy as np

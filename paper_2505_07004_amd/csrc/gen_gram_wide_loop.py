@@ -46,10 +46,15 @@ S_FIRST, S_LAST = 84, 95
 
 
 # ---- the issue order inside a sub-step of 24 matrix instructions (slots 0..23) --------------------
+# Defaults = the fastest of the orders timed on an MI355X (X[65536,4096] and X[32768,8192], G = 4): the scaling
+# pieces one per slot in the slots that issue no LDS read (a raw fragment is re-read after slots 2, 5, 8, ...);
+# two pieces per slot, batched re-reads (2 or 4 fragments at once) or split re-reads were 1-3 % slower.
 B_BATCH = int(os.environ.get("GQW_BBATCH", "1"))            # raw fragments re-read per batch (after the last use of the batch)
 A_SLOTS = [int(v) for v in os.environ.get("GQW_ASLOTS", "0,1").split(",")]          # weights + scaled-operand reads
-DMA_SLOTS = [int(v) for v in os.environ.get("GQW_DMASLOTS", "3,11,19").split(",")]  # M0 set here, the load one slot later
-SCALE_SLOTS = [int(v) for v in os.environ.get("GQW_SCALESLOTS", "9,10,11,12,13,14,15,16,17,18,19,20").split(",")]
+DMA_SLOTS = [int(v) for v in os.environ.get("GQW_DMASLOTS", "4,13,22").split(",")]  # M0 set here, the load one slot later
+SCALE_SLOTS = [int(v) for v in os.environ.get("GQW_SCALESLOTS", "6,7,9,10,12,13,15,16,18,19,21,22").split(",")]
+B_SPLIT = os.environ.get("GQW_BSPLIT") == "1"                # the two reads of a raw fragment in two consecutive slots
+NO_BARRIER = os.environ.get("GQW_NOBARRIER") == "1"          # timing experiments only: results are wrong without it
 
 
 class Emitter:
@@ -180,8 +185,12 @@ def sub_step(e, cur_set, nxt_set, fetch_ks, dma, slot_fill, first=False, fetch=T
                 r(e)
         if fetch and x == MA - 1 and (y + 1) % B_BATCH == 0:       # the fragments whose last use has just been issued
             for yy in range(y + 1 - B_BATCH, y + 1):
-                for r in b_reads(fetch_ks, yy):
-                    r(e)
+                rr = b_reads(fetch_ks, yy)
+                rr[0](e)
+                if not B_SPLIT or y == NB - 1:
+                    rr[1](e)
+        if fetch and B_SPLIT and x == 0 and y > 0:                  # ... its second half one slot later
+            b_reads(fetch_ks, y - 1)[1](e)
         if i in DMA_SLOTS and DMA_SLOTS.index(i) < len(dma):          # M0 one matrix instruction ahead of its load
             dma_m0(e, dma[DMA_SLOTS.index(i)], slot_fill)
         if i - 1 in DMA_SLOTS and DMA_SLOTS.index(i - 1) < len(dma):
@@ -240,7 +249,7 @@ def build():
         m = (j + 1) % NS                          # slot that is entered
         slot_fill = (m + NS - 2) % NS             # slot of the stage two back, refilled with stage k0 + m + NS - 2
         e.raw("s_waitcnt vmcnt(%d)" % ((NS - 3) * LOADS))
-        e.raw("s_barrier")
+        e.raw("s_nop 0" if NO_BARRIER else "s_barrier")
         stage_setup(e, slot_fill)
         # tokens 16..31 of the previous stage (operands already in registers); fetches tokens 0..15 of the
         # stage entered: its addresses are formed first

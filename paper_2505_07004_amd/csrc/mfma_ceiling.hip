@@ -3,7 +3,9 @@
 // no memory traffic at all, (a) on constant operands and (b) on operands with random sign and
 // mantissa bits, as real activations have.  Under (b) the chip runs into its power limit and
 // clocks down, so (b), not the data-sheet number, is the ceiling a dense bf16 kernel fed with
-// real data can approach.  Prints one JSON line.
+// real data can approach.  Also measured, for the HBM-bound kernels of the path: what a plain read
+// stream and a plain copy of 1 GiB sustain (16-byte loads, grid-stride), and the shader clock the chip
+// holds under the matrix-core load (cycle counter against the 100 MHz wall clock).  Prints one JSON line.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -27,8 +29,37 @@ __device__ inline unsigned mix(unsigned x) {
   return x;
 }
 
+// Read stream: every thread sums 16-byte vectors, grid-stride, four loads in flight per step.
+__global__ __launch_bounds__(256) void read_stream(const u32x4* __restrict__ src, size_t n_vec, unsigned* out) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  unsigned acc = 0;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc += (a[0] ^ a[1] ^ a[2] ^ a[3]) + (b[0] ^ b[1] ^ b[2] ^ b[3]) + (c[0] ^ c[1] ^ c[2] ^ c[3]) + (d[0] ^ d[1] ^ d[2] ^ d[3]);
+  }
+  for (; i < n_vec; i += stride) {
+    const u32x4 a = src[i];
+    acc += a[0] ^ a[1] ^ a[2] ^ a[3];
+  }
+  if (acc == 0x12345678u) out[0] = acc;        // keeps the loads alive; practically never taken
+}
+// Copy: the same loop with a store per load.
+__global__ __launch_bounds__(256) void copy_stream(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n_vec) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n_vec; i += stride) dst[i] = src[i];
+}
+
 template <int RANDOM>
-__global__ __launch_bounds__(256) void mfma_only(float* out, int iters) {
+__global__ __launch_bounds__(256) void mfma_only(float* out, int iters, long long* clk) {
   u32x4 aw[2], bw[8];
   for (int i = 0; i < 2; ++i)
     for (int q = 0; q < 4; ++q) {
@@ -43,6 +74,7 @@ __global__ __launch_bounds__(256) void mfma_only(float* out, int iters) {
   f32x16 acc[16];
   for (int i = 0; i < 16; ++i)
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  const long long c0 = clock64(), w0 = wall_clock64();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < 16; ++i)
@@ -52,20 +84,24 @@ __global__ __launch_bounds__(256) void mfma_only(float* out, int iters) {
   float s = 0.f;
   for (int i = 0; i < 16; ++i)
     for (int r = 0; r < 16; ++r) s += acc[i][r];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {          // shader cycles and 100 MHz ticks the loop took
+    clk[0] = clock64() - c0;
+    clk[1] = wall_clock64() - w0;
+  }
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 template <int RANDOM>
-static int run(float* d, int cus, double* tflops) {
+static int run(float* d, int cus, double* tflops, long long* clk, double* ghz) {
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
   CK(hipEventCreate(&e1));
   const int iters = 40000;
-  mfma_only<RANDOM><<<cus, 256>>>(d, 4000);   // warm up: clocks settle under load
+  mfma_only<RANDOM><<<cus, 256>>>(d, 4000, clk);   // warm up: clocks settle under load
   double best = 0;
   for (int rep = 0; rep < 3; ++rep) {
     CK(hipEventRecord(e0));
-    mfma_only<RANDOM><<<cus, 256>>>(d, iters);
+    mfma_only<RANDOM><<<cus, 256>>>(d, iters, clk);
     CK(hipEventRecord(e1));
     CK(hipEventSynchronize(e1));
     float ms;
@@ -74,6 +110,43 @@ static int run(float* d, int cus, double* tflops) {
     if (rep > 0 && tf > best) best = tf;     // the first repetition still sees the ramp
   }
   *tflops = best;
+  long long h[2] = {0, 0};
+  CK(hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost));
+  *ghz = h[1] > 0 ? (double)h[0] / (double)h[1] * 0.1 : 0.0;
+  return 0;
+}
+
+// GB/s of the read stream (copy == 0) or the copy (bytes read + bytes written) over 1 GiB.
+static int stream(int copy, int cus, double* gbps) {
+  const size_t bytes = (size_t)1 << 30, n_vec = bytes / 16;
+  u32x4 *src, *dst = nullptr;
+  unsigned* out;
+  CK(hipMalloc(&src, bytes));
+  CK(hipMemset(src, 1, bytes));
+  CK(hipMalloc(&out, 256));
+  if (copy) CK(hipMalloc(&dst, bytes));
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  const int blocks = cus * 16;
+  double best = 0;
+  for (int rep = 0; rep < 6; ++rep) {
+    CK(hipEventRecord(e0));
+    if (copy)
+      copy_stream<<<blocks, 256>>>(src, dst, n_vec);
+    else
+      read_stream<<<blocks, 256>>>(src, n_vec, out);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    const double g = (copy ? 2.0 : 1.0) * (double)bytes / ms / 1e6;
+    if (rep > 0 && g > best) best = g;
+  }
+  *gbps = best;
+  CK(hipFree(src));
+  if (dst) CK(hipFree(dst));
+  CK(hipFree(out));
   return 0;
 }
 
@@ -83,10 +156,17 @@ int main() {
   const int cus = p.multiProcessorCount;
   float* d;
   CK(hipMalloc(&d, (size_t)cus * 256 * sizeof(float)));
-  double tc = 0, tr = 0;
-  if (run<0>(d, cus, &tc)) return 1;
-  if (run<1>(d, cus, &tr)) return 1;
+  long long* clk;
+  CK(hipMalloc(&clk, 64));
+  double tc = 0, tr = 0, gc = 0, gr = 0, rd = 0, cp = 0;
+  if (run<0>(d, cus, &tc, clk, &gc)) return 1;
+  if (run<1>(d, cus, &tr, clk, &gr)) return 1;
+  if (stream(0, cus, &rd)) return 1;
+  if (stream(1, cus, &cp)) return 1;
   printf("{\"kernel\": \"v_mfma_f32_32x32x16_bf16 only, 1 wave per SIMD, %d CUs\", \"constant_operands_tflops\": %.1f, "
-         "\"random_operands_tflops\": %.1f}\n", cus, tc, tr);
+         "\"random_operands_tflops\": %.1f, \"shader_clock_GHz_constant_operands\": %.3f, "
+         "\"shader_clock_GHz_random_operands\": %.3f, \"hbm_read_stream_GBps\": %.0f, \"hbm_copy_GBps\": %.0f, "
+         "\"device\": \"%s\", \"compute_units\": %d, \"max_clock_MHz\": %d}\n",
+         cus, tc, tr, gc, gr, rd, cp, p.name, cus, p.clockRate / 1000);
   return 0;
 }

@@ -31,7 +31,7 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
         H = gq.gq_fisher_gram(X, s, mirror=True)
     else:                                   # the fp32 Gram path wants 16-byte rows of X; H itself may have any size
         H = torch.einsum("nk,na,nb->kab", s.double(), X.double(), X.double()).float().contiguous()
-    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))   # damping, as every user of H adds
+    gq.gq_damp_diagonal(H, 0.01, 0.0)   # damping, as every user of H adds
     W = wl.make_w(d_out, d_in, seed + 2, DEV)
     What, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
     if ld:
@@ -132,7 +132,7 @@ def test_cd_at_the_llama2_7b_shape_on_sampled_channels():
     s = gq.gq_group_weights(wl.make_dz_for(spec, DEV), spec.G)
     H = gq.gq_fisher_gram(X, s, mirror=True)
     del X, s
-    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, spec.d_in))
+    gq.gq_damp_diagonal(H, 0.01, 0.0)
     W = wl.make_w(spec.d_out, spec.d_in, 7, DEV)
     What, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)
     old = What.clone()
@@ -168,7 +168,7 @@ def test_cd_with_a_number_of_grid_points_that_is_not_a_power_of_two(m):
     d_out, d_in, G = 80, 200, 2
     X = wl.make_x_outlier(400, d_in, 3, 20.0, 19, DEV, torch.float32)
     H = gq.gq_fisher_gram(X, gq.gq_group_weights(wl.make_dz(400, d_out, 1.0, 1.5, 20, DEV), G), mirror=True)
-    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+    gq.gq_damp_diagonal(H, 0.01, 0.0)
     W = wl.make_w(d_out, d_in, 21, DEV)
     g = torch.Generator(device="cpu").manual_seed(22 + m)
     C = (0.05 * torch.randn(d_out, m, generator=g)).to(DEV).contiguous()      # grids in no particular order

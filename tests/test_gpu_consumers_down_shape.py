@@ -75,7 +75,7 @@ def test_consumers_of_h_at_the_llama2_7b_down_shape():
 
         # --- one coordinate-descent cycle from plain rounding, against the damped H
         if k == groups[0]:
-            Hdg = H + 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+            Hdg = gq.gq_damp_diagonal(H.clone(), 0.01, 0.0)
             Wc = What0.clone()
             before = gq.gq_objective(W, Wc, Hdg)
             Qc = gq.gq_cd_assign(W, Wc, C, Hdg, n_cycles=1)

@@ -164,7 +164,7 @@ def test_cholesky_then_sequential_rounding_at_the_llama2_7b_shape():
     C = C.contiguous()
     What, Q = gq.gq_ldlq_assign(W, C, R)
     rtn = torch.gather(C, 1, torch.argmin((C[:, None, :] - W[:, :, None]).abs(), dim=2))
-    Hd = H + 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, spec.d_in))
+    Hd = gq.gq_damp_diagonal(H.clone(), 0.01, 0.0)
     o_seq, o_rtn = gq.gq_objective(W, What, Hd), gq.gq_objective(W, rtn, Hd)
     torch.cuda.synchronize()
     say(f"  objective: plain rounding {o_rtn.tolist()}, sequential rounding {o_seq.tolist()}")

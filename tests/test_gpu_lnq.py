@@ -28,7 +28,7 @@ def _case(n, d_in, d_out, G, bits, seed, ld=None):
     dZ = wl.make_dz(n, d_out, 1.0, 1.5, seed + 1, DEV)
     s = gq.gq_group_weights(dZ, G)
     H = gq.gq_fisher_gram(X, s, mirror=True)
-    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+    gq.gq_damp_diagonal(H, 0.01, 0.0)
     W = wl.make_w(d_out, d_in, seed + 2, DEV)
     What, C = wl.quantize_codebook_per_row(W, bits, return_codebook=True)
     Q = torch.argmin((C[:, None, :] - What[:, :, None]).abs(), dim=2).to(torch.uint8).contiguous()
@@ -109,7 +109,7 @@ def test_codebook_step_at_the_llama2_7b_shape_on_sampled_channels():
     s = gq.gq_group_weights(wl.make_dz_for(spec, DEV), spec.G)
     H = gq.gq_fisher_gram(X, s, mirror=True)
     del X, s
-    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, spec.d_in))
+    gq.gq_damp_diagonal(H, 0.01, 0.0)
     W = wl.make_w(spec.d_out, spec.d_in, 7, DEV)
     per = spec.d_out // spec.G
     g = torch.Generator().manual_seed(5)
@@ -139,7 +139,7 @@ def test_codebook_step_with_a_number_of_grid_points_that_is_not_a_power_of_two(m
     d_out, d_in, G = 140, 200, 2                                         # 70 channels per group: two tiles for m = 5, 11
     X = wl.make_x_outlier(400, d_in, 3, 20.0, 9, DEV, torch.float32)
     H = gq.gq_fisher_gram(X, gq.gq_group_weights(wl.make_dz(400, d_out, 1.0, 1.5, 10, DEV), G), mirror=True)
-    H += 0.01 * torch.diag_embed(torch.diagonal(H, dim1=1, dim2=2).mean(dim=1, keepdim=True).expand(-1, d_in))
+    gq.gq_damp_diagonal(H, 0.01, 0.0)
     W = wl.make_w(d_out, d_in, 11, DEV)
     g = torch.Generator(device="cpu").manual_seed(12 + m)
     Q = torch.randint(0, m, (d_out, d_in), generator=g, dtype=torch.uint8).to(DEV)

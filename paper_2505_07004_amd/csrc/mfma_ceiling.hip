@@ -29,14 +29,18 @@ __device__ inline unsigned mix(unsigned x) {
   return x;
 }
 
-// Read stream: every thread sums 16-byte vectors, grid-stride, four loads in flight per step.
+// Read stream: every thread sums 16-byte vectors, grid-stride, U loads in flight per step.
+template <int U>
 __global__ __launch_bounds__(256) void read_stream(const u32x4* __restrict__ src, size_t n_vec, unsigned* out) {
   const size_t stride = (size_t)gridDim.x * 256;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   unsigned acc = 0;
-  for (; i + 3 * stride < n_vec; i += 4 * stride) {
-    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc += (a[0] ^ a[1] ^ a[2] ^ a[3]) + (b[0] ^ b[1] ^ b[2] ^ b[3]) + (c[0] ^ c[1] ^ c[2] ^ c[3]) + (d[0] ^ d[1] ^ d[2] ^ d[3]);
+  for (; i + (U - 1) * stride < n_vec; i += U * stride) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
   }
   for (; i < n_vec; i += stride) {
     const u32x4 a = src[i];
@@ -45,15 +49,16 @@ __global__ __launch_bounds__(256) void read_stream(const u32x4* __restrict__ src
   if (acc == 0x12345678u) out[0] = acc;        // keeps the loads alive; practically never taken
 }
 // Copy: the same loop with a store per load.
+template <int U>
 __global__ __launch_bounds__(256) void copy_stream(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n_vec) {
   const size_t stride = (size_t)gridDim.x * 256;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n_vec; i += 4 * stride) {
-    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    dst[i] = a;
-    dst[i + stride] = b;
-    dst[i + 2 * stride] = c;
-    dst[i + 3 * stride] = d;
+  for (; i + (U - 1) * stride < n_vec; i += U * stride) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
   }
   for (; i < n_vec; i += stride) dst[i] = src[i];
 }
@@ -128,20 +133,27 @@ static int stream(int copy, int cus, double* gbps) {
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
   CK(hipEventCreate(&e1));
-  const int blocks = cus * 16;
   double best = 0;
-  for (int rep = 0; rep < 6; ++rep) {
-    CK(hipEventRecord(e0));
-    if (copy)
-      copy_stream<<<blocks, 256>>>(src, dst, n_vec);
-    else
-      read_stream<<<blocks, 256>>>(src, n_vec, out);
-    CK(hipEventRecord(e1));
-    CK(hipEventSynchronize(e1));
-    float ms;
-    CK(hipEventElapsedTime(&ms, e0, e1));
-    const double g = (copy ? 2.0 : 1.0) * (double)bytes / ms / 1e6;
-    if (rep > 0 && g > best) best = g;
+  // the ceiling is the best of a few plain launch shapes (blocks per compute unit x loads in flight per thread)
+  for (int shape = 0; shape < 6; ++shape) {
+    const int blocks = cus * (shape % 3 == 0 ? 8 : shape % 3 == 1 ? 16 : 32);
+    const bool deep = shape >= 3;
+    for (int rep = 0; rep < 4; ++rep) {
+      CK(hipEventRecord(e0));
+      if (copy) {
+        if (deep) copy_stream<8><<<blocks, 256>>>(src, dst, n_vec);
+        else copy_stream<4><<<blocks, 256>>>(src, dst, n_vec);
+      } else {
+        if (deep) read_stream<8><<<blocks, 256>>>(src, n_vec, out);
+        else read_stream<4><<<blocks, 256>>>(src, n_vec, out);
+      }
+      CK(hipEventRecord(e1));
+      CK(hipEventSynchronize(e1));
+      float ms;
+      CK(hipEventElapsedTime(&ms, e0, e1));
+      const double g = (copy ? 2.0 : 1.0) * (double)bytes / ms / 1e6;
+      if (rep > 0 && g > best) best = g;
+    }
   }
   *gbps = best;
   CK(hipFree(src));

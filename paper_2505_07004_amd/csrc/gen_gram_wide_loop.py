@@ -49,11 +49,9 @@ S_FIRST, S_LAST = 84, 95
 # Defaults = the fastest of the orders timed on an MI355X (X[65536,4096] and X[32768,8192], G = 4): the scaling
 # pieces one per slot in the slots that issue no LDS read (a raw fragment is re-read after slots 2, 5, 8, ...);
 # two pieces per slot, batched re-reads (2 or 4 fragments at once) or split re-reads were 1-3 % slower.
-B_BATCH = int(os.environ.get("GQW_BBATCH", "1"))            # raw fragments re-read per batch (after the last use of the batch)
 A_SLOTS = [int(v) for v in os.environ.get("GQW_ASLOTS", "0,1").split(",")]          # weights + scaled-operand reads
 DMA_SLOTS = [int(v) for v in os.environ.get("GQW_DMASLOTS", "4,13,22").split(",")]  # M0 set here, the load one slot later
 SCALE_SLOTS = [int(v) for v in os.environ.get("GQW_SCALESLOTS", "6,7,9,10,12,13,15,16,18,19,21,22").split(",")]
-B_SPLIT = os.environ.get("GQW_BSPLIT") == "1"                # the two reads of a raw fragment in two consecutive slots
 NO_BARRIER = os.environ.get("GQW_NOBARRIER") == "1"          # timing experiments only: results are wrong without it
 
 
@@ -165,42 +163,42 @@ def dma_load(e, k):
     e.raw("global_load_lds_dwordx4 %%[vo%d], s[%d:%d]" % (k, base, base + 1))
 
 
-def sub_step(e, cur_set, nxt_set, fetch_ks, dma, slot_fill, first=False, fetch=True):
-    """24 matrix instructions on (A set cur_set, B); in between: fetch of the next sub-step's operands
-    from the stage BASE points at (sub-step fetch_ks of it), their scaling into A set nxt_set, and the
-    direct loads `dma` (indices) of the stage in ring slot slot_fill."""
-    reads = fetch_reads(fetch_ks) if fetch else []
-    pieces = [(x, q) for x in range(MA) for q in range(4)] if fetch else []
-    dma = list(dma)
-    for i in range(MA * NB):
+def sub_step(e, cur_set, nxt_set, fetch_ks, dma, slot_fill, first=False, fetch=True, nb=NB):
+    """3 * nb matrix instructions on (A set cur_set, raw fragments 0 .. nb-1); in between: fetch of the next
+    sub-step's operands from the stage BASE points at (sub-step fetch_ks of it), their scaling into A set
+    nxt_set, and the direct loads `dma` (indices) of the stage in ring slot slot_fill.  The issue order is
+    given for the full sub-step (slots 0..23); with fewer live fragments every slot maps proportionally onto
+    the matrix instructions that remain."""
+    n_live = MA * nb
+
+    def pos(s):
+        return min(n_live - 1, (s * n_live) // (MA * NB))
+
+    extras = [[] for _ in range(n_live)]
+    if fetch:
+        reads = fetch_reads(fetch_ks)
+        extras[pos(A_SLOTS[0])] += [r for _, r in reads[:4]]
+        extras[pos(A_SLOTS[1])] += [r for _, r in reads[4:]]
+        for y in range(nb):                                   # a raw fragment is re-read right after its last use
+            extras[MA * y + MA - 1] += b_reads(fetch_ks, y)
+    for idx, k in enumerate(dma):                             # M0 one slot ahead of its load
+        extras[pos(DMA_SLOTS[idx])].append(lambda e, k=k: (dma_m0(e, k, slot_fill), e.raw("s_nop 0")))
+        extras[pos(DMA_SLOTS[idx] + 1)].append(lambda e, k=k: dma_load(e, k))
+    if fetch:
+        pieces = [(x, q) for x in range(MA) for q in range(4)]
+        for s, (px, pq) in zip(SCALE_SLOTS, pieces):
+            extras[pos(s)].append(lambda e, px=px, pq=pq: scale_piece(e, px, pq, nxt_set))
+    for i in range(n_live):
         y, x = divmod(i, MA)
         e.need(list(range(BREG + 4 * y, BREG + 4 * y + 4)))
         c = "0" if first else acc(x, y)
         e.raw("v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (acc(x, y), frag(A_SET[cur_set], x), frag(BREG, y), c))
-        if fetch and i == A_SLOTS[0]:
-            for _, r in reads[:4]:
-                r(e)
-        if fetch and i == A_SLOTS[1]:
-            for _, r in reads[4:]:
-                r(e)
-        if fetch and x == MA - 1 and (y + 1) % B_BATCH == 0:       # the fragments whose last use has just been issued
-            for yy in range(y + 1 - B_BATCH, y + 1):
-                rr = b_reads(fetch_ks, yy)
-                rr[0](e)
-                if not B_SPLIT or y == NB - 1:
-                    rr[1](e)
-        if fetch and B_SPLIT and x == 0 and y > 0:                  # ... its second half one slot later
-            b_reads(fetch_ks, y - 1)[1](e)
-        if i in DMA_SLOTS and DMA_SLOTS.index(i) < len(dma):          # M0 one matrix instruction ahead of its load
-            dma_m0(e, dma[DMA_SLOTS.index(i)], slot_fill)
-        if i - 1 in DMA_SLOTS and DMA_SLOTS.index(i - 1) < len(dma):
-            dma_load(e, dma[DMA_SLOTS.index(i - 1)])
-        if fetch:
-            for px, pq in [p for s, p in zip(SCALE_SLOTS, pieces) if s == i]:
-                scale_piece(e, px, pq, nxt_set)
+        for fn in extras[i]:
+            fn(e)
 
 
-def build():
+def build(nb=NB):
+    """The statement for work items of which only the first nb raw fragments (32 columns each) are live."""
     e = Emitter()
     # ---------------- prologue: fill the ring, fetch and scale the first sub-step --------------
     # Scalar loads of the surrounding code must not be counted against the LDS reads below.  Its vector
@@ -229,7 +227,7 @@ def build():
     set_base(0)
     for _, r in fetch_reads(0):
         r(e)
-    for y in range(NB):
+    for y in range(nb):
         for r in b_reads(0, y):
             r(e)
     e.wait_all_lds()
@@ -238,7 +236,7 @@ def build():
             scale_piece(e, x, q, 0)
     e.raw("s_nop 7")
     # first sub-step: tokens 0..15 of the first stage, accumulators start from 0; fetches tokens 16..31
-    sub_step(e, 0, 1, 1, [], 0, first=True)
+    sub_step(e, 0, 1, 1, [], 0, first=True, nb=nb)
     join_state = e.state()
     e.raw("s_sub_u32 s%d, s%d, 1" % (S_CNT, S_CNT))
     e.raw("s_cmp_eq_u32 s%d, 0" % S_CNT)
@@ -254,9 +252,9 @@ def build():
         # tokens 16..31 of the previous stage (operands already in registers); fetches tokens 0..15 of the
         # stage entered: its addresses are formed first
         set_base(m)
-        sub_step(e, 1, 0, 0, [0, 1, 2], slot_fill)
+        sub_step(e, 1, 0, 0, [0, 1, 2], slot_fill, nb=nb)
         # tokens 0..15 of the stage entered; fetches its tokens 16..31
-        sub_step(e, 0, 1, 1, [3, 4, 5], slot_fill)
+        sub_step(e, 0, 1, 1, [3, 4, 5], slot_fill, nb=nb)
         assert e.state() == join_state, "LDS scoreboard differs between the paths that meet at a label"
         e.raw("s_sub_u32 s%d, s%d, 1" % (S_CNT, S_CNT))
         e.raw("s_cmp_eq_u32 s%d, 0" % S_CNT)
@@ -266,7 +264,7 @@ def build():
             e.raw("s_cbranch_scc0 GQW_LOOP%=")
     # ---------------- tail: tokens 16..31 of the last stage -------------------------------------
     e.raw("GQW_TAIL%=:")
-    sub_step(e, 1, 0, 0, [], 0, fetch=False)
+    sub_step(e, 1, 0, 0, [], 0, fetch=False, nb=nb)
     e.raw("s_waitcnt vmcnt(0)")
     e.raw("s_nop 15")
     e.raw("s_nop 15")
@@ -274,14 +272,16 @@ def build():
 
 
 HEADER = """// GENERATED by gen_gram_wide_loop.py -- do not edit.  The token loop of the wide bf16 Gram kernel
-// (one run of token steps of one work item) as a single inline-assembly statement; the variables
-// named in the operand lists are those of fisher_gram_bf16_wide.hip.
+// (one run of token steps of one work item) as inline-assembly statements, one per number of live
+// raw fragments (work items that cross the diagonal or the right edge skip the matrix instructions of
+// the 32-column fragments that lie wholly outside the upper triangle); the variables named in the
+// operand lists are those of fisher_gram_bf16_wide.hip.
 """
 
 
-def main():
-    lines = build()
-    out = [HEADER, "asm volatile("]
+def statement(nb):
+    lines = build(nb)
+    out = ["asm volatile("]
     for l in lines:
         out.append('    "%s\\n"' % l)
     outs = ", ".join('[acc%d] "=%s"(acc[%d])' % (i, "a" if i < 16 else "&v", i) for i in range(MA * NB))
@@ -299,11 +299,23 @@ def main():
     out.append("    : " + outs)
     out.append("    : " + ", ".join(ins))
     out.append("    : " + ", ".join(clob) + ");")
+    return out, sum(1 for l in lines if l.startswith("v_mfma"))
+
+
+def main():
+    out = [HEADER, "switch (nb_live) {"]
+    total = 0
+    for nb in range(NB, 0, -1):
+        body, n_mfma = statement(nb)
+        total += n_mfma
+        out.append("  case %d:   // the first %d raw fragments are live (%d columns)" % (nb, nb, 32 * nb))
+        out += ["  " + l for l in body]
+        out.append("    break;")
+    out.append("  default:\n    __builtin_unreachable();\n}")
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "fisher_gram_bf16_wide_loop.inc")
     with open(path, "w") as f:
         f.write("\n".join(out) + "\n")
-    n_mfma = sum(1 for l in lines if l.startswith("v_mfma"))
-    print("wrote %s: %d lines, %d matrix instructions" % (path, len(lines), n_mfma), file=sys.stderr)
+    print("wrote %s: %d statements, %d matrix instructions" % (path, NB, total), file=sys.stderr)
 
 
 if __name__ == "__main__":

@@ -337,6 +337,7 @@ def main():
         chol_fl = G * d_in ** 3 / 3.0                                   # flop of the factorization (d^3/3 per group)
         result["sequential_rounding"] = {
             "cholesky_ms": chol_ms, "ldlq_assign_ms": seq_ms, "levels": 8, "info": [int(v) for v in info.tolist()],
+            "positive_definite": not any(info.tolist()),
             "objective_plain_rounding": [float(v) for v in o_before.tolist()],
             "objective_after": [float(v) for v in o_seq.tolist()] if not any(info.tolist()) else None,
             "note": None if not any(info.tolist()) else

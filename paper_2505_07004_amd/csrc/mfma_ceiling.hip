@@ -5,7 +5,13 @@
 // clocks down, so (b), not the data-sheet number, is the ceiling a dense bf16 kernel fed with
 // real data can approach.  Also measured, for the HBM-bound kernels of the path: what a plain read
 // stream and a plain copy of 1 GiB sustain (16-byte loads, grid-stride), and the shader clock the chip
-// holds under the matrix-core load (cycle counter against the 100 MHz wall clock).  Prints one JSON line.
+// holds under the matrix-core load (cycle counter against the 100 MHz wall clock).  A third loop carries the
+// instruction mix of the Gram kernel per matrix instruction (one transposing LDS read of 8 bytes per lane, 2.6
+// vector ALU instructions, one direct global->LDS load of 1 KiB per 8 matrix instructions, random operands,
+// one wave per SIMD) spread evenly -- the same extras after every matrix instruction -- and nothing else of
+// the kernel: no barriers, no data dependences, no epilogue.  It shows what the mix costs against the loop of
+// matrix instructions alone (the kernel itself, which places the extras unevenly, sustains more).  Prints one
+// JSON line.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -96,6 +102,66 @@ __global__ __launch_bounds__(256) void mfma_only(float* out, int iters, long lon
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+constexpr unsigned long long kMixWindow = 1ull << 20;
+
+// The Gram kernel's instruction mix without its dependences: per 24 matrix instructions 24 transposing LDS
+// reads, 62 vector ALU instructions and 3 direct loads (addresses stay inside `src`: 3 KiB per step and wave).
+__global__ __launch_bounds__(256) void mfma_mix(float* out, const char* src, int iters, long long* clk) {
+  __shared__ __attribute__((aligned(1024))) char lds[65536];
+  for (int i = threadIdx.x * 16; i < 65536; i += 256 * 16) *(u32x4*)(lds + i) = u32x4{mix(i), mix(i + 1), mix(i + 2), mix(i + 3)};
+  __syncthreads();
+  u32x4 aw[3], bw[8];
+  for (int i = 0; i < 3; ++i)
+    for (int q = 0; q < 4; ++q) aw[i][q] = (mix(threadIdx.x * 131 + i * 17 + q) & 0x807f807fu) | 0x3f003f00u;
+  for (int i = 0; i < 8; ++i)
+    for (int q = 0; q < 4; ++q) bw[i][q] = (mix(threadIdx.x * 977 + i * 31 + q + 7) & 0x807f807fu) | 0x3f003f00u;
+  f32x16 acc[16];
+  for (int i = 0; i < 16; ++i)
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  float v0 = 1.0f + threadIdx.x, v1 = 2.0f, v2 = 3.0f;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned ldsaddr = (threadIdx.x & 63) * 16 + wave * 4096;
+  const unsigned lds_dst = (unsigned)(uintptr_t)(char __attribute__((address_space(3)))*)lds + 32768 + wave * 1024;
+  // every wave streams through its own window of kMixWindow bytes of `src` (plus 4 KiB of slack), round and round
+  const unsigned long long window = (unsigned long long)(uintptr_t)src +
+                                    ((unsigned long long)blockIdx.x * 4 + wave) * (kMixWindow + 4096);
+  const unsigned voff = (threadIdx.x & 63) * 16;
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 tr = {0, 0};
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+    const unsigned long long at = window + (((unsigned long long)it * 3072) & (kMixWindow - 1));
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)at), hi = __builtin_amdgcn_readfirstlane((unsigned)(at >> 32));
+    const char* sb = (const char*)(uintptr_t)(((unsigned long long)hi << 32) | lo);
+#pragma unroll
+    for (int i = 0; i < 24; ++i) {
+      acc[i % 16] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw[i % 3]),
+                                                            __builtin_bit_cast(bf16x8, bw[i / 3]), acc[i % 16], 0, 0, 0);
+      // "+v": the destination stays live from read to read, so the compiler never hands these registers to
+      // another value while an earlier read may still be returning into them
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "+v"(tr) : "v"(ldsaddr));
+      asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v0) : "v"(1.0001f));
+      asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v1) : "v"(1.0001f));
+      if (i % 5 != 4) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v2) : "v"(1.0001f));
+      if (i % 8 == 3)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:0" ::"s"(lds_dst), "v"(voff + (i / 8) * 1024), "s"(sb) : "memory");
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    bw[it & 7][0] ^= (tr[0] ^ tr[1]) & 0x00010001u;
+    if ((it & 15) == 15) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  float s = v0 + v1 + v2;
+  for (int i = 0; i < 16; ++i)
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    clk[0] = clock64() - c0;
+    clk[1] = wall_clock64() - w0;
+  }
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 template <int RANDOM>
 static int run(float* d, int cus, double* tflops, long long* clk, double* ghz) {
   hipEvent_t e0, e1;
@@ -118,6 +184,35 @@ static int run(float* d, int cus, double* tflops, long long* clk, double* ghz) {
   long long h[2] = {0, 0};
   CK(hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost));
   *ghz = h[1] > 0 ? (double)h[0] / (double)h[1] * 0.1 : 0.0;
+  return 0;
+}
+
+static int run_mix(float* d, int cus, double* tflops, long long* clk, double* ghz) {
+  char* src;
+  const size_t bytes = (size_t)cus * 4 * (kMixWindow + 4096);
+  CK(hipMalloc(&src, bytes));
+  CK(hipMemset(src, 1, bytes));
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  const int iters = 30000;
+  mfma_mix<<<cus, 256>>>(d, src, 3000, clk);
+  double best = 0;
+  for (int rep = 0; rep < 3; ++rep) {
+    CK(hipEventRecord(e0));
+    mfma_mix<<<cus, 256>>>(d, src, iters, clk);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    const double tf = (double)cus * 4 * 24 * (double)iters * 32768.0 / ms / 1e9;
+    if (rep > 0 && tf > best) best = tf;
+  }
+  *tflops = best;
+  long long h[2] = {0, 0};
+  CK(hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost));
+  *ghz = h[1] > 0 ? (double)h[0] / (double)h[1] * 0.1 : 0.0;
+  CK(hipFree(src));
   return 0;
 }
 
@@ -170,15 +265,17 @@ int main() {
   CK(hipMalloc(&d, (size_t)cus * 256 * sizeof(float)));
   long long* clk;
   CK(hipMalloc(&clk, 64));
-  double tc = 0, tr = 0, gc = 0, gr = 0, rd = 0, cp = 0;
+  double tc = 0, tr = 0, gc = 0, gr = 0, rd = 0, cp = 0, tm = 0, gm = 0;
   if (run<0>(d, cus, &tc, clk, &gc)) return 1;
   if (run<1>(d, cus, &tr, clk, &gr)) return 1;
+  if (run_mix(d, cus, &tm, clk, &gm)) return 1;
   if (stream(0, cus, &rd)) return 1;
   if (stream(1, cus, &cp)) return 1;
   printf("{\"kernel\": \"v_mfma_f32_32x32x16_bf16 only, 1 wave per SIMD, %d CUs\", \"constant_operands_tflops\": %.1f, "
-         "\"random_operands_tflops\": %.1f, \"shader_clock_GHz_constant_operands\": %.3f, "
+         "\"random_operands_tflops\": %.1f, \"gram_instruction_mix_tflops\": %.1f, \"shader_clock_GHz_gram_instruction_mix\": %.3f, "
+         "\"shader_clock_GHz_constant_operands\": %.3f, "
          "\"shader_clock_GHz_random_operands\": %.3f, \"hbm_read_stream_GBps\": %.0f, \"hbm_copy_GBps\": %.0f, "
          "\"device\": \"%s\", \"compute_units\": %d, \"max_clock_MHz\": %d}\n",
-         cus, tc, tr, gc, gr, rd, cp, p.name, cus, p.clockRate / 1000);
+         cus, tc, tr, tm, gm, gc, gr, rd, cp, p.name, cus, p.clockRate / 1000);
   return 0;
 }

@@ -64,7 +64,8 @@ typedef enum {
 enum {
   GQ_ACCUMULATE = 1u << 0, /* H += ... ; without it the upper triangle of H is overwritten */
   GQ_MIRROR = 1u << 1,     /* after the update also fill the strictly lower triangle       */
-  GQ_TWO_TERMS = 1u << 2   /* GQ_BF16 only: carry the scaled operand as two bf16 terms     */
+  GQ_TWO_TERMS = 1u << 2,  /* GQ_BF16 only: carry the scaled operand as two bf16 terms     */
+  GQ_HEAVY_TWO_TERMS = 1u << 3 /* GQ_BF16 only: two terms for the heaviest tokens only      */
 };
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -135,6 +136,16 @@ size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in,
  *          matrix-core products per pair: twice the work of the one-term path, every
  *          product exact to 2^-17, the result within about 1e-5 of the fp32 path and
  *          positive semidefinite to that level.
+ *          GQ_HEAVY_TWO_TERMS (with GQ_BF16; ignored with GQ_F32 and when GQ_TWO_TERMS is
+ *          set): the same sum, with two terms only where the rounding matters.  Token i is
+ *          heavy if s[i,k] > 16 * mean_i s[i,k] for some k (mean over this call's n tokens);
+ *          the first 32*ceil(n/2048) heavy tokens in token order are left out of the one-term
+ *          pass and their rows run through a second, small two-term pass (further heavy
+ *          tokens, if any, stay in the one-term pass).  With heavy-tailed token weights
+ *          (squared gradients: Section 3.2) the rounding errors of those few tokens are what
+ *          makes the one-term result indefinite; this mode costs a few per cent and, on the
+ *          workloads measured, gives an H that a Cholesky factorization accepts with the
+ *          usual small diagonal constant (Section 4.2).  Deterministic like the other modes.
  *   workspace  device buffer of at least gq_fisher_gram_workspace_bytes() bytes,
  *          256-byte aligned (may be NULL when that size is 0); contents are
  *          scratch.

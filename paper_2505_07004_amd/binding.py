@@ -16,7 +16,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libgq.so")
 
 GQ_F32, GQ_BF16 = 0, 1
-GQ_ACCUMULATE, GQ_MIRROR, GQ_TWO_TERMS = 1, 2, 4
+GQ_ACCUMULATE, GQ_MIRROR, GQ_TWO_TERMS, GQ_HEAVY_TWO_TERMS = 1, 2, 4, 8
 
 _lib = None
 
@@ -167,9 +167,10 @@ def gq_fisher_gram_workspace_bytes(x_dtype: torch.dtype, n: int, d_in: int, G: i
 
 def gq_fisher_gram(X: torch.Tensor, s: torch.Tensor, H: Optional[torch.Tensor] = None,
                    accumulate: bool = False, mirror: bool = False, two_terms: bool = False,
-                   workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                   workspace: Optional[torch.Tensor] = None, heavy_two_terms: bool = False) -> torch.Tensor:
     """H[k] (+)= X^T Diag(s[:,k]) X on the upper triangle -> fp32 [G, d_in, d_in].
-    two_terms (bf16 X only): the scaled operand as two bf16 terms, twice the work, fp32-grade products."""
+    two_terms (bf16 X only): the scaled operand as two bf16 terms, twice the work, fp32-grade products.
+    heavy_two_terms (bf16 X only): two terms only for the tokens with the largest weights (GQ_HEAVY_TWO_TERMS)."""
     _require_gpu(X, s, H, workspace)
     n, d_in = X.shape
     G = int(s.shape[1])
@@ -186,7 +187,8 @@ def gq_fisher_gram(X: torch.Tensor, s: torch.Tensor, H: Optional[torch.Tensor] =
         ws_bytes = need
     else:
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    flags = (GQ_ACCUMULATE if accumulate else 0) | (GQ_MIRROR if mirror else 0) | (GQ_TWO_TERMS if two_terms else 0)
+    flags = ((GQ_ACCUMULATE if accumulate else 0) | (GQ_MIRROR if mirror else 0) | (GQ_TWO_TERMS if two_terms else 0)
+             | (GQ_HEAVY_TWO_TERMS if heavy_two_terms else 0))
     st = lib.gq_fisher_gram(X.data_ptr(), _dtype_code(X), n, d_in, _rows(X) if n > 0 else d_in,
                             s.data_ptr(), G, H.data_ptr(), flags, ws_ptr, ws_bytes, _stream())
     _check(st, "gq_fisher_gram")

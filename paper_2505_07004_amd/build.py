@@ -22,6 +22,7 @@ SOURCES = [
     "fisher_gram_f32.hip",
     "fisher_gram_bf16.hip",
     "fisher_gram_bf16_wide.hip",
+    "heavy_tokens.hip",
     "mirror.hip",
     "objective.hip",
     "cd_assign.hip", "lnq_codebook.hip", "cholesky.hip",

@@ -53,14 +53,14 @@ int gq_group_weights_strided(const void* dZ, gq_dtype dz_dtype, int64_t n, int64
 
 size_t gq_fisher_gram_workspace_bytes(gq_dtype x_dtype, int64_t n, int64_t d_in, int32_t G) {
   if (!valid_dtype((int)x_dtype) || n < 0 || d_in <= 0 || G <= 0) return 0;
-  return x_dtype == GQ_BF16 ? gq::fisher_gram_bf16_workspace(n, d_in, G) : 0;
+  return x_dtype == GQ_BF16 ? gq::fisher_gram_heavy_workspace(n, d_in, G) : 0;
 }
 
 int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int64_t ld_x, const float* s, int32_t G,
                    float* H, uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!valid_dtype((int)x_dtype)) return GQ_ERR_DTYPE;
   if (n < 0 || d_in <= 0 || G <= 0 || ld_x < d_in) return GQ_ERR_SHAPE;
-  if (flags & ~(uint32_t)(GQ_ACCUMULATE | GQ_MIRROR | GQ_TWO_TERMS)) return GQ_ERR_UNSUPPORTED;
+  if (flags & ~(uint32_t)(GQ_ACCUMULATE | GQ_MIRROR | GQ_TWO_TERMS | GQ_HEAVY_TWO_TERMS)) return GQ_ERR_UNSUPPORTED;
   if (!H) return GQ_ERR_NULLPTR;
   if (n > 0 && (!X || !s)) return GQ_ERR_NULLPTR;
   if (!aligned16(H)) return GQ_ERR_ALIGN;
@@ -77,6 +77,8 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
     if (!accumulate) e = gq::launch_zero_upper(H, d_in, G, st);
   } else if (x_dtype == GQ_F32) {
     e = gq::launch_fisher_gram_f32((const float*)X, n, d_in, ld_x, s, G, H, accumulate, st);
+  } else if ((flags & GQ_HEAVY_TWO_TERMS) && !(flags & GQ_TWO_TERMS)) {
+    e = gq::launch_fisher_gram_bf16_heavy(X, n, d_in, ld_x, s, G, H, accumulate, workspace, st);
   } else {
     e = gq::launch_fisher_gram_bf16(X, n, d_in, ld_x, s, G, H, accumulate, (flags & GQ_TWO_TERMS) != 0, workspace,
                                     false, st);

@@ -177,6 +177,13 @@ size_t fisher_gram_bf16_wide_workspace(int64_t n, int64_t d_in, int G);
 hipError_t launch_fisher_gram_bf16_wide(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                         float* H, bool accumulate, void* ws, bool no_partials, hipStream_t st);
 
+// GQ_HEAVY_TWO_TERMS: the tokens whose weight exceeds 16 times the mean weight of a group (at most
+// heavy_capacity(n) of them, in token order) are taken out of the main call and run as a second, small call
+// with the scaled operand in two bf16 terms.  The workspace is the plain one plus the gathered rows.
+int64_t heavy_capacity(int64_t n);
+size_t fisher_gram_heavy_workspace(int64_t n, int64_t d_in, int G);
+hipError_t launch_fisher_gram_bf16_heavy(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
+                                         float* H, bool accumulate, void* ws, hipStream_t st);
 hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_damp_diagonal(float* H, int64_t d_in, int G, double damp_rel, double damp_abs, hipStream_t st);

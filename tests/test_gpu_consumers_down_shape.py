@@ -1,9 +1,10 @@
 """The four consumers of H (coordinate-descent step, codebook step, Cholesky, sequential rounding) at the
 shape of workload configuration 3, the Llama-2-7B down projection: d_in = 11008 (86 blocks of 128, not a
 power of two), d_out = 4096, G = 4.  H comes from 16384 of the configuration's tokens (the consumers do not
-care how many tokens went into it) with the scaled operand carried as two bf16 terms: the one-term path
-rounds one operand of every product, which at this shape (largest eigenvalue 1700 times the mean diagonal)
-leaves H indefinite by more than the 1 % damping used here, and a factorization needs an H that is positive
+care how many tokens went into it) with the scaled operand carried as two bf16 terms for the heaviest
+tokens (GQ_HEAVY_TWO_TERMS): the one-term path rounds one operand of every product, which at this shape
+(largest eigenvalue 1700 times the mean diagonal, a few tokens carrying most of the weight) leaves H
+indefinite by more than the 1 % damping used here, and a factorization needs an H that is positive
 definite.  The fp64 checks run on sampled channels of the first and the last group.
 """
 import numpy as np
@@ -28,10 +29,10 @@ def test_consumers_of_h_at_the_llama2_7b_down_shape():
     s = gq.gq_group_weights(wl.make_dz_for(spec, DEV, n=n), G)
     H1 = gq.gq_fisher_gram(X, s, mirror=True)
     _, info1 = gq.gq_damped_cholesky(H1, 0.01, 0.0, reverse=True)
-    H = gq.gq_fisher_gram(X, s, mirror=True, two_terms=True)
+    H = gq.gq_fisher_gram(X, s, mirror=True, heavy_two_terms=True)
     torch.cuda.synchronize()
     say(f"  first non-positive pivot with the one-term H: {info1.tolist()}")
-    assert all(v > 0 for v in info1.tolist())                 # the reason for the two-term path
+    assert all(v > 0 for v in info1.tolist())                 # the reason for the second term
     del X, s, H1
     W = wl.make_w(d_out, d_in, 7, DEV)
     What0, C = wl.quantize_codebook_per_row(W, 3, return_codebook=True)

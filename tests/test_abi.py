@@ -117,6 +117,9 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_lnq_workspace_bytes(8, 8, 4, 8) >= lib.gq_cd_workspace_bytes(8, 8, 4)
     # codebook step
     lam = 1e-7
+    # no [d_out * m, d_in] intermediate and no full copy of H in three terms: the 70B down projection stays under 1 GiB
+    assert 0 < lib.gq_lnq_codebook_workspace_bytes(8192, 28672, 4, 8) < (1 << 30)
+    assert 0 < lib.gq_lnq_codebook_workspace_bytes(8192, 28672, 4, 16) < (1 << 30)
     assert lib.gq_lnq_codebook(a16, 10, 8, 8, a16, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -2   # G does not divide d_out
     assert lib.gq_lnq_codebook(a16, 8, 8, 4, a16, a16, 4, 4, lam, a16, None, P(0x1100), big, None) == -2    # pitch < width
     assert lib.gq_lnq_codebook(a16, 8, 8, 8, a16, a16, 4, 0, lam, a16, None, P(0x1100), big, None) == -2    # no grid points

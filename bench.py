@@ -101,6 +101,8 @@ def main():
                     help="also run one plain 1 GiB elementwise copy kernel (reference point for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the pure-MFMA ceiling measurement")
+    ap.add_argument("--no-xcd-calibration", action="store_true",
+                    help="leave the Gram kernel's schedule at its default (equal XCD speeds)")
     ap.add_argument("--cd-cycles", type=int, default=1,
                     help="cycles of the coordinate-descent assignment step timed after the main loop, followed by one "
                          "codebook step (0: skip both)")
@@ -174,6 +176,49 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+
+    # Schedule tuning, part of the warm-up (outside the timed region): the eight XCDs of a chip run the Gram
+    # kernel at different speeds; every call records them in its workspace, and the library cuts the left-over
+    # work accordingly once it is told.  The Gram call is timed before and after so that both figures are on
+    # record; the timed steps below run with the measured speeds unless --no-xcd-calibration is given.
+    def gram_call():
+        if chunks == 1:
+            gq.gq_fisher_gram(X, s, H=H, workspace=ws_g)
+        else:
+            c = n // chunks
+            for i in range(chunks):
+                gq.gq_fisher_gram(X[i * c:(i + 1) * c], s[i * c:(i + 1) * c], H=H, accumulate=i > 0, workspace=ws_g)
+
+    def gram_median_ms(reps=5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(reps):
+            e0.record()
+            gram_call()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return sorted(ts)[len(ts) // 2]
+
+    schedule = {"xcd_speeds": None, "note": "default schedule (equal XCD speeds)"}
+    if not args.no_xcd_calibration:
+        try:
+            default_ms = gram_median_ms()
+            acc = [0.0] * 8
+            for _ in range(3):
+                gram_call()
+                m = gq.gq_fisher_gram_measured_xcd_speeds(n // chunks, d_in, G, ws_g)
+                acc = [a + v / 3.0 for a, v in zip(acc, m)]
+            gq.gq_fisher_gram_set_xcd_speeds(acc)
+            gram_call()
+            schedule = {"xcd_speeds": acc, "fisher_gram_ms_default_schedule": default_ms,
+                        "fisher_gram_ms_with_measured_speeds": gram_median_ms(),
+                        "note": "relative XCD speeds measured during the warm-up from the records the Gram kernel leaves "
+                                "in its workspace and set with gq_fisher_gram_set_xcd_speeds; they only move the cuts "
+                                "between the runs of the left-over work items"}
+            log("schedule:", json.dumps(schedule))
+        except gq.GQError as err:                 # shapes without left-over items to cut record nothing
+            schedule = {"xcd_speeds": None, "note": f"default schedule ({err})"}
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -213,6 +258,7 @@ def main():
         "pct_of_mfma_peak": 100.0 * achieved / PEAK_BF16_TFLOPS,
         "ms_per_call": per_kernel, "ms_per_call_median": per_kernel_median, "ms_per_call_min": per_kernel_min,
         "ms_per_step_median": per_kernel_median["step"], "ms_per_step_min": per_kernel_min["step"],
+        "schedule": schedule,
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "hbm_GiB": round(props.total_memory / 2 ** 30, 1)},
         "group_weights_GBps": dz_gbs,

@@ -160,6 +160,30 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Schedule tuning of the bf16 Gram kernel (no passage of the paper: a property of the chip).  The eight
+ * XCDs of one MI355X do not run the kernel at the same speed (shared power budget, silicon spread:
+ * up to +-5 % around the mean, stable for a device), and the work items left over after the whole
+ * rounds are cut into runs of equal COST.  With relative speeds set, the runs are cut so that all
+ * workgroups finish at the same TIME instead.
+ *
+ *   gq_fisher_gram_set_xcd_speeds(speeds): host pointer to 8 floats in [0.5, 2] (relative speed of
+ *       XCD 0..7; only their ratios matter), or NULL for the default (all equal).  A setting of the
+ *       current device for the rest of the process; used by every later GQ_BF16 gq_fisher_gram /
+ *       gq_fisher_gram_noalloc call on it.  GQ_ERR_SHAPE for a value outside the range.
+ *   gq_fisher_gram_measured_xcd_speeds(n, d_in, G, workspace, speeds): every plain one-term GQ_BF16
+ *       call with G % 4 == 0 records, per workgroup, the time and the cost of its whole work items in
+ *       its workspace; this call copies those records of the LAST such call with these sizes and this
+ *       workspace to the host (it waits for the device) and writes the 8 relative speeds (mean 1) to
+ *       the host array `speeds`.  GQ_ERR_UNSUPPORTED when such a call records nothing (other group
+ *       counts, fewer than 256 work items, no left-over items) or the records are empty.
+ *
+ * The speeds decide where the runs are cut, hence the rounding of the sums: results are bit-identical
+ * for identical arguments and identical speeds, and within the documented tolerance for any speeds.
+ */
+int gq_fisher_gram_set_xcd_speeds(const float* speeds);
+int gq_fisher_gram_measured_xcd_speeds(int64_t n, int64_t d_in, int32_t G, const void* workspace, float* speeds);
+
+/*
  * gq_fisher_gram for callers that cannot allocate device memory and so cannot bring a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments (minus the workspace), same arithmetic and same results up to the order of the fp32

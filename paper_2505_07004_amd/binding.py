@@ -56,6 +56,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_fisher_gram_noalloc.restype = c.c_int
     lib.gq_fisher_gram_noalloc.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
                                            c.c_int32, c.c_void_p, c.c_uint32, c.c_void_p]
+    lib.gq_fisher_gram_set_xcd_speeds.restype = c.c_int
+    lib.gq_fisher_gram_set_xcd_speeds.argtypes = [c.c_void_p]
+    lib.gq_fisher_gram_measured_xcd_speeds.restype = c.c_int
+    lib.gq_fisher_gram_measured_xcd_speeds.argtypes = [c.c_int64, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p]
     lib.gq_fisher_gram_noalloc_max_scratch_bytes.restype = c.c_size_t
     lib.gq_fisher_gram_noalloc_max_scratch_bytes.argtypes = []
     lib.gq_fisher_mirror.restype = c.c_int
@@ -193,6 +197,27 @@ def gq_fisher_gram(X: torch.Tensor, s: torch.Tensor, H: Optional[torch.Tensor] =
                             s.data_ptr(), G, H.data_ptr(), flags, ws_ptr, ws_bytes, _stream())
     _check(st, "gq_fisher_gram")
     return H
+
+
+def gq_fisher_gram_set_xcd_speeds(speeds=None) -> None:
+    """Relative speeds of the 8 XCDs for the schedule of the bf16 Gram kernel on the current device (None: equal)."""
+    if speeds is None:
+        st = load_library().gq_fisher_gram_set_xcd_speeds(None)
+    else:
+        arr = (ctypes.c_float * 8)(*[float(v) for v in speeds])
+        st = load_library().gq_fisher_gram_set_xcd_speeds(ctypes.cast(arr, ctypes.c_void_p))
+    _check(st, "gq_fisher_gram_set_xcd_speeds")
+
+
+def gq_fisher_gram_measured_xcd_speeds(n: int, d_in: int, G: int, workspace: torch.Tensor):
+    """The relative XCD speeds recorded by the last plain one-term bf16 gq_fisher_gram call with these sizes and
+    this workspace (waits for the device); a list of 8 floats with mean 1."""
+    _require_gpu(workspace)
+    arr = (ctypes.c_float * 8)()
+    st = load_library().gq_fisher_gram_measured_xcd_speeds(n, d_in, G, workspace.data_ptr(),
+                                                           ctypes.cast(arr, ctypes.c_void_p))
+    _check(st, "gq_fisher_gram_measured_xcd_speeds")
+    return [float(v) for v in arr]
 
 
 def gq_fisher_gram_noalloc(X: torch.Tensor, s: torch.Tensor, H: torch.Tensor, accumulate: bool = False,

@@ -88,6 +88,21 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
   return from_hip(e);
 }
 
+int gq_fisher_gram_set_xcd_speeds(const float* speeds) {
+  if (speeds)
+    for (int i = 0; i < 8; ++i)
+      if (!(speeds[i] >= 0.5f && speeds[i] <= 2.0f)) return GQ_ERR_SHAPE;
+  return from_hip(gq::fisher_gram_set_xcd_speeds(speeds));
+}
+
+int gq_fisher_gram_measured_xcd_speeds(int64_t n, int64_t d_in, int32_t G, const void* workspace, float* speeds) {
+  if (n <= 0 || d_in <= 0 || G <= 0) return GQ_ERR_SHAPE;
+  if (!workspace || !speeds) return GQ_ERR_NULLPTR;
+  const hipError_t e = gq::fisher_gram_measured_xcd_speeds(n, d_in, G, workspace, speeds);
+  if (e == hipErrorInvalidValue) return GQ_ERR_UNSUPPORTED;
+  return from_hip(e);
+}
+
 int gq_fisher_mirror(float* H, int64_t d_in, int32_t G, void* hip_stream) {
   if (d_in <= 0 || G <= 0) return GQ_ERR_SHAPE;
   if (!H) return GQ_ERR_NULLPTR;

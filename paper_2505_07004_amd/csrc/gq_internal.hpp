@@ -184,6 +184,10 @@ int64_t heavy_capacity(int64_t n);
 size_t fisher_gram_heavy_workspace(int64_t n, int64_t d_in, int G);
 hipError_t launch_fisher_gram_bf16_heavy(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                          float* H, bool accumulate, void* ws, hipStream_t st);
+// Relative speeds of the eight XCDs for the schedule of the wide Gram kernel (nullptr: all equal), a setting of
+// the current device; and the speeds measured by the last plain one-term call that used workspace `ws`.
+hipError_t fisher_gram_set_xcd_speeds(const float* a8);
+hipError_t fisher_gram_measured_xcd_speeds(int64_t n, int64_t d_in, int G, const void* ws, float* a8);
 hipError_t launch_zero_upper(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_mirror(float* H, int64_t d_in, int G, hipStream_t st);
 hipError_t launch_damp_diagonal(float* H, int64_t d_in, int G, double damp_rel, double damp_abs, hipStream_t st);

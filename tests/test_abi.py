@@ -115,6 +115,11 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_lnq(a16, P(0x2000), a16, a16, 17, 8, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), big, None) == -7
     assert lib.gq_lnq(a16, P(0x2000), a16, a16, 8, 8, 8, 8, a16, 4, 2, 4, 1e-7, P(0x1100), 16, None) == -5
     assert lib.gq_lnq_workspace_bytes(8, 8, 4, 8) >= lib.gq_cd_workspace_bytes(8, 8, 4)
+    # schedule tuning of the Gram kernel: argument checks come before any HIP call
+    bad = (ctypes.c_float * 8)(1, 1, 1, 1, 1, 1, 1, 3.0)
+    assert lib.gq_fisher_gram_set_xcd_speeds(ctypes.cast(bad, ctypes.c_void_p)) == -2
+    assert lib.gq_fisher_gram_measured_xcd_speeds(1024, 4096, 4, None, ctypes.cast(bad, ctypes.c_void_p)) == -1
+    assert lib.gq_fisher_gram_measured_xcd_speeds(0, 4096, 4, a16, ctypes.cast(bad, ctypes.c_void_p)) == -2
     # codebook step
     lam = 1e-7
     # no [d_out * m, d_in] intermediate and no full copy of H in three terms: the 70B down projection stays under 1 GiB

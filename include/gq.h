@@ -317,6 +317,9 @@ size_t gq_cholesky_workspace_bytes(int64_t d_in, int32_t G);
  *
  * The paper leaves the constant open; the relative form is the convention of the GPTQ line
  * of work it cites (1 % of the mean diagonal).
+ * Part of the work is enqueued on a second stream that the library keeps per device (created on
+ * the first call: that call allocates a stream and three events) and is joined back into
+ * `hip_stream` before the call returns; to the caller everything is ordered on `hip_stream`.
  * Errors: GQ_ERR_NULLPTR, GQ_ERR_SHAPE (d_in <= 0, G <= 0, a damping constant negative or
  * NaN, F == H), GQ_ERR_UNSUPPORTED (unknown flag), GQ_ERR_ALIGN (H or F not 16-byte aligned),
  * GQ_ERR_WORKSPACE, GQ_ERR_HIP.

@@ -14,6 +14,8 @@
 // accuracy (U12 as three bf16 terms, six products).
 // Only the upper triangle of H is read.  A non-positive pivot is recorded in info[k] (its
 // coordinate + 1, the first one) and replaced by 1 so that everything stays finite.
+#include <mutex>
+
 #include "gq_internal.hpp"
 
 namespace gq {
@@ -43,12 +45,13 @@ __global__ __launch_bounds__(256) void chol_eps_kernel(const float* __restrict__
   }
 }
 
-// Working matrix, upper triangle: Uw[r][c] = A'[r][c] for r <= c.  One workgroup per 64 x 64 tile.
+// Working matrix, upper triangle: Uw[r][c] = A'[r][c] for r <= c.  One workgroup per 64 x 64 tile; the grid's
+// y range selects the tile rows by0, by0 + 1, ...
 __global__ __launch_bounds__(256) void chol_load_kernel(const float* __restrict__ H, int64_t d, int reverse,
-                                                        const double* __restrict__ eps, float* __restrict__ Uw) {
+                                                        const double* __restrict__ eps, float* __restrict__ Uw, int by0) {
   __shared__ float tile[64][65];
   const int k = blockIdx.z;
-  const int by = blockIdx.y, bx = blockIdx.x;              // tile of rows r, of columns c
+  const int by = by0 + blockIdx.y, bx = blockIdx.x;        // tile of rows r (from tile row by0 on), of columns c
   if (by > bx) return;
   const float* Hk = H + (int64_t)k * d * d;
   float* Uk = Uw + (int64_t)k * d * d;
@@ -564,14 +567,17 @@ __global__ __launch_bounds__(256) void chol_syrk2_kernel(float* __restrict__ Uw,
 
 // The factor in the requested form, every entry of F written: L[i][j] = U[j][i] (i >= j), zeros above
 // the diagonal; or R[i][j] = U[d-1-j][d-1-i] (i <= j), zeros below.  One workgroup per 64 x 64 tile of F.
+// A launch writes the columns [j_lo, j_hi) of F (a column of F is a row of U, so finished block rows can
+// leave while later ones are still being factored); blockIdx.x counts tile columns from j_lo / 64.
 __global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict__ Uw, const float* __restrict__ Ud,
-                                                        int64_t d, int reverse, float* __restrict__ F) {
+                                                        int64_t d, int reverse, float* __restrict__ F, int64_t j_lo,
+                                                        int64_t j_hi) {
   __shared__ float tile[64][65];
   const int k = blockIdx.z;
   const float* Uk = Uw + (int64_t)k * d * d;
   float* Fk = F + (int64_t)k * d * d;
   const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
-  const int64_t i0 = (int64_t)blockIdx.y * 64, j0 = (int64_t)blockIdx.x * 64;   // tile of F: rows i, columns j
+  const int64_t i0 = (int64_t)blockIdx.y * 64, j0 = (j_lo / 64 + (int64_t)blockIdx.x) * 64;   // tile of F: rows i, columns j
   // source entry of F[i0+li][j0+lj]:  U[sr][sc], sr = j (or d-1-j), sc = i (or d-1-i); tile[lj][li]
   for (int lj = ty; lj < 64; lj += 4) {
     const int64_t j = j0 + lj, i = i0 + tx;
@@ -587,7 +593,7 @@ __global__ __launch_bounds__(256) void chol_emit_kernel(const float* __restrict_
   __syncthreads();
   for (int li = ty; li < 64; li += 4) {
     const int64_t i = i0 + li, j = j0 + tx;
-    if (i < d && j < d) Fk[i * d + j] = tile[tx][li];
+    if (i < d && j >= j_lo && j < j_hi) Fk[i * d + j] = tile[tx][li];
   }
 }
 
@@ -606,59 +612,163 @@ Layout make_layout(int64_t d, int G) {
   return L;
 }
 
+// A second stream and a few events per device, created on first use and kept for the life of the process
+// (see the order of work below).  Calls are enqueued under the mutex, so the record / wait pairs of one
+// call never interleave with another's.
+constexpr int kMaxDevices = 64;
+struct Aux {
+  hipStream_t side = nullptr;
+  hipEvent_t fork = nullptr, strip_done = nullptr, rest_done = nullptr;
+};
+std::mutex g_aux_mutex;
+Aux g_aux[kMaxDevices];
+
+hipError_t aux_of_current_device(Aux** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  Aux& a = g_aux[dev];
+  if (!a.side) {
+    if ((e = hipStreamCreateWithFlags(&a.side, hipStreamNonBlocking)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&a.fork, hipEventDisableTiming)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&a.strip_done, hipEventDisableTiming)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&a.rest_done, hipEventDisableTiming)) != hipSuccess) return e;
+  }
+  *out = &a;
+  return hipSuccess;
+}
+
 }  // namespace
 
 size_t cholesky_workspace(int64_t d, int G) {
   const Layout L = make_layout(d, G);
-  return L.u_bytes + L.ud_bytes + L.p3_bytes + L.eps_bytes;
+  return L.u_bytes + L.ud_bytes + 2 * L.p3_bytes + L.eps_bytes;
 }
 
+// Order of work.  Block rows go in pairs (r0, t0 = r0 + 128); t1 = r0 + 256 is the next pair's first.  The
+// chain that nothing can shorten runs on the caller's stream:
+//   factor r0 -> strip of t0 (128 rows of U) -> factor t0 -> strip of t1 (the pair's 256 rows) -> factor t1 -> ...
+// (a block row can be factored once every earlier block row has been subtracted from it).  Everything else runs
+// beside it on a second stream, forked after "factor t0":
+//   the pair's update of block row t1 + 128        needed before the next pair's "strip of t0"     (strip_done)
+//   the pair's update of all rows from t1 + 256 on  needed before the next pair's "strip of t1"     (rest_done)
+//   the pair's finished rows of U leave for F       needed at the end
+// and, before the first pair, the load of everything but the first block row (the first pair treats it like a
+// previous pair's update).  The two pairs in flight write their panels (three bf16 terms) to alternating buffers.
 hipError_t launch_damped_cholesky(const float* H, int64_t d, int G, double damp_rel, double damp_abs, bool reverse,
                                   float* F, int* info, void* ws, hipStream_t st) {
   const Layout L = make_layout(d, G);
   float* Uw = (float*)ws;
   float* Ud = (float*)((char*)ws + L.u_bytes);
-  unsigned short* P3 = (unsigned short*)((char*)ws + L.u_bytes + L.ud_bytes);
-  double* eps = (double*)((char*)ws + L.u_bytes + L.ud_bytes + L.p3_bytes);
-  hipError_t e;
+  unsigned short* P3buf[2] = {(unsigned short*)((char*)ws + L.u_bytes + L.ud_bytes),
+                              (unsigned short*)((char*)ws + L.u_bytes + L.ud_bytes + L.p3_bytes)};
+  double* eps = (double*)((char*)ws + L.u_bytes + L.ud_bytes + 2 * L.p3_bytes);
+  std::lock_guard<std::mutex> lock(g_aux_mutex);
+  Aux* aux = nullptr;
+  hipError_t e = aux_of_current_device(&aux);
+  if (e != hipSuccess) return e;
+  hipStream_t side = aux->side;
+  const unsigned t64 = (unsigned)((d + 63) / 64);
+  const int rev = reverse ? 1 : 0;
+  bool wait_strip = false, wait_rest = false;                 // work on the second stream that this stream has not waited for yet
+  auto fork = [&]() -> hipError_t {
+    hipError_t f = hipEventRecord(aux->fork, st);
+    return f != hipSuccess ? f : hipStreamWaitEvent(side, aux->fork, 0);
+  };
+  auto join_strip = [&]() -> hipError_t {
+    if (!wait_strip) return hipSuccess;
+    wait_strip = false;
+    return hipStreamWaitEvent(st, aux->strip_done, 0);
+  };
+  auto join_rest = [&]() -> hipError_t {
+    if (!wait_rest) return hipSuccess;
+    wait_rest = false;
+    return hipStreamWaitEvent(st, aux->rest_done, 0);
+  };
+  // the columns of F that hold the rows [u_lo, u_hi) of U
+  auto emit = [&](int64_t u_lo, int64_t u_hi, hipStream_t s) -> hipError_t {
+    if (u_hi > d) u_hi = d;
+    if (u_hi <= u_lo) return hipSuccess;
+    const int64_t j_lo = reverse ? d - u_hi : u_lo, j_hi = reverse ? d - u_lo : u_hi;
+    const unsigned cols = (unsigned)((j_hi - 1) / 64 - j_lo / 64 + 1);
+    chol_emit_kernel<<<dim3(cols, t64, (unsigned)G), dim3(256), 0, s>>>(Uw, Ud, d, rev, F, j_lo, j_hi);
+    return hipGetLastError();
+  };
+
   chol_eps_kernel<<<dim3((unsigned)G), dim3(256), 0, st>>>(H, d, damp_rel, damp_abs, eps, info);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const unsigned t64 = (unsigned)((d + 63) / 64);
-  chol_load_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d, reverse ? 1 : 0, eps, Uw);
+  const unsigned first_tiles = t64 < 2 ? t64 : 2;             // the first block row: two tile rows of 64
+  chol_load_kernel<<<dim3(t64, first_tiles, (unsigned)G), dim3(256), 0, st>>>(H, d, rev, eps, Uw, 0);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (t64 > first_tiles) {
+    if ((e = fork()) != hipSuccess) return e;
+    chol_load_kernel<<<dim3(t64, t64 - first_tiles, (unsigned)G), dim3(256), 0, side>>>(H, d, rev, eps, Uw, (int)first_tiles);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = hipEventRecord(aux->strip_done, side)) != hipSuccess) return e;
+    if ((e = hipEventRecord(aux->rest_done, side)) != hipSuccess) return e;
+    wait_strip = wait_rest = true;
+  }
   // one block row: its diagonal block and, if there is anything to its right, the panel
-  auto block_row = [&](int64_t r0, int koff) -> hipError_t {
+  auto block_row = [&](int64_t r0, int koff, unsigned short* P3) -> hipError_t {
     const int64_t trail = d - (r0 + kNb);
     const int64_t tt = trail > 0 ? (trail + kNb - 1) / kNb : 0;
     chol_block_row_kernel<<<dim3((unsigned)(tt > 0 ? tt : 1), (unsigned)G), dim3(tt > 0 ? 512 : 256), 0, st>>>(
         Uw, d, r0, Ud, P3, L.ldc, koff, info);
     return hipGetLastError();
   };
-  for (int64_t r0 = 0; r0 < d; r0 += 2 * kNb) {              // a pair of block rows per turn
-    if ((e = block_row(r0, 0)) != hipSuccess) return e;
+  int64_t emitted = 0;                                        // rows of U already on their way to F
+  int pair = 0;
+  for (int64_t r0 = 0; r0 < d; r0 += 2 * kNb, ++pair) {
+    unsigned short* P3 = P3buf[pair % 2];
+    if ((e = block_row(r0, 0, P3)) != hipSuccess) return e;
     const int64_t t0 = r0 + kNb, trail = d - t0;
     if (trail <= 0) break;
+    if ((e = join_strip()) != hipSuccess) return e;           // block row t0 has everything from before this pair
     const int64_t tt = (trail + kNb - 1) / kNb;
     chol_syrk_kernel<<<dim3((unsigned)tt, (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kNb, t0, 1);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = block_row(t0, kNb)) != hipSuccess) return e;
+    if ((e = block_row(t0, kNb, P3)) != hipSuccess) return e;
     const int64_t t1 = t0 + kNb, trail1 = d - t1;
     if (trail1 <= 0) break;
     const int64_t tt1 = (trail1 + kNb - 1) / kNb;
-    // Large trailing matrices take the 256 x 128 tiles (less operand traffic per product); small ones, where
-    // a launch is only a few rounds of workgroups, the 128 x 128 tiles (twice as many, shorter workgroups).
-    // Measured cross-over on MI355X: about 3000 workgroups of the smaller kind.
-    if (tri_count(tt1) * G >= 3000) {
-      int64_t n_tiles2 = 0;                                   // tile row p has tt1 - 2p tiles
-      for (int64_t p = 0; 2 * p < tt1; ++p) n_tiles2 += tt1 - 2 * p;
-      chol_syrk2_kernel<<<dim3((unsigned)n_tiles2, (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, (int)tt1);
-    } else {
-      chol_syrk_kernel<<<dim3((unsigned)tri_count(tt1), (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, 0);
+    // (waited for here, before this pair's events are recorded: a wait refers to the latest record)
+    if ((e = join_rest()) != hipSuccess) return e;            // the previous pair's update of block row t1 (and beyond) is in
+    // ---- second stream: the pair's updates from block row t1 + 128 on, then its finished rows to F
+    if ((e = fork()) != hipSuccess) return e;
+    if (tt1 > 1) {
+      const int64_t t2 = t1 + kNb;
+      chol_syrk_kernel<<<dim3((unsigned)(tt1 - 1), (unsigned)G), dim3(256), 0, side>>>(Uw, d, P3, L.ldc, kPair, t2, 1);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      if ((e = hipEventRecord(aux->strip_done, side)) != hipSuccess) return e;
+      wait_strip = true;
     }
+    if (tt1 > 2) {
+      const int64_t t3 = t1 + 2 * kNb, tt3 = tt1 - 2;
+      // Large trailing matrices take the 256 x 128 tiles (less operand traffic per product); small ones, where
+      // a launch is only a few rounds of workgroups, the 128 x 128 tiles (twice as many, shorter workgroups).
+      // Measured cross-over on MI355X: about 3000 workgroups of the smaller kind.
+      if (tri_count(tt3) * G >= 3000) {
+        int64_t n_tiles2 = 0;                                 // tile row p has tt3 - 2p tiles
+        for (int64_t p = 0; 2 * p < tt3; ++p) n_tiles2 += tt3 - 2 * p;
+        chol_syrk2_kernel<<<dim3((unsigned)n_tiles2, (unsigned)G), dim3(256), 0, side>>>(Uw, d, P3, L.ldc, kPair, t3, (int)tt3);
+      } else {
+        chol_syrk_kernel<<<dim3((unsigned)tri_count(tt3), (unsigned)G), dim3(256), 0, side>>>(Uw, d, P3, L.ldc, kPair, t3, 0);
+      }
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      if ((e = hipEventRecord(aux->rest_done, side)) != hipSuccess) return e;
+      wait_rest = true;
+    }
+    if ((e = emit(emitted, t1, side)) != hipSuccess) return e;
+    emitted = t1;
+    // ---- this stream: the strip of the next pair's first block row, with the 256 rows of this pair at once
+    chol_syrk_kernel<<<dim3((unsigned)tt1, (unsigned)G), dim3(256), 0, st>>>(Uw, d, P3, L.ldc, kPair, t1, 1);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  chol_emit_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(Uw, Ud, d, reverse ? 1 : 0, F);
-  return hipGetLastError();
+  // the rows of U not yet sent to F, and nothing of this call may outlive the caller's stream
+  if ((e = emit(emitted, d, st)) != hipSuccess) return e;
+  if ((e = hipEventRecord(aux->rest_done, side)) != hipSuccess) return e;
+  return hipStreamWaitEvent(st, aux->rest_done, 0);
 }
 
 }  // namespace gq

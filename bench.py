@@ -211,8 +211,13 @@ def main():
                 acc = [a + v / 3.0 for a, v in zip(acc, m)]
             gq.gq_fisher_gram_set_xcd_speeds(acc)
             gram_call()
-            schedule = {"xcd_speeds": acc, "fisher_gram_ms_default_schedule": default_ms,
-                        "fisher_gram_ms_with_measured_speeds": gram_median_ms(),
+            tuned_ms = gram_median_ms()
+            if tuned_ms > default_ms:             # speeds that do not hold from call to call: keep the default schedule
+                gq.gq_fisher_gram_set_xcd_speeds(None)
+                gram_call()
+            schedule = {"xcd_speeds": acc if tuned_ms <= default_ms else None, "measured_xcd_speeds": acc,
+                        "fisher_gram_ms_default_schedule": default_ms,
+                        "fisher_gram_ms_with_measured_speeds": tuned_ms,
                         "note": "relative XCD speeds measured during the warm-up from the records the Gram kernel leaves "
                                 "in its workspace and set with gq_fisher_gram_set_xcd_speeds; they only move the cuts "
                                 "between the runs of the left-over work items"}

@@ -165,7 +165,7 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
                                                              const float* __restrict__ W, const float* __restrict__ What,
                                                              int64_t d_out, int64_t d, int64_t ld, int64_t ldp, int G,
                                                              int n_pairs, int n_rb2, int chunk, int n_slots,
-                                                             float* __restrict__ partial) {
+                                                             int deal, float* __restrict__ partial) {
   __shared__ __attribute__((aligned(1024))) char smem[kStages * kStageBytes];
   // (the row-sum exchange at the end reuses the staging memory, after a barrier)
 
@@ -175,14 +175,20 @@ __global__ __launch_bounds__(512) void objective_mfma_kernel(const unsigned shor
   // first): the workgroups resident on an XCD then share both their H tiles and their delta
   // tiles through its L2.
   // The contraction of pair P (P + 1 pair blocks of 16 stages) is cut into slots of at most
-  // `chunk` pair blocks, so that small problems still give every CU several workgroups of
-  // similar length; slot 0 is the last (diagonal) part of the heaviest pair.
+  // `chunk` pair blocks: workgroups of similar length keep pace with their neighbours (and keep
+  // sharing tiles), and small problems still give every CU several workgroups; slot 0 is the
+  // last (diagonal) part of the heaviest pair.
   int k, sl, rb2;
   {
-    constexpr int kXcd = 8;
+    constexpr int kXcd = 8, kDeal = kOrderP * kOrderR;      // 32: what the 32 CUs of an XCD run at a time
     const int64_t total = gridDim.x, id = blockIdx.x;
     const int64_t x = id % kXcd, idx = id / kXcd, q = total / kXcd, r = total % kXcd;
-    const int64_t logical = x * q + (x < r ? x : r) + idx;
+    // Large grids (`deal`): stretches of 32 consecutive workgroups of the logical order go to the XCDs in
+    // turn; the order is heavy first, so every XCD gets the same share of the work and runs one stretch
+    // (one block of pairs x row blocks) at a time.  Small grids: one contiguous stretch per XCD.
+    const int64_t dealt = total / (kXcd * kDeal) * (kXcd * kDeal);
+    const int64_t logical = !deal ? x * q + (x < r ? x : r) + idx
+                                  : (id < dealt ? ((idx / kDeal) * kXcd + x) * kDeal + idx % kDeal : id);
     const int64_t per_group = (int64_t)n_slots * n_rb2;
     k = (int)(logical / per_group);
     int64_t rem = logical - (int64_t)k * per_group;
@@ -458,7 +464,7 @@ __global__ void objective_groups_kernel(const double* __restrict__ block_sum, in
 
 struct Layout {
   int64_t ldp, n_pairs, n_rb2;
-  int chunk, n_slots;                           // pair blocks per workgroup, workgroups per (group, row block)
+  int chunk, n_slots, deal;                     // pair blocks per workgroup, workgroups per (group, row block), XCD mapping
   int64_t n_blocks;                             // 256-row blocks per group in the final reduction
   size_t partial_bytes, sums_bytes, delta_bytes, h_bytes;   // delta_bytes / h_bytes: one of the hi/lo arrays
 };
@@ -467,9 +473,22 @@ Layout make_layout(int64_t d_out, int64_t d_in, int G) {
   L.n_pairs = (d_in + 2 * kTile - 1) / (2 * kTile);
   L.ldp = L.n_pairs * 2 * kTile;                // contraction length padded to whole tile pairs
   L.n_rb2 = (d_out / G + 2 * kTile - 1) / (2 * kTile);
-  // cut the heavy pairs while the grid would give a CU fewer than ~4 workgroups
-  L.chunk = (int)L.n_pairs;
-  while (L.chunk > 2 && L.n_pairs * L.n_rb2 * G * (L.n_pairs / L.chunk) < 1024) L.chunk = (L.chunk + 1) / 2;
+  // Slots of at most `chunk` pair blocks (measured on MI355X over the 7B ... 70B shapes, chunk 1 ... 32, both
+  // mappings): grids of a thousand workgroups and more run fastest with 12 and stretches dealt to the XCDs in
+  // turn (the order is heavy first; a contiguous eighth per XCD leaves the XCD with the heavy pairs up to 30 %
+  // behind); small grids (a few workgroups per CU) with three tenths of the pairs per slot and one contiguous
+  // stretch per XCD.
+  auto slots_with = [&](int64_t c) {
+    int64_t n = 0;
+    for (int64_t P = 0; P < L.n_pairs; ++P) n += (P + c) / c;
+    return n;
+  };
+  L.chunk = (int)(L.n_pairs < 12 ? L.n_pairs : 12);
+  L.deal = slots_with(L.chunk) * L.n_rb2 * G >= 1024 ? 1 : 0;
+  if (!L.deal) {
+    L.chunk = (int)((3 * L.n_pairs + 9) / 10);
+    if (L.chunk < 2) L.chunk = (int)(L.n_pairs < 2 ? L.n_pairs : 2);
+  }
   L.n_slots = 0;
   for (int64_t P = 0; P < L.n_pairs; ++P) L.n_slots += (int)((P + L.chunk) / L.chunk);
   L.partial_bytes = ((size_t)((int64_t)L.n_slots * d_out) * sizeof(float) + 255) / 256 * 256;
@@ -512,7 +531,7 @@ hipError_t launch_objective(const float* W, const float* What, int64_t d_out, in
   split_h_kernel<<<dim3((unsigned)(8 * tri_count(n_pairs)), (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, n_st, Hh, Hl);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   objective_mfma_kernel<<<dim3((unsigned)((int64_t)L.n_slots * n_rb2 * G)), dim3(512), 0, st>>>(
-      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_pairs, n_rb2, L.chunk, L.n_slots, partial);
+      Dh, Dl, Hh, Hl, W, What, d_out, d_in, ld, L.ldp, G, n_pairs, n_rb2, L.chunk, L.n_slots, L.deal, partial);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   objective_rows_kernel<<<dim3((unsigned)L.n_blocks, (unsigned)G), dim3(256), 0, st>>>(partial, d_out, G, L.n_slots, obj_row,
                                                                                        block_sum);

@@ -11,9 +11,10 @@
 // one-hot operand never exists in memory: every lane builds its fragment from eight code bytes
 // with a few integer operations, so only H travels from L2 to LDS.  T never exists in memory
 // either: a workgroup bins every 256 x 128 tile of it into its share of A and b while the
-// tile is still on chip (through LDS, one thread per half row, fixed order) and carries the
-// bins over the column tiles it works through; what leaves the kernel is one partial
-// [m][m + 1] system per channel and chunk of column tiles.  A second kernel adds the partial
+// tile is still on chip (through LDS; A by one more one-hot product on the matrix cores, b by
+// a plain dot, both in a fixed order) and carries the sums over the column tiles it works
+// through; what leaves the kernel is one partial [m][m + 1] system per channel and chunk of
+// column tiles.  A second kernel adds the partial
 // systems in chunk order and solves the m x m system in fp64 by Gauss-Jordan elimination
 // with partial pivoting.
 #include "gq_internal.hpp"

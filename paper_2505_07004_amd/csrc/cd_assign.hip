@@ -773,7 +773,7 @@ namespace {
 // feedback coefficients of the factor R passed as H (What out only).
 hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
                       int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q, void* ws,
-                      hipStream_t st) {
+                      bool prep_done, hipStream_t st) {
   const Layout L = make_layout(d_out, d_in, G);
   char* p = (char*)ws;
   unsigned short* Hth = (unsigned short*)p;                 // hi and lo halves interleaved per row and stage
@@ -788,9 +788,10 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
 
   hipError_t e;
   const unsigned t64 = (unsigned)(L.ldp / 64);
+  // (prep_done: an earlier call with the same H and this workspace has left the split coefficients in place)
   if (ldlq)
     ldlq_prep_kernel<<<dim3(t64, t64, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
-  else
+  else if (!prep_done)
     cd_prep_kernel<<<dim3(t64 * (t64 + 1) / 2, 1, (unsigned)G), dim3(256), 0, st>>>(H, d_in, L.ldp, Hth, Htl, Cd);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
@@ -838,14 +839,14 @@ hipError_t run_assign(bool ldlq, const float* W, float* What, const float* codeb
 
 hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
                             int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q,
-                            void* ws, hipStream_t st) {
-  return run_assign(false, W, What, codebook, n_levels, d_out, d_in, ld, H, G, n_cycles, Q, ws, st);
+                            void* ws, bool prep_done, hipStream_t st) {
+  return run_assign(false, W, What, codebook, n_levels, d_out, d_in, ld, H, G, n_cycles, Q, ws, prep_done, st);
 }
 
 hipError_t launch_ldlq_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
                               int64_t d_in, int64_t ld, const float* R, int G, unsigned char* Q, void* ws,
                               hipStream_t st) {
-  return run_assign(true, W, What, codebook, n_levels, d_out, d_in, ld, R, G, 1, Q, ws, st);
+  return run_assign(true, W, What, codebook, n_levels, d_out, d_in, ld, R, G, 1, Q, ws, false, st);
 }
 
 }  // namespace gq

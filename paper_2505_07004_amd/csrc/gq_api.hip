@@ -148,7 +148,7 @@ int gq_cd_assign(const float* W, float* What, const float* codebook, int32_t n_l
   const size_t need = gq_cd_workspace_bytes(d_out, d_in, G);
   if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
   if (n_cycles == 0) return GQ_OK;
-  return from_hip(gq::launch_cd_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, H, G, n_cycles, Q, workspace,
+  return from_hip(gq::launch_cd_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, H, G, n_cycles, Q, workspace, false,
                                        (hipStream_t)hip_stream));
 }
 
@@ -200,14 +200,20 @@ int gq_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld_w, c
     return GQ_ERR_ALIGN;
   const size_t need = gq_lnq_codebook_workspace_bytes(d_out, d_in, G, n_levels);
   if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
-  return from_hip(gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, workspace,
+  return from_hip(gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, workspace, false,
                                           (hipStream_t)hip_stream));
+}
+
+// gq_lnq keeps the two steps' preparations of H (split coefficients of the CD step, the three bf16 terms of
+// the codebook step) side by side, so that only the first round of the alternation builds them.
+static size_t lnq_cd_part(int64_t d_out, int64_t d_in, int32_t G) {
+  return (gq_cd_workspace_bytes(d_out, d_in, G) + 255) / 256 * 256;
 }
 
 size_t gq_lnq_workspace_bytes(int64_t d_out, int64_t d_in, int32_t G, int32_t n_levels) {
   const size_t a = gq_cd_workspace_bytes(d_out, d_in, G), b = gq_lnq_codebook_workspace_bytes(d_out, d_in, G, n_levels);
   if (a == 0 || b == 0) return 0;
-  return a > b ? a : b;
+  return lnq_cd_part(d_out, d_in, G) + b;
 }
 
 int gq_lnq(const float* W, float* What, uint8_t* Q, float* codebook, int32_t n_levels, int64_t d_out, int64_t d_in,
@@ -223,14 +229,16 @@ int gq_lnq(const float* W, float* What, uint8_t* Q, float* codebook, int32_t n_l
   const size_t need = gq_lnq_workspace_bytes(d_out, d_in, G, n_levels);
   if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
+  void* ws_cd = workspace;
+  void* ws_cb = (char*)workspace + lnq_cd_part(d_out, d_in, G);
   hipError_t e = hipSuccess;
   for (int t = 0; t < n_iters && e == hipSuccess; ++t) {
-    e = gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, workspace, st);
+    e = gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, ws_cb, t > 0, st);
     if (e == hipSuccess && n_cycles > 0)
-      e = gq::launch_cd_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, H, G, n_cycles, Q, workspace, st);
+      e = gq::launch_cd_assign(W, What, codebook, n_levels, d_out, d_in, ld_w, H, G, n_cycles, Q, ws_cd, t > 0, st);
   }
   if (e == hipSuccess)
-    e = gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, workspace, st);
+    e = gq::launch_lnq_codebook(W, d_out, d_in, ld_w, Q, H, G, n_levels, lam, codebook, What, ws_cb, n_iters > 0, st);
   return from_hip(e);
 }
 

@@ -199,7 +199,7 @@ size_t objective_workspace(int64_t d_out, int64_t d_in, int G);
 
 hipError_t launch_cd_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
                             int64_t d_in, int64_t ld, const float* H, int G, int n_cycles, unsigned char* Q,
-                            void* ws, hipStream_t st);
+                            void* ws, bool prep_done, hipStream_t st);
 size_t cd_workspace(int64_t d_out, int64_t d_in, int G);
 hipError_t launch_ldlq_assign(const float* W, float* What, const float* codebook, int n_levels, int64_t d_out,
                               int64_t d_in, int64_t ld, const float* R, int G, unsigned char* Q, void* ws,
@@ -211,7 +211,7 @@ size_t cholesky_workspace(int64_t d, int G);
 
 hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld, const unsigned char* Q,
                                const float* H, int G, int n_levels, double lam, float* codebook, float* What,
-                               void* ws, hipStream_t st);
+                               void* ws, bool splits_done, hipStream_t st);
 size_t lnq_codebook_workspace(int64_t d_out, int64_t d_in, int G, int n_levels);
 
 }  // namespace gq

@@ -511,8 +511,11 @@ size_t lnq_codebook_workspace(int64_t d_out, int64_t d_in, int G, int n_levels) 
 
 hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int64_t ld, const unsigned char* Q,
                                const float* H, int G, int n_levels, double lam, float* codebook, float* What,
-                               void* ws, hipStream_t st) {
+                               void* ws, bool splits_done, hipStream_t st) {
   const Layout L = make_layout(d_out, d_in, G, n_levels);
+  // splits_done: an earlier call with the same H and this workspace has left the three terms of H in place
+  // (they survive a call only when one pass holds all of them)
+  const bool keep_splits = splits_done && L.groups_per_pass == G && L.pass_cts == L.n_ct;
   char* p = (char*)ws;
   unsigned short* Hh = (unsigned short*)p;
   p += L.h_bytes;
@@ -535,9 +538,11 @@ hipError_t launch_lnq_codebook(const float* W, int64_t d_out, int64_t d_in, int6
     for (int ct0 = 0; ct0 < L.n_ct; ct0 += L.pass_cts) {
       const int n_ct = ct0 + L.pass_cts <= L.n_ct ? L.pass_cts : L.n_ct - ct0;
       const int n_chunks = (n_ct + L.cts_per - 1) / L.cts_per;
-      lnq_split_h_kernel<<<dim3((unsigned)(L.ldp / 64), (unsigned)(n_ct * (kCols / 64)), (unsigned)L.groups_per_pass),
-                           dim3(256), 0, st>>>(H, d_in, L.ldp, k0, (int64_t)ct0 * kCols, L.pass_rows, Hh, Hm, Hl);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
+      if (!keep_splits) {
+        lnq_split_h_kernel<<<dim3((unsigned)(L.ldp / 64), (unsigned)(n_ct * (kCols / 64)), (unsigned)L.groups_per_pass),
+                             dim3(256), 0, st>>>(H, d_in, L.ldp, k0, (int64_t)ct0 * kCols, L.pass_rows, Hh, Hm, Hl);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
       const int64_t n_blocks = (int64_t)L.n_rt * L.groups_per_pass * n_chunks;
       const int64_t grid = (n_blocks + 7) / 8 * 8;
       if (grid > 0x7fffffff) return hipErrorInvalidValue;

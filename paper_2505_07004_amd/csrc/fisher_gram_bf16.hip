@@ -645,7 +645,7 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
   if (n <= 0) return 0;
   const Plan pl = make_plan(n, d_in, G);
   size_t need = pl.sp_bytes + pl.partial_bytes;
-  if (fisher_gram_bf16_wide_applies(n, G, false)) {      // the flags are not known here: enough for either kernel
+  if (fisher_gram_bf16_wide_chosen(n, d_in, G, false)) {      // the flags are not known here: enough for either kernel
     const size_t wide = fisher_gram_bf16_wide_workspace(n, d_in, G);
     if (wide > need) need = wide;
   }
@@ -654,7 +654,7 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                    float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st) {
-  if (fisher_gram_bf16_wide_applies(n, G, two_terms))
+  if (fisher_gram_bf16_wide_chosen(n, d_in, G, two_terms))
     return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, no_partials, st);
   Plan pl = make_plan(n, d_in, G);
   float* sp = (float*)ws;

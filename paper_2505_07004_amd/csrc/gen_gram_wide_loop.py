@@ -20,6 +20,12 @@ What the statement does, for one run of token steps [k0, k0 + count) of one work
   * LDS waits (`lgkmcnt`) are derived here from the issue order by a small scoreboard.
 The first sub-step starts the accumulators from the constant 0, so no register is cleared.
 
+Two variants are generated.  fisher_gram_bf16_wide_loop.inc: a workgroup's four waves are four groups on one
+row block of 96 rows (group counts divisible by 4).  fisher_gram_bf16_wide2_loop.inc: two groups on two row
+blocks (even group counts): the stage holds two tiles of the scaled operand (its lane address is what tells a
+wave's tile), so a stage is 6 KiB larger, the ring has five stages instead of six and a wave issues eight direct
+loads per stage, the last one the weights.  The statements are otherwise the same.
+
 Run by build.py before compiling; the output is committed next to this file.
 """
 import os
@@ -29,6 +35,18 @@ NS = 6                  # ring stages
 LOADS = 6               # direct loads per wave and stage
 STAGE = 23552           # bytes per ring stage: A 6144 + B 16384 + weights 1024
 A_ROW, B_ROW = 192, 512  # bytes per token row of the two staged tiles
+OUT_NAME = "fisher_gram_bf16_wide_loop.inc"
+
+
+def configure(row_blocks):
+    """Sets the constants of a variant: `row_blocks` row blocks of the scaled operand per workgroup."""
+    global NS, LOADS, STAGE, DMA_SLOTS, OUT_NAME
+    if row_blocks == 1:
+        NS, LOADS, STAGE, OUT_NAME = 6, 6, 23552, "fisher_gram_bf16_wide_loop.inc"
+        DMA_SLOTS = [int(v) for v in os.environ.get("GQW_DMASLOTS", "4,13,22").split(",")]
+    else:
+        NS, LOADS, STAGE, OUT_NAME = 5, 8, 2 * 6144 + 16384 + 1024, "fisher_gram_bf16_wide2_loop.inc"
+        DMA_SLOTS = [int(v) for v in os.environ.get("GQW_DMASLOTS2", "3,9,15,21").split(",")]
 MA, NB = 3, 8           # fragments of the scaled / raw operand per wave
 
 # ---- fixed vector registers (all listed as clobbers) -------------------------------------------
@@ -159,7 +177,7 @@ def dma_m0(e, k, slot_fill):
 
 
 def dma_load(e, k):
-    base = S_B5 if k == 5 else S_XB
+    base = S_B5 if k == LOADS - 1 else S_XB
     e.raw("global_load_lds_dwordx4 %%[vo%d], s[%d:%d]" % (k, base, base + 1))
 
 
@@ -252,9 +270,9 @@ def build(nb=NB):
         # tokens 16..31 of the previous stage (operands already in registers); fetches tokens 0..15 of the
         # stage entered: its addresses are formed first
         set_base(m)
-        sub_step(e, 1, 0, 0, [0, 1, 2], slot_fill, nb=nb)
+        sub_step(e, 1, 0, 0, list(range(LOADS // 2)), slot_fill, nb=nb)
         # tokens 0..15 of the stage entered; fetches its tokens 16..31
-        sub_step(e, 0, 1, 1, [3, 4, 5], slot_fill, nb=nb)
+        sub_step(e, 0, 1, 1, list(range(LOADS // 2, LOADS)), slot_fill, nb=nb)
         assert e.state() == join_state, "LDS scoreboard differs between the paths that meet at a label"
         e.raw("s_sub_u32 s%d, s%d, 1" % (S_CNT, S_CNT))
         e.raw("s_cmp_eq_u32 s%d, 0" % S_CNT)
@@ -312,11 +330,13 @@ def main():
         out += ["  " + l for l in body]
         out.append("    break;")
     out.append("  default:\n    __builtin_unreachable();\n}")
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "fisher_gram_bf16_wide_loop.inc")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), OUT_NAME)
     with open(path, "w") as f:
         f.write("\n".join(out) + "\n")
     print("wrote %s: %d statements, %d matrix instructions" % (path, NB, total), file=sys.stderr)
 
 
 if __name__ == "__main__":
-    main()
+    for rb in (1, 2):
+        configure(rb)
+        main()

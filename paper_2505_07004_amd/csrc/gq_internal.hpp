@@ -122,21 +122,23 @@ __host__ __device__ inline void band_decode(int64_t t, int rpt, int64_t NT, int&
 // matrix).  Items are walked in bands of two tile columns, row block slow, so that consecutive items
 // (the workgroups resident on one XCD take such a run) share few row panels and few column panels.
 constexpr int kWideRows = 96, kWideCols = 256;
-__host__ __device__ inline int64_t wide_rows_of_column(int64_t J, int64_t NR) {
-  const int64_t c = (kWideCols * (J + 1) - 1) / kWideRows + 1;
+// (`rows`: the height of a row block; 96 for four groups per workgroup, 192 when a workgroup takes two row
+// blocks of two groups each)
+__host__ __device__ inline int64_t wide_rows_of_column(int64_t J, int64_t NR, int64_t rows = kWideRows) {
+  const int64_t c = (kWideCols * (J + 1) - 1) / rows + 1;
   return c < NR ? c : NR;
 }
-__host__ __device__ inline int64_t wide_tile_count(int64_t d) {
-  const int64_t NT = (d + kWideCols - 1) / kWideCols, NR = (d + kWideRows - 1) / kWideRows;
+__host__ __device__ inline int64_t wide_tile_count(int64_t d, int64_t rows = kWideRows) {
+  const int64_t NT = (d + kWideCols - 1) / kWideCols, NR = (d + rows - 1) / rows;
   int64_t t = 0;
-  for (int64_t J = 0; J < NT; ++J) t += wide_rows_of_column(J, NR);
+  for (int64_t J = 0; J < NT; ++J) t += wide_rows_of_column(J, NR, rows);
   return t;
 }
 // Item t in [0, wide_tile_count(d)) -> row block I, tile column J.
-__host__ __device__ inline void wide_decode(int64_t t, int64_t d, int& I, int& J) {
-  const int64_t NT = (d + kWideCols - 1) / kWideCols, NR = (d + kWideRows - 1) / kWideRows;
+__host__ __device__ inline void wide_decode(int64_t t, int64_t d, int& I, int& J, int64_t rows = kWideRows) {
+  const int64_t NT = (d + kWideCols - 1) / kWideCols, NR = (d + rows - 1) / rows;
   for (int64_t J0 = 0; J0 < NT; J0 += 2) {
-    const int64_t c0 = wide_rows_of_column(J0, NR), c1 = (J0 + 1 < NT) ? wide_rows_of_column(J0 + 1, NR) : 0;
+    const int64_t c0 = wide_rows_of_column(J0, NR, rows), c1 = (J0 + 1 < NT) ? wide_rows_of_column(J0 + 1, NR, rows) : 0;
     if (t < c0 + c1) {
       if (c1 == 0) {
         I = (int)t;
@@ -171,8 +173,11 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
 size_t fisher_gram_bf16_weights_bytes(int64_t n, int G);
 size_t fisher_gram_bf16_wide_weights_bytes(int64_t n, int G);
 size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
-// the wide kernel (96 x 256 blocks per wave; group counts divisible by 4, one-term products, n >= 32)
+// the wide kernel (96 x 256 blocks per wave; even group counts, one-term products, n >= 32): whether it can
+// take such a call at all, and whether it is the one that runs (group counts not divisible by 4 need at
+// least one whole round of work items)
 bool fisher_gram_bf16_wide_applies(int64_t n, int G, bool two_terms);
+bool fisher_gram_bf16_wide_chosen(int64_t n, int64_t d_in, int G, bool two_terms);
 size_t fisher_gram_bf16_wide_workspace(int64_t n, int64_t d_in, int G);
 hipError_t launch_fisher_gram_bf16_wide(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                         float* H, bool accumulate, void* ws, bool no_partials, hipStream_t st);

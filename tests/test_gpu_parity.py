@@ -154,12 +154,56 @@ def test_gram_bf16_config1_values():
     (700, 300, 4, 304, "outlier"),     # d_in not a multiple of 8, padded pitch
     (33, 72, 2, None, "outlier"),      # barely more than one token step
     (5, 16, 4, None, "outlier"),       # tiny
+    (1999, 1160, 6, 1168, "outlier"),  # even group count, too few items for two row blocks per workgroup
+    (640, 2304, 2, None, "outlier"),   # the same with more items
 ])
 def test_gram_bf16_shapes(n, d_in, G, ld, kind):
     say(f"gram bf16 n={n} d_in={d_in} G={G} ld={ld} {kind}")
     X, s = _gram_case(n, d_in, G, torch.bfloat16, 300 + n, ld, kind)
     H = gq.gq_fisher_gram(X, s)
     _check_gram(H, X, s, TOL_BF16, f"bf16 n={n} d_in={d_in} G={G}")
+
+
+def _two_row_block_kernel_ran(X, s, **kw):
+    """Runs the Gram call in a workspace of the test's own; the kernel that puts two groups on two row blocks
+    per workgroup leaves the timing records that the measured XCD speeds are read from, the others do not."""
+    n, d_in = X.shape
+    G = int(s.shape[1])
+    assert G % 2 == 0 and G % 4 != 0
+    ws = torch.empty(gq.gq_fisher_gram_workspace_bytes(X.dtype, n, d_in, G), dtype=torch.uint8, device=DEV)
+    H = gq.gq_fisher_gram(X, s, workspace=ws, **kw)
+    speeds = gq.gq_fisher_gram_measured_xcd_speeds(n, d_in, G, ws)      # raises if that kernel did not run
+    assert len(speeds) == 8
+    return H
+
+
+@pytest.mark.parametrize("n,d_in,G,ld,kind", [
+    (1999, 1160, 26, 1168, "outlier"),  # 13 sets of two groups, 286 items: one round and left-over runs; ragged, padded pitch
+    (1100, 200, 258, None, "silu"),     # a single tile column, 192 rows do not divide 200; 258 items on 256 workgroups
+    (1000, 2304, 10, None, "outlier"),  # 315 items, staircase of the tile columns
+])
+def test_gram_bf16_two_groups_on_two_row_blocks_shapes(n, d_in, G, ld, kind):
+    say(f"gram bf16, two row blocks n={n} d_in={d_in} G={G} ld={ld} {kind}")
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 400 + n, ld, kind)
+    H = _two_row_block_kernel_ran(X, s)
+    _check_gram(H, X, s, TOL_BF16, f"bf16 n={n} d_in={d_in} G={G}")
+
+
+def test_gram_bf16_two_groups_accumulate_over_chunks_mirror_and_repeat_bit_for_bit():
+    """Even group counts not divisible by four: two groups on two row blocks per workgroup."""
+    G = 38                                                                # 15 items per set of two groups: 285 items
+    X, s = _gram_case(1300, 1000, G, torch.bfloat16, 91)
+    H = None
+    for c0 in range(0, 1300, 650):
+        H = gq.gq_fisher_gram(X[c0:c0 + 650], s[c0:c0 + 650], H=H, accumulate=c0 > 0, mirror=c0 > 0)
+    ref = _check_gram(H, X, s, TOL_BF16, "2 chunks, two groups per workgroup")
+    got = to_np64(H)
+    assert np.array_equal(got, np.transpose(got, (0, 2, 1)))
+    assert max(rel_fro(got[k], ref[k]) for k in range(G)) <= TOL_BF16
+    a = _two_row_block_kernel_ran(X, s).clone()
+    b = gq.gq_fisher_gram(X, s)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.triu(a), torch.triu(b))
 
 
 def test_gram_bf16_matches_its_documented_rounding():

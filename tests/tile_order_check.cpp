@@ -28,32 +28,35 @@ int main() {
         }
       }
     }
-  // the wide kernel's order: row blocks of 96 rows against tile columns of 256 columns
-  for (int64_t d = 8; d <= 4608; d += 8) {
-    const int64_t NT = (d + 255) / 256, NR = (d + 95) / 96;
-    int64_t expect = 0;
-    for (int64_t I = 0; I < NR; ++I)
-      for (int64_t J = 0; J < NT; ++J)
-        if (256 * J + 255 >= 96 * I) ++expect;               // some column of the tile is >= some row of the block
-    const int64_t T = gq::wide_tile_count(d);
-    if (T != expect) {
-      std::printf("wide count: d %ld: %ld items, %ld tiles meet the upper triangle\n", (long)d, (long)T, (long)expect);
-      return 1;
-    }
-    std::set<std::pair<int, int>> seen;
-    for (int64_t t = 0; t < T; ++t) {
-      int I, J;
-      gq::wide_decode(t, d, I, J);
-      if (J < 0 || J >= NT || I < 0 || I >= NR || 256 * (int64_t)J + 255 < 96 * (int64_t)I) {
-        std::printf("wide out of range: d %ld t %ld -> (%d, %d)\n", (long)d, (long)t, I, J);
+  // the wide kernel's order: row blocks of 96 rows (192 when a workgroup takes two of them) against tile
+  // columns of 256 columns
+  for (int64_t rows : {96, 192})
+    for (int64_t d = 8; d <= 4608; d += 8) {
+      const int64_t NT = (d + 255) / 256, NR = (d + rows - 1) / rows;
+      int64_t expect = 0;
+      for (int64_t I = 0; I < NR; ++I)
+        for (int64_t J = 0; J < NT; ++J)
+          if (256 * J + 255 >= rows * I) ++expect;             // some column of the tile is >= some row of the block
+      const int64_t T = gq::wide_tile_count(d, rows);
+      if (T != expect) {
+        std::printf("wide count: rows %ld d %ld: %ld items, %ld tiles meet the upper triangle\n", (long)rows, (long)d, (long)T,
+                    (long)expect);
         return 1;
       }
-      if (!seen.insert({I, J}).second) {
-        std::printf("wide visited twice: d %ld t %ld -> (%d, %d)\n", (long)d, (long)t, I, J);
-        return 1;
+      std::set<std::pair<int, int>> seen;
+      for (int64_t t = 0; t < T; ++t) {
+        int I, J;
+        gq::wide_decode(t, d, I, J, rows);
+        if (J < 0 || J >= NT || I < 0 || I >= NR || 256 * (int64_t)J + 255 < rows * (int64_t)I) {
+          std::printf("wide out of range: rows %ld d %ld t %ld -> (%d, %d)\n", (long)rows, (long)d, (long)t, I, J);
+          return 1;
+        }
+        if (!seen.insert({I, J}).second) {
+          std::printf("wide visited twice: rows %ld d %ld t %ld -> (%d, %d)\n", (long)rows, (long)d, (long)t, I, J);
+          return 1;
+        }
       }
     }
-  }
   std::printf("OK\n");
   return 0;
 }

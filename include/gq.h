@@ -171,8 +171,8 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
  *       current device for the rest of the process; used by every later GQ_BF16 gq_fisher_gram /
  *       gq_fisher_gram_noalloc call on it.  GQ_ERR_SHAPE for a value outside the range.
  *   gq_fisher_gram_measured_xcd_speeds(n, d_in, G, workspace, speeds): every plain one-term GQ_BF16
- *       call with G % 4 == 0 (or G % 2 == 0 and d_in large enough that two groups' items of 192 rows x
- *       256 columns number at least 256) records, per workgroup, the time and the cost of its whole
+ *       call with G % 4 == 0 (or G % 2 == 0 and d_in large enough: two groups' items of 192 rows x 256
+ *       columns, times up to three token segments, number at least 256) records, per workgroup, the time and the cost of its whole
  *       work items in its workspace; this call copies those records of the LAST such call with these
  *       sizes and this workspace to the host (it waits for the device) and writes the 8 relative
  *       speeds (mean 1) to the host array `speeds`.  GQ_ERR_UNSUPPORTED when such a call records nothing (other group

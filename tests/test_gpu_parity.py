@@ -155,6 +155,8 @@ def test_gram_bf16_config1_values():
     (33, 72, 2, None, "outlier"),      # barely more than one token step
     (5, 16, 4, None, "outlier"),       # tiny
     (1999, 1160, 6, 1168, "outlier"),  # even group count, too few items for two row blocks per workgroup
+    (3207, 1896, 4, None, "outlier"),  # 97 items on 256 workgroups: three token segments per item, 35 units in runs
+    (6001, 1000, 8, 1008, "silu"),     # 56 items: five segments, ragged last token step, 24 units in runs
     (640, 2304, 2, None, "outlier"),   # the same with more items
 ])
 def test_gram_bf16_shapes(n, d_in, G, ld, kind):
@@ -181,6 +183,7 @@ def _two_row_block_kernel_ran(X, s, **kw):
     (1999, 1160, 26, 1168, "outlier"),  # 13 sets of two groups, 286 items: one round and left-over runs; ragged, padded pitch
     (1100, 200, 258, None, "silu"),     # a single tile column, 192 rows do not divide 200; 258 items on 256 workgroups
     (1000, 2304, 10, None, "outlier"),  # 315 items, staircase of the tile columns
+    (3207, 3072, 2, None, "outlier"),   # 108 items: three token segments per item make 324 units
 ])
 def test_gram_bf16_two_groups_on_two_row_blocks_shapes(n, d_in, G, ld, kind):
     say(f"gram bf16, two row blocks n={n} d_in={d_in} G={G} ld={ld} {kind}")

@@ -127,11 +127,12 @@ def test_config4_q_k_v_stacked_in_one_gram_call():
                            n_random=8, n_probe=2, seed=70 + l, what=f"config 4 stacked q/k/v, layer {l}")
 
 
-@pytest.mark.parametrize("name", ["llama2_70b_attn", "llama2_70b_up"])
-def test_config5_llama2_70b_8192(name):
-    spec, X, s = _layer(name)
+@pytest.mark.parametrize("name,G", [("llama2_70b_attn", None), ("llama2_70b_up", None),
+                                    ("llama2_70b_attn", 2)])     # 2: the group count of the paper's 70B runs (appendix on hyperparameters)
+def test_config5_llama2_70b_8192(name, G):
+    spec, X, s = _layer(name, G)
     H = gq.gq_fisher_gram(X, s, mirror=True)
-    sampled_gram_check(oracle, X, s, H, TOL_BF16, n_random=12, seed=50, what=f"config 5 {name}")
+    sampled_gram_check(oracle, X, s, H, TOL_BF16, n_random=12, seed=50, what=f"config 5 {name} G={spec.G}")
     W, What = wl.make_weights(spec, DEV)
     obj, rows = gq.gq_objective(W, What, H, want_rows=True)
     sampled_objective_check(oracle, X, s, W, What, obj, rows, spec.G, TOL_BF16, rows_per_group=8, seed=51, what=f"config 5 {name}")

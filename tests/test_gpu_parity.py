@@ -209,6 +209,24 @@ def test_gram_bf16_two_groups_accumulate_over_chunks_mirror_and_repeat_bit_for_b
     assert torch.equal(torch.triu(a), torch.triu(b))
 
 
+def test_gram_bf16_token_segments_accumulate_mirror_and_repeat_bit_for_bit():
+    """Fewer work items than workgroups: every item is written by the second pass from parked segments and runs;
+    accumulating calls add to H there, and the order of the parts is fixed."""
+    n, d_in, G = 6414, 1896, 4                        # two chunks of 3207 tokens: 97 items in three segments each
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 93)
+    H = None
+    for c0 in range(0, n, 3207):
+        H = gq.gq_fisher_gram(X[c0:c0 + 3207], s[c0:c0 + 3207], H=H, accumulate=c0 > 0, mirror=c0 > 0)
+    ref = _check_gram(H, X, s, TOL_BF16, "2 chunks, token segments")
+    got = to_np64(H)
+    assert np.array_equal(got, np.transpose(got, (0, 2, 1)))
+    assert max(rel_fro(got[k], ref[k]) for k in range(G)) <= TOL_BF16
+    a = gq.gq_fisher_gram(X[:3207], s[:3207]).clone()
+    b = gq.gq_fisher_gram(X[:3207], s[:3207])
+    torch.cuda.synchronize()
+    assert torch.equal(torch.triu(a), torch.triu(b))
+
+
 def test_gram_bf16_matches_its_documented_rounding():
     """The bf16 path rounds exactly one operand, bf16_rne(fp32(s)*fp32(x)); with that
     operand reproduced on the host the remaining difference is fp32 accumulation only."""

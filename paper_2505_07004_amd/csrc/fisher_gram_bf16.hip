@@ -156,6 +156,14 @@ constexpr int kTileFloats = 4 * kMA * kNB * 16 * 64;   // accumulators of one wo
 // an item goes straight into H; a partial run is parked in the workspace and a second small
 // kernel adds the parts of every split item in a fixed order.  No workgroup ever waits for
 // another one.
+// Fewer items than workgroups: there is no whole round then, every item would be cut at token positions that
+// differ from workgroup to workgroup and nobody would find a neighbour's rows in L2.  Such a call cuts the
+// token steps of every item into `segs` segments of seg_steps steps; the units (segment, item), numbered
+// segment-major, take the place of the items (one lock-step round of P units, the rest in runs).  No unit is a
+// whole item, so every part is parked -- a unit that one workgroup computes whole in slot 2 P + unit (there are
+// fewer than 2 P units) -- and the second kernel writes every item.  The last segment may be shorter than the
+// others; the left-over units all belong to it (the plan sees to that), so they are all equally long.
+// segs == 1, seg_steps == steps otherwise.
 // SPLIT: the scaled operand s * x is carried as TWO bf16 terms (hi + lo, 16 mantissa bits) and every
 // fragment pair takes two MFMAs: twice the matrix-core work for products that are exact to 2^-17, so
 // that the result is positive semidefinite up to ~1e-5 of its largest eigenvalue instead of ~5e-4.
@@ -163,7 +171,8 @@ template <int GPC, bool SPLIT>
 __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __restrict__ X, int64_t n, int64_t d,
                                                                int64_t ld, const float* __restrict__ sp,
                                                                int64_t n_pad, float* __restrict__ H, int accumulate,
-                                                               int n_gsets, int64_t n_items, float* __restrict__ partial) {
+                                                               int n_gsets, int64_t n_items, float* __restrict__ partial,
+                                                               int segs, int seg_steps) {
   using C = Cfg<GPC>;
   constexpr int kAChunks = C::kAChunks, kBChunks = C::kBChunks;
   constexpr int kABytes = C::kABytes, kBBytes = C::kBBytes, kStageBytes = C::kStageBytes, NS = C::kStages;
@@ -186,8 +195,10 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
   const int64_t steps = (n + kStep - 1) / kStep;
   // Without a place to park partial tiles (partial == nullptr: the entry point that allocates nothing)
   // every item is computed whole: ceil(n_items / P) rounds, the last one not full, no left-over runs.
-  const int64_t rounds = partial ? n_items / P : (n_items + P - 1) / P;     // whole items per workgroup
-  const int64_t units = partial ? (n_items - rounds * P) * steps : 0;       // left-over work, dealt out in runs
+  const int64_t n_units = n_items * segs;
+  const int64_t rounds = partial ? n_units / P : (n_units + P - 1) / P;     // whole units per workgroup
+  const int tail_steps = (int)(steps - (int64_t)(segs - 1) * seg_steps);    // steps of a unit of the last segment
+  const int64_t units = partial ? (n_units - rounds * P) * tail_steps : 0;  // left-over work, dealt out in runs
   const int64_t u_begin = first_unit(p, units, P), u_end = first_unit(p + 1, units, P);
 
   const int tid = threadIdx.x;
@@ -219,18 +230,36 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
 
   int64_t round = 0;
   for (int64_t u = u_begin; round < rounds || u < u_end;) {
-    int64_t item, k0, k1;
-    if (round < rounds) {            // a whole item, in step with every other workgroup
-      item = round * P + p;
-      if (item >= n_items) break;    // the last round of the schedule without left-over runs
-      k0 = 0;
-      k1 = steps;
-    } else {                         // (part of) a left-over item
-      item = rounds * P + u / steps;
-      k0 = u - (u / steps) * steps;
-      const int64_t len = (steps - k0) < (u_end - u) ? (steps - k0) : (u_end - u);
-      k1 = k0 + len;
+    // the unit and the steps [r0, r1) of it that this pass computes: all uniform, 32-bit, in scalar registers
+    auto uniform = [](int64_t v) { return (int)__builtin_amdgcn_readfirstlane((int)v); };
+    int unit, r0, r1;
+    const bool in_round = round < rounds;
+    if (in_round) {                  // a whole unit, in step with every other workgroup
+      if (round * P + p >= n_units) break;    // the last round of the schedule without left-over runs
+      unit = uniform(round * P + p);
+      r0 = 0;
+      r1 = -1;                       // all of it
+    } else {                         // (part of) a left-over unit
+      const int64_t j = u / tail_steps;
+      unit = uniform(rounds * P + j);
+      r0 = uniform(u - j * tail_steps);
+      const int64_t len = (tail_steps - r0) < (u_end - u) ? (tail_steps - r0) : (u_end - u);
+      r1 = r0 + uniform(len);
+      u += len;                      // the next part starts here
     }
+    const int n_items_i = uniform(n_items);
+    const int seg = unit / n_items_i, item = unit - seg * n_items_i;
+    const int unit_steps = seg == segs - 1 ? tail_steps : seg_steps;
+    if (in_round) r1 = unit_steps;
+    // Where the result is parked if it is not a whole item: the first part of a workgroup's run in slot 2p, a
+    // later one that is not a whole unit (necessarily the last) in 2p+1, a unit computed whole here (in the
+    // round, or inside a run) that is a segment of an item in its own slot.  Fixed now: one scalar register
+    // across the token loop instead of what it is made of.
+    const bool first_part = !in_round && u - (r1 - r0) == u_begin;
+    const bool covers_unit = r0 == 0 && r1 == unit_steps;
+    const int slot_i = uniform((segs > 1 && covers_unit) ? 2 * P + unit : 2 * p + (first_part ? 0 : 1));
+    const int64_t k0 = seg * seg_steps + r0, k1 = seg * seg_steps + r1;
+    if (in_round) ++round;
     const Item it = decode_item<GPC>(item, n_gsets, d);
     const int64_t row_t = it.row_t, col_t = it.col_t;
     const int gbase = it.gbase;
@@ -529,8 +558,7 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
         }
       }
     } else {
-      // the first run of a workgroup parks in slot 2p, a later (necessarily last) one in 2p+1
-      float* slot = partial + (size_t)(2 * p + (u == u_begin ? 0 : 1)) * kTileFloats + (size_t)wave * (kTileFloats / 4);
+      float* slot = partial + (size_t)slot_i * kTileFloats + (size_t)wave * (kTileFloats / 4);
 #pragma unroll
       for (int x = 0; x < kMA; ++x)
 #pragma unroll
@@ -539,51 +567,64 @@ __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __r
           for (int r = 0; r < 16; ++r) slot[((x * kNB + y) * 16 + r) * 64 + lane] = acc[x][y][r];
     }
     __syncthreads();   // every wave is done with the ring before the next run refills it
-    if (round < rounds)
-      ++round;
-    else
-      u += k1 - k0;
   }
 }
 
-// Adds the parked parts of every left-over item that was split between workgroups, in
-// workgroup order, and stores the sum into H.  One workgroup per left-over item.
+// Adds the parked parts of every item that was split between workgroups, in a fixed order, and stores the
+// sum into H.  blockIdx.x: the left-over item (segs == 1) or the item (segs > 1: every item is split then);
+// blockIdx.y: one 32 x 32 accumulator fragment of every wave.  Order: the item's segments by token position,
+// the parts of a left-over unit in workgroup order.
 template <int GPC>
 __global__ __launch_bounds__(256) void fisher_gram_fixup_kernel(int64_t n, int64_t d, float* __restrict__ H,
                                                                 int accumulate, int n_gsets, int64_t n_items, int64_t P,
-                                                                const float* __restrict__ partial) {
+                                                                const float* __restrict__ partial, int segs,
+                                                                int seg_steps) {
   const int64_t steps = (n + kStep - 1) / kStep;
-  const int64_t rounds = n_items / P;
-  const int64_t units = (n_items - rounds * P) * steps;
-  const int64_t j = blockIdx.x;                                    // index among the left-over items
-  const int64_t lo = j * steps, hi = lo + steps;                   // its units
-  // first workgroup whose run reaches into the item
-  int64_t q0 = lo * P / units;
-  if (q0 >= P) q0 = P - 1;
-  while (q0 > 0 && first_unit(q0, units, P) > lo) --q0;
-  while (q0 + 1 < P && first_unit(q0 + 1, units, P) <= lo) ++q0;
-  if (first_unit(q0, units, P) <= lo && first_unit(q0 + 1, units, P) >= hi) return;   // one run covers the item: already in H
-  const Item it = decode_item<GPC>(rounds * P + j, n_gsets, d);
+  const bool split = segs > 1;
+  const int64_t rounds = n_items * segs / P;
+  const int64_t tail_steps = steps - (int64_t)(segs - 1) * seg_steps;   // every left-over unit is one of the last segment
+  const int64_t units = (n_items * segs - rounds * P) * tail_steps;
+  const int64_t item = split ? (int64_t)blockIdx.x : rounds * P + blockIdx.x;
+  const Item it = decode_item<GPC>(item, n_gsets, d);
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int g_local = wave % GPC, sub = wave / GPC;
   const int64_t row_w = it.row_t + 64 * sub;
   float* Hk = H + (int64_t)(it.gbase + g_local) * d * d;
-  const size_t in_tile = (size_t)wave * (kTileFloats / 4) + lane;
   // blockIdx.y picks one 32x32 accumulator fragment (x, y) of every wave
   const int x = blockIdx.y / kNB, y = blockIdx.y % kNB;
+  const size_t in_tile = (size_t)wave * (kTileFloats / 4) + lane + (size_t)((x * kNB + y) * 16) * 64;
   const int64_t col = it.col_t + 32 * y + lane % 32;
   float v[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) v[r] = 0.f;
-  for (int64_t q = q0; q < P; ++q) {
-    const int64_t b0 = first_unit(q, units, P), b1 = first_unit(q + 1, units, P);
-    if (b0 >= hi) break;
-    if (b1 == b0) continue;                                        // this workgroup had no left-over run
-    // a run parks its first part in slot 2q and a later (necessarily last) part in 2q+1
-    const float* part = partial + (size_t)(2 * q + (b0 >= lo ? 0 : 1)) * kTileFloats + in_tile +
-                        (size_t)((x * kNB + y) * 16) * 64;
+  for (int seg = 0; seg < segs; ++seg) {
+    const int64_t unit = (int64_t)seg * n_items + item;
+    if (unit < rounds * P) {                                       // (split only) a whole unit of the lock-step round
+      const float* part = partial + (size_t)(2 * P + unit) * kTileFloats + in_tile;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) v[r] += part[r * 64];
+      for (int r = 0; r < 16; ++r) v[r] += part[r * 64];
+      continue;
+    }
+    const int64_t j = unit - rounds * P;                           // index among the left-over units
+    const int64_t lo = j * tail_steps, hi = lo + tail_steps;       // its place in the runs
+    // first workgroup whose run reaches into the unit
+    int64_t q0 = lo * P / units;
+    if (q0 >= P) q0 = P - 1;
+    while (q0 > 0 && first_unit(q0, units, P) > lo) --q0;
+    while (q0 + 1 < P && first_unit(q0 + 1, units, P) <= lo) ++q0;
+    if (!split && first_unit(q0, units, P) <= lo && first_unit(q0 + 1, units, P) >= hi) return;   // one run covers the item: already in H
+    for (int64_t q = q0; q < P; ++q) {
+      const int64_t b0 = first_unit(q, units, P), b1 = first_unit(q + 1, units, P);
+      if (b0 >= hi) break;
+      if (b1 == b0) continue;                                      // this workgroup had no left-over run
+      const int64_t r0 = (b0 > lo ? b0 : lo) - lo, r1 = (b1 < hi ? b1 : hi) - lo;   // its part of the unit
+      // a run parks its first part in slot 2q and a later (necessarily last) part in 2q+1; with segments, a
+      // part that is the whole unit in the unit's own slot
+      const int64_t slot_i = (split && r0 == 0 && r1 == tail_steps) ? 2 * P + unit : 2 * q + (b0 >= lo ? 0 : 1);
+      const float* part = partial + (size_t)slot_i * kTileFloats + in_tile;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[r] += part[r * 64];
+    }
   }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -610,12 +651,16 @@ int64_t padded_tokens(int64_t n) { return (n + kStep - 1) / kStep * kStep + (int
 constexpr int kMaxWorkgroups = 256;   // one persistent workgroup per compute unit of an MI355X
 constexpr int kMinUnitsPerWorkgroup = 32;
 
+constexpr int64_t kMinSegmentSteps = 32;   // a segment of an item's token steps is at least 1024 tokens
+constexpr int64_t kMaxSegments = 3;        // more of them cost more in parked tiles than the shared panels save
 struct Plan {
-  int gpc, n_gsets;
-  int64_t n_pad, n_items, P;
+  int gpc, n_gsets, segs;
+  int64_t n_pad, n_items, P, seg_steps;
   size_t sp_bytes, partial_bytes;
+  int64_t n_units() const { return n_items * segs; }
 };
-Plan make_plan(int64_t n, int64_t d_in, int G) {
+// with_workspace: the call can park partial tiles (runs of left-over units, segments of items)
+Plan make_plan(int64_t n, int64_t d_in, int G, bool with_workspace = true) {
   Plan pl;
   pl.gpc = groups_per_workgroup(G);
   pl.n_gsets = G / pl.gpc;
@@ -625,9 +670,24 @@ Plan make_plan(int64_t n, int64_t d_in, int G) {
   int64_t P = pl.n_items * steps / kMinUnitsPerWorkgroup;
   if (P < 1) P = 1;
   if (P > kMaxWorkgroups) P = kMaxWorkgroups;
+  pl.segs = 1;
+  pl.seg_steps = steps;
+  if (with_workspace && pl.n_items < P) {                   // no whole round of items: segments of their token steps
+    const int64_t want = (P + pl.n_items - 1) / pl.n_items;
+    const int64_t len = (steps + want - 1) / want;
+    const int64_t count = (steps + len - 1) / len;           // no empty last segment
+    // fewer than 2 P units: one slot per unit behind the 2 P slots of the runs; the lock-step round takes all
+    // units of the segments before the last one, so that the left-over units are equally long
+    if (len >= kMinSegmentSteps && count <= kMaxSegments && count * pl.n_items < 2 * P &&
+        (count * pl.n_items / P) * P >= (count - 1) * pl.n_items) {
+      pl.seg_steps = len;
+      pl.segs = (int)count;
+    }
+  }
+  if (!with_workspace) P = pl.n_items < kMaxWorkgroups ? pl.n_items : kMaxWorkgroups;   // whole items only
   pl.P = P;
   pl.sp_bytes = ((size_t)(pl.n_pad * G) * sizeof(float) + 255) / 256 * 256;
-  pl.partial_bytes = (size_t)(2 * P) * kTileFloats * sizeof(float);
+  pl.partial_bytes = (size_t)((pl.segs > 1 ? 4 : 2) * P) * kTileFloats * sizeof(float);
   return pl;
 }
 
@@ -656,28 +716,31 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
                                    float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st) {
   if (fisher_gram_bf16_wide_chosen(n, d_in, G, two_terms))
     return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, no_partials, st);
-  Plan pl = make_plan(n, d_in, G);
+  const Plan pl = make_plan(n, d_in, G, !no_partials);
   float* sp = (float*)ws;
   float* partial = no_partials ? nullptr : (float*)((char*)ws + pl.sp_bytes);
-  if (no_partials) pl.P = pl.n_items < kMaxWorkgroups ? pl.n_items : kMaxWorkgroups;   // whole items only
   pack_weights_kernel<<<dim3((unsigned)((pl.n_pad + 255) / 256)), dim3(256), 0, st>>>(s, n, G, pl.n_pad, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int64_t left_over = no_partials ? 0 : pl.n_items % pl.P;
-  const dim3 grid((unsigned)pl.P), fix((unsigned)left_over, (unsigned)(kMA * kNB));
+  const int64_t left_over = no_partials ? 0 : pl.n_units() % pl.P;
+  const int64_t fix_items = pl.segs > 1 ? pl.n_items : left_over;   // segments: every item is summed from its parts
+  const dim3 grid((unsigned)pl.P), fix((unsigned)(fix_items > 0 ? fix_items : 1), (unsigned)(kMA * kNB));
+  const int segs = pl.segs, seg_steps = (int)pl.seg_steps;
   const __bf16* Xb = (const __bf16*)X;
   const int acc = accumulate ? 1 : 0;
 #define GQ_LAUNCH_GRAM(GPC)                                                                                     \
   if (two_terms)                                                                                                \
     fisher_gram_bf16_kernel<GPC, true><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc,        \
-                                                                   pl.n_gsets, pl.n_items, partial);             \
+                                                                   pl.n_gsets, pl.n_items, partial, segs,        \
+                                                                   seg_steps);                                   \
   else                                                                                                          \
     fisher_gram_bf16_kernel<GPC, false><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc,       \
-                                                                    pl.n_gsets, pl.n_items, partial);            \
+                                                                    pl.n_gsets, pl.n_items, partial, segs,       \
+                                                                    seg_steps);                                  \
   e = hipGetLastError();                                                                                        \
-  if (e == hipSuccess && left_over > 0) {                                                                            \
+  if (e == hipSuccess && fix_items > 0) {                                                                       \
     fisher_gram_fixup_kernel<GPC><<<fix, dim3(256), 0, st>>>(n, d_in, H, acc, pl.n_gsets, pl.n_items, pl.P,      \
-                                                             partial);                                         \
+                                                             partial, segs, seg_steps);                         \
     e = hipGetLastError();                                                                                      \
   }
   if (pl.gpc == 4) {

@@ -157,6 +157,8 @@ def test_gram_bf16_config1_values():
     (1999, 1160, 6, 1168, "outlier"),  # even group count, too few items for two row blocks per workgroup
     (3207, 1896, 4, None, "outlier"),  # 97 items on 256 workgroups: three token segments per item, 35 units in runs
     (6001, 1000, 8, 1008, "silu"),     # 56 items: five segments, ragged last token step, 24 units in runs
+    (3207, 3584, 1, None, "outlier"),  # one group, 105 items of 256 x 256: three token segments (34, 34, 33 steps)
+    (3207, 2304, 2, 2312, "silu"),     # two groups, 99 items of 128 x 256: the same on the other tile shape
     (640, 2304, 2, None, "outlier"),   # the same with more items
 ])
 def test_gram_bf16_shapes(n, d_in, G, ld, kind):
@@ -227,6 +229,22 @@ def test_gram_bf16_token_segments_accumulate_mirror_and_repeat_bit_for_bit():
     assert torch.equal(torch.triu(a), torch.triu(b))
 
 
+def test_gram_bf16_one_group_token_segments_accumulate_and_repeat_bit_for_bit():
+    n, d_in, G = 6414, 3584, 1                        # two chunks of 3207 tokens: 105 items in three segments each
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 95)
+    H = None
+    for c0 in range(0, n, 3207):
+        H = gq.gq_fisher_gram(X[c0:c0 + 3207], s[c0:c0 + 3207], H=H, accumulate=c0 > 0, mirror=c0 > 0)
+    ref = _check_gram(H, X, s, TOL_BF16, "2 chunks, one group, token segments")
+    got = to_np64(H)
+    assert np.array_equal(got, np.transpose(got, (0, 2, 1)))
+    assert rel_fro(got[0], ref[0]) <= TOL_BF16
+    a = gq.gq_fisher_gram(X[:3207], s[:3207]).clone()
+    b = gq.gq_fisher_gram(X[:3207], s[:3207])
+    torch.cuda.synchronize()
+    assert torch.equal(torch.triu(a), torch.triu(b))
+
+
 def test_gram_bf16_matches_its_documented_rounding():
     """The bf16 path rounds exactly one operand, bf16_rne(fp32(s)*fp32(x)); with that
     operand reproduced on the host the remaining difference is fp32 accumulation only."""
@@ -254,6 +272,7 @@ TOL_TWO_TERMS = 2e-5     # two bf16 terms carry s*x to 2^-17 (random sign: ~3e-6
     (1000, 328, 3, None, "silu"),
     (700, 300, 4, 304, "outlier"),
     (5, 16, 4, None, "outlier"),
+    (3207, 3584, 1, None, "outlier"),  # 105 items on 256 workgroups: three token segments per item
 ])
 def test_gram_bf16_two_terms_shapes(n, d_in, G, ld, kind):
     say(f"gram bf16, two terms n={n} d_in={d_in} G={G} ld={ld} {kind}")

@@ -167,13 +167,24 @@ constexpr int kTileFloats = 4 * kMA * kNB * 16 * 64;   // accumulators of one wo
 // SPLIT: the scaled operand s * x is carried as TWO bf16 terms (hi + lo, 16 mantissa bits) and every
 // fragment pair takes two MFMAs: twice the matrix-core work for products that are exact to 2^-17, so
 // that the result is positive semidefinite up to ~1e-5 of its largest eigenvalue instead of ~5e-4.
+// The number of token rows a call really holds when only the device knows it (n_dev != nullptr: the rows of the
+// heaviest tokens gathered by the call before; the rows past *n_dev are zero with zero weights, so leaving their
+// token steps out changes nothing): *n_dev rounded up to whole steps, at least one step, at most n.
+__device__ __forceinline__ int64_t tokens_in_use(int64_t n, const int* __restrict__ n_dev) {
+  if (!n_dev) return n;
+  const int64_t t = *n_dev < 1 ? 1 : *n_dev;
+  const int64_t whole = (t + kStep - 1) / kStep * kStep;
+  return whole < n ? whole : n;
+}
+
 template <int GPC, bool SPLIT>
 __global__ __launch_bounds__(256) void fisher_gram_bf16_kernel(const __bf16* __restrict__ X, int64_t n, int64_t d,
                                                                int64_t ld, const float* __restrict__ sp,
                                                                int64_t n_pad, float* __restrict__ H, int accumulate,
                                                                int n_gsets, int64_t n_items, float* __restrict__ partial,
-                                                               int segs, int seg_steps) {
+                                                               int segs, int seg_steps, const int* __restrict__ n_dev) {
   using C = Cfg<GPC>;
+  n = tokens_in_use(n, n_dev);
   constexpr int kAChunks = C::kAChunks, kBChunks = C::kBChunks;
   constexpr int kABytes = C::kABytes, kBBytes = C::kBBytes, kStageBytes = C::kStageBytes, NS = C::kStages;
 
@@ -578,7 +589,8 @@ template <int GPC>
 __global__ __launch_bounds__(256) void fisher_gram_fixup_kernel(int64_t n, int64_t d, float* __restrict__ H,
                                                                 int accumulate, int n_gsets, int64_t n_items, int64_t P,
                                                                 const float* __restrict__ partial, int segs,
-                                                                int seg_steps) {
+                                                                int seg_steps, const int* __restrict__ n_dev) {
+  n = tokens_in_use(n, n_dev);
   const int64_t steps = (n + kStep - 1) / kStep;
   const bool split = segs > 1;
   const int64_t rounds = n_items * segs / P;
@@ -713,7 +725,9 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
 }
 
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                   float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st) {
+                                   float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st,
+                                   const int* n_dev) {
+  if (n_dev && !two_terms) return hipErrorInvalidValue;        // only the two-term pass over gathered rows uses it
   if (fisher_gram_bf16_wide_chosen(n, d_in, G, two_terms))
     return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, no_partials, st);
   const Plan pl = make_plan(n, d_in, G, !no_partials);
@@ -732,15 +746,15 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
   if (two_terms)                                                                                                \
     fisher_gram_bf16_kernel<GPC, true><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc,        \
                                                                    pl.n_gsets, pl.n_items, partial, segs,        \
-                                                                   seg_steps);                                   \
+                                                                   seg_steps, n_dev);                            \
   else                                                                                                          \
     fisher_gram_bf16_kernel<GPC, false><<<grid, dim3(256), 0, st>>>(Xb, n, d_in, ld, sp, pl.n_pad, H, acc,       \
                                                                     pl.n_gsets, pl.n_items, partial, segs,       \
-                                                                    seg_steps);                                  \
+                                                                    seg_steps, nullptr);                         \
   e = hipGetLastError();                                                                                        \
   if (e == hipSuccess && fix_items > 0) {                                                                       \
     fisher_gram_fixup_kernel<GPC><<<fix, dim3(256), 0, st>>>(n, d_in, H, acc, pl.n_gsets, pl.n_items, pl.P,      \
-                                                             partial, segs, seg_steps);                         \
+                                                             partial, segs, seg_steps, n_dev);                  \
     e = hipGetLastError();                                                                                      \
   }
   if (pl.gpc == 4) {

@@ -165,9 +165,11 @@ hipError_t launch_group_weights(const void* dZ, gq_dtype dt, int64_t n, int64_t 
 hipError_t launch_fisher_gram_f32(const float* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
                                   int G, float* H, bool accumulate, hipStream_t st);
 
+// n_dev (two-term calls only, may be null): device pointer to the number of leading rows of X that are in use;
+// the rows from there to n are zero with zero weights, and the kernels leave their token steps out.
 hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s,
                                    int G, float* H, bool accumulate, bool two_terms, void* ws, bool no_partials,
-                                   hipStream_t st);
+                                   hipStream_t st, const int* n_dev = nullptr);
 // `no_partials`: ws holds only the repacked weights (fisher_gram_bf16_weights_bytes); every work item is then
 // computed whole by one workgroup (no left-over runs, no second pass)
 size_t fisher_gram_bf16_weights_bytes(int64_t n, int G);

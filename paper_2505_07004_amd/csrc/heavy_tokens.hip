@@ -222,7 +222,8 @@ hipError_t launch_fisher_gram_bf16_heavy(const void* X, int64_t n, int64_t d_in,
   if ((e = hipGetLastError()) != hipSuccess) return e;
   e = launch_fisher_gram_bf16(X, n, d_in, ld, s_main, G, H, accumulate, false, ws, false, st);
   if (e != hipSuccess) return e;
-  return launch_fisher_gram_bf16(X_h, L.n_cap, d_in, L.ld_h, s_h, G, H, true, true, ws, false, st);
+  // the gathered rows past the number taken are zero: the second pass runs over the token steps in use only
+  return launch_fisher_gram_bf16(X_h, L.n_cap, d_in, L.ld_h, s_h, G, H, true, true, ws, false, st, counts + L.n_blocks);
 }
 
 }  // namespace gq

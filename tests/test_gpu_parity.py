@@ -245,6 +245,34 @@ def test_gram_bf16_one_group_token_segments_accumulate_and_repeat_bit_for_bit():
     assert torch.equal(torch.triu(a), torch.triu(b))
 
 
+def _random_gram_shapes(count, seed):
+    """Seeded shapes over all the tilings of the bf16 Gram call: group counts 1..12, ragged everything, token counts
+    on both sides of what token segments need; sized so that the fp64 oracle stays under a second per shape."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        G = int(rng.choice([1, 1, 2, 2, 3, 4, 4, 6, 8, 10, 12]))
+        d_in = int(rng.integers(2, 330)) * 8
+        n = int(rng.integers(1, 5200))
+        if n * d_in * d_in * G > 3e10:
+            continue
+        out.append((n, d_in, G, d_in + 8 * int(rng.integers(0, 3)), bool(rng.integers(0, 2)), bool(rng.integers(0, 3) == 0)))
+    return out
+
+
+@pytest.mark.parametrize("n,d_in,G,ld,chunked,heavy", _random_gram_shapes(24, 250507004))
+def test_gram_bf16_random_shapes(n, d_in, G, ld, chunked, heavy):
+    say(f"gram bf16 random shape n={n} d_in={d_in} G={G} ld={ld} chunked={chunked} heavy={heavy}")
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 7000 + n + d_in, ld if ld != d_in else None, "outlier")
+    if chunked and n >= 2:
+        cut = n // 2 + 1
+        H = gq.gq_fisher_gram(X[:cut], s[:cut], heavy_two_terms=heavy)
+        H = gq.gq_fisher_gram(X[cut:], s[cut:], H=H, accumulate=True, heavy_two_terms=heavy)
+    else:
+        H = gq.gq_fisher_gram(X, s, heavy_two_terms=heavy)
+    _check_gram(H, X, s, TOL_BF16, f"random shape n={n} d_in={d_in} G={G}")
+
+
 def test_gram_bf16_matches_its_documented_rounding():
     """The bf16 path rounds exactly one operand, bf16_rne(fp32(s)*fp32(x)); with that
     operand reproduced on the host the remaining difference is fp32 accumulation only."""

@@ -109,12 +109,13 @@ struct Cfg {
   static_assert((kStages - 3) * kLoads <= 63, "vmcnt is a 6-bit counter");
 };
 
-// Weights repacked group-major with zero padding: sp[g][i] = s[i][g] for i < n, 0 for n <= i < n_pad.
-__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ s, int64_t n, int G,
+// Weights repacked group-major with zero padding: sp[g][i] = s[i][g] for i < n, 0 for n <= i < n_pad
+// (ld_s: the row pitch of s in floats).
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ s, int64_t ld_s, int64_t n, int G,
                                                            int64_t n_pad, float* __restrict__ sp) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n_pad) return;
-  for (int g = 0; g < G; ++g) sp[(int64_t)g * n_pad + i] = (i < n) ? s[i * G + g] : 0.f;
+  for (int g = 0; g < G; ++g) sp[(int64_t)g * n_pad + i] = (i < n) ? s[i * ld_s + g] : 0.f;
 }
 
 // A work item is one tile (TM rows x 256 columns of the upper triangle) for one set of GPC
@@ -705,11 +706,19 @@ Plan make_plan(int64_t n, int64_t d_in, int G, bool with_workspace = true) {
 
 }  // namespace
 
+// An odd group count from 3 on whose even part the wide kernel takes: that part runs there and the last group
+// on the narrow kernel (one-term calls).  Three groups on X[65536,5120]: 4.5 ms instead of 5.0.
+static bool runs_in_two_parts(int64_t n, int64_t d_in, int G, bool two_terms) {
+  return !two_terms && G >= 3 && G % 2 == 1 && fisher_gram_bf16_wide_chosen(n, d_in, G - 1, false);
+}
+
 // Bytes of the repacked weights alone (what a call without partial tiles needs), for either kernel.
 size_t fisher_gram_bf16_weights_bytes(int64_t n, int G) {
   if (n <= 0) return 0;
   const size_t narrow = make_plan(n, 8, G).sp_bytes;
-  const size_t wide = fisher_gram_bf16_wide_applies(n, G, false) ? fisher_gram_bf16_wide_weights_bytes(n, G) : 0;
+  size_t wide = fisher_gram_bf16_wide_applies(n, G, false) ? fisher_gram_bf16_wide_weights_bytes(n, G) : 0;
+  // an odd group count may run as its even part on the wide kernel (d_in is not known here)
+  if (G >= 3 && G % 2 == 1 && fisher_gram_bf16_wide_applies(n, G - 1, false)) wide = fisher_gram_bf16_wide_weights_bytes(n, G - 1);
   return narrow > wide ? narrow : wide;
 }
 
@@ -721,19 +730,24 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G) {
     const size_t wide = fisher_gram_bf16_wide_workspace(n, d_in, G);
     if (wide > need) need = wide;
   }
+  if (runs_in_two_parts(n, d_in, G, false)) {                 // one part after the other in the same workspace
+    const size_t even = fisher_gram_bf16_workspace(n, d_in, G - 1), last = fisher_gram_bf16_workspace(n, d_in, 1);
+    if (even > need) need = even;
+    if (last > need) need = last;
+  }
   return need;
 }
 
-hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                   float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st,
-                                   const int* n_dev) {
-  if (n_dev && !two_terms) return hipErrorInvalidValue;        // only the two-term pass over gathered rows uses it
+namespace {
+// G groups whose weights are the columns s[:, 0 .. G-1] of an array with row pitch ld_s, into H[0 .. G-1]
+hipError_t launch_groups(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int64_t ld_s, int G, float* H,
+                         bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st, const int* n_dev) {
   if (fisher_gram_bf16_wide_chosen(n, d_in, G, two_terms))
-    return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, G, H, accumulate, ws, no_partials, st);
+    return launch_fisher_gram_bf16_wide(X, n, d_in, ld, s, ld_s, G, H, accumulate, ws, no_partials, st);
   const Plan pl = make_plan(n, d_in, G, !no_partials);
   float* sp = (float*)ws;
   float* partial = no_partials ? nullptr : (float*)((char*)ws + pl.sp_bytes);
-  pack_weights_kernel<<<dim3((unsigned)((pl.n_pad + 255) / 256)), dim3(256), 0, st>>>(s, n, G, pl.n_pad, sp);
+  pack_weights_kernel<<<dim3((unsigned)((pl.n_pad + 255) / 256)), dim3(256), 0, st>>>(s, ld_s, n, G, pl.n_pad, sp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t left_over = no_partials ? 0 : pl.n_units() % pl.P;
@@ -766,6 +780,21 @@ hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64
   }
 #undef GQ_LAUNCH_GRAM
   return e;
+}
+}  // namespace
+
+hipError_t launch_fisher_gram_bf16(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
+                                   float* H, bool accumulate, bool two_terms, void* ws, bool no_partials, hipStream_t st,
+                                   const int* n_dev) {
+  if (n_dev && !two_terms) return hipErrorInvalidValue;        // only the two-term pass over gathered rows uses it
+  if (!runs_in_two_parts(n, d_in, G, two_terms))
+    return launch_groups(X, n, d_in, ld, s, G, G, H, accumulate, two_terms, ws, no_partials, st, n_dev);
+  // the even part, then the last group; the second launch reuses the workspace once the first is through with it
+  // (same stream)
+  hipError_t e = launch_groups(X, n, d_in, ld, s, G, G - 1, H, accumulate, false, ws, no_partials, st, nullptr);
+  if (e != hipSuccess) return e;
+  return launch_groups(X, n, d_in, ld, s + (G - 1), G, 1, H + (int64_t)(G - 1) * d_in * d_in, accumulate, false, ws,
+                       no_partials, st, nullptr);
 }
 
 }  // namespace gq

@@ -181,8 +181,8 @@ size_t fisher_gram_bf16_workspace(int64_t n, int64_t d_in, int G);
 bool fisher_gram_bf16_wide_applies(int64_t n, int G, bool two_terms);
 bool fisher_gram_bf16_wide_chosen(int64_t n, int64_t d_in, int G, bool two_terms);
 size_t fisher_gram_bf16_wide_workspace(int64_t n, int64_t d_in, int G);
-hipError_t launch_fisher_gram_bf16_wide(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
-                                        float* H, bool accumulate, void* ws, bool no_partials, hipStream_t st);
+hipError_t launch_fisher_gram_bf16_wide(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int64_t ld_s,
+                                        int G, float* H, bool accumulate, void* ws, bool no_partials, hipStream_t st);
 
 // GQ_HEAVY_TWO_TERMS: the tokens whose weight exceeds 16 times the mean weight of a group (at most
 // heavy_capacity(n) of them, in token order) are taken out of the main call and run as a second, small call

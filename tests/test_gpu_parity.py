@@ -158,6 +158,9 @@ def test_gram_bf16_config1_values():
     (3207, 1896, 4, None, "outlier"),  # 97 items on 256 workgroups: three token segments per item, 35 units in runs
     (6001, 1000, 8, 1008, "silu"),     # 56 items: five segments, ragged last token step, 24 units in runs
     (3207, 3584, 1, None, "outlier"),  # one group, 105 items of 256 x 256: three token segments (34, 34, 33 steps)
+    (1000, 328, 5, None, "silu"),      # odd group count: four groups on the wide kernel, the fifth on the narrow one
+    (2100, 520, 9, 528, "outlier"),    # eight + one, ragged, padded pitch
+    (288, 4864, 3, None, "outlier"),   # three groups: two on two row blocks (260 items), the third on the narrow kernel
     (3207, 2304, 2, 2312, "silu"),     # two groups, 99 items of 128 x 256: the same on the other tile shape
     (640, 2304, 2, None, "outlier"),   # the same with more items
 ])
@@ -271,6 +274,23 @@ def test_gram_bf16_random_shapes(n, d_in, G, ld, chunked, heavy):
     else:
         H = gq.gq_fisher_gram(X, s, heavy_two_terms=heavy)
     _check_gram(H, X, s, TOL_BF16, f"random shape n={n} d_in={d_in} G={G}")
+
+
+def test_gram_bf16_odd_group_count_in_two_parts_accumulates_and_equals_separate_calls():
+    """Five groups run as four (wide kernel) + one (narrow kernel): the same bits as those two calls made by hand."""
+    n, d_in, G = 1500, 520, 5
+    X, s = _gram_case(n, d_in, G, torch.bfloat16, 97)
+    H = None
+    for c0 in range(0, n, 750):
+        H = gq.gq_fisher_gram(X[c0:c0 + 750], s[c0:c0 + 750], H=H, accumulate=c0 > 0, mirror=c0 > 0)
+    _check_gram(H, X, s, TOL_BF16, "2 chunks, five groups")
+    got = to_np64(H)
+    assert np.array_equal(got, np.transpose(got, (0, 2, 1)))
+    whole = gq.gq_fisher_gram(X, s)
+    four = gq.gq_fisher_gram(X, s[:, :4].contiguous())
+    last = gq.gq_fisher_gram(X, s[:, 4:].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(torch.triu(whole[:4]), torch.triu(four)) and torch.equal(torch.triu(whole[4:]), torch.triu(last))
 
 
 def test_gram_bf16_matches_its_documented_rounding():

@@ -371,6 +371,34 @@ def main():
                 torch.cuda.synchronize()
                 ts.append(e0.elapsed_time(e1))
             mode_ms[label] = statistics.median(ts)
+        if chunks > 1:
+            # chunked calls: the heavy rows of all chunks gathered in a pool, ONE two-term pass at the end instead of
+            # a read-modify-write of the whole H per chunk
+            c = n // chunks
+            pool_rows = 32 * chunks * max(1, -(-c // 2048))
+            pool = gq.gq_fisher_gram_heavy_pool(d_in, G, pool_rows, dev)
+            ws_p = torch.empty(max(int(lib.gq_fisher_gram_workspace_bytes(gq.GQ_BF16, pool_rows, d_in, G)), 256),
+                               dtype=torch.uint8, device=dev)
+
+            def gram_deferred():
+                for i in range(chunks):
+                    gq.gq_fisher_gram_heavy_deferred(X[i * c:(i + 1) * c], s[i * c:(i + 1) * c], pool, pool_rows, H=H,
+                                                     accumulate=i > 0, workspace=ws_g)
+                gq.gq_fisher_gram_heavy_flush(pool, pool_rows, H, workspace=ws_p)
+            gram_deferred()                                                               # warm-up
+            ts = []
+            for _ in range(5):
+                e0.record()
+                gram_deferred()
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            mode_ms["heavy_deferred"] = statistics.median(ts)
+            result["fisher_gram_heavy_deferred"] = {
+                "ms": mode_ms["heavy_deferred"], "pool_rows": pool_rows,
+                "frac_of_peak": fl / (mode_ms["heavy_deferred"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "note": "gq_fisher_gram_heavy_deferred per chunk + one gq_fisher_gram_heavy_flush: the same heavy rows in "
+                        "two bf16 terms, their pass once instead of once per chunk; this H is the one factored below"}
         gq.gq_fisher_mirror(H)
         torch.cuda.synchronize()
         gram2_ms = mode_ms["two_terms"]

@@ -160,6 +160,36 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * GQ_HEAVY_TWO_TERMS for callers that feed the tokens in chunks (Algorithm 1, line 4, accumulated over
+ * token chunks).  The two-term pass over a call's heaviest tokens adds to every entry of H, so with
+ * gq_fisher_gram every chunk pays a read-modify-write of the whole H for a few dozen rows.  Here the
+ * heavy rows of every chunk are gathered into a pool the caller keeps, and their pass runs once:
+ *
+ *   pool = device memory of gq_fisher_gram_heavy_pool_bytes(d_in, G, pool_rows) bytes, 256-byte aligned,
+ *       filled with zero bytes ONCE before its first use; pool_rows (a multiple of 32, >= 32) is the
+ *       number of token rows it takes.  The first 4 bytes hold the number of rows in use.
+ *   gq_fisher_gram_heavy_deferred(...): gq_fisher_gram with GQ_BF16 and GQ_HEAVY_TWO_TERMS (the same
+ *       selection rule, per call; flags: GQ_ACCUMULATE only), except that the heavy rows go to the
+ *       pool instead of through their two-term pass.  Rows that the pool has no room for stay in the
+ *       one-term pass, as rows beyond a call's capacity do.  workspace as for gq_fisher_gram.
+ *   gq_fisher_gram_heavy_flush(...): adds the two-term products of the rows in the pool to H (upper
+ *       triangle; GQ_MIRROR allowed, no other flag) and leaves the pool empty.  Call it after the last
+ *       chunk, or whenever the pool may be full; an empty pool adds nothing.  workspace:
+ *       gq_fisher_gram_workspace_bytes(GQ_BF16, pool_rows, d_in, G).
+ *
+ * H after the flush is the H of the same chunk calls made with gq_fisher_gram and GQ_HEAVY_TWO_TERMS up
+ * to the order of the fp32 additions; identical arguments and pool contents give identical bits.
+ * d_in and G must be the same in all calls on one pool between two flushes.  Calls on one pool must
+ * not overlap.  Errors as gq_fisher_gram; GQ_ERR_SHAPE for a bad pool_rows.
+ */
+size_t gq_fisher_gram_heavy_pool_bytes(int64_t d_in, int32_t G, int64_t pool_rows);
+int gq_fisher_gram_heavy_deferred(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int64_t ld_x, const float* s,
+                                  int32_t G, float* H, uint32_t flags, void* workspace, size_t workspace_bytes,
+                                  void* pool, int64_t pool_rows, void* hip_stream);
+int gq_fisher_gram_heavy_flush(void* pool, int64_t pool_rows, int64_t d_in, int32_t G, float* H, uint32_t flags,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Schedule tuning of the bf16 Gram kernel (no passage of the paper: a property of the chip).  The eight
  * XCDs of one MI355X do not run the kernel at the same speed (shared power budget, silicon spread:
  * up to +-5 % around the mean, stable for a device), and the work items left over after the whole

@@ -60,6 +60,15 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gq_fisher_gram_set_xcd_speeds.argtypes = [c.c_void_p]
     lib.gq_fisher_gram_measured_xcd_speeds.restype = c.c_int
     lib.gq_fisher_gram_measured_xcd_speeds.argtypes = [c.c_int64, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p]
+    lib.gq_fisher_gram_heavy_pool_bytes.restype = c.c_size_t
+    lib.gq_fisher_gram_heavy_pool_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int64]
+    lib.gq_fisher_gram_heavy_deferred.restype = c.c_int
+    lib.gq_fisher_gram_heavy_deferred.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
+                                                  c.c_int32, c.c_void_p, c.c_uint32, c.c_void_p, c.c_size_t,
+                                                  c.c_void_p, c.c_int64, c.c_void_p]
+    lib.gq_fisher_gram_heavy_flush.restype = c.c_int
+    lib.gq_fisher_gram_heavy_flush.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int32, c.c_void_p, c.c_uint32,
+                                               c.c_void_p, c.c_size_t, c.c_void_p]
     lib.gq_fisher_gram_noalloc_max_scratch_bytes.restype = c.c_size_t
     lib.gq_fisher_gram_noalloc_max_scratch_bytes.argtypes = []
     lib.gq_fisher_mirror.restype = c.c_int
@@ -196,6 +205,61 @@ def gq_fisher_gram(X: torch.Tensor, s: torch.Tensor, H: Optional[torch.Tensor] =
     st = lib.gq_fisher_gram(X.data_ptr(), _dtype_code(X), n, d_in, _rows(X) if n > 0 else d_in,
                             s.data_ptr(), G, H.data_ptr(), flags, ws_ptr, ws_bytes, _stream())
     _check(st, "gq_fisher_gram")
+    return H
+
+
+def gq_fisher_gram_heavy_pool(d_in: int, G: int, pool_rows: int, device) -> torch.Tensor:
+    """An empty pool (zero bytes) for gq_fisher_gram_heavy_deferred / gq_fisher_gram_heavy_flush."""
+    need = int(load_library().gq_fisher_gram_heavy_pool_bytes(d_in, G, pool_rows))
+    if need == 0:
+        raise ValueError("pool_rows must be a multiple of 32, at least 32")
+    return torch.zeros(need, dtype=torch.uint8, device=device)
+
+
+def gq_fisher_gram_heavy_deferred(X: torch.Tensor, s: torch.Tensor, pool: torch.Tensor, pool_rows: int,
+                                  H: Optional[torch.Tensor] = None, accumulate: bool = False,
+                                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """gq_fisher_gram with heavy_two_terms for chunked callers: the heavy rows go to `pool`, their two-term pass
+    runs in gq_fisher_gram_heavy_flush."""
+    _require_gpu(X, s, H, workspace, pool)
+    n, d_in = X.shape
+    G = int(s.shape[1])
+    assert s.dtype == torch.float32 and s.is_contiguous() and s.shape[0] == n
+    if H is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs an existing H")
+        H = torch.empty((G, d_in, d_in), dtype=torch.float32, device=X.device)
+    assert H.dtype == torch.float32 and H.is_contiguous() and tuple(H.shape) == (G, d_in, d_in)
+    lib = load_library()
+    need = int(lib.gq_fisher_gram_workspace_bytes(_dtype_code(X), n, d_in, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(need, X.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    st = lib.gq_fisher_gram_heavy_deferred(X.data_ptr(), _dtype_code(X), n, d_in, _rows(X) if n > 0 else d_in,
+                                           s.data_ptr(), G, H.data_ptr(), GQ_ACCUMULATE if accumulate else 0,
+                                           ws_ptr, ws_bytes, pool.data_ptr(), pool_rows, _stream())
+    _check(st, "gq_fisher_gram_heavy_deferred")
+    return H
+
+
+def gq_fisher_gram_heavy_flush(pool: torch.Tensor, pool_rows: int, H: torch.Tensor, mirror: bool = False,
+                               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Adds the two-term products of the rows gathered in `pool` to H and empties the pool."""
+    _require_gpu(H, workspace, pool)
+    G, d_in = int(H.shape[0]), int(H.shape[1])
+    assert H.dtype == torch.float32 and H.is_contiguous() and tuple(H.shape) == (G, d_in, d_in)
+    lib = load_library()
+    need = int(lib.gq_fisher_gram_workspace_bytes(GQ_BF16, pool_rows, d_in, G))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(need, H.device)
+        ws_bytes = need
+    else:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    st = lib.gq_fisher_gram_heavy_flush(pool.data_ptr(), pool_rows, d_in, G, H.data_ptr(), GQ_MIRROR if mirror else 0,
+                                        ws_ptr, ws_bytes, _stream())
+    _check(st, "gq_fisher_gram_heavy_flush")
     return H
 
 

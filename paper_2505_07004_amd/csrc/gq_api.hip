@@ -88,6 +88,47 @@ int gq_fisher_gram(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int
   return from_hip(e);
 }
 
+size_t gq_fisher_gram_heavy_pool_bytes(int64_t d_in, int32_t G, int64_t pool_rows) {
+  if (d_in <= 0 || G <= 0 || pool_rows < 32 || pool_rows % 32 != 0 || pool_rows >= ((int64_t)1 << 28)) return 0;
+  return gq::fisher_gram_heavy_pool_bytes(d_in, G, pool_rows);
+}
+
+int gq_fisher_gram_heavy_deferred(const void* X, gq_dtype x_dtype, int64_t n, int64_t d_in, int64_t ld_x, const float* s,
+                                  int32_t G, float* H, uint32_t flags, void* workspace, size_t workspace_bytes, void* pool,
+                                  int64_t pool_rows, void* hip_stream) {
+  if (!valid_dtype((int)x_dtype)) return GQ_ERR_DTYPE;
+  if (x_dtype != GQ_BF16) return GQ_ERR_UNSUPPORTED;
+  if (n < 0 || d_in <= 0 || G <= 0 || ld_x < d_in) return GQ_ERR_SHAPE;
+  if (pool_rows < 32 || pool_rows % 32 != 0 || pool_rows >= ((int64_t)1 << 28)) return GQ_ERR_SHAPE;
+  if (flags & ~(uint32_t)(GQ_ACCUMULATE | GQ_HEAVY_TWO_TERMS)) return GQ_ERR_UNSUPPORTED;
+  if (!H || !pool) return GQ_ERR_NULLPTR;
+  if (n > 0 && (!X || !s)) return GQ_ERR_NULLPTR;
+  if (!aligned16(H) || !aligned256(pool)) return GQ_ERR_ALIGN;
+  if (n > 0 && (!aligned16(X) || ((size_t)ld_x * 2) % 16 != 0)) return GQ_ERR_ALIGN;
+  if (ld_x >= ((int64_t)1 << 26) || n >= ((int64_t)1 << 28)) return GQ_ERR_UNSUPPORTED;
+  const size_t need = gq_fisher_gram_workspace_bytes(x_dtype, n, d_in, G);
+  if (need > 0 && (!workspace || workspace_bytes < need || !aligned256(workspace))) return GQ_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool accumulate = (flags & GQ_ACCUMULATE) != 0;
+  if (n == 0) return accumulate ? GQ_OK : from_hip(gq::launch_zero_upper(H, d_in, G, st));
+  return from_hip(gq::launch_fisher_gram_bf16_heavy_deferred(X, n, d_in, ld_x, s, G, H, accumulate, workspace, pool, pool_rows, st));
+}
+
+int gq_fisher_gram_heavy_flush(void* pool, int64_t pool_rows, int64_t d_in, int32_t G, float* H, uint32_t flags,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (d_in <= 0 || G <= 0 || pool_rows < 32 || pool_rows % 32 != 0 || pool_rows >= ((int64_t)1 << 28)) return GQ_ERR_SHAPE;
+  if (flags & ~(uint32_t)GQ_MIRROR) return GQ_ERR_UNSUPPORTED;
+  if (!H || !pool) return GQ_ERR_NULLPTR;
+  if (!aligned16(H) || !aligned256(pool)) return GQ_ERR_ALIGN;
+  const size_t need = gq_fisher_gram_workspace_bytes(GQ_BF16, pool_rows, d_in, G);
+  if (!workspace || workspace_bytes < need || !aligned256(workspace)) return GQ_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = gq::launch_fisher_gram_bf16_heavy_flush(pool, pool_rows, d_in, G, H, workspace, st);
+  if (e != hipSuccess) return GQ_ERR_HIP;
+  if (flags & GQ_MIRROR) e = gq::launch_mirror(H, d_in, G, st);
+  return from_hip(e);
+}
+
 int gq_fisher_gram_set_xcd_speeds(const float* speeds) {
   if (speeds)
     for (int i = 0; i < 8; ++i)

@@ -191,6 +191,15 @@ int64_t heavy_capacity(int64_t n);
 size_t fisher_gram_heavy_workspace(int64_t n, int64_t d_in, int G);
 hipError_t launch_fisher_gram_bf16_heavy(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
                                          float* H, bool accumulate, void* ws, hipStream_t st);
+// The deferred form: a chunk call gathers its heavy rows into the caller's pool (pool_rows rows, a multiple of 32)
+// and runs the main call only; the flush runs the two-term call over the rows in the pool, adding to H, and
+// leaves the pool empty.
+size_t fisher_gram_heavy_pool_bytes(int64_t d_in, int G, int64_t rows);
+hipError_t launch_fisher_gram_bf16_heavy_deferred(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
+                                                  float* H, bool accumulate, void* ws, void* pool, int64_t pool_rows,
+                                                  hipStream_t st);
+hipError_t launch_fisher_gram_bf16_heavy_flush(void* pool, int64_t pool_rows, int64_t d_in, int G, float* H, void* ws,
+                                               hipStream_t st);
 // Relative speeds of the eight XCDs for the schedule of the wide Gram kernel (nullptr: all equal), a setting of
 // the current device; and the speeds measured by the last plain one-term call that used workspace `ws`.
 hipError_t fisher_gram_set_xcd_speeds(const float* a8);

@@ -15,6 +15,12 @@
 // The first heavy_capacity(n) heavy tokens in token order are gathered; further ones, if any,
 // stay in the main call.  Everything is decided on the device in a fixed order (no atomics),
 // so identical arguments give identical bits.
+//
+// Chunked calls.  The second call adds to every entry of H, so a caller that feeds the tokens in chunks pays a
+// read-modify-write of the whole H per chunk for a few dozen rows.  The deferred form gathers the heavy rows of
+// every chunk into a pool the caller keeps (header: the number of rows in use; then the rows' weights, then the
+// rows) and the second call runs once, over the pool, when the caller flushes it.  A full pool leaves further
+// heavy tokens in the main calls, as a full capacity does.
 #include "gq_internal.hpp"
 
 namespace gq {
@@ -120,7 +126,12 @@ __global__ __launch_bounds__(256) void heavy_count_kernel(const float* __restric
 __global__ __launch_bounds__(256) void heavy_assign_kernel(const float* __restrict__ s, int64_t n, int G,
                                                            const double* __restrict__ sums, int64_t n_blocks,
                                                            int* __restrict__ counts, int n_cap, int* __restrict__ idx,
-                                                           float* __restrict__ s_main) {
+                                                           float* __restrict__ s_main, const int* __restrict__ pool_cursor,
+                                                           int pool_rows) {
+  if (pool_cursor) {                                 // deferred form: no more than the pool still takes
+    const int room = pool_rows - *pool_cursor;
+    n_cap = room < n_cap ? (room > 0 ? room : 0) : n_cap;
+  }
   extern __shared__ float thr[];
   __shared__ long long red[256];
   __shared__ int scan[256];
@@ -187,7 +198,99 @@ __global__ __launch_bounds__(256) void heavy_gather_kernel(const __bf16* __restr
   for (int k = threadIdx.x; k < G; k += 256) sh[(int64_t)r * G + k] = live ? s[t * G + k] : 0.f;
 }
 
+// ---- the pool of the deferred form ---------------------------------------------------------------
+struct PoolLayout {
+  int64_t ld_h;
+  size_t off_s, off_x, bytes;
+};
+PoolLayout pool_layout(int64_t d_in, int G, int64_t rows) {
+  PoolLayout P;
+  P.ld_h = (d_in + 7) / 8 * 8;
+  size_t o = 256;                                             // header: [0] = rows in use
+  P.off_s = o; o += up256((size_t)rows * G * sizeof(float));
+  P.off_x = o; o += up256((size_t)rows * P.ld_h * 2);
+  P.bytes = o;
+  return P;
+}
+
+// Row r of this call's heavy tokens goes to pool row cursor + r; the rows from there up to the next multiple
+// of 32 are cleared (weights 0), so that the pass over the pool can always run whole token steps.
+__global__ __launch_bounds__(256) void heavy_gather_pool_kernel(const __bf16* __restrict__ X, int64_t d_in, int64_t ld,
+                                                                const float* __restrict__ s, int G,
+                                                                const int* __restrict__ idx, const int* __restrict__ taken,
+                                                                const int* __restrict__ cursor, int64_t ld_h,
+                                                                __bf16* __restrict__ Xp, float* __restrict__ sp) {
+  const int r = blockIdx.x, n_taken = *taken, base = *cursor;
+  const int end32 = (base + n_taken + 31) / 32 * 32;
+  const bool live = r < n_taken;
+  if (!live && base + r >= end32) return;                      // uniform for the block
+  const int64_t t = live ? idx[r] : 0;
+  const uint4* src = reinterpret_cast<const uint4*>(X + t * ld);
+  uint4* dst = reinterpret_cast<uint4*>(Xp + (int64_t)(base + r) * ld_h);
+  const int64_t chunks = ld_h / 8, src_chunks = (d_in + 7) / 8;
+  for (int64_t c = threadIdx.x; c < chunks; c += 256) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (live && c < src_chunks) v = src[c];
+    dst[c] = v;
+  }
+  for (int k = threadIdx.x; k < G; k += 256) sp[(int64_t)(base + r) * G + k] = live ? s[t * G + k] : 0.f;
+}
+__global__ void heavy_pool_advance_kernel(int* __restrict__ cursor, const int* __restrict__ taken) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *cursor += *taken;
+}
+// An empty pool: no rows in use, and a first token step of weight 0 (the pass over the pool runs at least one).
+__global__ __launch_bounds__(256) void heavy_pool_reset_kernel(int* __restrict__ cursor, float* __restrict__ sp, int G) {
+  for (int i = threadIdx.x; i < 32 * G; i += 256) sp[i] = 0.f;
+  if (threadIdx.x == 0) *cursor = 0;
+}
+
 }  // namespace
+
+size_t fisher_gram_heavy_pool_bytes(int64_t d_in, int G, int64_t rows) { return pool_layout(d_in, G, rows).bytes; }
+
+hipError_t launch_fisher_gram_bf16_heavy_deferred(const void* X, int64_t n, int64_t d_in, int64_t ld, const float* s, int G,
+                                                  float* H, bool accumulate, void* ws, void* pool, int64_t pool_rows,
+                                                  hipStream_t st) {
+  const HeavyLayout L = heavy_layout(n, d_in, G);
+  const PoolLayout P = pool_layout(d_in, G, pool_rows);
+  const size_t a = fisher_gram_bf16_workspace(n, d_in, G), b = fisher_gram_bf16_workspace(L.n_cap, d_in, G);
+  char* hw = (char*)ws + up256(a > b ? a : b);
+  double* sums = (double*)(hw + L.off_sums);
+  int* counts = (int*)(hw + L.off_counts);
+  int* idx = (int*)(hw + L.off_idx);
+  float* s_main = (float*)(hw + L.off_smain);
+  int* cursor = (int*)pool;
+  float* s_p = (float*)((char*)pool + P.off_s);
+  __bf16* X_p = (__bf16*)((char*)pool + P.off_x);
+  const dim3 grid((unsigned)L.n_blocks), block(256);
+  const size_t thr_bytes = (size_t)G * sizeof(float);
+  heavy_sums_kernel<<<grid, block, 0, st>>>(s, n, G, sums);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  heavy_count_kernel<<<grid, block, thr_bytes, st>>>(s, n, G, sums, L.n_blocks, counts);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  heavy_assign_kernel<<<grid, block, thr_bytes, st>>>(s, n, G, sums, L.n_blocks, counts, (int)L.n_cap, idx, s_main, cursor,
+                                                      (int)pool_rows);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  heavy_gather_pool_kernel<<<dim3((unsigned)(L.n_cap + 32)), block, 0, st>>>((const __bf16*)X, d_in, ld, s, G, idx,
+                                                                           counts + L.n_blocks, cursor, P.ld_h, X_p, s_p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  heavy_pool_advance_kernel<<<dim3(1), dim3(64), 0, st>>>(cursor, counts + L.n_blocks);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  return launch_fisher_gram_bf16(X, n, d_in, ld, s_main, G, H, accumulate, false, ws, false, st);
+}
+
+hipError_t launch_fisher_gram_bf16_heavy_flush(void* pool, int64_t pool_rows, int64_t d_in, int G, float* H, void* ws,
+                                               hipStream_t st) {
+  const PoolLayout P = pool_layout(d_in, G, pool_rows);
+  int* cursor = (int*)pool;
+  float* s_p = (float*)((char*)pool + P.off_s);
+  const __bf16* X_p = (const __bf16*)((char*)pool + P.off_x);
+  hipError_t e = launch_fisher_gram_bf16(X_p, pool_rows, d_in, P.ld_h, s_p, G, H, true, true, ws, false, st, cursor);
+  if (e != hipSuccess) return e;
+  heavy_pool_reset_kernel<<<dim3(1), dim3(256), 0, st>>>(cursor, s_p, G);
+  return hipGetLastError();
+}
 
 int64_t heavy_capacity(int64_t n) { return 32 * ((n + 2047) / 2048 > 0 ? (n + 2047) / 2048 : 1); }
 
@@ -215,7 +318,8 @@ hipError_t launch_fisher_gram_bf16_heavy(const void* X, int64_t n, int64_t d_in,
   if (e != hipSuccess) return e;
   heavy_count_kernel<<<grid, block, thr_bytes, st>>>(s, n, G, sums, L.n_blocks, counts);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  heavy_assign_kernel<<<grid, block, thr_bytes, st>>>(s, n, G, sums, L.n_blocks, counts, (int)L.n_cap, idx, s_main);
+  heavy_assign_kernel<<<grid, block, thr_bytes, st>>>(s, n, G, sums, L.n_blocks, counts, (int)L.n_cap, idx, s_main,
+                                                      nullptr, 0);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   heavy_gather_kernel<<<dim3((unsigned)L.n_cap), block, 0, st>>>((const __bf16*)X, d_in, ld, s, G, idx,
                                                                 counts + L.n_blocks, L.ld_h, X_h, s_h);

@@ -120,3 +120,65 @@ def test_heavy_mode_accumulates_over_chunks_mirrors_and_gives_a_factorable_h():
     b = gq.gq_fisher_gram(X, s, heavy_two_terms=True)
     torch.cuda.synchronize()
     assert torch.equal(torch.triu(a), torch.triu(b))              # deterministic
+
+
+def _deferred(chunks, pool_rows, d_in, G):
+    pool = gq.gq_fisher_gram_heavy_pool(d_in, G, pool_rows, DEV)
+    H = None
+    for i, (Xc, sc) in enumerate(chunks):
+        H = gq.gq_fisher_gram_heavy_deferred(Xc, sc, pool, pool_rows, H=H, accumulate=i > 0)
+    in_use = int(pool[:4].view(torch.int32).item())
+    gq.gq_fisher_gram_heavy_flush(pool, pool_rows, H)
+    torch.cuda.synchronize()
+    assert int(pool[:4].view(torch.int32).item()) == 0          # the flush leaves the pool empty
+    return H, in_use, pool
+
+
+@pytest.mark.parametrize("sizes,d_in,G,pool_rows", [
+    ((3000, 2500, 1777), 520, 4, 256),     # wide main passes; 48 + 64 + 32 rows of capacity fit
+    ((2048, 2048, 2048, 2048), 264, 3, 64),   # narrow main passes; the pool fills up: later heavy tokens stay one-term
+    ((700,), 136, 1, 32),
+])
+def test_heavy_rows_gathered_over_chunks_and_flushed_once(sizes, d_in, G, pool_rows):
+    """The deferred form: per chunk the same selection as the plain heavy-token call, the rows of all chunks in one
+    pool, one two-term pass at the end.  Against the oracle, against the same passes made by hand (selection rule
+    retyped on the host; the hand-made second pass sees fewer rows, so fp32 sums may be grouped differently), and
+    bit for bit against itself."""
+    n = sum(sizes)
+    say(f"deferred heavy rows: chunks {sizes} d_in={d_in} G={G} pool of {pool_rows} rows")
+    X, s = _case(n, d_in, G, 1300 + n)
+    cuts = np.cumsum((0,) + tuple(sizes))
+    chunks = [(X[a:b], s[a:b]) for a, b in zip(cuts[:-1], cuts[1:])]
+    H, in_use, pool = _deferred(chunks, pool_rows, d_in, G)
+    # by hand
+    ref2, rows_x, rows_s, room = None, [], [], pool_rows
+    for i, (Xc, sc) in enumerate(chunks):
+        idx, s_main, _, _, _ = _split_on_host(Xc, sc)
+        idx = idx[:room]                                        # what the pool still takes
+        s_main = sc.clone()
+        s_main[idx] = 0
+        room -= idx.numel()
+        rows_x.append(Xc[idx])
+        rows_s.append(sc[idx])
+        ref2 = gq.gq_fisher_gram(Xc, s_main.contiguous(), H=ref2, accumulate=i > 0)
+    Xh, sh = torch.cat(rows_x), torch.cat(rows_s)
+    assert in_use == Xh.shape[0]
+    say(f"  {in_use} rows in the pool before the flush")
+    if in_use:
+        gq.gq_fisher_gram(Xh.contiguous(), sh.contiguous(), H=ref2, accumulate=True, two_terms=True)
+    torch.cuda.synchronize()
+    iu = torch.triu_indices(d_in, d_in, device=DEV)
+    a, b = H[:, iu[0], iu[1]], ref2[:, iu[0], iu[1]]
+    assert float((a - b).abs().max() / b.abs().max()) < 2e-6
+    ref = oracle.fisher_gram(to_np64(X), to_np64(s))
+    got = to_np64(H)
+    errs = [rel_fro(np.triu(got[k]), np.triu(ref[k])) for k in range(G)]
+    say(f"  rel-Frobenius per group {['%.2e' % e for e in errs]}")
+    assert max(errs) <= TOL_BF16
+    again, _, _ = _deferred(chunks, pool_rows, d_in, G)
+    assert torch.equal(again[:, iu[0], iu[1]], a)
+    # an empty pool adds nothing
+    before = H.clone()
+    gq.gq_fisher_gram_heavy_flush(pool, pool_rows, H)
+    torch.cuda.synchronize()
+    assert torch.equal(H[:, iu[0], iu[1]], before[:, iu[0], iu[1]])

@@ -194,7 +194,8 @@ int gq_fisher_gram_heavy_flush(void* pool, int64_t pool_rows, int64_t d_in, int3
  * XCDs of one MI355X do not run the kernel at the same speed (shared power budget, silicon spread:
  * up to +-5 % around the mean, stable for a device), and the work items left over after the whole
  * rounds are cut into runs of equal COST.  With relative speeds set, the runs are cut so that all
- * workgroups finish at the same TIME instead.
+ * workgroups finish at the same TIME instead (and calls with several rounds deal their whole items
+ * to the XCDs in proportion to the speeds).
  *
  *   gq_fisher_gram_set_xcd_speeds(speeds): host pointer to 8 floats in [0.5, 2] (relative speed of
  *       XCD 0..7; only their ratios matter), or NULL for the default (all equal).  A setting of the

@@ -120,6 +120,24 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gq_fisher_gram_set_xcd_speeds(ctypes.cast(bad, ctypes.c_void_p)) == -2
     assert lib.gq_fisher_gram_measured_xcd_speeds(1024, 4096, 4, None, ctypes.cast(bad, ctypes.c_void_p)) == -1
     assert lib.gq_fisher_gram_measured_xcd_speeds(0, 4096, 4, a16, ctypes.cast(bad, ctypes.c_void_p)) == -2
+    # heavy-token rows gathered over chunk calls: the pool and its two calls
+    w256 = P(0x1100)
+    assert lib.gq_fisher_gram_heavy_pool_bytes(4096, 4, 1024) == 256 + 1024 * 4 * 4 + 1024 * 4096 * 2
+    assert lib.gq_fisher_gram_heavy_pool_bytes(4096, 4, 100) == 0                       # not a multiple of 32
+    assert lib.gq_fisher_gram_heavy_pool_bytes(4096, 4, 0) == 0
+    defer = lambda **kw: lib.gq_fisher_gram_heavy_deferred(
+        kw.get("X", a16), kw.get("dt", 1), kw.get("n", 64), 64, kw.get("ld", 64), a16, 4, kw.get("H", a16),
+        kw.get("flags", 0), w256, big, kw.get("pool", P(0x2000)), kw.get("rows", 64), None)
+    assert defer(rows=48) == -2                                                         # pool_rows not a multiple of 32
+    assert defer(dt=0) == -7                                                            # fp32 X: no heavy-token mode
+    assert defer(flags=2) == -7                                                         # GQ_MIRROR belongs to the flush
+    assert defer(pool=None) == -1
+    assert defer(pool=P(0x2010)) == -4                                                  # pool not 256-byte aligned
+    assert defer(ld=60) == -2
+    assert lib.gq_fisher_gram_heavy_flush(P(0x2000), 64, 64, 4, a16, 1, w256, big, None) == -7    # only GQ_MIRROR
+    assert lib.gq_fisher_gram_heavy_flush(P(0x2000), 40, 64, 4, a16, 0, w256, big, None) == -2
+    assert lib.gq_fisher_gram_heavy_flush(P(0x2000), 64, 64, 4, None, 0, w256, big, None) == -1
+    assert lib.gq_fisher_gram_heavy_flush(P(0x2000), 64, 64, 4, a16, 0, w256, 16, None) == -5     # workspace too small
     # codebook step
     lam = 1e-7
     # no [d_out * m, d_in] intermediate and no full copy of H in three terms: the 70B down projection stays under 1 GiB

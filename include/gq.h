@@ -206,8 +206,11 @@ int gq_fisher_gram_heavy_flush(void* pool, int64_t pool_rows, int64_t d_in, int3
  *       columns, times up to three token segments, number at least 256) records, per workgroup, the time and the cost of its whole
  *       work items in its workspace; this call copies those records of the LAST such call with these
  *       sizes and this workspace to the host (it waits for the device) and writes the 8 relative
- *       speeds (mean 1) to the host array `speeds`.  GQ_ERR_UNSUPPORTED when such a call records nothing (other group
- *       counts, fewer than 256 work items, no left-over items) or the records are empty.
+ *       speeds (mean 1) to the host array `speeds`.  The speeds are coupled through the chip's power
+ *       budget (an XCD runs faster while others wait): measuring again under the tuned schedule and
+ *       averaging with the setting, two or three times, gives a better setting than one measurement.
+ *       GQ_ERR_UNSUPPORTED when such a call records nothing (other group counts, fewer than 256
+ *       work items, no left-over items) or the records are empty.
  *
  * The speeds decide where the runs are cut, hence the rounding of the sums: results are bit-identical
  * for identical arguments and identical speeds, and within the documented tolerance for any speeds.

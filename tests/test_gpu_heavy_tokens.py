@@ -48,6 +48,7 @@ def _case(n, d_in, G, seed, kind="silu", sigma=1.5):
     (3000, 264, 3, "outlier"),       # narrow kernel for both passes
     (40, 72, 4, "silu"),             # fewer tokens than the capacity
     (2048, 256, 1, "silu"),
+    (2100, 520, 5, "silu"),          # odd group count: the main pass runs as four groups (wide kernel) + one (narrow)
 ])
 def test_heavy_mode_is_its_two_passes_and_matches_the_oracle(n, d_in, G, kind):
     say(f"heavy-token mode n={n} d_in={d_in} G={G} {kind}")

@@ -439,8 +439,18 @@ __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __rest
   double acc = 0.0;
   if (jj < m) {
     const int64_t j = (int64_t)k * m + jj;
+    // the partials are added in the order tb = 0, 1, ...; eight loads at a time are in flight (a loop of one load
+    // and one add per turn waits for every load in turn)
     float v = 0.f;
-    for (int tb = 0; tb < n_tb; ++tb) v += partial[(int64_t)tb * d_out + j];
+    int tb = 0;
+    for (; tb + 8 <= n_tb; tb += 8) {
+      float p[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) p[u] = partial[(int64_t)(tb + u) * d_out + j];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v += p[u];
+    }
+    for (; tb < n_tb; ++tb) v += partial[(int64_t)tb * d_out + j];
     if (obj_row) obj_row[j] = v;
     acc = (double)v;
   }
